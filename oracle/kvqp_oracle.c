@@ -1,0 +1,632 @@
+/*
+ * kvqp_oracle.c -- CPU oracle for the quantized-pruned KV cache.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  It is a plain, slow,
+ * step-by-step statement of what the hot path computes, written from the
+ * paper (arXiv 2412.12706, "More Tokens, Lower Precision"), used only by the
+ * tests, the smoke check and the benchmark's CPU-baseline leg.  It shares no
+ * code, header, table or helper with the HIP library and must never be
+ * called from the product path.
+ *
+ * Parity pins (tests/test_oracle_*.py): identity selection when the budget
+ * covers the prefix; top-k of raw logits when W=1, pool=1, Gq=1; brute force
+ * on tiny L; quantization closed forms (ramp, constant, two-valued groups,
+ * end codes, scale/2 error bound, exact rational cross-check); 16-bit mode
+ * equal to textbook softmax attention computed by an independent library
+ * routine; half<->float conversions against numpy.  No function here is
+ * "parity unpinned"; what is *defined* rather than derived (window votes,
+ * pooling, tie rule, bit layout) is listed with each function.
+ *
+ * Arithmetic: float64 everywhere a real-valued result is produced (votes,
+ * attention).  Quantized codes are integers decided by floating point, so
+ * that decision is taken in the precision the kernel uses: a fixed IEEE
+ * binary32 operation sequence, round-to-nearest-even, no fused multiply-add
+ * (build with -ffp-contract=off, never -ffast-math).
+ *
+ * Notation follows the paper, Section 3 (Methods): X_K, X_V are the cached
+ * keys/values, s the token budget, B the bit width, G_i a quantization
+ * group with minimum z_i, maximum m_i and scale s_i.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ */
+/* binary16 <-> binary32/64, written out bit by bit (gcc 11 has no      */
+/* _Float16 on x86-64).  Pinned against numpy's float16 in the tests.   */
+/* ------------------------------------------------------------------ */
+
+double orc_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int m = h & 0x3ff;
+    double v;
+    if (e == 0)
+        v = ldexp((double)m, -24); /* zero and subnormals */
+    else if (e == 31)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexp((double)(1024 + m), e - 25);
+    return sign ? -v : v;
+}
+
+/* binary32 -> binary16, round to nearest, ties to even. */
+uint16_t orc_float_to_half(float f)
+{
+    uint32_t x;
+    memcpy(&x, &f, 4);
+    uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    uint32_t a = x & 0x7fffffffu;
+    if (a >= 0x7f800000u) /* inf / nan */
+        return (uint16_t)(sign | 0x7c00u | (a > 0x7f800000u ? 0x200u : 0));
+    if (a >= 0x477ff000u) /* >= 65520 rounds to inf */
+        return (uint16_t)(sign | 0x7c00u);
+    if (a < 0x33000000u) /* below 2^-25: rounds to zero (2^-25 itself is handled below) */
+        return sign;
+    int e = (int)(a >> 23) - 127; /* unbiased */
+    uint32_t man = (a & 0x7fffffu) | 0x800000u; /* 24-bit significand */
+    int shift; /* number of low bits dropped */
+    uint32_t base;
+    if (e < -14) { /* result is subnormal: value = man * 2^(e-23), unit 2^-24 */
+        shift = -1 - e; /* (e-23) - (-24) = e+1 -> drop -(e+1) bits */
+        base = 0;
+    } else {
+        shift = 13;
+        base = (uint32_t)(e + 15) << 10;
+        man &= 0x7fffffu;
+    }
+    uint32_t q = man >> shift;
+    uint32_t rem = man & ((1u << shift) - 1);
+    uint32_t half = 1u << (shift - 1);
+    if (rem > half || (rem == half && (q & 1)))
+        q += 1; /* carry may roll into the exponent, which is the right answer */
+    return (uint16_t)(sign | (base + q));
+}
+
+void orc_float_to_half_array(const float *in, uint16_t *out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        out[i] = orc_float_to_half(in[i]);
+}
+
+void orc_half_to_double_array(const uint16_t *in, double *out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        out[i] = orc_half_to_double(in[i]);
+}
+
+static float half_to_float(uint16_t h) { return (float)orc_half_to_double(h); /* exact */ }
+
+/* ------------------------------------------------------------------ */
+/* Selection (KV pruning, Section 3 "KV Pruning": pick s < n tokens at  */
+/* prefill).  The paper cites an attention-score method and keeps the   */
+/* last 32 tokens (Appendix B); the scoring details below -- window     */
+/* votes, causal mask inside the window, sum over the query-head group, */
+/* one max-pool, (score desc, index asc) order -- are this build's      */
+/* stated reading, since the paper is silent on them.                   */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Window votes.  For KV head g and each query head h of its group, each of
+ * the last W prompt positions i (absolute position P+i, P = L-W) attends
+ * causally over keys 0..P+i with Softmax(sm_scale * q k^T) (the decode
+ * attention form of Section 3, Eq. "attno", with an explicit scale); the
+ * vote of prefix key j < P is the sum of those probabilities over the group's
+ * heads and the W rows.
+ *   q_obs [B,Hq,W,D] half, k [B,Hkv,L,D] half -> vote [B,Hkv,P] double
+ */
+int orc_window_votes(int B, int Hq, int Hkv, int D, int L, int W, double sm_scale,
+                     const uint16_t *q_obs, const uint16_t *k, double *vote)
+{
+    if (B < 1 || Hkv < 1 || Hq % Hkv || W < 1 || W > L || D < 1)
+        return -1;
+    const int Gq = Hq / Hkv, P = L - W;
+    int status = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hkv; ++g) {
+            double *a = (double *)malloc(sizeof(double) * (size_t)L);
+            double *kd = (double *)malloc(sizeof(double) * (size_t)L * D);
+            if (!a || !kd) {
+                status = -2;
+                free(a);
+                free(kd);
+                continue;
+            }
+            const uint16_t *kh = k + ((size_t)b * Hkv + g) * (size_t)L * D;
+            for (size_t e = 0; e < (size_t)L * D; ++e)
+                kd[e] = orc_half_to_double(kh[e]);
+            double *vt = vote + ((size_t)b * Hkv + g) * (size_t)P;
+            for (int j = 0; j < P; ++j)
+                vt[j] = 0.0;
+            for (int h = g * Gq; h < (g + 1) * Gq; ++h)
+                for (int i = 0; i < W; ++i) {
+                    const uint16_t *qr = q_obs + (((size_t)b * Hq + h) * W + i) * (size_t)D;
+                    const int last = P + i; /* causal: keys 0..P+i */
+                    double mx = -INFINITY;
+                    for (int j = 0; j <= last; ++j) {
+                        double s = 0.0;
+                        for (int d = 0; d < D; ++d)
+                            s += orc_half_to_double(qr[d]) * kd[(size_t)j * D + d];
+                        a[j] = sm_scale * s;
+                        if (a[j] > mx)
+                            mx = a[j];
+                    }
+                    double Z = 0.0;
+                    for (int j = 0; j <= last; ++j)
+                        Z += exp(a[j] - mx);
+                    for (int j = 0; j < P; ++j)
+                        vt[j] += exp(a[j] - mx) / Z;
+                }
+            free(a);
+            free(kd);
+        }
+    return status;
+}
+
+/* 1-D max-pool, stride 1, same length, window clipped at both ends (a kernel
+ * of 1 is the identity).  Applied to the prefix votes only. */
+int orc_max_pool(int rows, int P, int pool, const double *vote, double *pooled)
+{
+    if (pool < 1 || pool % 2 == 0)
+        return -1;
+    const int r = (pool - 1) / 2;
+    for (int row = 0; row < rows; ++row)
+        for (int j = 0; j < P; ++j) {
+            double best = -INFINITY;
+            for (int t = -r; t <= r; ++t)
+                if (j + t >= 0 && j + t < P && vote[(size_t)row * P + j + t] > best)
+                    best = vote[(size_t)row * P + j + t];
+            pooled[(size_t)row * P + j] = best;
+        }
+    return 0;
+}
+
+typedef struct {
+    double score;
+    int32_t index;
+} scored;
+
+static int by_score_desc_index_asc(const void *pa, const void *pb)
+{
+    const scored *a = (const scored *)pa, *b = (const scored *)pb;
+    if (a->score > b->score)
+        return -1;
+    if (a->score < b->score)
+        return 1;
+    return (a->index > b->index) - (a->index < b->index);
+}
+
+static int by_int_asc(const void *pa, const void *pb)
+{
+    int32_t a = *(const int32_t *)pa, b = *(const int32_t *)pb;
+    return (a > b) - (a < b);
+}
+
+/* The k highest pooled scores of one head; equal scores go to the lower
+ * position; the result is listed in ascending position. */
+int orc_topk(int P, int k, const double *pooled, int32_t *idx)
+{
+    if (k < 0 || k > P)
+        return -1;
+    scored *c = (scored *)malloc(sizeof(scored) * (size_t)(P > 0 ? P : 1));
+    if (!c)
+        return -2;
+    for (int j = 0; j < P; ++j) {
+        c[j].score = pooled[j];
+        c[j].index = j;
+    }
+    qsort(c, (size_t)P, sizeof(scored), by_score_desc_index_asc);
+    for (int t = 0; t < k; ++t)
+        idx[t] = c[t].index;
+    qsort(idx, (size_t)k, sizeof(int32_t), by_int_asc);
+    free(c);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Quantization (Section 3 "KV Quantization"):                          */
+/*   z = min G, m = max G, s = (m - z)/(2^B - 1), Q(G) = round((G-z)/s) */
+/* and G' = Q(G)*s + z.  The stored s is binary16, rounded before the   */
+/* codes are formed so that codes and dequantization agree; z is an     */
+/* input value, hence exact in binary16.                                */
+/* ------------------------------------------------------------------ */
+
+/*
+ * One group of n binary16 values x[0], x[stride], ...  Writes the stored
+ * scale and zero (binary16 bit patterns) and n codes in [0, 2^bits).
+ * binary32 sequence: r = m - z; s32 = r / (2^bits - 1); s_h = half(s32);
+ * if s_h == 0 every code is 0 (constant group, or range below half
+ * resolution); else inv = 1 / float(s_h); code = clamp(rint((x - z) * inv)).
+ * Ties in rint go to even.  When the group holds both -0 and +0 as extremes
+ * the minimum is -0 (IEEE minimum ordering).
+ */
+int orc_quantize_group(const uint16_t *x, int n, int stride, int bits, uint16_t *scale,
+                       uint16_t *zero, uint8_t *codes)
+{
+    if (n < 1 || !(bits == 2 || bits == 4 || bits == 8))
+        return -1;
+    uint16_t zb = x[0], mb = x[0];
+    for (int i = 1; i < n; ++i) {
+        uint16_t xb = x[(size_t)i * stride];
+        double v = orc_half_to_double(xb), lo = orc_half_to_double(zb), hi = orc_half_to_double(mb);
+        if (v < lo || (v == lo && (xb & 0x8000) && !(zb & 0x8000)))
+            zb = xb;
+        if (v > hi || (v == hi && !(xb & 0x8000) && (mb & 0x8000)))
+            mb = xb;
+    }
+    const float zf = half_to_float(zb), mf = half_to_float(mb);
+    const float levels = (float)((1 << bits) - 1);
+    volatile float r = mf - zf;
+    volatile float s32 = r / levels;
+    const uint16_t sh = orc_float_to_half(s32);
+    const float sf = half_to_float(sh);
+    *scale = sh;
+    *zero = zb;
+    if (sf == 0.0f) {
+        for (int i = 0; i < n; ++i)
+            codes[i] = 0;
+        return 0;
+    }
+    volatile float inv = 1.0f / sf;
+    for (int i = 0; i < n; ++i) {
+        volatile float diff = half_to_float(x[(size_t)i * stride]) - zf;
+        volatile float scaled = diff * inv;
+        float c = rintf(scaled);
+        if (c < 0.0f)
+            c = 0.0f;
+        if (c > levels)
+            c = levels;
+        codes[i] = (uint8_t)c;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Bit layout of the packed cache.  The paper gives none; this is the   */
+/* library's storage format, restated here from its specification.      */
+/*                                                                      */
+/* A 32-bit word holds E = 32/bits fields.  Field p of the low half     */
+/* (bits [bits*p, bits*p+bits)) and field p of the high half (16 bits   */
+/* higher) always hold a *pair*.                                        */
+/*  Keys: row-major [token][channel]; word (t, d / E); within the word  */
+/*    the pair is two adjacent channels: r = d % E, p = r / 2,          */
+/*    half = r % 2.  At 16 bits this is plain little-endian binary16.   */
+/*  Values: tokens are taken in blocks of 32; token t = 32*blk + 16*H   */
+/*    + 4*kb + i (H in {0,1}, kb, i in 0..3); channel d = 16*tile + n.  */
+/*    The pair is (H=0, H=1): tokens 16 apart.  For fixed (kb, d) the   */
+/*    fields with running index 4*blk + i fill successive low halves    */
+/*    (and the H=1 partners the high halves), E/2 per word.  A          */
+/*    superblock is SB = max(32, 2E) tokens and holds, per lane         */
+/*    (kb, n), nw = (D/16) * (SB/2) / (E/2) ... words, ordered          */
+/*    y = tile * wpt + (word within tile); the word sits at             */
+/*    ((y / 4) * 64 + kb * 16 + n) * 4 + y % 4 inside the superblock.   */
+/*    Tokens past n_kept inside the last superblock hold code 0.        */
+/* ------------------------------------------------------------------ */
+
+static int fields_per_word(int bits) { return 32 / bits; }
+
+size_t orc_k_words(int n_tok, int D, int bits) { return (size_t)n_tok * D * bits / 32; }
+
+static void k_locate(int D, int bits, int t, int d, size_t *word, int *shift)
+{
+    const int E = fields_per_word(bits);
+    const int r = d % E;
+    *word = (size_t)t * (D / E) + d / E;
+    *shift = 16 * (r % 2) + bits * (r / 2);
+}
+
+static int v_superblock(int bits) { return bits == 2 ? 64 : 32; }
+
+/* words one lane (kb, n) holds per tile per superblock */
+static int v_words_per_tile(int bits) { return bits == 16 ? 4 : bits == 8 ? 2 : 1; }
+
+size_t orc_v_words(int n_tok, int D, int bits)
+{
+    const int SB = v_superblock(bits);
+    const size_t nsb = ((size_t)n_tok + SB - 1) / SB;
+    return nsb * 64 * (size_t)(D / 16) * v_words_per_tile(bits);
+}
+
+static void v_locate(int D, int bits, int t, int d, size_t *word, int *shift)
+{
+    const int E = fields_per_word(bits);
+    const int SB = v_superblock(bits);
+    const int wpt = v_words_per_tile(bits);
+    const int sb = t / SB, ts = t % SB;
+    const int blk = ts / 32, H = (ts % 32) / 16, kb = (ts % 16) / 4, i = ts % 4;
+    const int tile = d / 16, n = d % 16;
+    const int run = 4 * blk + i;    /* running field index inside the superblock */
+    const int wl = run / (E / 2);   /* word within the tile                       */
+    const int p = run % (E / 2);    /* field within the half                      */
+    const int y = tile * wpt + wl;
+    const size_t sb_words = 64 * (size_t)(D / 16) * wpt;
+    *word = sb * sb_words + ((size_t)(y / 4) * 64 + kb * 16 + n) * 4 + y % 4;
+    *shift = 16 * H + bits * p;
+}
+
+static uint32_t field_mask(int bits) { return bits == 16 ? 0xffffu : ((1u << bits) - 1u); }
+
+uint32_t orc_k_code_get(const uint32_t *codes, int D, int bits, int t, int d)
+{
+    size_t w;
+    int sh;
+    k_locate(D, bits, t, d, &w, &sh);
+    return (codes[w] >> sh) & field_mask(bits);
+}
+
+uint32_t orc_v_code_get(const uint32_t *codes, int D, int bits, int t, int d)
+{
+    size_t w;
+    int sh;
+    v_locate(D, bits, t, d, &w, &sh);
+    return (codes[w] >> sh) & field_mask(bits);
+}
+
+static void k_code_put(uint32_t *codes, int D, int bits, int t, int d, uint32_t c)
+{
+    size_t w;
+    int sh;
+    k_locate(D, bits, t, d, &w, &sh);
+    codes[w] |= (c & field_mask(bits)) << sh;
+}
+
+static void v_code_put(uint32_t *codes, int D, int bits, int t, int d, uint32_t c)
+{
+    size_t w;
+    int sh;
+    v_locate(D, bits, t, d, &w, &sh);
+    codes[w] |= (c & field_mask(bits)) << sh;
+}
+
+/* ------------------------------------------------------------------ */
+/* Quantized pruning of given survivors (Section 3 "Quantized Pruning": */
+/* prune first, then quantize the preserved states).  idx lists, per    */
+/* (b, g), n_kept ascending prefix positions.  Keys: key_axis 0 groups  */
+/* G consecutive *kept tokens* of one channel (per-channel, the KIVI    */
+/* axis); key_axis 1 groups G consecutive channels of one token         */
+/* (per-token, the FlexGen axis).  Values are always per-token.  The    */
+/* last W prompt rows are copied unquantized into the tail.             */
+/*   k_scale/k_zero: [B,Hkv,n_kept/G,D] (axis 0) or [B,Hkv,n_kept,D/G]  */
+/*   v_scale/v_zero: [B,Hkv,n_kept,D/G]                                 */
+/*   tail_k/tail_v : [B,Hkv,tail_cap,D], first W rows written           */
+/* ------------------------------------------------------------------ */
+int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int bits, int G,
+                          int key_axis, int tail_cap, const uint16_t *k, const uint16_t *v,
+                          const int32_t *idx, uint32_t *k_codes, uint32_t *v_codes,
+                          uint16_t *k_scale, uint16_t *k_zero, uint16_t *v_scale,
+                          uint16_t *v_zero, uint16_t *tail_k, uint16_t *tail_v)
+{
+    if (!(bits == 2 || bits == 4 || bits == 8 || bits == 16) || D % 64 || W > tail_cap || W > L)
+        return -1;
+    if (bits != 16 && (G < 1 || D % G || (key_axis == 0 && n_kept % G)))
+        return -1;
+    const int P = L - W;
+    const size_t kw = orc_k_words(n_kept, D, bits), vw = orc_v_words(n_kept, D, bits);
+    uint8_t *codes = (uint8_t *)malloc((size_t)(G > D ? G : D) + 1);
+    if (!codes)
+        return -2;
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hkv; ++g) {
+            const size_t head = (size_t)b * Hkv + g;
+            const uint16_t *kh = k + head * (size_t)L * D, *vh = v + head * (size_t)L * D;
+            const int32_t *id = idx + head * (size_t)n_kept;
+            uint32_t *kc = k_codes + head * kw, *vc = v_codes + head * vw;
+            memset(kc, 0, kw * 4);
+            memset(vc, 0, vw * 4);
+            for (int t = 0; t < n_kept; ++t)
+                if (id[t] < 0 || id[t] >= P) {
+                    free(codes);
+                    return -3;
+                }
+            if (bits == 16) {
+                for (int t = 0; t < n_kept; ++t)
+                    for (int d = 0; d < D; ++d) {
+                        k_code_put(kc, D, 16, t, d, kh[(size_t)id[t] * D + d]);
+                        v_code_put(vc, D, 16, t, d, vh[(size_t)id[t] * D + d]);
+                    }
+            } else {
+                if (key_axis == 0) {
+                    uint16_t *gath = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)G);
+                    for (int u = 0; u < n_kept / G; ++u)
+                        for (int d = 0; d < D; ++d) {
+                            for (int e = 0; e < G; ++e)
+                                gath[e] = kh[(size_t)id[u * G + e] * D + d];
+                            size_t m = (head * (size_t)(n_kept / G) + u) * D + d;
+                            orc_quantize_group(gath, G, 1, bits, &k_scale[m], &k_zero[m], codes);
+                            for (int e = 0; e < G; ++e)
+                                k_code_put(kc, D, bits, u * G + e, d, codes[e]);
+                        }
+                    free(gath);
+                } else {
+                    for (int t = 0; t < n_kept; ++t)
+                        for (int c = 0; c < D / G; ++c) {
+                            size_t m = (head * (size_t)n_kept + t) * (D / G) + c;
+                            orc_quantize_group(kh + (size_t)id[t] * D + c * G, G, 1, bits,
+                                               &k_scale[m], &k_zero[m], codes);
+                            for (int e = 0; e < G; ++e)
+                                k_code_put(kc, D, bits, t, c * G + e, codes[e]);
+                        }
+                }
+                for (int t = 0; t < n_kept; ++t)
+                    for (int c = 0; c < D / G; ++c) {
+                        size_t m = (head * (size_t)n_kept + t) * (D / G) + c;
+                        orc_quantize_group(vh + (size_t)id[t] * D + c * G, G, 1, bits, &v_scale[m],
+                                           &v_zero[m], codes);
+                        for (int e = 0; e < G; ++e)
+                            v_code_put(vc, D, bits, t, c * G + e, codes[e]);
+                    }
+            }
+            for (int i = 0; i < W; ++i) {
+                memcpy(tail_k + (head * tail_cap + i) * (size_t)D, kh + (size_t)(P + i) * D,
+                       sizeof(uint16_t) * (size_t)D);
+                memcpy(tail_v + (head * tail_cap + i) * (size_t)D, vh + (size_t)(P + i) * D,
+                       sizeof(uint16_t) * (size_t)D);
+            }
+        }
+    free(codes);
+    return 0;
+}
+
+/*
+ * Prefill-time compression of one layer, start to end: votes, pool, top-k
+ * with k = min(budget, P), then quantize the survivors.  idx [B,Hkv,k] and,
+ * when not NULL, pooled [B,Hkv,P] (the scores the selection was made on) are
+ * returned for the tests.
+ */
+int orc_compress(int B, int Hq, int Hkv, int D, int L, int W, int pool, int budget, int bits,
+                 int G, int key_axis, double sm_scale, int tail_cap, const uint16_t *q_obs,
+                 const uint16_t *k, const uint16_t *v, int32_t *idx, double *pooled_out,
+                 uint32_t *k_codes, uint32_t *v_codes, uint16_t *k_scale, uint16_t *k_zero,
+                 uint16_t *v_scale, uint16_t *v_zero, uint16_t *tail_k, uint16_t *tail_v)
+{
+    if (W < 1 || W > L)
+        return -1;
+    const int P = L - W;
+    const int n_kept = budget < P ? budget : P;
+    const size_t heads = (size_t)B * Hkv;
+    double *vote = (double *)malloc(sizeof(double) * heads * (size_t)(P > 0 ? P : 1));
+    double *pooled = (double *)malloc(sizeof(double) * heads * (size_t)(P > 0 ? P : 1));
+    if (!vote || !pooled) {
+        free(vote);
+        free(pooled);
+        return -2;
+    }
+    int rc = orc_window_votes(B, Hq, Hkv, D, L, W, sm_scale, q_obs, k, vote);
+    if (!rc)
+        rc = orc_max_pool((int)heads, P, pool, vote, pooled);
+    for (size_t h = 0; h < heads && !rc; ++h)
+        rc = orc_topk(P, n_kept, pooled + h * P, idx + h * n_kept);
+    if (!rc && pooled_out)
+        memcpy(pooled_out, pooled, sizeof(double) * heads * (size_t)P);
+    free(vote);
+    free(pooled);
+    if (rc)
+        return rc;
+    return orc_quantize_selected(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap, k, v, idx,
+                                 k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k,
+                                 tail_v);
+}
+
+/* ------------------------------------------------------------------ */
+/* Decode (Section 3: G' = Q(G)*s + z, then Softmax(h_Q X_K'^T) X_V'    */
+/* over the n_kept dequantized survivors followed by tail_len exact     */
+/* binary16 rows; no mask, every cached token precedes the query).      */
+/* ------------------------------------------------------------------ */
+
+/* Dequantize one head into dense rows: Kd, Vd [n_kept + tail_len, D]. */
+static void dequantize_head(int D, int n_kept, int bits, int G, int key_axis, int tail_len,
+                            const uint32_t *kc, const uint32_t *vc, const uint16_t *ks,
+                            const uint16_t *kz, const uint16_t *vs, const uint16_t *vz,
+                            const uint16_t *tk, const uint16_t *tv, double *Kd, double *Vd)
+{
+    for (int t = 0; t < n_kept; ++t)
+        for (int d = 0; d < D; ++d) {
+            uint32_t ck = orc_k_code_get(kc, D, bits, t, d), cv = orc_v_code_get(vc, D, bits, t, d);
+            if (bits == 16) {
+                Kd[(size_t)t * D + d] = orc_half_to_double((uint16_t)ck);
+                Vd[(size_t)t * D + d] = orc_half_to_double((uint16_t)cv);
+            } else {
+                size_t mk = key_axis == 0 ? (size_t)(t / G) * D + d : (size_t)t * (D / G) + d / G;
+                size_t mv = (size_t)t * (D / G) + d / G;
+                Kd[(size_t)t * D + d] =
+                    (double)ck * orc_half_to_double(ks[mk]) + orc_half_to_double(kz[mk]);
+                Vd[(size_t)t * D + d] =
+                    (double)cv * orc_half_to_double(vs[mv]) + orc_half_to_double(vz[mv]);
+            }
+        }
+    for (int t = 0; t < tail_len; ++t)
+        for (int d = 0; d < D; ++d) {
+            Kd[(size_t)(n_kept + t) * D + d] = orc_half_to_double(tk[(size_t)t * D + d]);
+            Vd[(size_t)(n_kept + t) * D + d] = orc_half_to_double(tv[(size_t)t * D + d]);
+        }
+}
+
+/* q [B,Hq,D] half -> out [B,Hq,D] double.  Query head h reads KV head h/Gq. */
+int orc_decode_attn(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G, int key_axis,
+                    double sm_scale, int tail_len, int tail_cap, const uint16_t *q,
+                    const uint32_t *k_codes, const uint32_t *v_codes, const uint16_t *k_scale,
+                    const uint16_t *k_zero, const uint16_t *v_scale, const uint16_t *v_zero,
+                    const uint16_t *tail_k, const uint16_t *tail_v, double *out)
+{
+    if (Hq % Hkv || tail_len > tail_cap || n_kept + tail_len < 1)
+        return -1;
+    const int Gq = Hq / Hkv, T = n_kept + tail_len;
+    const size_t kw = orc_k_words(n_kept, D, bits), vw = orc_v_words(n_kept, D, bits);
+    const size_t kmeta = bits == 16 ? 0
+                         : key_axis == 0 ? (size_t)(n_kept / G) * D
+                                         : (size_t)n_kept * (D / G);
+    const size_t vmeta = bits == 16 ? 0 : (size_t)n_kept * (D / G);
+    int status = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hkv; ++g) {
+            const size_t head = (size_t)b * Hkv + g;
+            double *Kd = (double *)malloc(sizeof(double) * (size_t)T * D);
+            double *Vd = (double *)malloc(sizeof(double) * (size_t)T * D);
+            double *a = (double *)malloc(sizeof(double) * (size_t)T);
+            if (!Kd || !Vd || !a) {
+                status = -2;
+                free(Kd);
+                free(Vd);
+                free(a);
+                continue;
+            }
+            dequantize_head(D, n_kept, bits, G, key_axis, tail_len, k_codes + head * kw,
+                            v_codes + head * vw, k_scale + head * kmeta, k_zero + head * kmeta,
+                            v_scale + head * vmeta, v_zero + head * vmeta,
+                            tail_k + head * (size_t)tail_cap * D,
+                            tail_v + head * (size_t)tail_cap * D, Kd, Vd);
+            for (int h = g * Gq; h < (g + 1) * Gq; ++h) {
+                const uint16_t *qr = q + ((size_t)b * Hq + h) * (size_t)D;
+                double mx = -INFINITY;
+                for (int t = 0; t < T; ++t) {
+                    double s = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        s += orc_half_to_double(qr[d]) * Kd[(size_t)t * D + d];
+                    a[t] = sm_scale * s;
+                    if (a[t] > mx)
+                        mx = a[t];
+                }
+                double Z = 0.0;
+                for (int t = 0; t < T; ++t) {
+                    a[t] = exp(a[t] - mx);
+                    Z += a[t];
+                }
+                double *o = out + ((size_t)b * Hq + h) * (size_t)D;
+                for (int d = 0; d < D; ++d) {
+                    double acc = 0.0;
+                    for (int t = 0; t < T; ++t)
+                        acc += a[t] * Vd[(size_t)t * D + d];
+                    o[d] = acc / Z;
+                }
+            }
+            free(Kd);
+            free(Vd);
+            free(a);
+        }
+    return status;
+}
+
+/* Dense dequantized K', V' of one head, for tests of the error bound. */
+int orc_dequantize_head(int D, int n_kept, int bits, int G, int key_axis, const uint32_t *kc,
+                        const uint32_t *vc, const uint16_t *ks, const uint16_t *kz,
+                        const uint16_t *vs, const uint16_t *vz, double *Kd, double *Vd)
+{
+    dequantize_head(D, n_kept, bits, G, key_axis, 0, kc, vc, ks, kz, vs, vz, NULL, NULL, Kd, Vd);
+    return 0;
+}
+
+int orc_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
