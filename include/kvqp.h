@@ -1,0 +1,193 @@
+/*
+ * kvqp.h -- C ABI of the quantized-pruned KV cache for MI355X (gfx950).
+ *
+ * Method: "More Tokens, Lower Precision" (arXiv 2412.12706), Section 3:
+ * at prefill the cache is first pruned along the token axis to a fixed budget
+ * ("KV Pruning": keep s < n tokens) and the survivors are then quantized
+ * ("KV Quantization": z = min, m = max, s = (m - z)/(2^B - 1),
+ * Q(G) = round((G - z)/s)); at decode the attention of Eq. (3),
+ * Softmax(h_Q X_K^T) X_V, runs on the dequantized survivors G' = Q(G) s + z
+ * ("Quantized Pruning").  Grouping axes follow Section 2 / Section 5.4: keys
+ * per channel, values per token (KIVI), or keys per token as the ablation
+ * (FlexGen).  The paper's Limitations section names the missing piece this
+ * library supplies: dequantization fused into the attention products.
+ *
+ * Everything the paper leaves open (how prompt tokens are scored, the bit
+ * layout, the precision of stored scales) is stated below; the library and
+ * its independent CPU checker both implement these statements.
+ *
+ * General rules
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates or frees device memory, never synchronises the device,
+ *     and enqueues work only on the HIP stream passed in (hipStream_t cast to
+ *     void*, NULL = default stream).  Inputs are never modified.
+ *   - cfg / cache structs are HOST memory, read during the call only.
+ *   - Return value: KVQP_OK or a negative KVQP_ERR_* code; nothing throws.
+ *     Arguments are validated on the host before anything is launched.
+ *   - One call handles one layer.  `batch` is the number of independent
+ *     caches, so several layers with identical shapes may be passed as a
+ *     larger batch when their buffers are contiguous.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - binary16 ("half") everywhere data is 16-bit floating point.
+ */
+#ifndef KVQP_H
+#define KVQP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVQP_OK 0
+#define KVQP_ERR_INVALID_ARG (-1)  /* bad shape, NULL pointer, inconsistent fields       */
+#define KVQP_ERR_UNSUPPORTED (-2)  /* valid request outside what this build implements   */
+#define KVQP_ERR_WORKSPACE (-3)    /* workspace NULL or smaller than kvqp_workspace_bytes */
+#define KVQP_ERR_HIP (-4)          /* a HIP call failed (launch error etc.)              */
+
+#define KVQP_KEY_PER_CHANNEL 0 /* a key group = G consecutive kept tokens of one channel */
+#define KVQP_KEY_PER_TOKEN 1   /* a key group = G consecutive channels of one token      */
+
+/*
+ * Problem statement of one layer (Section 3; the scoring parameters window
+ * and pool_kernel belong to the attention-score pruning rule below).
+ * Supported in this build: head_dim == 128; n_q_heads / n_kv_heads in
+ * {1,2,4,8}; bits in {2,4,8,16}; group_size in {32,64,128};
+ * window * (n_q_heads/n_kv_heads) <= 256; pool_kernel odd, <= 63.
+ */
+typedef struct kvqp_cfg {
+    int32_t batch;        /* number of independent caches                                */
+    int32_t n_q_heads;    /* Hq                                                          */
+    int32_t n_kv_heads;   /* Hkv, divides Hq                                             */
+    int32_t head_dim;     /* D                                                           */
+    int32_t seq_len;      /* L, prompt length (compress only)                            */
+    int32_t window;       /* W: the last W prompt tokens score the prefix and stay half  */
+    int32_t pool_kernel;  /* odd; 1 = no pooling                                         */
+    int32_t budget;       /* prefix tokens kept in low precision; n_kept = min(budget, L-W) */
+    int32_t bits;         /* B: 2, 4, 8, or 16 (16 = keep half, no scale/zero)           */
+    int32_t group_size;   /* G; must divide D, and n_kept when keys are per channel      */
+    int32_t key_axis;     /* KVQP_KEY_PER_CHANNEL or KVQP_KEY_PER_TOKEN                  */
+    int32_t decode_splits;/* token-axis splits of decode attention; 0 = library chooses  */
+    float sm_scale;       /* logit scale, e.g. 1/sqrt(D) (Eq. (3) omits it)              */
+} kvqp_cfg;
+
+/*
+ * The compressed cache of one layer.  All eight buffers are device memory of
+ * the sizes kvqp_cache_sizes reports, in this order.
+ *
+ * Key codes      k_codes  uint32 [batch, Hkv, n_kept * D * bits / 32]
+ *   Row-major [token][channel].  A 32-bit word holds E = 32/bits fields.
+ *   Field p of the low half-word (bits [bits*p, bits*p + bits)) and field p of
+ *   the high half-word (16 bits higher) hold two adjacent channels: channel d
+ *   of token t is in word t*(D/E) + d/E, with r = d % E, p = r/2, half = r%2.
+ *   At bits == 16 this is the plain little-endian half row.
+ * Value codes    v_codes  uint32 [batch, Hkv, ceil(n_kept/SB) * 64 * (D/16) * wpt]
+ *   Tile-transposed so that the P.V product can read it without a transpose.
+ *   SB = 64 tokens at 2 bits, 32 otherwise; wpt = 4 at 16 bits, 2 at 8, else 1.
+ *   Token t = SB*sb + 32*blk + 16*H + 4*kb + i  (H in {0,1}; kb, i in 0..3),
+ *   channel d = 16*tile + n.  The low/high half-word pair is (H=0, H=1): two
+ *   tokens 16 apart of the same channel.  For fixed (kb, d) the fields with
+ *   running index run = 4*blk + i fill the half-words in order, E/2 per word:
+ *   word-in-tile wl = run / (E/2), field p = run % (E/2).  With
+ *   y = tile*wpt + wl the word sits at
+ *     sb * (64*(D/16)*wpt) + ((y/4)*64 + kb*16 + n)*4 + y%4 .
+ *   Tokens >= n_kept inside the last superblock hold zeros.
+ * Key scale/zero k_scale, k_zero  half
+ *   per channel: [batch, Hkv, n_kept/G, D];  per token: [batch, Hkv, n_kept, D/G]
+ * Value scale/zero v_scale, v_zero  half [batch, Hkv, n_kept, D/G]
+ *   (absent, size 0, at bits == 16)
+ * Tail           tail_k, tail_v  half [batch, Hkv, tail_cap, D], row-major; the
+ *   first tail_len rows are attended at full precision after the kept tokens.
+ *   kvqp_compress writes the last W prompt rows there (Appendix B keeps the
+ *   most recent tokens); a caller may append decoded tokens' K/V rows and
+ *   raise tail_len up to tail_cap (the cache update of Eq. (2)).
+ *
+ * Quantizer, exactly (binary32, round-to-nearest-even, no fused multiply-add):
+ *   z = min, m = max of the group (binary16 values, -0 orders below +0);
+ *   r = float(m) - float(z);  s32 = r / float(2^bits - 1);  s = half(s32);
+ *   s == 0  ->  all codes 0;  else inv = 1.0f / float(s),
+ *   code = clamp(rint((float(x) - float(z)) * inv), 0, 2^bits - 1).
+ * NaN inputs are not supported.
+ */
+typedef struct kvqp_cache {
+    void *k_codes, *v_codes;
+    void *k_scale, *k_zero;
+    void *v_scale, *v_zero;
+    void *tail_k, *tail_v;
+    int32_t n_kept;   /* kept low-precision tokens; set by compress / quantize_selected */
+    int32_t tail_len; /* valid tail rows                                                */
+    int32_t tail_cap; /* allocated tail rows, >= window                                 */
+} kvqp_cache;
+
+/* Bytes of the eight cache buffers (order of the struct) for n_kept =
+ * min(budget, L - W) and the given tail capacity.  Host only. */
+int kvqp_cache_sizes(const kvqp_cfg *cfg, int32_t tail_cap, size_t sizes_out[8]);
+
+/* Workspace bytes needed by kvqp_compress and kvqp_decode_attn for this cfg
+ * (either pointer may be NULL).  Host only. */
+int kvqp_workspace_bytes(const kvqp_cfg *cfg, size_t *compress_bytes, size_t *decode_bytes);
+
+/*
+ * Prefill-time compression of one layer (Section 3, "Quantized Pruning").
+ *
+ * Pruning rule (the paper uses an attention-score method from the literature
+ * with the last 32 tokens retained, Section 4 / Appendix B, and gives no
+ * further detail; this is the rule implemented):
+ *   P = L - W.  Every query row of the last W positions, for every query head
+ *   of a KV head's group, attends causally over keys 0..P+i with
+ *   Softmax(sm_scale q k^T); vote[j], j < P, is the sum of those
+ *   probabilities over the group's heads and the W rows; votes are max-pooled
+ *   (stride 1, same length, window clipped at the ends); the n_kept highest
+ *   pooled scores are kept, equal scores going to the lower position, and the
+ *   survivors are stored in ascending position.
+ *   Scores are evaluated in binary32 on the matrix cores; candidates whose
+ *   pooled score lies within a relative 1e-4 of the cut are re-scored in
+ *   binary64 before the cut is made.
+ * The survivors are then quantized as described at kvqp_cache.
+ *
+ *   q_obs  half [batch, Hq, W, D]   queries of the last W prompt positions
+ *   k, v   half [batch, Hkv, L, D]  full prompt keys / values
+ *   cache  buffers filled; n_kept and tail_len (= W) set; tail_cap must be set
+ *          by the caller and be >= W
+ *   idx_out int32 [batch, Hkv, n_kept] ascending survivors, or NULL
+ * Errors: INVALID_ARG on NULL/shape problems (incl. n_kept % G != 0 for
+ * per-channel keys), UNSUPPORTED outside the supported set, WORKSPACE, HIP.
+ */
+int kvqp_compress(const kvqp_cfg *cfg, const void *q_obs, const void *k, const void *v,
+                  kvqp_cache *cache, int32_t *idx_out, void *workspace, size_t workspace_bytes,
+                  void *hip_stream);
+
+/*
+ * The quantization half alone (Section 3 "KV Quantization" applied to given
+ * survivors): idx int32 [batch, Hkv, n_kept] ascending positions < L - W
+ * chosen by any pruning method; cfg->budget is ignored and n_kept is taken
+ * from the argument.  Fills the cache exactly as kvqp_compress would for the
+ * same survivors.  Needs no workspace.
+ */
+int kvqp_quantize_selected(const kvqp_cfg *cfg, const void *k, const void *v, const int32_t *idx,
+                           int32_t n_kept, kvqp_cache *cache, void *hip_stream);
+
+/*
+ * One decode step of attention over the compressed cache (Section 3, Eq. (3)
+ * on G' = Q(G) s + z): for every query head, softmax over the n_kept
+ * dequantized tokens followed by tail_len full-precision rows, no mask.
+ * Codes are expanded in registers; no dequantized copy is written.
+ *   q   half [batch, Hq, D]
+ *   out half [batch, Hq, D]   binary32 accumulation, rounded once at the end
+ * cfg fields used: batch, heads, head_dim, bits, group_size, key_axis,
+ * decode_splits, sm_scale.  n_kept + tail_len must be >= 1.
+ */
+int kvqp_decode_attn(const kvqp_cfg *cfg, const void *q, const kvqp_cache *cache, void *out,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Static string for a return code. */
+const char *kvqp_strerror(int code);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int kvqp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQP_H */

@@ -1,0 +1,671 @@
+// Decode attention over the packed cache (paper Section 3: the attention of
+// Eq. (3), Softmax(h_Q X_K^T) X_V, evaluated on the dequantized survivors
+// G' = Q(G) s + z, plus the full-precision tail).  This is the fused
+// dequantize-and-multiply the paper's Limitations section leaves as future work.
+//
+// Design for gfx950.  The step is HBM-bound (every packed byte is read once
+// per step and used for only Gq query heads), but at 2-4 bits the plain vector
+// ALUs cannot even expand the codes and multiply them at HBM speed, so both
+// products run on the matrix cores with the *codes themselves* as one operand:
+//   QK:  S^T[token, row] = sum_d code[token, d] * (q[row, d] * s[group, d])
+//        + sum_d q[row, d] z[group, d]          (scale folded into q, per group)
+//   PV:  O[row, d] = sum_t (p[row, t] * s[t, cg(d)]) * code[t, d]
+//        + sum_t p[row, t] z[t, cg(d)]           (scale folded into p)
+// A b-bit field masked out of a packed word is, read as binary16, the
+// subnormal code * 2^-24 (times a power of two given by its bit position), and
+// v_mfma_f32_16x16x32_f16 takes subnormal inputs exactly; so "dequantization"
+// is one AND per two codes and the power of two is folded into the other
+// operand.  The folded operands q*s and p*s are split into binary16 hi + lo
+// parts that occupy separate rows of the 16-row MFMA tile (Gq <= 8 heads leave
+// room), which keeps them exact to ~2^-22 instead of 2^-11.
+// The value codes are stored tile-transposed (kvqp.h) so that the lane that
+// holds probabilities of tokens {4kb+i} after the QK product is the lane that
+// needs them as the P operand: nothing moves between lanes or through LDS
+// inside the token loop.  One workgroup = 4 waves streams a contiguous token
+// range (split-K); waves own interleaved 64-token chunks; partial (m, l, O)
+// go to the workspace and a second small kernel merges the splits.
+#include "kvqp_internal.h"
+
+namespace kvqp {
+namespace {
+
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+typedef _Float16 h8v __attribute__((ext_vector_type(8)));
+typedef float f4v __attribute__((ext_vector_type(4)));
+
+union Frag {  // one MFMA 16x16x32 f16 input operand of a lane: 8 halves
+    h8v v;
+    uint32_t u[4];
+    h2v h[4];
+};
+
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+constexpr int kChunk = 64;          // tokens per wave iteration
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNegBig = -1.0e30f; // finite stand-in for -inf in running maxima
+constexpr int kPartStride = kHeadDim + 2;  // floats per (partial, head): m, l, acc[128]
+
+__device__ __forceinline__ float xor16_max(float v) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xor32_max(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xor16_add(float v) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float xor32_add(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// sum / max over the four lanes that share (lane & 15)
+__device__ __forceinline__ float quad_rows_add(float v) { return xor32_add(xor16_add(v)); }
+__device__ __forceinline__ float quad_rows_max(float v) { return xor32_max(xor16_max(v)); }
+// value of the neighbouring lane (lane ^ 1)
+__device__ __forceinline__ float pair_other(float v) {
+    return __uint_as_float(__builtin_amdgcn_mov_dpp(__float_as_uint(v), 0xB1 /*quad_perm [1,0,3,2]*/, 0xf, 0xf, true));
+}
+
+__device__ __forceinline__ h2v as_h2(uint32_t u) { union { uint32_t u; h2v h; } c; c.u = u; return c.h; }
+__device__ __forceinline__ uint32_t as_u32(h2v h) { union { uint32_t u; h2v h; } c; c.h = h; return c.u; }
+
+// ---- key codes: BITS words per lane per 16-token tile (the lane's 32 channels) ----
+template <int BITS> struct KWords { uint32_t w[BITS]; };
+
+template <int BITS>
+__device__ __forceinline__ KWords<BITS> load_k_tile(const uint32_t* __restrict__ kc_head, int tok, int kb) {
+    KWords<BITS> r;
+    const uint32_t* p = kc_head + (size_t)tok * (4 * BITS) + kb * BITS;
+    if constexpr (BITS == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        r.w[0] = v.x; r.w[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < BITS / 4; ++i) {
+            const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+            r.w[4 * i] = v.x; r.w[4 * i + 1] = v.y; r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
+        }
+    }
+    return r;
+}
+
+// MFMA operand for contraction step s (8 of the lane's 32 channels, natural order).
+// Fields are left in place; their power-of-two position factor is KPosLog2.
+template <int BITS>
+__device__ __forceinline__ Frag k_frag(const KWords<BITS>& k, int s) {
+    Frag f;
+    if constexpr (BITS == 16) {
+        f.u[0] = k.w[4 * s]; f.u[1] = k.w[4 * s + 1]; f.u[2] = k.w[4 * s + 2]; f.u[3] = k.w[4 * s + 3];
+    } else if constexpr (BITS == 8) {
+        const uint32_t a = k.w[2 * s], b = k.w[2 * s + 1];
+        f.u[0] = a & 0x00FF00FFu; f.u[1] = (a >> 8) & 0x00FF00FFu;
+        f.u[2] = b & 0x00FF00FFu; f.u[3] = (b >> 8) & 0x00FF00FFu;
+    } else if constexpr (BITS == 4) {
+        const uint32_t a = k.w[s], b = a >> 8;
+        f.u[0] = a & 0x000F000Fu; f.u[1] = a & 0x00F000F0u;
+        f.u[2] = b & 0x000F000Fu; f.u[3] = b & 0x00F000F0u;
+    } else {
+        const uint32_t a = k.w[s >> 1];
+        if ((s & 1) == 0) {
+            f.u[0] = a & 0x00030003u; f.u[1] = a & 0x000C000Cu; f.u[2] = a & 0x00300030u; f.u[3] = a & 0x00C000C0u;
+        } else {
+            const uint32_t b = a >> 10;
+            f.u[0] = a & 0x03000300u; f.u[1] = b & 0x00030003u; f.u[2] = b & 0x000C000Cu; f.u[3] = b & 0x00300030u;
+        }
+    }
+    return f;
+}
+// log2 of the factor by which register r of step s is too large.
+template <int BITS>
+__device__ __forceinline__ constexpr int k_pos_log2(int s, int r) {
+    if (BITS == 4) return (r & 1) ? 4 : 0;
+    if (BITS == 2) return (s & 1) == 0 ? 2 * r : (r == 0 ? 8 : 2 * (r - 1));
+    return 0;
+}
+
+// ---- value codes: words per lane per 32-token block ----
+template <int BITS> struct VGeom {
+    static constexpr int kWpt = v_words_per_tile(BITS);
+    static constexpr int kWordsPerLoad = 8 * kWpt;                 // words a lane holds per superblock
+    static constexpr int kLoadsPerChunk = (BITS == 2) ? 1 : 2;     // superblocks per 64-token chunk
+};
+template <int BITS> struct VWords { uint32_t w[VGeom<BITS>::kWordsPerLoad]; };
+
+template <int BITS>
+__device__ __forceinline__ VWords<BITS> load_v_superblock(const uint32_t* __restrict__ vc_head, int sb, int lane) {
+    VWords<BITS> r;
+    const uint32_t* p = vc_head + (size_t)sb * v_superblock_words(BITS);
+#pragma unroll
+    for (int q = 0; q < VGeom<BITS>::kWordsPerLoad / 4; ++q) {
+        const uint4 v = reinterpret_cast<const uint4*>(p)[q * 64 + lane];
+        r.w[4 * q] = v.x; r.w[4 * q + 1] = v.y; r.w[4 * q + 2] = v.z; r.w[4 * q + 3] = v.w;
+    }
+    return r;
+}
+// MFMA operand of (block-in-superblock, channel tile): registers i = 0..3 hold
+// the token pairs (16H + 4kb + i, H = 0/1) in the (low, high) halves.
+template <int BITS>
+__device__ __forceinline__ Frag v_frag(const VWords<BITS>& v, int blk, int tile) {
+    Frag f;
+    if constexpr (BITS == 16) {
+        f.u[0] = v.w[4 * tile]; f.u[1] = v.w[4 * tile + 1]; f.u[2] = v.w[4 * tile + 2]; f.u[3] = v.w[4 * tile + 3];
+    } else if constexpr (BITS == 8) {
+        const uint32_t a = v.w[2 * tile], b = v.w[2 * tile + 1];
+        f.u[0] = a & 0x00FF00FFu; f.u[1] = (a >> 8) & 0x00FF00FFu;
+        f.u[2] = b & 0x00FF00FFu; f.u[3] = (b >> 8) & 0x00FF00FFu;
+    } else if constexpr (BITS == 4) {
+        const uint32_t a = v.w[tile], b = a >> 8;
+        f.u[0] = a & 0x000F000Fu; f.u[1] = a & 0x00F000F0u;
+        f.u[2] = b & 0x000F000Fu; f.u[3] = b & 0x00F000F0u;
+    } else {
+        const uint32_t a = v.w[tile];
+        if (blk == 0) {
+            f.u[0] = a & 0x00030003u; f.u[1] = a & 0x000C000Cu; f.u[2] = a & 0x00300030u; f.u[3] = a & 0x00C000C0u;
+        } else {
+            const uint32_t b = a >> 10;
+            f.u[0] = a & 0x03000300u; f.u[1] = b & 0x00030003u; f.u[2] = b & 0x000C000Cu; f.u[3] = b & 0x00300030u;
+        }
+    }
+    return f;
+}
+template <int BITS>
+__device__ __forceinline__ constexpr int v_pos_log2(int blk, int i) {
+    if (BITS == 4) return (i & 1) ? 4 : 0;
+    if (BITS == 2) return blk == 0 ? 2 * i : (i == 0 ? 8 : 2 * (i - 1));
+    return 0;
+}
+
+// binary16 hi / lo parts of the binary32 value x: hi = rn(x), lo = rn(x - hi).
+__device__ __forceinline__ uint32_t split_half(float x, bool want_lo) {
+    const _Float16 hi = (_Float16)x;
+    const _Float16 lo = (_Float16)(x - (float)hi);
+    union { _Float16 h; uint16_t u; } c;
+    c.h = want_lo ? lo : hi;
+    return c.u;
+}
+
+struct DecodeArgs {
+    const uint16_t* q;        // [B, Hq, D]
+    const uint32_t* k_codes;
+    const uint32_t* v_codes;
+    const uint16_t* k_scale;
+    const uint16_t* k_zero;
+    const uint16_t* v_scale;
+    const uint16_t* v_zero;
+    const uint16_t* tail_k;
+    const uint16_t* tail_v;
+    float* part;              // [B*Hkv, n_partials, GQ, D+2]
+    int n_kept, tail_len, tail_cap;
+    int n_q_heads, n_kv_heads;
+    int n_splits, chunks_per_split, n_partials;
+    int group;                // G
+    float sm_scale;
+};
+
+// Full-precision tail rows: a short plain loop, one wave per row at a time.
+template <int GQ>
+__device__ void tail_partial(const DecodeArgs& a, int bh, float* smem) {
+    const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint16_t* tk = a.tail_k + (size_t)bh * a.tail_cap * kHeadDim;
+    const uint16_t* tv = a.tail_v + (size_t)bh * a.tail_cap * kHeadDim;
+    float qa[GQ], qb[GQ], m[GQ], l[GQ], oa[GQ], ob[GQ];
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        const uint32_t u = *reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + h) * kHeadDim + 2 * lane);
+        const h2v qq = as_h2(u);
+        qa[h] = (float)qq[0] * (a.sm_scale * kLog2e); qb[h] = (float)qq[1] * (a.sm_scale * kLog2e);
+        m[h] = kNegBig; l[h] = 0.f; oa[h] = 0.f; ob[h] = 0.f;
+    }
+    for (int t = wave; t < a.tail_len; t += kWaves) {
+        const h2v kk = as_h2(*reinterpret_cast<const uint32_t*>(tk + (size_t)t * kHeadDim + 2 * lane));
+        const h2v vv = as_h2(*reinterpret_cast<const uint32_t*>(tv + (size_t)t * kHeadDim + 2 * lane));
+#pragma unroll
+        for (int h = 0; h < GQ; ++h) {
+            float s = __builtin_fmaf(qa[h], (float)kk[0], qb[h] * (float)kk[1]);
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+            const float mn = fmaxf(m[h], s);
+            const float alpha = exp2f(m[h] - mn), p = exp2f(s - mn);
+            l[h] = __builtin_fmaf(l[h], alpha, p);
+            oa[h] = __builtin_fmaf(oa[h], alpha, p * (float)vv[0]);
+            ob[h] = __builtin_fmaf(ob[h], alpha, p * (float)vv[1]);
+            m[h] = mn;
+        }
+    }
+    // merge the four waves through LDS: layout [wave][h][130]
+    float* sm = smem;
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        float* row = sm + (wave * GQ + h) * kPartStride;
+        row[2 + 2 * lane] = oa[h]; row[3 + 2 * lane] = ob[h];
+        if (lane == 0) { row[0] = m[h]; row[1] = l[h]; }
+    }
+    __syncthreads();
+    float* dst = a.part + ((size_t)bh * a.n_partials + a.n_splits) * GQ * kPartStride;
+    for (int item = threadIdx.x; item < GQ * kHeadDim; item += kThreads) {
+        const int h = item / kHeadDim, d = item % kHeadDim;
+        float M = kNegBig;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm[(w * GQ + h) * kPartStride]);
+        float acc = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float* row = sm + (w * GQ + h) * kPartStride;
+            const float wgt = exp2f(row[0] - M);
+            acc = __builtin_fmaf(wgt, row[2 + d], acc);
+            L = __builtin_fmaf(wgt, row[1], L);
+        }
+        dst[h * kPartStride + 2 + d] = acc;
+        if (d == 0) { dst[h * kPartStride] = M; dst[h * kPartStride + 1] = L; }
+    }
+}
+
+// BITS: code width; GQ: query heads per kv head (1,2,4 -> two token slots per
+// MFMA tile; 8 -> one); NCG = D / G value channel groups; AXIS: key grouping.
+template <int BITS, int GQ, int NCG, int AXIS>
+__global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs a) {
+    constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
+    constexpr int GQP = (GQ <= 4) ? 4 : 8;        // heads per slot incl. padding
+    constexpr int NT = (SLOTS == 2) ? 1 : 2;      // QK tiles a lane keeps per 32-token block
+    constexpr bool QUANT = BITS != 16;
+    constexpr float kCodeUnit = QUANT ? 16777216.0f : 1.0f;  // 2^24: undo the subnormal reading of codes
+    constexpr int G = kHeadDim / NCG;
+
+    __shared__ __align__(16) float smem[kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4)];
+
+    const int bh = blockIdx.y;
+    if ((int)blockIdx.x == a.n_splits) { tail_partial<GQ>(a, bh, smem); return; }
+
+    const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kb = lane >> 4;
+    const int part = n & 1;
+    const int slot = (SLOTS == 2) ? (n >> 3) : 0;
+    const int h = (SLOTS == 2) ? ((n & 7) >> 1) : (n >> 1);
+    const bool live_row = h < GQ;
+
+    const uint32_t* kc = a.k_codes + (size_t)bh * ((size_t)a.n_kept * kHeadDim * BITS / 32);
+    const uint32_t* vc = a.v_codes + (size_t)bh * v_superblock_words(BITS) * ((a.n_kept + v_superblock(BITS) - 1) / v_superblock(BITS));
+    const int n_kgroups = (AXIS == KVQP_KEY_PER_CHANNEL) ? a.n_kept / G : a.n_kept;
+    const uint16_t* ks = QUANT ? a.k_scale + (size_t)bh * n_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
+    const uint16_t* kz = QUANT ? a.k_zero + (size_t)bh * n_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
+    const uint16_t* vs = QUANT ? a.v_scale + (size_t)bh * a.n_kept * NCG : nullptr;
+    const uint16_t* vz = QUANT ? a.v_zero + (size_t)bh * a.n_kept * NCG : nullptr;
+
+    // The lane's 32 query channels [32kb, 32kb+32) of its head, as natural pairs.
+    h2v qn[16];
+    {
+        const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + 32 * kb;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 v = reinterpret_cast<const uint4*>(qp)[i];
+            qn[4 * i] = as_h2(live_row ? v.x : 0u); qn[4 * i + 1] = as_h2(live_row ? v.y : 0u);
+            qn[4 * i + 2] = as_h2(live_row ? v.z : 0u); qn[4 * i + 3] = as_h2(live_row ? v.w : 0u);
+        }
+    }
+    // Query pre-divided by the position factor of the code it will meet.
+    h2v qpos[16];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const _Float16 f = (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
+            qpos[4 * s + r] = qn[4 * s + r] * f;
+        }
+
+    // Per-token keys: the query operand is constant; per-channel-group sums of q.
+    float qsum_cg = 0.f;  // sum of the lane's own 32 channels (all inside one channel group)
+    if constexpr (QUANT && AXIS == KVQP_KEY_PER_TOKEN) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) qsum_cg += (float)qn[i][0] + (float)qn[i][1];
+    }
+
+    const float c_logit = a.sm_scale * kLog2e * kCodeUnit;  // MFMA sum -> log2-domain logit
+    const float c_bias = a.sm_scale * kLog2e;
+
+    f4v O[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) O[t] = (f4v){0.f, 0.f, 0.f, 0.f};
+    float oz[NCG];
+#pragma unroll
+    for (int c = 0; c < NCG; ++c) oz[c] = 0.f;
+    float m_run = kNegBig, l_run = 0.f;
+
+    const int n_chunks = (a.n_kept + kChunk - 1) / kChunk;
+    const int c_begin = blockIdx.x * a.chunks_per_split;
+    const int c_end = min(n_chunks, c_begin + a.chunks_per_split);
+
+    for (int chunk = c_begin + wave; chunk < c_end; chunk += kWaves) {
+        const int tok0 = chunk * kChunk;
+        const int nblk = (a.n_kept - tok0 >= kChunk) ? 2 : 1;  // n_kept is a multiple of 32
+
+        // ---------------- logits of the lane's tokens ----------------
+        float logit[2][NT][4];
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            if (blk >= nblk) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) logit[blk][t][i] = kNegBig;
+                continue;
+            }
+            const int tb = tok0 + 32 * blk;
+            const KWords<BITS> k0 = load_k_tile<BITS>(kc, tb + n, kb);
+            const KWords<BITS> k1 = load_k_tile<BITS>(kc, tb + 16 + n, kb);
+            f4v acc0 = (f4v){0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+            float bias = 0.f;
+            if constexpr (!QUANT) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    Frag bq;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) bq.h[r] = part ? (h2v){0, 0} : qn[4 * s + r];
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq.v, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq.v, acc1, 0, 0, 0);
+                }
+            } else if constexpr (AXIS == KVQP_KEY_PER_CHANNEL) {
+                const int u = tb / G;
+                const uint4* sp = reinterpret_cast<const uint4*>(ks + (size_t)u * kHeadDim + 32 * kb);
+                const uint4* zp = reinterpret_cast<const uint4*>(kz + (size_t)u * kHeadDim + 32 * kb);
+                uint32_t sw[16], zw[16];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint4 sv = sp[i], zv = zp[i];
+                    sw[4 * i] = sv.x; sw[4 * i + 1] = sv.y; sw[4 * i + 2] = sv.z; sw[4 * i + 3] = sv.w;
+                    zw[4 * i] = zv.x; zw[4 * i + 1] = zv.y; zw[4 * i + 2] = zv.z; zw[4 * i + 3] = zv.w;
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) bias = __builtin_amdgcn_fdot2(qn[i], as_h2(zw[i]), bias, false);
+                bias = quad_rows_add(bias);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    Frag bq;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const h2v sc = as_h2(sw[4 * s + r]);
+                        const h2v hi = qpos[4 * s + r] * sc;
+                        const h2v lo = __builtin_elementwise_fma(qpos[4 * s + r], sc, -hi);
+                        bq.h[r] = part ? lo : hi;
+                    }
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq.v, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq.v, acc1, 0, 0, 0);
+                }
+            } else {
+                // per-token keys: one masked product per channel group, scaled per token afterwards
+                constexpr int LPG = 4 / NCG;  // lane quads (kb values) per channel group
+                f4v sum0 = acc0, sum1 = acc0;
+#pragma unroll
+                for (int c = 0; c < NCG; ++c) {
+                    const bool mine = (kb / LPG) == c;
+                    f4v p0 = (f4v){0.f, 0.f, 0.f, 0.f}, p1 = p0;
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        Frag bq;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) bq.h[r] = (mine && !part) ? qpos[4 * s + r] : (h2v){0, 0};
+                        p0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq.v, p0, 0, 0, 0);
+                        p1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq.v, p1, 0, 0, 0);
+                    }
+                    // sum over the group's channels of q, broadcast to all lanes of the row
+                    const float qs_c = quad_rows_add(mine ? qsum_cg : 0.f);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int t0i = tb + 4 * kb + i, t1i = t0i + 16;
+                        const float s0 = __half2float(__ushort_as_half(ks[(size_t)t0i * NCG + c]));
+                        const float z0 = __half2float(__ushort_as_half(kz[(size_t)t0i * NCG + c]));
+                        const float s1 = __half2float(__ushort_as_half(ks[(size_t)t1i * NCG + c]));
+                        const float z1 = __half2float(__ushort_as_half(kz[(size_t)t1i * NCG + c]));
+                        // fold 1/kCodeUnit of the bias in, since the sum is scaled by c_logit later
+                        sum0[i] = __builtin_fmaf(p0[i], s0, sum0[i]) + (part ? 0.f : z0 * qs_c * (1.0f / kCodeUnit));
+                        sum1[i] = __builtin_fmaf(p1[i], s1, sum1[i]) + (part ? 0.f : z1 * qs_c * (1.0f / kCodeUnit));
+                    }
+                }
+                acc0 = sum0; acc1 = sum1;
+            }
+            // keep the slot's tile, add the hi and lo rows, scale into the log2 domain
+            if constexpr (SLOTS == 2) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float s = slot ? acc1[i] : acc0[i];
+                    s += pair_other(s);
+                    logit[blk][0][i] = __builtin_fmaf(s, c_logit, bias * c_bias);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float s0 = acc0[i], s1 = acc1[i];
+                    s0 += pair_other(s0); s1 += pair_other(s1);
+                    logit[blk][0][i] = __builtin_fmaf(s0, c_logit, bias * c_bias);
+                    logit[blk][1][i] = __builtin_fmaf(s1, c_logit, bias * c_bias);
+                }
+            }
+        }
+
+        // ---------------- online softmax bookkeeping ----------------
+        float mx = kNegBig;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) mx = fmaxf(mx, logit[blk][t][i]);
+        mx = quad_rows_max(mx);
+        const float m_new = fmaxf(m_run, mx);
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
+            const float alpha = exp2f(m_run - m_new);
+            l_run *= alpha;
+#pragma unroll
+            for (int c = 0; c < NCG; ++c) oz[c] *= alpha;
+            float ar[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ar[i] = __shfl(alpha, 4 * kb + i);  // row 4kb+i lives in lanes with n = 4kb+i
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) O[t][i] *= ar[i];
+            m_run = m_new;
+        }
+
+        // ---------------- probabilities, P.V ----------------
+        VWords<BITS> vw[VGeom<BITS>::kLoadsPerChunk];
+        if constexpr (BITS == 2) {
+            vw[0] = load_v_superblock<BITS>(vc, chunk, lane);
+        } else {
+            vw[0] = load_v_superblock<BITS>(vc, 2 * chunk, lane);
+            if (nblk == 2) vw[1] = load_v_superblock<BITS>(vc, 2 * chunk + 1, lane);
+        }
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            if (blk >= nblk) continue;
+            const int tb = tok0 + 32 * blk;
+            // p[t][i] already divided by the position factor of the value code it meets
+            float p[NT][4];
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = v_pos_log2<BITS>(blk, i);
+                    p[t][i] = exp2f(logit[blk][t][i] - (m_run + (float)e));
+                    l_run = __builtin_fmaf(p[t][i], (float)(1 << e), l_run);
+                }
+            // scale / zero of the lane's tokens: 4 consecutive tokens x NCG, per tile
+            Frag pa[NCG];
+#pragma unroll
+            for (int c = 0; c < NCG; ++c)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pa[c].u[i] = 0u;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int tile_h = (SLOTS == 2) ? slot : t;          // 0: tokens 4kb+i, 1: tokens 16+4kb+i
+                const int tokb = tb + 16 * tile_h + 4 * kb;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                    for (int c = 0; c < NCG; ++c) {
+                        float ps = p[t][i];
+                        if constexpr (QUANT) {
+                            const float sv = __half2float(__ushort_as_half(vs[(size_t)(tokb + i) * NCG + c]));
+                            const float zv = __half2float(__ushort_as_half(vz[(size_t)(tokb + i) * NCG + c]));
+                            ps *= sv;
+                            oz[c] = __builtin_fmaf(p[t][i] * (float)(1 << v_pos_log2<BITS>(blk, i)), zv, oz[c]);
+                        }
+                        pa[c].u[i] |= split_half(ps, part) << (16 * tile_h);
+                    }
+                }
+            }
+            const VWords<BITS>& vv = vw[(BITS == 2) ? 0 : blk];
+#pragma unroll
+            for (int t8 = 0; t8 < 8; ++t8) {
+                const int c = (t8 * 16) / G;
+                O[t8] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[c].v, v_frag<BITS>(vv, (BITS == 2) ? blk : 0, t8).v, O[t8], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---------------- merge the four waves, write the split's partial ----------------
+    l_run = quad_rows_add(l_run);
+#pragma unroll
+    for (int c = 0; c < NCG; ++c) oz[c] = quad_rows_add(oz[c]);
+    float* sO = smem;                                  // [wave][row 16][128]
+    float* sS = smem + kWaves * 16 * kHeadDim;         // [wave][row 16][m, l, oz0..3]
+#pragma unroll
+    for (int t8 = 0; t8 < 8; ++t8)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sO[(wave * 16 + 4 * kb + i) * kHeadDim + 16 * t8 + n] = O[t8][i];
+    if (kb == 0) {
+        float* st = sS + (wave * 16 + n) * 6;
+        st[0] = m_run; st[1] = l_run;
+#pragma unroll
+        for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
+    }
+    __syncthreads();
+    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
+    for (int item = threadIdx.x; item < GQ * kHeadDim; item += kThreads) {
+        const int hh = item / kHeadDim, d = item % kHeadDim;
+        const int cg = d / G;
+        float M = kNegBig;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+            for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[(w * 16 + sl * 8 + 2 * hh) * 6]);
+        float acc = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+            for (int sl = 0; sl < SLOTS; ++sl) {
+                const int row = sl * 8 + 2 * hh;  // hi row; lo row is row + 1
+                const float* st = sS + (w * 16 + row) * 6;
+                const float wgt = exp2f(st[0] - M);
+                const float o = (sO[(w * 16 + row) * kHeadDim + d] + sO[(w * 16 + row + 1) * kHeadDim + d]) * kCodeUnit + st[2 + cg];
+                acc = __builtin_fmaf(wgt, o, acc);
+                L = __builtin_fmaf(wgt, st[1], L);
+            }
+        dst[hh * kPartStride + 2 + d] = acc;
+        if (d == 0) { dst[hh * kPartStride] = M; dst[hh * kPartStride + 1] = L; }
+    }
+}
+
+// Merge the splits of one query head and round once to binary16.
+__global__ __launch_bounds__(kHeadDim) void decode_combine(const float* __restrict__ part, uint16_t* __restrict__ out,
+                                                           int n_partials, int gq, int n_kv_heads) {
+    const int bq = blockIdx.x;                 // b * Hq + hq
+    const int hq_per_b = gq * n_kv_heads;
+    const int b = bq / hq_per_b, hq = bq % hq_per_b;
+    const int bh = b * n_kv_heads + hq / gq, h = hq % gq;
+    const int d = threadIdx.x;
+    const float* base = part + (size_t)bh * n_partials * gq * kPartStride + (size_t)h * kPartStride;
+    const size_t stride = (size_t)gq * kPartStride;
+    float M = kNegBig;
+    for (int s = 0; s < n_partials; ++s) M = fmaxf(M, base[s * stride]);
+    float acc = 0.f, L = 0.f;
+    for (int s = 0; s < n_partials; ++s) {
+        const float wgt = exp2f(base[s * stride] - M);
+        acc = __builtin_fmaf(wgt, base[s * stride + 2 + d], acc);
+        L = __builtin_fmaf(wgt, base[s * stride + 1], L);
+    }
+    out[(size_t)bq * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc / L));
+}
+
+template <int BITS, int GQ, int NCG>
+hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t stream) {
+    const dim3 grid(a.n_partials, cfg.batch * cfg.n_kv_heads);
+    if (cfg.key_axis == KVQP_KEY_PER_TOKEN && BITS != 16)
+        hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 1>), grid, dim3(kThreads), 0, stream, a);
+    else
+        hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 0>), grid, dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+template <int BITS, int GQ>
+hipError_t launch_group(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t stream) {
+    if (BITS == 16) return launch_axis<BITS, GQ, 1>(cfg, a, stream);
+    switch (cfg.group_size) {
+        case 32: return launch_axis<BITS, GQ, 4>(cfg, a, stream);
+        case 64: return launch_axis<BITS, GQ, 2>(cfg, a, stream);
+        default: return launch_axis<BITS, GQ, 1>(cfg, a, stream);
+    }
+}
+template <int BITS>
+hipError_t launch_gq(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t stream) {
+    switch (cfg.n_q_heads / cfg.n_kv_heads) {
+        case 1: return launch_group<BITS, 1>(cfg, a, stream);
+        case 2: return launch_group<BITS, 2>(cfg, a, stream);
+        case 4: return launch_group<BITS, 4>(cfg, a, stream);
+        default: return launch_group<BITS, 8>(cfg, a, stream);
+    }
+}
+
+}  // namespace
+
+DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
+    DecodePlan p;
+    const int heads = cfg.batch * cfg.n_kv_heads;
+    const int n_chunks = (n_kept + kChunk - 1) / kChunk;
+    int splits = 0;
+    if (n_chunks > 0) {
+        splits = cfg.decode_splits > 0 ? cfg.decode_splits : (1024 + heads - 1) / heads;
+        const int max_splits = cfg.decode_splits > 0 ? n_chunks : (n_chunks + kWaves - 1) / kWaves;
+        if (splits > max_splits) splits = max_splits;
+        if (splits < 1) splits = 1;
+    }
+    p.chunks_per_split = splits ? (n_chunks + splits - 1) / splits : 0;
+    p.n_splits = splits ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 0;
+    p.n_partials = p.n_splits + (tail_len > 0 ? 1 : 0);
+    const int gq = cfg.n_q_heads / cfg.n_kv_heads;
+    p.ws_bytes = (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartStride * sizeof(float);
+    return p;
+}
+
+hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c, void* out, void* ws,
+                         const DecodePlan& plan, hipStream_t stream) {
+    DecodeArgs a;
+    a.q = (const uint16_t*)q;
+    a.k_codes = (const uint32_t*)c.k_codes; a.v_codes = (const uint32_t*)c.v_codes;
+    a.k_scale = (const uint16_t*)c.k_scale; a.k_zero = (const uint16_t*)c.k_zero;
+    a.v_scale = (const uint16_t*)c.v_scale; a.v_zero = (const uint16_t*)c.v_zero;
+    a.tail_k = (const uint16_t*)c.tail_k; a.tail_v = (const uint16_t*)c.tail_v;
+    a.part = (float*)ws;
+    a.n_kept = c.n_kept; a.tail_len = c.tail_len; a.tail_cap = c.tail_cap;
+    a.n_q_heads = cfg.n_q_heads; a.n_kv_heads = cfg.n_kv_heads;
+    a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;
+    a.group = cfg.group_size; a.sm_scale = cfg.sm_scale;
+    hipError_t e;
+    switch (cfg.bits) {
+        case 2: e = launch_gq<2>(cfg, a, stream); break;
+        case 4: e = launch_gq<4>(cfg, a, stream); break;
+        case 8: e = launch_gq<8>(cfg, a, stream); break;
+        default: e = launch_gq<16>(cfg, a, stream); break;
+    }
+    if (e != hipSuccess) return e;
+    const int gq = cfg.n_q_heads / cfg.n_kv_heads;
+    hipLaunchKernelGGL(decode_combine, dim3(cfg.batch * cfg.n_q_heads), dim3(kHeadDim), 0, stream, (const float*)ws,
+                       (uint16_t*)out, plan.n_partials, gq, cfg.n_kv_heads);
+    return hipGetLastError();
+}
+
+}  // namespace kvqp

@@ -1,0 +1,177 @@
+// Host side of the C ABI: argument validation, size queries, launch order.
+// Every entry point validates on the host before anything is enqueued, so a
+// bad call can never reach a kernel with shapes it does not expect.
+#include <hip/hip_runtime.h>
+
+#include "kvqp_internal.h"
+
+namespace kvqp {
+namespace {
+
+bool is_pow2_group(int g) { return g == 32 || g == 64 || g == 128; }
+
+// Checks of the fields every entry point reads.
+int check_common(const kvqp_cfg* c) {
+    if (!c) return KVQP_ERR_INVALID_ARG;
+    if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1) return KVQP_ERR_INVALID_ARG;
+    if (c->n_q_heads % c->n_kv_heads) return KVQP_ERR_INVALID_ARG;
+    if (!(c->bits == 2 || c->bits == 4 || c->bits == 8 || c->bits == 16)) return KVQP_ERR_INVALID_ARG;
+    if (c->key_axis != KVQP_KEY_PER_CHANNEL && c->key_axis != KVQP_KEY_PER_TOKEN) return KVQP_ERR_INVALID_ARG;
+    if (c->decode_splits < 0) return KVQP_ERR_INVALID_ARG;
+    if (c->bits != 16) {
+        if (c->group_size < 1 || c->head_dim % c->group_size) return KVQP_ERR_INVALID_ARG;
+    }
+    if (!(c->sm_scale == c->sm_scale)) return KVQP_ERR_INVALID_ARG;
+    const int gq = c->n_q_heads / c->n_kv_heads;
+    if (c->head_dim != kHeadDim) return KVQP_ERR_UNSUPPORTED;
+    if (!(gq == 1 || gq == 2 || gq == 4 || gq == 8)) return KVQP_ERR_UNSUPPORTED;
+    if (c->bits != 16 && !is_pow2_group(c->group_size)) return KVQP_ERR_UNSUPPORTED;
+    if ((long long)c->batch * c->n_kv_heads > 65535) return KVQP_ERR_UNSUPPORTED;
+    return KVQP_OK;
+}
+
+// Checks of the prompt-side fields (compress, quantize_selected, sizes).
+int check_prompt(const kvqp_cfg* c) {
+    if (c->seq_len < 1 || c->window < 1 || c->window > c->seq_len) return KVQP_ERR_INVALID_ARG;
+    if (c->pool_kernel < 1 || c->pool_kernel % 2 == 0) return KVQP_ERR_INVALID_ARG;
+    if (c->budget < 0) return KVQP_ERR_INVALID_ARG;
+    const int gq = c->n_q_heads / c->n_kv_heads;
+    if (c->window * gq > 256 || c->pool_kernel > 63) return KVQP_ERR_UNSUPPORTED;
+    return KVQP_OK;
+}
+
+int n_kept_of(const kvqp_cfg* c) {
+    const int P = c->seq_len - c->window;
+    return c->budget < P ? c->budget : P;
+}
+
+int check_n_kept(const kvqp_cfg* c, int n_kept) {
+    if (n_kept < 0) return KVQP_ERR_INVALID_ARG;
+    if (n_kept % 32) return KVQP_ERR_INVALID_ARG;  // value blocks hold 32 tokens
+    if (c->bits != 16 && c->key_axis == KVQP_KEY_PER_CHANNEL && n_kept % c->group_size) return KVQP_ERR_INVALID_ARG;
+    return KVQP_OK;
+}
+
+int check_cache_ptrs(const kvqp_cfg* c, const kvqp_cache* cache, int n_kept, bool need_tail) {
+    if (!cache) return KVQP_ERR_INVALID_ARG;
+    if (n_kept > 0) {
+        if (!cache->k_codes || !cache->v_codes) return KVQP_ERR_INVALID_ARG;
+        if (c->bits != 16 && (!cache->k_scale || !cache->k_zero || !cache->v_scale || !cache->v_zero))
+            return KVQP_ERR_INVALID_ARG;
+    }
+    if (need_tail && (!cache->tail_k || !cache->tail_v)) return KVQP_ERR_INVALID_ARG;
+    return KVQP_OK;
+}
+
+}  // namespace
+}  // namespace kvqp
+
+using namespace kvqp;
+
+extern "C" {
+
+int kvqp_version(void) { return 100; }
+
+const char* kvqp_strerror(int code) {
+    switch (code) {
+        case KVQP_OK: return "ok";
+        case KVQP_ERR_INVALID_ARG: return "invalid argument";
+        case KVQP_ERR_UNSUPPORTED: return "configuration not supported by this build";
+        case KVQP_ERR_WORKSPACE: return "workspace missing or too small";
+        case KVQP_ERR_HIP: return "HIP runtime error";
+        default: return "unknown error code";
+    }
+}
+
+int kvqp_cache_sizes(const kvqp_cfg* cfg, int32_t tail_cap, size_t sizes_out[8]) {
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if ((rc = check_prompt(cfg))) return rc;
+    if (!sizes_out || tail_cap < cfg->window) return KVQP_ERR_INVALID_ARG;
+    const int n_kept = n_kept_of(cfg);
+    if ((rc = check_n_kept(cfg, n_kept))) return rc;
+    const size_t heads = (size_t)cfg->batch * cfg->n_kv_heads;
+    const size_t km = k_meta_elems(n_kept, cfg->bits, cfg->group_size, cfg->key_axis) * 2 * heads;
+    const size_t vm = v_meta_elems(n_kept, cfg->bits, cfg->group_size) * 2 * heads;
+    const size_t tail = heads * (size_t)tail_cap * kHeadDim * 2;
+    sizes_out[0] = k_code_words(n_kept, cfg->bits) * 4 * heads;
+    sizes_out[1] = v_code_words(n_kept, cfg->bits) * 4 * heads;
+    sizes_out[2] = km; sizes_out[3] = km;
+    sizes_out[4] = vm; sizes_out[5] = vm;
+    sizes_out[6] = tail; sizes_out[7] = tail;
+    return KVQP_OK;
+}
+
+int kvqp_workspace_bytes(const kvqp_cfg* cfg, size_t* compress_bytes, size_t* decode_bytes) {
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if ((rc = check_prompt(cfg))) return rc;
+    const int n_kept = n_kept_of(cfg);
+    if ((rc = check_n_kept(cfg, n_kept))) return rc;
+    if (compress_bytes) *compress_bytes = plan_compress(*cfg).total;
+    // decode: sized for a non-empty tail so that appended tokens never outgrow it
+    if (decode_bytes) *decode_bytes = plan_decode(*cfg, n_kept, 1).ws_bytes;
+    return KVQP_OK;
+}
+
+int kvqp_quantize_selected(const kvqp_cfg* cfg, const void* k, const void* v, const int32_t* idx, int32_t n_kept,
+                           kvqp_cache* cache, void* hip_stream) {
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if ((rc = check_prompt(cfg))) return rc;
+    if ((rc = check_n_kept(cfg, n_kept))) return rc;
+    if (!k || !v || (n_kept > 0 && !idx)) return KVQP_ERR_INVALID_ARG;
+    if (n_kept > cfg->seq_len - cfg->window) return KVQP_ERR_INVALID_ARG;
+    if ((rc = check_cache_ptrs(cfg, cache, n_kept, true))) return rc;
+    if (cache->tail_cap < cfg->window) return KVQP_ERR_INVALID_ARG;
+    if (launch_quant_pack(*cfg, k, v, idx, n_kept, *cache, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    cache->n_kept = n_kept;
+    cache->tail_len = cfg->window;
+    return KVQP_OK;
+}
+
+int kvqp_compress(const kvqp_cfg* cfg, const void* q_obs, const void* k, const void* v, kvqp_cache* cache,
+                  int32_t* idx_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if ((rc = check_prompt(cfg))) return rc;
+    const int n_kept = n_kept_of(cfg);
+    if ((rc = check_n_kept(cfg, n_kept))) return rc;
+    if (!q_obs || !k || !v) return KVQP_ERR_INVALID_ARG;
+    if ((rc = check_cache_ptrs(cfg, cache, n_kept, true))) return rc;
+    if (cache->tail_cap < cfg->window) return KVQP_ERR_INVALID_ARG;
+    const CompressPlan plan = plan_compress(*cfg);
+    if (!workspace || workspace_bytes < plan.total) return KVQP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15) != 0) return KVQP_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    int32_t* idx = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.off_idx);
+    if (n_kept > 0) {
+        if (launch_select(*cfg, q_obs, k, idx, workspace, plan, stream) != hipSuccess) return KVQP_ERR_HIP;
+        if (idx_out) {
+            const size_t bytes = (size_t)cfg->batch * cfg->n_kv_heads * n_kept * sizeof(int32_t);
+            if (hipMemcpyAsync(idx_out, idx, bytes, hipMemcpyDeviceToDevice, stream) != hipSuccess) return KVQP_ERR_HIP;
+        }
+    }
+    if (launch_quant_pack(*cfg, k, v, idx, n_kept, *cache, stream) != hipSuccess) return KVQP_ERR_HIP;
+    cache->n_kept = n_kept;
+    cache->tail_len = cfg->window;
+    return KVQP_OK;
+}
+
+int kvqp_decode_attn(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache, void* out, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if (!q || !out || !cache) return KVQP_ERR_INVALID_ARG;
+    if (cache->n_kept < 0 || cache->tail_len < 0 || cache->tail_len > cache->tail_cap) return KVQP_ERR_INVALID_ARG;
+    if (cache->n_kept + cache->tail_len < 1) return KVQP_ERR_INVALID_ARG;
+    if ((rc = check_n_kept(cfg, cache->n_kept))) return rc;
+    if ((rc = check_cache_ptrs(cfg, cache, cache->n_kept, cache->tail_len > 0))) return rc;
+    const DecodePlan plan = plan_decode(*cfg, cache->n_kept, cache->tail_len);
+    if (!workspace || workspace_bytes < plan.ws_bytes) return KVQP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15) != 0) return KVQP_ERR_INVALID_ARG;
+    if (launch_decode(*cfg, q, *cache, out, workspace, plan, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    return KVQP_OK;
+}
+
+}  // extern "C"

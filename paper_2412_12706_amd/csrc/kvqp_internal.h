@@ -1,0 +1,58 @@
+// Internal declarations shared by the translation units of libkvqp.so.
+// Not part of the public ABI (that is include/kvqp.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "kvqp.h"
+
+namespace kvqp {
+
+constexpr int kHeadDim = 128;  // the only head size built
+
+// Value-code storage geometry (format statement in kvqp.h, "Value codes").
+__host__ __device__ constexpr int v_superblock(int bits) { return bits == 2 ? 64 : 32; }
+__host__ __device__ constexpr int v_words_per_tile(int bits) { return bits == 16 ? 4 : bits == 8 ? 2 : 1; }
+__host__ __device__ constexpr int v_superblock_words(int bits) { return 64 * (kHeadDim / 16) * v_words_per_tile(bits); }
+
+inline size_t k_code_words(int n_kept, int bits) { return (size_t)n_kept * kHeadDim * bits / 32; }
+inline size_t v_code_words(int n_kept, int bits) {
+    const int sb = v_superblock(bits);
+    return (size_t)((n_kept + sb - 1) / sb) * v_superblock_words(bits);
+}
+
+// Element counts of scale/zero arrays per (batch, kv-head).
+inline size_t k_meta_elems(int n_kept, int bits, int G, int key_axis) {
+    if (bits == 16) return 0;
+    return key_axis == KVQP_KEY_PER_CHANNEL ? (size_t)(n_kept / G) * kHeadDim : (size_t)n_kept * (kHeadDim / G);
+}
+inline size_t v_meta_elems(int n_kept, int bits, int G) { return bits == 16 ? 0 : (size_t)n_kept * (kHeadDim / G); }
+
+// Decode split-K geometry, a pure function of the problem so that the
+// workspace query and the launch agree.
+struct DecodePlan {
+    int n_splits;        // token-axis splits of the packed part
+    int chunks_per_split;// 64-token chunks handled by one workgroup
+    int n_partials;      // n_splits (+1 when a tail partial is written)
+    size_t ws_bytes;
+};
+DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len);
+
+// Compress workspace layout (bytes offsets), pure function of cfg.
+struct CompressPlan {
+    int P, n_kept, rows;          // rows = Gq * W query rows per kv head
+    int n_chunks;                 // key chunks of the scoring passes
+    size_t off_stats_part, off_stats, off_vote, off_pooled, off_sel, off_idx, total;
+};
+CompressPlan plan_compress(const kvqp_cfg& cfg);
+
+hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx,
+                             int n_kept, const kvqp_cache& cache, hipStream_t stream);
+hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& cache, void* out,
+                         void* ws, const DecodePlan& plan, hipStream_t stream);
+hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx,
+                         void* ws, const CompressPlan& plan, hipStream_t stream);
+
+}  // namespace kvqp

@@ -1,0 +1,38 @@
+"""Helpers for the GPU parity tests: move caches between the CPU checker's
+numpy layout and the library's device buffers (byte-for-byte, no arithmetic)."""
+import numpy as np
+import torch
+
+from paper_2412_12706_amd import kvqp
+
+NAMES = ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v")
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def upload_cache(oc, device="cuda"):
+    """oracle Cache (numpy) -> kvqp.Cache (device byte tensors)."""
+    bufs = {}
+    for n in NAMES:
+        arr = np.ascontiguousarray(getattr(oc, n))
+        bufs[n] = torch.from_numpy(arr.view(np.uint8).reshape(-1).copy()).to(device)
+    return kvqp.Cache(bufs, oc.n_kept, oc.tail_len, oc.tail_cap)
+
+
+def download(cache, name, dtype):
+    return cache.buffers[name].cpu().numpy().view(dtype)
+
+
+def assert_cache_equal(gc, oc):
+    """Every buffer of the device cache equals the checker's, bit for bit."""
+    assert gc.n_kept == oc.n_kept and gc.tail_len == oc.tail_len
+    for n in NAMES:
+        ref = np.ascontiguousarray(getattr(oc, n))
+        got = download(gc, n, ref.dtype)
+        if n.startswith("tail"):
+            got = got.reshape(ref.shape)[:, :, : oc.tail_len]
+            ref = ref[:, :, : oc.tail_len]
+        bad = np.flatnonzero(got.reshape(-1) != ref.reshape(-1))
+        assert bad.size == 0, f"{n}: {bad.size} of {ref.size} words differ, first at {bad[:5]}"
