@@ -44,6 +44,8 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len);
 struct CompressPlan {
     int P, n_kept, rows;          // rows = Gq * W query rows per kv head
     int n_chunks;                 // key chunks of the scoring passes
+    int n_wg, chunks_per_wg;      // scoring workgroups per kv head and their share
+    int n_row_slabs;              // 64-row slabs of query rows (1, 2 or 4)
     size_t off_stats_part, off_stats, off_vote, off_pooled, off_sel, off_idx, total;
 };
 CompressPlan plan_compress(const kvqp_cfg& cfg);
