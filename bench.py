@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-pruned KV cache hot path on one MI355X.
+
+Workload (benchmark configs[1]): Llama-3-8B-shaped KV cache -- 32 layers,
+32 query / 8 KV heads, head_dim 128, half precision, batch 1, prompt L = 32768,
+synthetic N(0,1) data with four x10 outlier key channels per head -- swept over
+the equal-memory settings (tokens, bits) in {(2048,16), (4096,8), (8192,4),
+(16384,2)}, group 32, window 32, pool 7, 128 decode steps per setting.
+
+One "step" = one pass of the whole hot path over that workload: for every
+setting, compress all 32 layers (score, pool, top-k, gather, quantize, pack)
+and then run 128 decode-attention steps over all 32 layers.  Inputs are
+resident in HBM before timing starts.
+
+`value` is decode-attention throughput in algorithmic GB/s (bytes of packed
+cache + tail + q + out that one decode step must move, summed over the sweep,
+divided by the HIP-event time of the decode calls).  The 32 layers' caches are
+passed to the library as one batch per call -- valid here because the synthetic
+decode queries do not depend on the previous layer's output; the same bytes
+issued as 32 per-layer calls are reported next to it (`per_layer_calls`).
+Compress throughput (prompt tokens/s through all 32 layers) is reported in the
+same line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, HERE)
+
+PEAK_HBM_GBS = 8000.0
+LAYERS, HQ, HKV, D, L, W, POOL, G = 32, 32, 8, 128, 32768, 32, 7, 32
+SWEEP = [(2048, 16), (4096, 8), (8192, 4), (16384, 2)]
+DECODE_STEPS = 128
+CONFIG_ID = 2
+
+
+def bytes_per_token(bits, group):
+    return 4 * D if bits == 16 else 2 * (D * bits // 8 + 4 * D // group)
+
+
+def decode_bytes(n_caches, n_kept, bits, group, tail):
+    """Algorithmic bytes of one decode step over n_caches caches (all KV heads)."""
+    return n_caches * HKV * (n_kept * bytes_per_token(bits, group) + tail * 4 * D) + 2 * n_caches * HQ * D * 2
+
+
+def compress_bytes(n_caches, n_kept, bits, group):
+    """Algorithmic bytes of compressing n_caches layers: K once, q_obs, selected V rows, outputs."""
+    per = HKV * L * 2 * D + HQ * W * D * 2 + HKV * n_kept * 2 * D + HKV * (n_kept * bytes_per_token(bits, group) + W * 4 * D + 4 * n_kept)
+    return n_caches * per
+
+
+def read_traffic_note(kernel_tag):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE/WRITE_SIZE),
+    recorded by hand in profiles/; None when no such note exists."""
+    path = os.path.join(HERE, "profiles", f"traffic_{kernel_tag}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(q_obs1, k1, v1, sm_scale):
+    """The CPU checker, untuned, timed on the host cores on a bounded sample:
+    one layer of the (8192 tokens, 4 bit) setting -- compress once, then 4
+    decode steps."""
+    import numpy as np
+    from oracle import kvqp_oracle as orc
+    from paper_2412_12706_amd import synth
+    t0 = time.perf_counter()
+    cache, idx, _ = orc.compress(q_obs1, k1, v1, window=W, pool=POOL, budget=8192, bits=4, G=G, sm_scale=sm_scale,
+                                 want_pooled=False)
+    t1 = time.perf_counter()
+    n_dec = 4
+    for s in range(n_dec):
+        q = synth.decode_query_host(1, HQ, D, config=CONFIG_ID, layer=0, step=s)
+        orc.decode_attn(q, cache, sm_scale)
+    t2 = time.perf_counter()
+    dec_gbs = decode_bytes(1, 8192, 4, G, W) * n_dec / (t2 - t1) / 1e9
+    return {
+        "value": round(dec_gbs, 4), "unit": "GB/s", "cores": orc.threads(), "kind": "oracle",
+        "sample": f"1 of 32 layers at (8192 tok, 4 bit): 1 compress ({t1 - t0:.2f} s) + {n_dec} decode steps ({t2 - t1:.2f} s)",
+        "compress_mtok_s_one_layer": round(L / (t1 - t0) / 1e6, 4),
+        "compress_mtok_s_32_layers_extrapolated": round(L / (t1 - t0) / 1e6 / LAYERS, 5),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2412_12706_amd import kvqp, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    kvqp.lib()  # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    sm_scale = float(np.float32(D ** -0.5))
+
+    # ---- inputs, resident in HBM: the 32 layers are the batch axis ----
+    q_obs, k, v = synth.prompt_device(LAYERS, HQ, HKV, L, W, D, outlier=10.0, config=CONFIG_ID, device=dev)
+    queries = [synth.decode_query_device(LAYERS, HQ, D, config=CONFIG_ID, step=s, device=dev) for s in range(DECODE_STEPS)]
+    out = torch.empty_like(queries[0])
+
+    settings = []
+    for n_kept, bits in SWEEP:
+        cfg = kvqp.Cfg(batch=LAYERS, n_q_heads=HQ, n_kv_heads=HKV, head_dim=D, seq_len=L, window=W, pool_kernel=POOL,
+                       budget=n_kept, bits=bits, group_size=G, sm_scale=sm_scale)
+        wc, wd = kvqp.workspace_bytes(cfg)
+        settings.append({
+            "cfg": cfg, "cache": kvqp.alloc_cache(cfg, device=dev), "ws_c": kvqp.alloc_workspace(wc, dev),
+            "ws_d": kvqp.alloc_workspace(wd, dev), "n_kept": n_kept, "bits": bits,
+            "t_compress_ms": 0.0, "t_decode_ms": 0.0,
+        })
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def one_step(record):
+        for s in settings:
+            e0, e1, e2 = ev(), ev(), ev()
+            e0.record()
+            kvqp.compress(s["cfg"], q_obs, k, v, s["cache"], workspace=s["ws_c"])
+            e1.record()
+            for t in range(DECODE_STEPS):
+                kvqp.decode_attn(s["cfg"], queries[t], s["cache"], out, s["ws_d"])
+            e2.record()
+            if record:
+                s["_ev"] = s.get("_ev", []) + [(e0, e1, e2)]
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    for s in settings:
+        for e0, e1, e2 in s["_ev"]:
+            s["t_compress_ms"] += e0.elapsed_time(e1)
+            s["t_decode_ms"] += e1.elapsed_time(e2)
+
+    # ---- per-setting figures ----
+    sweep = []
+    tot_bytes = tot_ms = 0.0
+    for s in settings:
+        n_calls = args.steps * DECODE_STEPS
+        b = decode_bytes(LAYERS, s["n_kept"], s["bits"], G, W)
+        us_call = s["t_decode_ms"] * 1e3 / n_calls
+        gbs = b / (us_call * 1e-6) / 1e9
+        c_ms = s["t_compress_ms"] / args.steps
+        sweep.append({
+            "tokens": s["n_kept"], "bits": s["bits"], "decode_us_per_step": round(us_call, 2),
+            "decode_gbs": round(gbs, 1), "pct_of_8TBs": round(100 * gbs / PEAK_HBM_GBS, 1),
+            "bytes_per_step": b, "compress_ms_32_layers": round(c_ms, 3),
+            "compress_mtok_s": round(L / (c_ms * 1e-3) / 1e6, 2),
+            "compress_gbs": round(compress_bytes(LAYERS, s["n_kept"], s["bits"], G) / (c_ms * 1e-3) / 1e9, 1),
+        })
+        tot_bytes += b * n_calls
+        tot_ms += s["t_decode_ms"]
+    value = tot_bytes / (tot_ms * 1e-3) / 1e9
+
+    # ---- the same decode bytes issued as 32 per-layer calls (outside the timed steps) ----
+    per_layer = []
+    for s in settings:
+        cfg1 = kvqp.Cfg(**{**s["cfg"].__dict__, "batch": 1})
+        caches = []
+        for l in range(LAYERS):
+            bufs = {}
+            for name, t in s["cache"].buffers.items():
+                per = t.numel() // LAYERS
+                bufs[name] = t[l * per:(l + 1) * per]
+            caches.append(kvqp.Cache(bufs, s["cache"].n_kept, s["cache"].tail_len, s["cache"].tail_cap))
+        ws1 = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg1)[1], dev)
+        reps = 8
+        for rep in range(reps + 1):
+            if rep == 1:
+                torch.cuda.synchronize()
+                a, bq = ev(), ev()
+                a.record()
+            for l in range(LAYERS):
+                kvqp.decode_attn(cfg1, queries[rep][l:l + 1], caches[l], out[l:l + 1], ws1)
+        bq.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(bq) * 1e3 / reps
+        b = decode_bytes(LAYERS, s["n_kept"], s["bits"], G, W)
+        per_layer.append({"tokens": s["n_kept"], "bits": s["bits"], "decode_us_per_step": round(us, 1),
+                          "decode_gbs": round(b / (us * 1e-6) / 1e9, 1)})
+
+    # ---- roofline of the dominant kernel: the decode launch that takes most of the step ----
+    dom = max(range(len(settings)), key=lambda i: settings[i]["t_decode_ms"])
+    dom_s, dom_r = settings[dom], sweep[dom]
+    tag = f"decode_attn_splitk_{dom_s['bits']}bit_cfg2"
+    roofline = {
+        "bound": "hbm", "kernel": f"decode_attn_splitk<{dom_s['bits']} bit> (+ decode_combine, same event window)",
+        "achieved": dom_r["decode_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+        "frac": round(dom_r["decode_gbs"] / PEAK_HBM_GBS, 4), "traffic": read_traffic_note(tag),
+        "algorithmic_bytes_per_launch": dom_r["bytes_per_step"], "launch_us": dom_r["decode_us_per_step"],
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(q_obs[:1].cpu().numpy(), k[:1].cpu().numpy(), v[:1].cpu().numpy(), sm_scale)
+
+    c4 = next(r for r in sweep if r["bits"] == 4)
+    line = {
+        "metric": "packed-KV decode attn HBM GB/s (% of peak) + compress Mtok/s at 32k ctx",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms / args.steps, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": "configs[1]: Llama-3-8B-shaped KV, 32 layers x (32 Q / 8 KV heads, d=128), batch 1, L=32768, "
+                        "sweep (tokens,bits) in {(2048,16),(4096,8),(8192,4),(16384,2)}, group 32, window 32, pool 7, "
+                        "128 decode steps per setting",
+            "launch": "all 32 layers' caches as one batch per library call",
+            "value_is": "sum of algorithmic decode bytes over the sweep / sum of decode HIP-event time",
+        },
+        "pct_of_peak_hbm": round(100 * value / PEAK_HBM_GBS, 1),
+        "compress_mtok_s": c4["compress_mtok_s"],
+        "compress_note": "prompt tokens/s through all 32 layers at the (8192 tok, 4 bit) setting",
+        "sweep": sweep, "per_layer_calls": per_layer,
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
