@@ -571,6 +571,386 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Software-pipelined variant for per-channel keys (the default axes) and for
+// the 16-bit cache.  Same arithmetic as above; differences are all about
+// keeping HBM, the texture-address path and the vector ALU busy at once:
+//   * every global load of a 32-token block is issued one block ahead into a
+//     second register set (A = first block of a 64-token chunk, B = second);
+//   * scales and zero-points are needed replicated (every row lane of a quad
+//     multiplies by the same 32 key scales; every row lane of a slot by the same
+//     token scales).  Loading them replicated costs a full 1 KB trip through the
+//     texture path per instruction, so each wave instead fetches every scale row
+//     once, one dword per lane, parks it in a wave-private LDS strip and reads
+//     it back with broadcast ds_read_b128;
+//   * the key zero-point term sum_d q[d] z[group, d] of a chunk's groups comes
+//     from one extra MFMA whose token rows are the z rows themselves;
+//   * hi/lo operand parts are produced with fused multiply-adds that round
+//     straight to binary16, and only the lanes that own a lo row compute it.
+// ---------------------------------------------------------------------------
+template <int BITS, int GQ, int NCG>
+__global__ __launch_bounds__(kThreads, 2) void decode_attn_pipe(const DecodeArgs a) {
+    constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
+    constexpr int NT = (SLOTS == 2) ? 1 : 2;
+    constexpr bool QUANT = BITS != 16;
+    constexpr float kCodeUnit = QUANT ? 16777216.0f : 1.0f;
+    constexpr int G = kHeadDim / NCG;
+    constexpr int NGRP = (QUANT && G == 32) ? 2 : 1;          // key groups per 64-token chunk
+    constexpr int VROW = 64 * NCG;                            // bytes of value scales of one 32-token block
+    constexpr int VSTRIP = 8 * NCG;                           // bytes of value scales of 4 consecutive tokens
+    // wave-private LDS strip: key scale row | key zero rows | value scales | value zeros
+    constexpr int OFF_KS = 0, OFF_KZ = 256, OFF_VS = OFF_KZ + 256 * NGRP, OFF_VZ = OFF_VS + VROW;
+    constexpr int STRIP = OFF_VZ + VROW;
+
+    __shared__ __align__(16) float smem[kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4)];
+    __shared__ __align__(16) unsigned char stage_all[QUANT ? kWaves * STRIP : 16];
+
+    const int bh = blockIdx.y;
+    if ((int)blockIdx.x == a.n_splits) { tail_partial<GQ>(a, bh, smem); return; }
+
+    const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kb = lane >> 4;
+    const int part = n & 1;
+    const int slot = (SLOTS == 2) ? (n >> 3) : 0;
+    const int h = (SLOTS == 2) ? ((n & 7) >> 1) : (n >> 1);
+    const bool live_row = h < GQ;
+    unsigned char* stage = stage_all + (QUANT ? wave * STRIP : 0);
+
+    // head bases (wave-uniform) and per-lane 32-bit byte offsets
+    const char* kc = reinterpret_cast<const char*>(a.k_codes) + (size_t)bh * ((size_t)a.n_kept * kHeadDim * BITS / 8);
+    const char* vc = reinterpret_cast<const char*>(a.v_codes) +
+                     (size_t)bh * v_superblock_words(BITS) * 4 * ((a.n_kept + v_superblock(BITS) - 1) / v_superblock(BITS));
+    const char* ks = QUANT ? reinterpret_cast<const char*>(a.k_scale) + (size_t)bh * (a.n_kept / G) * kHeadDim * 2 : nullptr;
+    const char* kz = QUANT ? reinterpret_cast<const char*>(a.k_zero) + (size_t)bh * (a.n_kept / G) * kHeadDim * 2 : nullptr;
+    const char* vs = QUANT ? reinterpret_cast<const char*>(a.v_scale) + (size_t)bh * a.n_kept * NCG * 2 : nullptr;
+    const char* vz = QUANT ? reinterpret_cast<const char*>(a.v_zero) + (size_t)bh * a.n_kept * NCG * 2 : nullptr;
+    const uint32_t k_lane = (uint32_t)n * (16 * BITS) + (uint32_t)kb * (4 * BITS);   // within a 16-token key tile
+    const uint32_t v_lane = (uint32_t)lane * 16;
+    const uint32_t row_lane = (uint32_t)lane * 4;                                     // dword of a 256-byte scale row
+    const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
+    const int n_kgroups = QUANT ? a.n_kept / G : 0;
+
+    h2v qn[16], qpos[16];
+    {
+        const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + 32 * kb;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 v = reinterpret_cast<const uint4*>(qp)[i];
+            qn[4 * i] = as_h2(live_row ? v.x : 0u); qn[4 * i + 1] = as_h2(live_row ? v.y : 0u);
+            qn[4 * i + 2] = as_h2(live_row ? v.z : 0u); qn[4 * i + 3] = as_h2(live_row ? v.w : 0u);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                qpos[4 * s + r] = qn[4 * s + r] * (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
+    }
+    const float c_logit = a.sm_scale * kLog2e * kCodeUnit;
+    const float c_bias = a.sm_scale * kLog2e;
+
+    f4v O[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) O[t] = (f4v){0.f, 0.f, 0.f, 0.f};
+    float oz[NCG];
+#pragma unroll
+    for (int c = 0; c < NCG; ++c) oz[c] = 0.f;
+    float m_run = kNegBig, l_run = 0.f;
+    Frag bq[4];                       // query-times-scale operand of the current key group
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bq[s].h[r] = part ? (h2v){0, 0} : qn[4 * s + r];   // 16-bit cache: plain q in the hi rows
+
+    // ---- the two register sets (codes as MFMA operands; one dword per lane of every scale row) ----
+    KWords<BITS> ak0, ak1, bk0, bk1;
+    VWords<BITS> av, bv;
+    uint32_t a_ks = 0, a_kz[NGRP], a_vs = 0, a_vz = 0, b_ks = 0, b_vs = 0, b_vz = 0;
+#pragma unroll
+    for (int i = 0; i < NGRP; ++i) a_kz[i] = 0;
+
+    auto load_k = [&](int tok, KWords<BITS>& dst) {
+        const char* p = kc + (size_t)tok * (16 * BITS) + k_lane;
+        if constexpr (BITS == 2) {
+            const uint2 v = *reinterpret_cast<const uint2*>(p);
+            dst.w[0] = v.x; dst.w[1] = v.y;
+        } else {
+#pragma unroll
+            for (int i = 0; i < BITS / 4; ++i) {
+                const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+                dst.w[4 * i] = v.x; dst.w[4 * i + 1] = v.y; dst.w[4 * i + 2] = v.z; dst.w[4 * i + 3] = v.w;
+            }
+        }
+    };
+    auto load_v = [&](int sb, VWords<BITS>& dst) {
+        const char* p = vc + (size_t)sb * (v_superblock_words(BITS) * 4) + v_lane;
+#pragma unroll
+        for (int q = 0; q < VGeom<BITS>::kWordsPerLoad / 4; ++q) {
+            const uint4 v = *reinterpret_cast<const uint4*>(p + q * 1024);
+            dst.w[4 * q] = v.x; dst.w[4 * q + 1] = v.y; dst.w[4 * q + 2] = v.z; dst.w[4 * q + 3] = v.w;
+        }
+    };
+    auto dword_at = [](const char* base, uint32_t off) { return *reinterpret_cast<const uint32_t*>(base + off); };
+    // Loads are unconditional (indices clamped to valid blocks) so that the loop body is
+    // straight-line code and the hardware wait counters can be tracked exactly.
+    auto load_A = [&](int chunk) {
+        const int tb = chunk * kChunk;
+        load_k(tb + 0, ak0); load_k(tb + 16, ak1);
+        if constexpr (QUANT) {
+            const int u = tb / G;
+            a_ks = dword_at(ks, (uint32_t)u * 256 + row_lane);
+#pragma unroll
+            for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_lane);
+            a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_lane);
+            a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_lane);
+        }
+        load_v((BITS == 2) ? chunk : 2 * chunk, av);
+    };
+    auto load_B = [&](int chunk, bool two) {
+        const int tb = chunk * kChunk + (two ? 32 : 0);
+        load_k(tb + 0, bk0); load_k(tb + 16, bk1);
+        if constexpr (QUANT) {
+            if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_lane);
+            b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_lane);
+            b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_lane);
+        }
+        if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv);
+    };
+    auto lds_put = [&](int off, uint32_t v) { *reinterpret_cast<uint32_t*>(stage + off + row_lane) = v; };
+    auto lds_put_v = [&](int off, uint32_t v) { if (lane < VROW / 4) *reinterpret_cast<uint32_t*>(stage + off + row_lane) = v; };
+    auto lds_get16 = [&](int off, uint32_t* dst) {   // 64 bytes -> 16 registers
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + off + 16 * i);
+            dst[4 * i] = v.x; dst[4 * i + 1] = v.y; dst[4 * i + 2] = v.z; dst[4 * i + 3] = v.w;
+        }
+    };
+    auto lds_get_strip = [&](int off, uint32_t* dst) {  // the scales of 4 consecutive tokens
+        if constexpr (VSTRIP == 32) {
+            const uint4 x = *reinterpret_cast<const uint4*>(stage + off), y = *reinterpret_cast<const uint4*>(stage + off + 16);
+            dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w; dst[4] = y.x; dst[5] = y.y; dst[6] = y.z; dst[7] = y.w;
+        } else if constexpr (VSTRIP == 16) {
+            const uint4 x = *reinterpret_cast<const uint4*>(stage + off);
+            dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+        } else {
+            const uint2 x = *reinterpret_cast<const uint2*>(stage + off);
+            dst[0] = x.x; dst[1] = x.y;
+        }
+    };
+
+    // one 32-token block: QK product, online softmax update, PV product
+    auto compute = [&](const KWords<BITS>& k0, const KWords<BITS>& k1, uint32_t r_ks, bool new_group, float bias,
+                       const VWords<BITS>& vv, int vblk, uint32_t r_vs, uint32_t r_vz) {
+        uint32_t vsr[QUANT ? NT * 2 * NCG : 1], vzr[QUANT ? NT * 2 * NCG : 1];
+        if constexpr (QUANT) {
+            if (new_group) lds_put(OFF_KS, r_ks);
+            lds_put_v(OFF_VS, r_vs); lds_put_v(OFF_VZ, r_vz);
+            if (new_group) {
+                uint32_t sw[16];
+                lds_get16(OFF_KS + 64 * kb, sw);
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) bq[s].h[r] = qpos[4 * s + r] * as_h2(sw[4 * s + r]);
+                if (part) {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            bq[s].h[r] = __builtin_elementwise_fma(qpos[4 * s + r], as_h2(sw[4 * s + r]), -bq[s].h[r]);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int th = (SLOTS == 2) ? slot : t;
+                lds_get_strip(OFF_VS + (16 * th + 4 * kb) * (2 * NCG), vsr + t * 2 * NCG);
+                lds_get_strip(OFF_VZ + (16 * th + 4 * kb) * (2 * NCG), vzr + t * 2 * NCG);
+            }
+        }
+        f4v acc0 = (f4v){0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq[s].v, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq[s].v, acc1, 0, 0, 0);
+        }
+        const float bias_l2 = bias * c_bias;
+        float lg[NT][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (SLOTS == 2) {
+                float s = slot ? acc1[i] : acc0[i];
+                s += pair_other(s);
+                lg[0][i] = __builtin_fmaf(s, c_logit, bias_l2);
+            } else {
+                float s0 = acc0[i], s1 = acc1[i];
+                s0 += pair_other(s0); s1 += pair_other(s1);
+                lg[0][i] = __builtin_fmaf(s0, c_logit, bias_l2);
+                lg[NT - 1][i] = __builtin_fmaf(s1, c_logit, bias_l2);
+            }
+        }
+        float mx = lg[0][0];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lg[t][i]);
+        mx = quad_rows_max(mx);
+        const float m_new = fmaxf(m_run, mx);
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run *= alpha;
+#pragma unroll
+            for (int c = 0; c < NCG; ++c) oz[c] *= alpha;
+            float ar[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ar[i] = __shfl(alpha, 4 * kb + i);
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) O[t][i] *= ar[i];
+            m_run = m_new;
+        }
+        float p[NT][4];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = v_pos_log2<BITS>(vblk, i);
+                p[t][i] = __builtin_amdgcn_exp2f(lg[t][i] - (m_run + (float)e));
+                l_run = __builtin_fmaf(p[t][i], (float)(1 << e), l_run);
+            }
+        Frag pa[NCG];
+        if constexpr (!QUANT) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t w = 0;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int th = (SLOTS == 2) ? slot : t;
+                    w |= split_half(p[t][i], part) << (16 * th);
+                }
+                pa[0].u[i] = w;
+            }
+        } else {
+            _Float16 hv[NT][4][NCG];
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int c = 0; c < NCG; ++c) {
+                        const int e = i * NCG + c;                       // half index inside the lane's 4-token strip
+                        const h2v sv2 = as_h2(vsr[t * 2 * NCG + (e >> 1)]), zv2 = as_h2(vzr[t * 2 * NCG + (e >> 1)]);
+                        const float sv = (float)sv2[e & 1], zv = (float)zv2[e & 1];
+                        hv[t][i][c] = (_Float16)__builtin_fmaf(p[t][i], sv, 0.0f);
+                        oz[c] = __builtin_fmaf(p[t][i] * (float)(1 << v_pos_log2<BITS>(vblk, i)), zv, oz[c]);
+                    }
+            if (part) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int c = 0; c < NCG; ++c) {
+                            const int e = i * NCG + c;
+                            const h2v sv2 = as_h2(vsr[t * 2 * NCG + (e >> 1)]);
+                            hv[t][i][c] = (_Float16)__builtin_fmaf(p[t][i], (float)sv2[e & 1], -(float)hv[t][i][c]);
+                        }
+            }
+#pragma unroll
+            for (int c = 0; c < NCG; ++c)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        union { _Float16 f; uint16_t u; } cv; cv.f = hv[t][i][c];
+                        const int th = (SLOTS == 2) ? slot : t;
+                        w |= (uint32_t)cv.u << (16 * th);
+                    }
+                    pa[c].u[i] = w;
+                }
+        }
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8)
+            O[t8] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[(t8 * 16) / G].v, v_frag<BITS>(vv, vblk, t8).v, O[t8], 0, 0, 0);
+    };
+
+    const int n_chunks = (a.n_kept + kChunk - 1) / kChunk;
+    const int c_begin = blockIdx.x * a.chunks_per_split;
+    const int c_end = min(n_chunks, c_begin + a.chunks_per_split);
+    int chunk = c_begin + wave;
+    if (chunk < c_end) load_A(chunk);
+    for (; chunk < c_end; chunk += kWaves) {
+        const int tok0 = chunk * kChunk;
+        const bool two = a.n_kept - tok0 >= kChunk;         // n_kept is a multiple of 32
+        load_B(chunk, two);
+        // key zero-point terms of this chunk's groups: token rows = z rows, unscaled q as the other operand
+        float bias0 = 0.f, bias1 = 0.f;
+        if constexpr (QUANT) {
+#pragma unroll
+            for (int i = 0; i < NGRP; ++i) lds_put(OFF_KZ + 256 * i, a_kz[i]);
+            uint32_t zw[16];
+            lds_get16(OFF_KZ + 256 * min(n, NGRP - 1) + 64 * kb, zw);
+            f4v zc = (f4v){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                Frag zf, qf;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) { zf.u[r] = (n < NGRP) ? zw[4 * s + r] : 0u; qf.h[r] = qn[4 * s + r]; }
+                zc = __builtin_amdgcn_mfma_f32_16x16x32_f16(zf.v, qf.v, zc, 0, 0, 0);
+            }
+            bias0 = quad_rows_add(zc[0]);                     // rows >= NGRP are zero, so the sum is a broadcast
+            if constexpr (NGRP == 2) bias1 = quad_rows_add(zc[1]);
+        }
+        compute(ak0, ak1, a_ks, true, bias0, av, 0, a_vs, a_vz);
+        if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
+        load_A((chunk + kWaves < c_end) ? chunk + kWaves : chunk);
+        if (two) compute(bk0, bk1, b_ks, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
+    }
+
+    // ---- merge the four waves, write the split's partial (same as the plain variant) ----
+    l_run = quad_rows_add(l_run);
+#pragma unroll
+    for (int c = 0; c < NCG; ++c) oz[c] = quad_rows_add(oz[c]);
+    float* sO = smem;
+    float* sS = smem + kWaves * 16 * kHeadDim;
+#pragma unroll
+    for (int t8 = 0; t8 < 8; ++t8)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sO[(wave * 16 + 4 * kb + i) * kHeadDim + 16 * t8 + n] = O[t8][i];
+    if (kb == 0) {
+        float* st = sS + (wave * 16 + n) * 6;
+        st[0] = m_run; st[1] = l_run;
+#pragma unroll
+        for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
+    }
+    __syncthreads();
+    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
+    for (int item = threadIdx.x; item < GQ * kHeadDim; item += kThreads) {
+        const int hh = item / kHeadDim, d = item % kHeadDim;
+        const int cg = d / G;
+        float M = kNegBig;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+            for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[(w * 16 + sl * 8 + 2 * hh) * 6]);
+        float acc = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+            for (int sl = 0; sl < SLOTS; ++sl) {
+                const int row = sl * 8 + 2 * hh;
+                const float* st = sS + (w * 16 + row) * 6;
+                const float wgt = exp2f(st[0] - M);
+                const float o = (sO[(w * 16 + row) * kHeadDim + d] + sO[(w * 16 + row + 1) * kHeadDim + d]) * kCodeUnit + st[2 + cg];
+                acc = __builtin_fmaf(wgt, o, acc);
+                L = __builtin_fmaf(wgt, st[1], L);
+            }
+        dst[hh * kPartStride + 2 + d] = acc;
+        if (d == 0) { dst[hh * kPartStride] = M; dst[hh * kPartStride + 1] = L; }
+    }
+}
+
 // Merge the splits of one query head and round once to binary16.
 __global__ __launch_bounds__(kHeadDim) void decode_combine(const float* __restrict__ part, uint16_t* __restrict__ out,
                                                            int n_partials, int gq, int n_kv_heads) {
@@ -598,7 +978,7 @@ hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t str
     if (cfg.key_axis == KVQP_KEY_PER_TOKEN && BITS != 16)
         hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 1>), grid, dim3(kThreads), 0, stream, a);
     else
-        hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 0>), grid, dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG>), grid, dim3(kThreads), 0, stream, a);
     return hipGetLastError();
 }
 template <int BITS, int GQ>
