@@ -44,6 +44,10 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kChunk = 64;          // tokens per wave iteration
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f; // finite stand-in for -inf in running maxima
+#ifndef KVQP_PIPE_WAVES
+#define KVQP_PIPE_WAVES 2
+#endif
+constexpr float kLazyLog2 = 8.0f;   // slack of the lazily updated softmax reference
 constexpr int kPartStride = kHeadDim + 2;  // floats per (partial, head): m, l, acc[128]
 
 __device__ __forceinline__ float xor16_max(float v) {
@@ -589,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 //     straight to binary16, and only the lanes that own a lo row compute it.
 // ---------------------------------------------------------------------------
 template <int BITS, int GQ, int NCG>
-__global__ __launch_bounds__(kThreads, 2) void decode_attn_pipe(const DecodeArgs a) {
+__global__ __launch_bounds__(kThreads, KVQP_PIPE_WAVES) void decode_attn_pipe(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int NT = (SLOTS == 2) ? 1 : 2;
     constexpr bool QUANT = BITS != 16;
@@ -604,6 +608,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_pipe(const DecodeArgs
 
     __shared__ __align__(16) float smem[kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4)];
     __shared__ __align__(16) unsigned char stage_all[QUANT ? kWaves * STRIP : 16];
+    __shared__ __align__(16) uint16_t sq[8 * kHeadDim];   // the group's query rows (zero rows past GQ), for the z-term product
 
     const int bh = blockIdx.y;
     if ((int)blockIdx.x == a.n_splits) { tail_partial<GQ>(a, bh, smem); return; }
@@ -631,8 +636,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_pipe(const DecodeArgs
     const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
     const int n_kgroups = QUANT ? a.n_kept / G : 0;
 
-    h2v qn[16], qpos[16];
+    if constexpr (QUANT) {
+        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += kThreads) {
+            const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
+            const uint32_t v = hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
+            reinterpret_cast<uint32_t*>(sq)[item] = v;
+        }
+        __syncthreads();
+    }
+    h2v qpos[16];
     {
+        h2v qn[16];
         const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + 32 * kb;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -660,7 +674,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_pipe(const DecodeArgs
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) bq[s].h[r] = part ? (h2v){0, 0} : qn[4 * s + r];   // 16-bit cache: plain q in the hi rows
+        for (int r = 0; r < 4; ++r) bq[s].h[r] = part ? (h2v){0, 0} : qpos[4 * s + r];   // 16-bit cache: plain q in the hi rows
 
     // ---- the two register sets (codes as MFMA operands; one dword per lane of every scale row) ----
     KWords<BITS> ak0, ak1, bk0, bk1;
@@ -794,8 +808,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_pipe(const DecodeArgs
 #pragma unroll
             for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lg[t][i]);
         mx = quad_rows_max(mx);
+        // The running maximum is only a scaling reference: it is moved (and O, l rescaled) when
+        // some row's maximum has grown by more than 2^kLazyLog2, so probabilities stay below that.
         const float m_new = fmaxf(m_run, mx);
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run + kLazyLog2) != 0ull) {
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             l_run *= alpha;
 #pragma unroll
@@ -889,14 +905,24 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attn_pipe(const DecodeArgs
         if constexpr (QUANT) {
 #pragma unroll
             for (int i = 0; i < NGRP; ++i) lds_put(OFF_KZ + 256 * i, a_kz[i]);
-            uint32_t zw[16];
+            uint32_t zw[16], qw[16];
             lds_get16(OFF_KZ + 256 * min(n, NGRP - 1) + 64 * kb, zw);
+            {
+                // re-read q every chunk rather than pinning 16 registers for the whole loop
+                const uint16_t* qrow = sq + h * kHeadDim + 32 * kb;
+                asm volatile("" : "+v"(qrow));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(qrow + 8 * i);
+                    qw[4 * i] = v.x; qw[4 * i + 1] = v.y; qw[4 * i + 2] = v.z; qw[4 * i + 3] = v.w;
+                }
+            }
             f4v zc = (f4v){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 Frag zf, qf;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) { zf.u[r] = (n < NGRP) ? zw[4 * s + r] : 0u; qf.h[r] = qn[4 * s + r]; }
+                for (int r = 0; r < 4; ++r) { zf.u[r] = (n < NGRP) ? zw[4 * s + r] : 0u; qf.u[r] = qw[4 * s + r]; }
                 zc = __builtin_amdgcn_mfma_f32_16x16x32_f16(zf.v, qf.v, zc, 0, 0, 0);
             }
             bias0 = quad_rows_add(zc[0]);                     // rows >= NGRP are zero, so the sum is a broadcast
