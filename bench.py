@@ -100,6 +100,8 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known size) so that profiler byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); use --gpus 1",
@@ -212,13 +214,19 @@ def main():
     # ---- roofline of the dominant kernel: the decode launch that takes most of the step ----
     dom = max(range(len(settings)), key=lambda i: settings[i]["t_decode_ms"])
     dom_s, dom_r = settings[dom], sweep[dom]
-    tag = f"decode_attn_splitk_{dom_s['bits']}bit_cfg2"
+    tag = f"decode_attn_pipe_{dom_s['bits']}bit_cfg2"
     roofline = {
-        "bound": "hbm", "kernel": f"decode_attn_splitk<{dom_s['bits']} bit> (+ decode_combine, same event window)",
+        "bound": "hbm", "kernel": f"decode_attn_pipe<{dom_s['bits']} bit> (+ decode_combine, same event window)",
         "achieved": dom_r["decode_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": round(dom_r["decode_gbs"] / PEAK_HBM_GBS, 4), "traffic": read_traffic_note(tag),
         "algorithmic_bytes_per_launch": dom_r["bytes_per_step"], "launch_us": dom_r["decode_us_per_step"],
     }
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -1,0 +1,125 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/kvqp.h declares, answers its size queries, and rejects bad
+arguments before anything could be launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2412_12706_amd import kvqp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(kvqp.LIB_PATH):
+        from paper_2412_12706_amd import build
+        build.build()
+    return kvqp.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "kvqp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvqp_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(kvqp.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_strerror(lib):
+    assert kvqp.version() >= 100
+    assert kvqp.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert kvqp.strerror(code) and kvqp.strerror(code) != kvqp.strerror(0)
+    assert "unknown" in kvqp.strerror(-99)
+
+
+def bpt(bits, G):
+    return 512 if bits == 16 else 2 * (128 * bits // 8 + 4 * 128 // G)
+
+
+@pytest.mark.parametrize("bits,G", [(2, 32), (2, 64), (4, 32), (4, 128), (8, 32), (16, 32)])
+def test_cache_sizes_match_bytes_per_token(lib, bits, G):
+    cfg = kvqp.Cfg(batch=3, n_q_heads=32, n_kv_heads=8, seq_len=4096 + 32, window=32, budget=1024, bits=bits, group_size=G)
+    sizes = kvqp.cache_sizes(cfg, tail_cap=40)
+    heads = 3 * 8
+    assert sum(sizes[:6]) == heads * 1024 * bpt(bits, G)
+    assert sizes[6] == sizes[7] == heads * 40 * 128 * 2
+    # 2-bit value codes are padded to 64-token superblocks
+    cfg2 = kvqp.Cfg(batch=1, n_q_heads=8, n_kv_heads=2, seq_len=1000, window=32, budget=96, bits=2, group_size=32)
+    s2 = kvqp.cache_sizes(cfg2, 32)
+    assert s2[0] == 2 * 96 * 128 * 2 // 8 and s2[1] == 2 * 128 * 128 * 2 // 8
+
+
+def test_workspace_sizes_are_positive_and_grow_with_the_problem(lib):
+    small = kvqp.Cfg(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024)
+    big = kvqp.Cfg(batch=32, n_q_heads=32, n_kv_heads=8, seq_len=32768, window=32, budget=8192)
+    (c0, d0), (c1, d1) = kvqp.workspace_bytes(small), kvqp.workspace_bytes(big)
+    assert 0 < c0 < c1 and 0 < d0 < d1
+
+
+BAD = [
+    (dict(bits=3), -1), (dict(bits=0), -1), (dict(group_size=48), -1), (dict(group_size=16), -2),
+    (dict(head_dim=64), -2), (dict(n_q_heads=30), -1), (dict(n_q_heads=8 * 16), -2), (dict(pool_kernel=4), -1),
+    (dict(pool_kernel=0), -1), (dict(window=0), -1), (dict(window=5000), -1), (dict(budget=-1), -1),
+    (dict(budget=1000), -1),            # not a multiple of the group size
+    (dict(key_axis=2), -1), (dict(batch=0), -1), (dict(window=128), -2), (dict(decode_splits=-1), -1),
+    (dict(sm_scale=float("nan")), -1),
+]
+
+
+@pytest.mark.parametrize("patch,code", BAD)
+def test_invalid_configurations_are_rejected_on_the_host(lib, patch, code):
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, seq_len=4096, window=32, pool_kernel=7, budget=1024,
+                bits=4, group_size=32, key_axis=0, decode_splits=0, sm_scale=0.088)
+    base.update(patch)
+    cfg = kvqp.Cfg(**base)
+    sizes = (C.c_size_t * 8)()
+    assert lib.kvqp_cache_sizes(C.byref(cfg.struct()), max(cfg.window, 1), sizes) == code
+
+
+def test_entry_points_reject_null_pointers_without_touching_the_device(lib):
+    cfg = kvqp.Cfg(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024)
+    cs = kvqp.CacheStruct()
+    st = cfg.struct()
+    assert lib.kvqp_compress(C.byref(st), None, None, None, C.byref(cs), None, None, 0, None) == -1
+    assert lib.kvqp_compress(None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.kvqp_quantize_selected(C.byref(st), None, None, None, 1024, C.byref(cs), None) == -1
+    assert lib.kvqp_decode_attn(C.byref(st), None, C.byref(cs), None, None, 0, None) == -1
+    # plausible non-null data pointers but cache buffers missing
+    fake = C.c_void_p(0x1000)
+    cs.tail_cap = 32
+    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, None, 0, None) == -1
+    # complete pointers, workspace missing -> workspace error, still nothing launched
+    for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
+        setattr(cs, name, 0x1000)
+    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, None, 0, None) == -3
+    cs.n_kept, cs.tail_len = 1024, 32
+    assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, None, 0, None) == -3
+    assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 16, None) == -3
+    cs.tail_len = 64                      # beyond tail_cap
+    assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1
+    cs.n_kept, cs.tail_len = 0, 0         # empty cache
+    assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1
+
+
+def test_binding_raises_with_the_library_message(lib):
+    cfg = kvqp.Cfg(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024, bits=5)
+    with pytest.raises(kvqp.KvqpError) as e:
+        kvqp.cache_sizes(cfg, 32)
+    assert "invalid argument" in str(e.value)
+
+
+def test_product_package_does_not_import_the_checker():
+    for root, _, files in os.walk(os.path.join(ROOT, "paper_2412_12706_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(root, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the checker"

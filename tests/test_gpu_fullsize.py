@@ -1,0 +1,93 @@
+"""Parity at the benchmark's full size and launch configuration: the
+Llama-3-8B-shaped workload (32 layers as the batch axis, 32 Q / 8 KV heads,
+L = 32768) compressed and decoded exactly as bench.py does, checked against
+the CPU checker on sampled (layer, KV head) slices of the very bytes the GPU
+used.  Sampling keeps the checker's share to a few seconds per slice."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_12706_amd import kvqp, synth
+
+pytestmark = pytest.mark.gpu
+
+LAYERS, HQ, HKV, D, L, W, POOL, G = 32, 32, 8, 128, 32768, 32, 7, 32
+GQ = HQ // HKV
+SAMPLES = [(0, 0), (13, 5), (31, 7)]
+
+
+@pytest.fixture(scope="module")
+def workload():
+    q_obs, k, v = synth.prompt_device(LAYERS, HQ, HKV, L, W, D, outlier=10.0, config=2, device="cuda:0")
+    return q_obs, k, v
+
+
+def head_bytes(cache, name, layer, g):
+    t = cache.buffers[name]
+    per = t.numel() // (LAYERS * HKV)
+    i = layer * HKV + g
+    return t[i * per:(i + 1) * per].cpu().numpy()
+
+
+@pytest.mark.parametrize("n_kept,bits", [(8192, 4), (16384, 2), (4096, 8), (2048, 16)])
+def test_full_size_compress_and_decode(orc, workload, n_kept, bits):
+    print(f"case tokens={n_kept} bits={bits}", flush=True)
+    q_obs, k, v = workload
+    sm = float(np.float32(D ** -0.5))
+    cfg = kvqp.Cfg(batch=LAYERS, n_q_heads=HQ, n_kv_heads=HKV, seq_len=L, window=W, pool_kernel=POOL, budget=n_kept,
+                   bits=bits, group_size=G, sm_scale=sm)
+    cache = kvqp.alloc_cache(cfg, device="cuda:0")
+    idx_dev = torch.empty((LAYERS, HKV, n_kept), dtype=torch.int32, device="cuda:0")
+    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev)
+    q = synth.decode_query_device(LAYERS, HQ, D, config=2, step=0, device="cuda:0")
+    out = kvqp.decode_attn(cfg, q, cache)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    idx_all = idx_dev.cpu().numpy()
+    assert np.all(np.diff(idx_all, axis=-1) > 0) and idx_all.min() >= 0 and idx_all.max() < L - W
+
+    for layer, g in SAMPLES:
+        print(f"  slice layer={layer} kv_head={g}", flush=True)
+        qs = q_obs[layer:layer + 1, g * GQ:(g + 1) * GQ].cpu().numpy()
+        ks = k[layer:layer + 1, g:g + 1].cpu().numpy()
+        vs = v[layer:layer + 1, g:g + 1].cpu().numpy()
+        oc, idx_ref, pooled = orc.compress(qs, ks, vs, window=W, pool=POOL, budget=n_kept, bits=bits, G=G, sm_scale=sm)
+        got = idx_all[layer, g]
+        if not np.array_equal(got, idx_ref[0, 0]):
+            kth = np.sort(pooled[0, 0])[-n_kept]
+            diff = np.setxor1d(got, idx_ref[0, 0])
+            rel = np.abs(pooled[0, 0][diff] - kth) / kth
+            assert np.all(rel <= 1e-6), f"{diff.size} indices differ, worst relative gap {rel.max():.3e}"
+            print(f"    {diff.size} index differences inside the 1e-6 tie band", flush=True)
+            oc = orc.quantize_selected(ks, vs, got.reshape(1, 1, -1), W=W, bits=bits, G=G)
+        for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
+            ref = np.ascontiguousarray(getattr(oc, name)).view(np.uint8).reshape(-1)
+            assert np.array_equal(head_bytes(cache, name, layer, g), ref), f"{name} differs at layer {layer}, head {g}"
+        qd = q[layer:layer + 1, g * GQ:(g + 1) * GQ].cpu().numpy()
+        ref = orc.decode_attn(qd, oc, sm)
+        err = np.abs(out[layer, g * GQ:(g + 1) * GQ].cpu().numpy().astype(np.float64) - ref[0]).max()
+        print(f"    decode max-abs error {err:.2e}", flush=True)
+        assert err <= 2e-3
+
+
+def test_per_layer_calls_agree_with_the_batched_call(workload):
+    """bench.py also issues the same work as 32 per-layer calls; both launch
+    shapes must give the same bytes."""
+    q_obs, k, v = workload
+    sm = float(np.float32(D ** -0.5))
+    cfg = kvqp.Cfg(batch=LAYERS, n_q_heads=HQ, n_kv_heads=HKV, seq_len=L, window=W, budget=8192, bits=4, group_size=G, sm_scale=sm)
+    cache = kvqp.alloc_cache(cfg, device="cuda:0")
+    kvqp.compress(cfg, q_obs, k, v, cache)
+    q = synth.decode_query_device(LAYERS, HQ, D, config=2, step=1, device="cuda:0")
+    out = kvqp.decode_attn(cfg, q, cache)
+    cfg1 = kvqp.Cfg(**{**cfg.__dict__, "batch": 1})
+    for layer in (0, 17, 31):
+        c1 = kvqp.alloc_cache(cfg1, device="cuda:0")
+        kvqp.compress(cfg1, q_obs[layer:layer + 1], k[layer:layer + 1], v[layer:layer + 1], c1)
+        for name, t in c1.buffers.items():
+            per = cache.buffers[name].numel() // LAYERS
+            assert torch.equal(t, cache.buffers[name][layer * per:(layer + 1) * per]), name
+        o1 = kvqp.decode_attn(cfg1, q[layer:layer + 1], c1)
+        # split counts differ between the two launch shapes, so sums are reassociated
+        assert (o1.float() - out[layer:layer + 1].float()).abs().max().item() <= 2e-3
+    torch.cuda.synchronize()
