@@ -203,12 +203,89 @@ struct DecodeArgs {
     const uint16_t* tail_k;
     const uint16_t* tail_v;
     float* part;              // [B*Hkv, n_partials, GQ, D+2]
+    uint16_t* out;            // [B, Hq, D]
     int n_kept, tail_len, tail_cap;
     int n_q_heads, n_kv_heads;
     int n_splits, chunks_per_split, n_partials;
     int group;                // G
     float sm_scale;
 };
+
+// Partials cross workgroups (and XCDs, whose L2 caches are not coherent with each other inside a
+// kernel) without device-wide fences, which would write back / invalidate whole L2s: they are
+// written and read with device-scope accesses that go to the coherence point directly.
+__device__ __forceinline__ void st_dev(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Arrival counters, one per (batch, kv head).  Every workgroup of a head bumps its counter after
+// its partial is written; the last one to arrive merges the head's partials and puts the counter
+// back to zero, so the array is all zeros again when the launch has drained (it starts that way:
+// static storage).  Launches that overlap in time on one device would share these counters.
+__device__ unsigned int g_arrivals[65536];
+
+// Merge the splits of one KV head's query heads and round once to binary16 (last workgroup only).
+template <int GQ>
+__device__ void merge_if_last(const DecodeArgs& a, int bh) {
+    __shared__ int s_last;
+    // this workgroup's partial stores (device scope, write-through) must have completed
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned prev = __hip_atomic_fetch_add(&g_arrivals[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = prev == (unsigned)(a.n_partials - 1);
+        if (last) __hip_atomic_store(&g_arrivals[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = last;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
+    const float* base = a.part + (size_t)bh * a.n_partials * GQ * kPartStride;
+    const size_t stride = (size_t)GQ * kPartStride;
+    // Device-scope loads are slow (they go to the coherence point) and are kept in program order,
+    // so many are put in flight per round trip: kMergeBatch partials of both of a thread's outputs.
+    constexpr int kMergeBatch = 12;
+    constexpr int ITEMS = (GQ * kHeadDim + kThreads - 1) / kThreads;
+    float M[ITEMS], acc[ITEMS], L[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) { M[it] = kNegBig; acc[it] = 0.f; L[it] = 0.f; }
+    for (int s0 = 0; s0 < a.n_partials; s0 += kMergeBatch) {
+        float m[ITEMS][kMergeBatch], l[ITEMS][kMergeBatch], o[ITEMS][kMergeBatch];
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
+            const int h = item / kHeadDim, d = item % kHeadDim;
+#pragma unroll
+            for (int u = 0; u < kMergeBatch; ++u) {
+                const float* q = base + (size_t)h * kPartStride + (size_t)min(s0 + u, a.n_partials - 1) * stride;
+                m[it][u] = ld_dev(q); l[it][u] = ld_dev(q + 1); o[it][u] = ld_dev(q + 2 + d);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            float Mn = M[it];
+#pragma unroll
+            for (int u = 0; u < kMergeBatch; ++u) Mn = fmaxf(Mn, m[it][u]);
+            const float keep = exp2f(M[it] - Mn);
+            acc[it] *= keep; L[it] *= keep;
+#pragma unroll
+            for (int u = 0; u < kMergeBatch; ++u) {
+                const float wgt = (s0 + u < a.n_partials) ? exp2f(m[it][u] - Mn) : 0.f;
+                acc[it] = __builtin_fmaf(wgt, o[it][u], acc[it]);
+                L[it] = __builtin_fmaf(wgt, l[it][u], L[it]);
+            }
+            M[it] = Mn;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int item = threadIdx.x + it * kThreads;
+        if (item < GQ * kHeadDim) {
+            const int h = item / kHeadDim, d = item % kHeadDim;
+            a.out[((size_t)b * a.n_q_heads + g * GQ + h) * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc[it] / L[it]));
+        }
+    }
+}
 
 // Full-precision tail rows: a short plain loop, one wave per row at a time.
 template <int GQ>
@@ -264,9 +341,10 @@ __device__ void tail_partial(const DecodeArgs& a, int bh, float* smem) {
             acc = __builtin_fmaf(wgt, row[2 + d], acc);
             L = __builtin_fmaf(wgt, row[1], L);
         }
-        dst[h * kPartStride + 2 + d] = acc;
-        if (d == 0) { dst[h * kPartStride] = M; dst[h * kPartStride + 1] = L; }
+        st_dev(dst + h * kPartStride + 2 + d, acc);
+        if (d == 0) { st_dev(dst + h * kPartStride, M); st_dev(dst + h * kPartStride + 1, L); }
     }
+    merge_if_last<GQ>(a, bh);
 }
 
 // BITS: code width; GQ: query heads per kv head (1,2,4 -> two token slots per
@@ -570,9 +648,10 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                 acc = __builtin_fmaf(wgt, o, acc);
                 L = __builtin_fmaf(wgt, st[1], L);
             }
-        dst[hh * kPartStride + 2 + d] = acc;
-        if (d == 0) { dst[hh * kPartStride] = M; dst[hh * kPartStride + 1] = L; }
+        st_dev(dst + hh * kPartStride + 2 + d, acc);
+        if (d == 0) { st_dev(dst + hh * kPartStride, M); st_dev(dst + hh * kPartStride + 1, L); }
     }
+    merge_if_last<GQ>(a, bh);
 }
 
 // ---------------------------------------------------------------------------
@@ -972,30 +1051,10 @@ __global__ __launch_bounds__(kThreads, KVQP_PIPE_WAVES) void decode_attn_pipe(co
                 acc = __builtin_fmaf(wgt, o, acc);
                 L = __builtin_fmaf(wgt, st[1], L);
             }
-        dst[hh * kPartStride + 2 + d] = acc;
-        if (d == 0) { dst[hh * kPartStride] = M; dst[hh * kPartStride + 1] = L; }
+        st_dev(dst + hh * kPartStride + 2 + d, acc);
+        if (d == 0) { st_dev(dst + hh * kPartStride, M); st_dev(dst + hh * kPartStride + 1, L); }
     }
-}
-
-// Merge the splits of one query head and round once to binary16.
-__global__ __launch_bounds__(kHeadDim) void decode_combine(const float* __restrict__ part, uint16_t* __restrict__ out,
-                                                           int n_partials, int gq, int n_kv_heads) {
-    const int bq = blockIdx.x;                 // b * Hq + hq
-    const int hq_per_b = gq * n_kv_heads;
-    const int b = bq / hq_per_b, hq = bq % hq_per_b;
-    const int bh = b * n_kv_heads + hq / gq, h = hq % gq;
-    const int d = threadIdx.x;
-    const float* base = part + (size_t)bh * n_partials * gq * kPartStride + (size_t)h * kPartStride;
-    const size_t stride = (size_t)gq * kPartStride;
-    float M = kNegBig;
-    for (int s = 0; s < n_partials; ++s) M = fmaxf(M, base[s * stride]);
-    float acc = 0.f, L = 0.f;
-    for (int s = 0; s < n_partials; ++s) {
-        const float wgt = exp2f(base[s * stride] - M);
-        acc = __builtin_fmaf(wgt, base[s * stride + 2 + d], acc);
-        L = __builtin_fmaf(wgt, base[s * stride + 1], L);
-    }
-    out[(size_t)bq * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc / L));
+    merge_if_last<GQ>(a, bh);
 }
 
 template <int BITS, int GQ, int NCG>
@@ -1035,7 +1094,9 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
     int splits = 0;
     if (n_chunks > 0) {
         splits = cfg.decode_splits > 0 ? cfg.decode_splits : (1024 + heads - 1) / heads;
-        const int max_splits = cfg.decode_splits > 0 ? n_chunks : (n_chunks + kWaves - 1) / kWaves;
+        // at least two 64-token chunks per wave: below that the fixed cost of a workgroup and of the
+        // split merge (device-scope round trips) outweighs the extra parallelism
+        const int max_splits = cfg.decode_splits > 0 ? n_chunks : (n_chunks + 2 * kWaves - 1) / (2 * kWaves);
         if (splits > max_splits) splits = max_splits;
         if (splits < 1) splits = 1;
     }
@@ -1056,6 +1117,7 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.v_scale = (const uint16_t*)c.v_scale; a.v_zero = (const uint16_t*)c.v_zero;
     a.tail_k = (const uint16_t*)c.tail_k; a.tail_v = (const uint16_t*)c.tail_v;
     a.part = (float*)ws;
+    a.out = (uint16_t*)out;
     a.n_kept = c.n_kept; a.tail_len = c.tail_len; a.tail_cap = c.tail_cap;
     a.n_q_heads = cfg.n_q_heads; a.n_kv_heads = cfg.n_kv_heads;
     a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;
@@ -1067,11 +1129,7 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
         case 8: e = launch_gq<8>(cfg, a, stream); break;
         default: e = launch_gq<16>(cfg, a, stream); break;
     }
-    if (e != hipSuccess) return e;
-    const int gq = cfg.n_q_heads / cfg.n_kv_heads;
-    hipLaunchKernelGGL(decode_combine, dim3(cfg.batch * cfg.n_q_heads), dim3(kHeadDim), 0, stream, (const float*)ws,
-                       (uint16_t*)out, plan.n_partials, gq, cfg.n_kv_heads);
-    return hipGetLastError();
+    return e;
 }
 
 }  // namespace kvqp
