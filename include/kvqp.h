@@ -69,7 +69,7 @@ typedef struct kvqp_cfg {
     int32_t group_size;   /* G; must divide D, and n_kept when keys are per channel      */
     int32_t key_axis;     /* KVQP_KEY_PER_CHANNEL or KVQP_KEY_PER_TOKEN                  */
     int32_t decode_splits;/* token-axis splits of decode attention; 0 = library chooses  */
-    float sm_scale;       /* logit scale, e.g. 1/sqrt(D) (Eq. (3) omits it)              */
+    float sm_scale;       /* logit scale > 0, e.g. 1/sqrt(D) (Eq. (3) omits it)          */
 } kvqp_cfg;
 
 /*

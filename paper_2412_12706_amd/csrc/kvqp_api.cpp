@@ -21,7 +21,7 @@ int check_common(const kvqp_cfg* c) {
     if (c->bits != 16) {
         if (c->group_size < 1 || c->head_dim % c->group_size) return KVQP_ERR_INVALID_ARG;
     }
-    if (!(c->sm_scale == c->sm_scale)) return KVQP_ERR_INVALID_ARG;
+    if (!(c->sm_scale > 0.0f) || c->sm_scale > 3.0e38f) return KVQP_ERR_INVALID_ARG;   /* positive and finite */
     const int gq = c->n_q_heads / c->n_kv_heads;
     if (c->head_dim != kHeadDim) return KVQP_ERR_UNSUPPORTED;
     if (!(gq == 1 || gq == 2 || gq == 4 || gq == 8)) return KVQP_ERR_UNSUPPORTED;

@@ -112,17 +112,28 @@ __global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
 
     const int c_begin = blockIdx.x * a.chunks_per_wg;
     const int c_end = min(a.n_chunks, c_begin + a.chunks_per_wg);
+
+    // The chunk after the one being computed is already on its way from HBM into registers;
+    // it is parked in LDS only when every wave has finished reading the current one.
+    constexpr int NPRE = CK * 16 / kThreads;
+    typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+    u4v pre[NPRE];
+    const int pre_row = threadIdx.x >> 4, pre_col = threadIdx.x & 15;   // item i of a thread: key row pre_row + 16 i
+#define KVQP_ISSUE(chunk_)                                                                             \
+    _Pragma("unroll") for (int i_ = 0; i_ < NPRE; ++i_) {                                              \
+        const int key_ = min((chunk_) * CK + pre_row + 16 * i_, a.L - 1); /* rows past the end are masked */ \
+        pre[i_] = *reinterpret_cast<const u4v*>(kh + (size_t)key_ * kHeadDim + pre_col * 8);        \
+    }
+#define KVQP_COMMIT()                                                                                  \
+    _Pragma("unroll") for (int i_ = 0; i_ < NPRE; ++i_)                                                \
+        *reinterpret_cast<u4v*>(sk + (pre_row + 16 * i_) * kKeyStride + pre_col * 16) = pre[i_];
+    KVQP_ISSUE(min(c_begin, a.n_chunks - 1))
+    KVQP_COMMIT()
+    __syncthreads();
+
     for (int chunk = c_begin; chunk < c_end; ++chunk) {
         const int key0 = chunk * CK;
-        __syncthreads();  // previous chunk fully consumed
-        // cooperative, coalesced copy of the chunk's keys into LDS (zero past the end)
-        for (int item = threadIdx.x; item < CK * 16; item += kThreads) {
-            const int kr = item >> 4, c = item & 15;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (key0 + kr < a.L) v = *reinterpret_cast<const uint4*>(kh + (size_t)(key0 + kr) * kHeadDim + c * 8);
-            *reinterpret_cast<uint4*>(sk + kr * kKeyStride + c * 16) = v;
-        }
-        __syncthreads();
+        KVQP_ISSUE(min(chunk + 1, c_end - 1))
 
         f4v acc[kMT][KT];
 #pragma unroll
@@ -139,35 +150,34 @@ __global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
                 acc[mt][kt] = c;
             }
         }
-        // log2-domain logits; causal mask only where the chunk reaches the window
-        const bool need_mask = key0 + CK > a.P;
+        // causal mask only where the chunk reaches the window (raw scores; the scale is positive)
+        if (key0 + CK > a.P) {
 #pragma unroll
-        for (int mt = 0; mt < kMT; ++mt)
+            for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
+                for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float s = acc[mt][kt][i] * a.scale_log2;
-                    if (need_mask) {
+                    for (int i = 0; i < 4; ++i) {
                         const int key = key0 + 16 * (ks * KT + kt) + n;
-                        if (key > a.P + wrow[mt][i] || key >= a.L) s = -INFINITY;
+                        if (key > a.P + wrow[mt][i] || key >= a.L) acc[mt][kt][i] = -INFINITY;
                     }
-                    acc[mt][kt][i] = s;
-                }
+        }
 
         if (PASS == PASS_STATS) {
 #pragma unroll
             for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float mx = m_run[mt][i];
+                    float raw = acc[mt][0][i];
 #pragma unroll
-                    for (int kt = 0; kt < KT; ++kt) mx = fmaxf(mx, acc[mt][kt][i]);
+                    for (int kt = 1; kt < KT; ++kt) raw = fmaxf(raw, acc[mt][kt][i]);
+                    const float mx = fmaxf(m_run[mt][i], raw * a.scale_log2);   // log2-domain running maximum
                     float z = z_run[mt][i] * __builtin_amdgcn_exp2f(m_run[mt][i] - mx);
 #pragma unroll
-                    for (int kt = 0; kt < KT; ++kt) z += __builtin_amdgcn_exp2f(acc[mt][kt][i] - mx);
+                    for (int kt = 0; kt < KT; ++kt) z += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[mt][kt][i], a.scale_log2, -mx));
                     m_run[mt][i] = mx; z_run[mt][i] = z;
                 }
+            __syncthreads();                 // all waves are done with this chunk's keys
         } else {
             // normalised probabilities summed over this wave's 64 rows, per key
 #pragma unroll
@@ -177,13 +187,14 @@ __global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
                 for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        col = __builtin_fmaf(__builtin_amdgcn_exp2f(acc[mt][kt][i] - m_run[mt][i]), z_run[mt][i], col);
+                        col = __builtin_fmaf(__builtin_amdgcn_exp2f(__builtin_fmaf(acc[mt][kt][i], a.scale_log2, -m_run[mt][i])),
+                                             z_run[mt][i], col);
                 // rows 4kb+i of all four lane quads
                 col += __shfl_xor(col, 16);
                 col += __shfl_xor(col, 32);
                 if (kb == 0) svote[rw * CK + 16 * (ks * KT + kt) + n] = col;
             }
-            __syncthreads();
+            __syncthreads();                 // votes of all row slabs parked; keys of this chunk consumed
             for (int kk = threadIdx.x; kk < CK; kk += kThreads) {
                 float v = 0.f;
 #pragma unroll
@@ -191,7 +202,11 @@ __global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
                 if (key0 + kk < a.P) a.vote[(size_t)head * a.P + key0 + kk] = v;
             }
         }
+        KVQP_COMMIT()
+        __syncthreads();
     }
+#undef KVQP_ISSUE
+#undef KVQP_COMMIT
 
     if (PASS == PASS_STATS) {
         // merge the 16 key columns a row is spread over, then one lane per row writes
