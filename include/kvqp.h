@@ -54,7 +54,8 @@ extern "C" {
  * and pool_kernel belong to the attention-score pruning rule below).
  * Supported in this build: head_dim == 128; n_q_heads / n_kv_heads in
  * {1,2,4,8}; bits in {2,4,8,16}; group_size in {32,64,128};
- * window * (n_q_heads/n_kv_heads) <= 256; pool_kernel odd, <= 63.
+ * window * (n_q_heads/n_kv_heads) <= 256; pool_kernel odd, <= 63;
+ * seq_len - window <= 131072.
  */
 typedef struct kvqp_cfg {
     int32_t batch;        /* number of independent caches                                */
@@ -142,7 +143,7 @@ int kvqp_workspace_bytes(const kvqp_cfg *cfg, size_t *compress_bytes, size_t *de
  *   pooled scores are kept, equal scores going to the lower position, and the
  *   survivors are stored in ascending position.
  *   Scores are evaluated in binary32 on the matrix cores; candidates whose
- *   pooled score lies within a relative 1e-4 of the cut are re-scored in
+ *   pooled score lies within a relative 2e-5 of the cut are re-scored in
  *   binary64 before the cut is made.
  * The survivors are then quantized as described at kvqp_cache.
  *
@@ -177,6 +178,9 @@ int kvqp_quantize_selected(const kvqp_cfg *cfg, const void *k, const void *v, co
  *   out half [batch, Hq, D]   binary32 accumulation, rounded once at the end
  * cfg fields used: batch, heads, head_dim, bits, group_size, key_axis,
  * decode_splits, sm_scale.  n_kept + tail_len must be >= 1.
+ * Calls of kvqp_decode_attn must not overlap in time on one device: the merge of the
+ * token-axis splits uses device-wide arrival counters owned by the library (calls
+ * issued on one stream never overlap).
  */
 int kvqp_decode_attn(const kvqp_cfg *cfg, const void *q, const kvqp_cache *cache, void *out,
                      void *workspace, size_t workspace_bytes, void *hip_stream);

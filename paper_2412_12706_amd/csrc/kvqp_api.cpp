@@ -37,6 +37,7 @@ int check_prompt(const kvqp_cfg* c) {
     if (c->budget < 0) return KVQP_ERR_INVALID_ARG;
     const int gq = c->n_q_heads / c->n_kv_heads;
     if (c->window * gq > 256 || c->pool_kernel > 63) return KVQP_ERR_UNSUPPORTED;
+    if (c->seq_len - c->window > 131072) return KVQP_ERR_UNSUPPORTED;   // selection sweeps at most 128 rows of 1024 candidates
     return KVQP_OK;
 }
 

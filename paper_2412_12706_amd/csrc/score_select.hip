@@ -255,6 +255,8 @@ __global__ void stats_combine(const float2* __restrict__ part, float2* __restric
 // stays in L2.
 // ---------------------------------------------------------------------------
 constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kMaxRows = 128;         // rows of 1024 candidates: prefixes up to 131072 tokens
 constexpr int kMaxBand = 512;         // candidates re-scored per head; beyond that binary32 decides
 constexpr float kBandRel = 1.0e-4f;
 
@@ -273,41 +275,56 @@ struct SelectArgs {
 
 __device__ __forceinline__ uint32_t score_key(float v) { return __float_as_uint(v); }  // scores are >= 0: bits order like values
 
-// Block-wide exclusive scan of one int per thread (kSelThreads threads).
-__device__ int block_exclusive_scan(int v, int* total, int* swarp) {
+// Exclusive scan, in place, of a table of n <= 2 * kSelThreads ints in LDS; returns the total.
+__device__ int scan_table(int* tab, int n, int* swave) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    int inc = v;
+    const int e0 = 2 * threadIdx.x, e1 = e0 + 1;
+    const int v0 = e0 < n ? tab[e0] : 0, v1 = e1 < n ? tab[e1] : 0;
+    int inc = v0 + v1;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         const int o = __shfl_up(inc, off);
         if (lane >= off) inc += o;
     }
     __syncthreads();
-    if (lane == 63) swarp[w] = inc;
+    if (lane == 63) swave[w] = inc;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int i = 0; i < kSelThreads / 64; ++i) { const int t = swarp[i]; swarp[i] = run; run += t; }
-        swarp[kSelThreads / 64] = run;
+    int base = 0, total = 0;
+#pragma unroll
+    for (int i = 0; i < kSelWaves; ++i) {
+        const int t = swave[i];
+        if (i < w) base += t;
+        total += t;
     }
+    const int excl = base + inc - (v0 + v1);
+    if (e0 < n) tab[e0] = excl;
+    if (e1 < n) tab[e1] = excl + v0;
     __syncthreads();
-    *total = swarp[kSelThreads / 64];
-    return swarp[w] + inc - v;
+    return total;
 }
 
-// binary64 vote of one prefix key: sum over the group's window rows of
+// binary64 vote of one prefix key, computed by one wave: sum over the group's window rows of
 // exp2(logit - m_r) / Z_r with exact products and the pass-1 statistics.
 __device__ double vote_f64(const SelectArgs& a, int head, int key) {
     const int b = head / a.n_kv_heads, g = head % a.n_kv_heads;
-    const uint16_t* kr = a.k + ((size_t)head * a.L + key) * kHeadDim;
+    const uint4* kr = reinterpret_cast<const uint4*>(a.k + ((size_t)head * a.L + key) * kHeadDim);
     const int lane = threadIdx.x & 63;
     double acc = 0.0;
     for (int r = lane; r < a.rows; r += 64) {
         const int hl = r / a.W, i = r % a.W;
-        const uint16_t* qr = a.q_obs + (((size_t)b * a.n_q_heads + g * a.gq + hl) * a.W + i) * kHeadDim;
+        const uint4* qr = reinterpret_cast<const uint4*>(a.q_obs + (((size_t)b * a.n_q_heads + g * a.gq + hl) * a.W + i) * kHeadDim);
         double s = 0.0;
-        for (int d = 0; d < kHeadDim; ++d)
-            s += (double)__half2float(__ushort_as_half(qr[d])) * (double)__half2float(__ushort_as_half(kr[d]));
+        for (int c = 0; c < kHeadDim / 8; ++c) {
+            const uint4 qv = qr[c], kv = kr[c];
+            const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w}, kw[4] = {kv.x, kv.y, kv.z, kv.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                s += (double)__half2float(__ushort_as_half((uint16_t)(qw[e] & 0xffff))) *
+                     (double)__half2float(__ushort_as_half((uint16_t)(kw[e] & 0xffff)));
+                s += (double)__half2float(__ushort_as_half((uint16_t)(qw[e] >> 16))) *
+                     (double)__half2float(__ushort_as_half((uint16_t)(kw[e] >> 16)));
+            }
+        }
         const double m = (double)a.stats[(size_t)head * a.rows_pad + r].x;
         acc += exp2(s * ((double)a.sm_scale * 1.4426950408889634074) - m) / a.zsum[(size_t)head * a.rows_pad + r];
     }
@@ -316,28 +333,38 @@ __device__ double vote_f64(const SelectArgs& a, int head, int key) {
     return acc;
 }
 
+// One workgroup per (batch, kv head).  Candidate j lives at (row j / 1024, thread j % 1024), so
+// every sweep is coalesced and "position order" is (row, wave, lane): ordered compaction needs only
+// per-(row, wave) counts (one ballot each), one table scan, and a popcount below the lane.
 __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
-    __shared__ int hist[256];
-    __shared__ int swarp[kSelThreads / 64 + 1];
-    __shared__ uint32_t s_prefix;
-    __shared__ int s_need, s_nband, s_sure;
+    __shared__ int hist[kSelWaves][256];
+    __shared__ int tab_a[kMaxRows * kSelWaves];   // per (row, wave): survivors that need no second look
+    __shared__ int tab_b[kMaxRows * kSelWaves];   // per (row, wave): band members (or ties at the cut)
+    __shared__ int swave[kSelWaves];
+    __shared__ uint32_t s_red[2 * kSelWaves];
+    __shared__ uint32_t s_prefix, s_kmin;
+    __shared__ int s_need;
     __shared__ int band_idx[kMaxBand];
     __shared__ double band_score[kMaxBand];
-    __shared__ unsigned char band_take[kMaxBand];
+    __shared__ int band_take[kMaxBand + 1];       // after the scan: taken band members before position c
 
     const int head = blockIdx.x;
     const int P = a.P, k = a.n_kept;
     const float* vote = a.vote + (size_t)head * P;
     float* pooled = a.pooled + (size_t)head * P;
     int32_t* idx = a.idx + (size_t)head * k;
-    const int r = (a.pool - 1) / 2;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n_rows = (P + kSelThreads - 1) / kSelThreads;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
     if (k >= P) {  // budget covers the prefix: identity, no scores were computed
         for (int j = threadIdx.x; j < k; j += kSelThreads) idx[j] = j;
         return;
     }
 
-    // ---- max-pool, clipped at both ends ----
+    // ---- max-pool (clipped at both ends) and the range of the pooled scores ----
+    const int r = (a.pool - 1) / 2;
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
     for (int j = threadIdx.x; j < P; j += kSelThreads) {
         float best = vote[j];
         for (int t = 1; t <= r; ++t) {
@@ -345,71 +372,104 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
             if (j + t < P) best = fmaxf(best, vote[j + t]);
         }
         pooled[j] = best;
+        kmin = min(kmin, score_key(best)); kmax = max(kmax, score_key(best));
     }
-    __syncthreads();
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off));
+    }
+    if (lane == 0) { s_red[wave] = kmin; s_red[kSelWaves + wave] = kmax; }
+    __syncthreads();   // also orders the pooled[] writes before the sweeps below (same workgroup)
+    kmin = s_red[0]; kmax = s_red[kSelWaves];
+#pragma unroll
+    for (int i = 1; i < kSelWaves; ++i) { kmin = min(kmin, s_red[i]); kmax = max(kmax, s_red[kSelWaves + i]); }
 
-    // ---- radix select: bit pattern of the k-th largest pooled score ----
+    // ---- radix select of the k-th largest score, on keys relative to the minimum so that the
+    // digits that all candidates share (sign, exponent) do not pile into one histogram bin ----
+    const uint32_t span = kmax - kmin;
+    int top_shift = 24;
+    while (top_shift > 0 && (span >> top_shift) == 0) top_shift -= 8;
     if (threadIdx.x == 0) { s_prefix = 0u; s_need = k; }
-    __syncthreads();
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+    for (int shift = top_shift; shift >= 0; shift -= 8) {
+        for (int i = threadIdx.x; i < kSelWaves * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
         __syncthreads();
         const uint32_t prefix = s_prefix;
+        const int need = s_need;
         const uint32_t himask = (shift == 24) ? 0u : (0xffffffffu << (shift + 8));
         for (int j = threadIdx.x; j < P; j += kSelThreads) {
-            const uint32_t key = score_key(pooled[j]);
-            if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
+            const uint32_t key = score_key(pooled[j]) - kmin;
+            if ((key & himask) == prefix) atomicAdd(&hist[wave][(key >> shift) & 255], 1);
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            int need = s_need, bin = 255;
-            for (; bin > 0; --bin) {
-                if (hist[bin] >= need) break;
-                need -= hist[bin];
+        // bins summed over the waves, then "how many candidates in bins above mine" per bin
+        if (wave < 4) {
+            const int bin = threadIdx.x;                  // 256 threads, one bin each
+            int c = 0;
+#pragma unroll
+            for (int w = 0; w < kSelWaves; ++w) c += hist[w][bin];
+            // suffix sum within the wave (bins descend with rank), then across the four waves
+            int suf = c;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int o = __shfl_down(suf, off);
+                if (lane + off < 64) suf += o;
             }
-            s_need = need;                      // how many of this bin (and, at the end, of the cut value) are taken
-            s_prefix = prefix | ((uint32_t)bin << shift);
+            if (lane == 0) swave[wave] = suf;             // total of this wave's 64 bins
+            hist[0][bin] = c;                             // (own column only: no other thread reads hist[0][bin])
+            tab_a[bin] = suf;
+        }
+        __syncthreads();
+        if (wave < 4) {
+            const int bin = threadIdx.x;
+            int above = tab_a[bin] - hist[0][bin];        // candidates in higher bins of this wave's 64
+            for (int w = wave + 1; w < 4; ++w) above += swave[w];
+            if (above < need && above + hist[0][bin] >= need) {   // exactly one bin satisfies this
+                s_need = need - above;
+                s_prefix = prefix | ((uint32_t)bin << shift);
+            }
         }
         __syncthreads();
     }
-    const float cut = __uint_as_float(s_prefix);
+    const float cut = __uint_as_float(s_prefix + kmin);
+    const int need_at_cut = s_need;   // how many candidates equal to the cut are taken (binary32 rule)
     // band of scores that binary32 rounding could move across the cut
     const float lo = cut * (1.0f - kBandRel), hi = cut * (1.0f + kBandRel);
 
-    // ---- collect the band (position order) and count the sure survivors ----
-    int my_band = 0, my_sure = 0;
-    const int per = (P + kSelThreads - 1) / kSelThreads;
-    const int j0 = threadIdx.x * per, j1 = min(P, j0 + per);
-    for (int j = j0; j < j1; ++j) {
-        const float v = pooled[j];
-        my_sure += (v > hi);
-        my_band += (v >= lo && v <= hi);
-    }
-    int tot_band, tot_sure;
-    const int band_off = block_exclusive_scan(my_band, &tot_band, swarp);
-    (void)block_exclusive_scan(my_sure, &tot_sure, swarp);
-    const bool refine = tot_band <= kMaxBand;
-    if (refine) {
-        int o = band_off;
-        for (int j = j0; j < j1; ++j) {
-            const float v = pooled[j];
-            if (v >= lo && v <= hi) band_idx[o++] = j;
-        }
+    // ---- per-(row, wave) counts: sure survivors (> hi) and band members ----
+    for (int row = 0; row < n_rows; ++row) {
+        const int j = row * kSelThreads + threadIdx.x;
+        const float v = j < P ? pooled[j] : -1.0f;
+        const unsigned long long bs = __builtin_amdgcn_ballot_w64(v > hi);
+        const unsigned long long bb = __builtin_amdgcn_ballot_w64(v >= lo && v <= hi);
+        if (lane == 0) { tab_a[row * kSelWaves + wave] = __popcll(bs); tab_b[row * kSelWaves + wave] = __popcll(bb); }
     }
     __syncthreads();
+    const int tot_sure = scan_table(tab_a, n_rows * kSelWaves, swave);
+    const int tot_band = scan_table(tab_b, n_rows * kSelWaves, swave);
+    const bool refine = tot_band <= kMaxBand;
 
     if (refine) {
-        // ---- binary64 re-scoring of the band: one wave per candidate ----
-        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-        for (int c = wave; c < tot_band; c += kSelThreads / 64) {
-            const int j = band_idx[c];
-            double best = -1.0;
-            for (int t = -r; t <= r; ++t) {
-                if (j + t < 0 || j + t >= P) continue;
-                const double v = vote_f64(a, head, j + t);
-                best = v > best ? v : best;
-            }
-            if (lane == 0) band_score[c] = best;
+        // ---- band members in position order ----
+        for (int row = 0; row < n_rows; ++row) {
+            const int j = row * kSelThreads + threadIdx.x;
+            const float v = j < P ? pooled[j] : -1.0f;
+            const bool inb = v >= lo && v <= hi;
+            const unsigned long long bb = __builtin_amdgcn_ballot_w64(inb);
+            if (inb) band_idx[tab_b[row * kSelWaves + wave] + __popcll(bb & lt_mask)] = j;
+        }
+        __syncthreads();
+        // ---- binary64 re-scoring: one wave per (band member, pool offset) ----
+        const int width = 2 * r + 1;
+        for (int c = threadIdx.x; c < tot_band; c += kSelThreads) band_score[c] = 0.0;   // votes are >= 0
+        __syncthreads();
+        for (int item = wave; item < tot_band * width; item += kSelWaves) {
+            const int c = item / width, t = item % width - r;
+            const int j = band_idx[c] + t;
+            if (j < 0 || j >= P) continue;
+            const double v = vote_f64(a, head, j);
+            // several waves may hold offsets of the same member: combine with an order-free maximum
+            if (lane == 0) atomicMax(reinterpret_cast<unsigned long long*>(&band_score[c]), (unsigned long long)__double_as_longlong(v));
         }
         __syncthreads();
         // rank inside the band by (score desc, position asc); band_idx is ascending
@@ -421,51 +481,48 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
             band_take[c] = rank < take;
         }
         __syncthreads();
-    }
-
-    // ---- ordered compaction ----
-    int my_keep = 0;
-    if (refine) {
-        int bo = band_off;
-        for (int j = j0; j < j1; ++j) {
-            const float v = pooled[j];
-            if (v > hi) ++my_keep;
-            else if (v >= lo) my_keep += band_take[bo++];
+        if (threadIdx.x == 0) {   // exclusive prefix over at most 512 flags
+            int run = 0;
+            for (int c = 0; c < tot_band; ++c) { const int t = band_take[c]; band_take[c] = run; run += t; }
+            band_take[tot_band] = run;
+        }
+        __syncthreads();
+        // ---- ordered compaction ----
+        for (int row = 0; row < n_rows; ++row) {
+            const int j = row * kSelThreads + threadIdx.x;
+            const float v = j < P ? pooled[j] : -1.0f;
+            const bool sure = v > hi, inb = v >= lo && v <= hi;
+            const unsigned long long bs = __builtin_amdgcn_ballot_w64(sure);
+            const unsigned long long bb = __builtin_amdgcn_ballot_w64(inb);
+            const int sure_before = tab_a[row * kSelWaves + wave] + __popcll(bs & lt_mask);
+            const int band_before = tab_b[row * kSelWaves + wave] + __popcll(bb & lt_mask);
+            bool keep = sure;
+            if (inb) keep = band_take[band_before + 1] > band_take[band_before];
+            if (keep) idx[sure_before + band_take[band_before]] = j;
         }
     } else {
-        // binary32 decides: everything above the cut, then the first s_need equal to it
-        int my_eq = 0;
-        for (int j = j0; j < j1; ++j) my_eq += (pooled[j] == cut);
-        int tot_eq;
-        int eq_off = block_exclusive_scan(my_eq, &tot_eq, swarp);
-        const int need = s_need;
-        for (int j = j0; j < j1; ++j) {
-            const float v = pooled[j];
-            if (v > cut) ++my_keep;
-            else if (v == cut) my_keep += (eq_off++ < need);
+        // binary32 decides: everything above the cut, then the first need_at_cut equal to it
+        __syncthreads();
+        for (int row = 0; row < n_rows; ++row) {
+            const int j = row * kSelThreads + threadIdx.x;
+            const float v = j < P ? pooled[j] : -1.0f;
+            const unsigned long long bs = __builtin_amdgcn_ballot_w64(v > cut);
+            const unsigned long long bb = __builtin_amdgcn_ballot_w64(v == cut);
+            if (lane == 0) { tab_a[row * kSelWaves + wave] = __popcll(bs); tab_b[row * kSelWaves + wave] = __popcll(bb); }
         }
-    }
-    int tot_keep;
-    int out = block_exclusive_scan(my_keep, &tot_keep, swarp);
-    if (refine) {
-        int bo = band_off;
-        for (int j = j0; j < j1; ++j) {
-            const float v = pooled[j];
-            bool keep = v > hi;
-            if (!keep && v >= lo) keep = band_take[bo++];
-            if (keep && out < k) idx[out++] = j;
-        }
-    } else {
-        int my_eq = 0;
-        for (int j = j0; j < j1; ++j) my_eq += (pooled[j] == cut);
-        int tot_eq;
-        int eq_off = block_exclusive_scan(my_eq, &tot_eq, swarp);
-        const int need = s_need;
-        for (int j = j0; j < j1; ++j) {
-            const float v = pooled[j];
-            bool keep = v > cut;
-            if (!keep && v == cut) keep = (eq_off++ < need);
-            if (keep && out < k) idx[out++] = j;
+        __syncthreads();
+        (void)scan_table(tab_a, n_rows * kSelWaves, swave);
+        (void)scan_table(tab_b, n_rows * kSelWaves, swave);
+        for (int row = 0; row < n_rows; ++row) {
+            const int j = row * kSelThreads + threadIdx.x;
+            const float v = j < P ? pooled[j] : -1.0f;
+            const bool above = v > cut, eq = v == cut;
+            const unsigned long long bs = __builtin_amdgcn_ballot_w64(above);
+            const unsigned long long bb = __builtin_amdgcn_ballot_w64(eq);
+            const int above_before = tab_a[row * kSelWaves + wave] + __popcll(bs & lt_mask);
+            const int eq_before = tab_b[row * kSelWaves + wave] + __popcll(bb & lt_mask);
+            if (above) idx[above_before + min(eq_before, need_at_cut)] = j;
+            else if (eq && eq_before < need_at_cut) idx[above_before + eq_before] = j;
         }
     }
 }
