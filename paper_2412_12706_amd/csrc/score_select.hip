@@ -257,8 +257,12 @@ __global__ void stats_combine(const float2* __restrict__ part, float2* __restric
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxRows = 128;         // rows of 1024 candidates: prefixes up to 131072 tokens
-constexpr int kMaxBand = 512;         // candidates re-scored per head; beyond that binary32 decides
-constexpr float kBandRel = 1.0e-4f;
+constexpr int kRegRows = 32;          // rows whose pooled scores stay in registers (prefixes up to 32768)
+constexpr int kMaxBand = 256;         // candidates re-scored per head; beyond that binary32 decides
+constexpr int kVoteSlots = 2048;       // binary64 partial votes held in LDS during the re-scoring
+constexpr int kStageRows = 4;          // rows of votes staged in LDS per pooling step
+constexpr int kMaxPoolRadius = 31;     // pool_kernel <= 63
+constexpr float kBandRel = 2.0e-5f;   // >> the binary32 error of a vote (a few 1e-7 relative)
 
 struct SelectArgs {
     const float* vote;      // [heads, P]
@@ -303,50 +307,82 @@ __device__ int scan_table(int* tab, int n, int* swave) {
     return total;
 }
 
-// binary64 vote of one prefix key, computed by one wave: sum over the group's window rows of
-// exp2(logit - m_r) / Z_r with exact products and the pass-1 statistics.
-__device__ double vote_f64(const SelectArgs& a, int head, int key) {
+__device__ __forceinline__ float half_lo(uint32_t w) { return __half2float(__ushort_as_half((uint16_t)(w & 0xffffu))); }
+__device__ __forceinline__ float half_hi(uint32_t w) { return __half2float(__ushort_as_half((uint16_t)(w >> 16))); }
+
+// Part of the binary64 vote of one prefix key, computed by one wave: the sum over 32 of the group's
+// window rows (row_base + lane/2; the two lanes of a row split the channels) of
+// exp2(logit - m_r) / Z_r with the pass-1 statistics.  A product of two binary16 values is exact in
+// binary32; the products are summed in binary64.
+__device__ double vote_f64_part(const SelectArgs& a, int head, int key, int row_base) {
     const int b = head / a.n_kv_heads, g = head % a.n_kv_heads;
-    const uint4* kr = reinterpret_cast<const uint4*>(a.k + ((size_t)head * a.L + key) * kHeadDim);
-    const int lane = threadIdx.x & 63;
-    double acc = 0.0;
-    for (int r = lane; r < a.rows; r += 64) {
-        const int hl = r / a.W, i = r % a.W;
-        const uint4* qr = reinterpret_cast<const uint4*>(a.q_obs + (((size_t)b * a.n_q_heads + g * a.gq + hl) * a.W + i) * kHeadDim);
-        double s = 0.0;
-        for (int c = 0; c < kHeadDim / 8; ++c) {
-            const uint4 qv = qr[c], kv = kr[c];
-            const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w}, kw[4] = {kv.x, kv.y, kv.z, kv.w};
+    const int lane = threadIdx.x & 63, half = lane & 1;
+    const int r = row_base + (lane >> 1);
+    const bool live = r < a.rows;
+    const int rc = live ? r : 0;
+    const int hl = rc / a.W, i = rc % a.W;
+    const uint4* kr = reinterpret_cast<const uint4*>(a.k + ((size_t)head * a.L + key) * kHeadDim) + 8 * half;
+    const uint4* qr = reinterpret_cast<const uint4*>(a.q_obs + (((size_t)b * a.n_q_heads + g * a.gq + hl) * a.W + i) * kHeadDim) + 8 * half;
+    const double m = (double)a.stats[(size_t)head * a.rows_pad + rc].x;
+    const double z = a.zsum[(size_t)head * a.rows_pad + rc];
+    double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+    for (int c0 = 0; c0 < 8; c0 += 4) {
+        uint4 qv[4], kv[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { qv[c] = qr[c0 + c]; kv[c] = kr[c0 + c]; }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t qw[4] = {qv[c].x, qv[c].y, qv[c].z, qv[c].w}, kw[4] = {kv[c].x, kv[c].y, kv[c].z, kv[c].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                s += (double)__half2float(__ushort_as_half((uint16_t)(qw[e] & 0xffff))) *
-                     (double)__half2float(__ushort_as_half((uint16_t)(kw[e] & 0xffff)));
-                s += (double)__half2float(__ushort_as_half((uint16_t)(qw[e] >> 16))) *
-                     (double)__half2float(__ushort_as_half((uint16_t)(kw[e] >> 16)));
+                s0 += (double)(half_lo(qw[e]) * half_lo(kw[e]));
+                s1 += (double)(half_hi(qw[e]) * half_hi(kw[e]));
             }
         }
-        const double m = (double)a.stats[(size_t)head * a.rows_pad + r].x;
-        acc += exp2(s * ((double)a.sm_scale * 1.4426950408889634074) - m) / a.zsum[(size_t)head * a.rows_pad + r];
     }
+    double s = s0 + s1;
+    s += __shfl_xor(s, 1);
+    double acc = (live && half == 0) ? exp2(s * ((double)a.sm_scale * 1.4426950408889634074) - m) / z : 0.0;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    for (int off = 32; off >= 2; off >>= 1) acc += __shfl_xor(acc, off);
     return acc;
 }
 
+// Visit every candidate of this thread: j = row * 1024 + thread, v = its pooled score (-1 past the
+// end).  The first kRegRows rows come from registers, the rest from the pooled array.
+#define KVQP_FOR_ROWS(...)                                                            \
+    _Pragma("unroll") for (int row = 0; row < kRegRows; ++row) {                      \
+        if (row < n_rows) {                                                           \
+            const int j = row * kSelThreads + (int)threadIdx.x;                       \
+            const float v = pv[row];                                                  \
+            __VA_ARGS__                                                               \
+        }                                                                             \
+    }                                                                                 \
+    for (int row = kRegRows; row < n_rows; ++row) {                                   \
+        const int j = row * kSelThreads + (int)threadIdx.x;                           \
+        const float v = j < P ? pooled[j] : -1.0f;                                    \
+        __VA_ARGS__                                                                   \
+    }
+
 // One workgroup per (batch, kv head).  Candidate j lives at (row j / 1024, thread j % 1024), so
 // every sweep is coalesced and "position order" is (row, wave, lane): ordered compaction needs only
-// per-(row, wave) counts (one ballot each), one table scan, and a popcount below the lane.
+// per-(row, wave) counts (one ballot each), one table scan, and a popcount below the lane.  The
+// pooled scores of prefixes up to 32768 tokens never leave the registers.
 __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
-    __shared__ int hist[kSelWaves][256];
+    __shared__ __align__(16) int hist[kSelWaves][256];   // later reused for the binary64 votes (2048 doubles)
     __shared__ int tab_a[kMaxRows * kSelWaves];   // per (row, wave): survivors that need no second look
     __shared__ int tab_b[kMaxRows * kSelWaves];   // per (row, wave): band members (or ties at the cut)
     __shared__ int swave[kSelWaves];
     __shared__ uint32_t s_red[2 * kSelWaves];
-    __shared__ uint32_t s_prefix, s_kmin;
+    __shared__ uint32_t s_prefix;
     __shared__ int s_need;
     __shared__ int band_idx[kMaxBand];
+    __shared__ int band_start[kMaxBand];          // first position whose vote this member owns
+    __shared__ int band_off[kMaxBand + 1];        // offset of its owned votes in the vote list
     __shared__ double band_score[kMaxBand];
     __shared__ int band_take[kMaxBand + 1];       // after the scan: taken band members before position c
+    __shared__ float stage[kStageRows * kSelThreads + 2 * kMaxPoolRadius];   // votes of a few rows plus halo
 
     const int head = blockIdx.x;
     const int P = a.P, k = a.n_kept;
@@ -365,15 +401,37 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
     // ---- max-pool (clipped at both ends) and the range of the pooled scores ----
     const int r = (a.pool - 1) / 2;
     uint32_t kmin = 0xffffffffu, kmax = 0u;
-    for (int j = threadIdx.x; j < P; j += kSelThreads) {
-        float best = vote[j];
-        for (int t = 1; t <= r; ++t) {
-            if (j - t >= 0) best = fmaxf(best, vote[j - t]);
-            if (j + t < P) best = fmaxf(best, vote[j + t]);
-        }
-        pooled[j] = best;
-        kmin = min(kmin, score_key(best)); kmax = max(kmax, score_key(best));
+    float pv[kRegRows];
+#pragma unroll
+    for (int row = 0; row < kRegRows; ++row) pv[row] = -1.0f;
+    // A step stages kStageRows * 1024 consecutive votes plus r on either side in LDS (-1, below any
+    // vote, outside the prefix); every thread then takes the maximum over its window per row.
+#define KVQP_POOL_STEP(ROW0, STORE)                                                                \
+    {                                                                                              \
+        const int base = (ROW0) * kSelThreads - r;                                                 \
+        for (int i = threadIdx.x; i < kStageRows * kSelThreads + 2 * r; i += kSelThreads) {        \
+            const int j = base + i;                                                                \
+            stage[i] = (j >= 0 && j < P) ? vote[j] : -1.0f;                                        \
+        }                                                                                          \
+        __syncthreads();                                                                           \
+        _Pragma("unroll") for (int q = 0; q < kStageRows; ++q) {                                   \
+            const int row = (ROW0) + q;                                                            \
+            const int j = row * kSelThreads + (int)threadIdx.x;                                    \
+            if (j < P) {                                                                           \
+                const float* w = stage + q * kSelThreads + threadIdx.x;                            \
+                float best = w[0];                                                                 \
+                for (int t = 1; t <= 2 * r; ++t) best = fmaxf(best, w[t]);                         \
+                STORE;                                                                             \
+                kmin = min(kmin, score_key(best)); kmax = max(kmax, score_key(best));              \
+            }                                                                                      \
+        }                                                                                          \
+        __syncthreads();                                                                           \
     }
+#pragma unroll
+    for (int row0 = 0; row0 < kRegRows; row0 += kStageRows)
+        if (row0 < n_rows) KVQP_POOL_STEP(row0, pv[row] = best)
+    for (int row0 = kRegRows; row0 < n_rows; row0 += kStageRows) KVQP_POOL_STEP(row0, pooled[j] = best)
+#undef KVQP_POOL_STEP
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
         kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off));
@@ -394,13 +452,18 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
     for (int shift = top_shift; shift >= 0; shift -= 8) {
         for (int i = threadIdx.x; i < kSelWaves * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
         __syncthreads();
-        const uint32_t prefix = s_prefix;
-        const int need = s_need;
+        // (scalar copies: nothing in the sweep below then waits on LDS, so its atomics overlap)
+        const uint32_t prefix = __builtin_amdgcn_readfirstlane(s_prefix);
+        const int need = __builtin_amdgcn_readfirstlane(s_need);
         const uint32_t himask = (shift == 24) ? 0u : (0xffffffffu << (shift + 8));
-        for (int j = threadIdx.x; j < P; j += kSelThreads) {
-            const uint32_t key = score_key(pooled[j]) - kmin;
-            if ((key & himask) == prefix) atomicAdd(&hist[wave][(key >> shift) & 255], 1);
-        }
+        KVQP_FOR_ROWS(
+            const uint32_t key = score_key(v) - kmin;
+            const bool act = j < P && (key & himask) == prefix;
+            const int bin = (key >> shift) & 255;
+            // (an LDS atomic costs the CU a fixed time even with no lane active: skip those)
+            if (__builtin_amdgcn_ballot_w64(act) != 0ull)
+                if (act) atomicAdd(&hist[wave][bin], 1);
+        )
         __syncthreads();
         // bins summed over the waves, then "how many candidates in bins above mine" per bin
         if (wave < 4) {
@@ -437,39 +500,82 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
     const float lo = cut * (1.0f - kBandRel), hi = cut * (1.0f + kBandRel);
 
     // ---- per-(row, wave) counts: sure survivors (> hi) and band members ----
-    for (int row = 0; row < n_rows; ++row) {
-        const int j = row * kSelThreads + threadIdx.x;
-        const float v = j < P ? pooled[j] : -1.0f;
+    KVQP_FOR_ROWS(
         const unsigned long long bs = __builtin_amdgcn_ballot_w64(v > hi);
         const unsigned long long bb = __builtin_amdgcn_ballot_w64(v >= lo && v <= hi);
         if (lane == 0) { tab_a[row * kSelWaves + wave] = __popcll(bs); tab_b[row * kSelWaves + wave] = __popcll(bb); }
-    }
+        (void)j;
+    )
     __syncthreads();
     const int tot_sure = scan_table(tab_a, n_rows * kSelWaves, swave);
     const int tot_band = scan_table(tab_b, n_rows * kSelWaves, swave);
-    const bool refine = tot_band <= kMaxBand;
+    const int n_parts = (a.rows + 31) / 32;       // a wave re-scores 32 window rows of one position
+    bool refine = tot_band <= kMaxBand;
+    double* pos_vote = reinterpret_cast<double*>(&hist[0][0]);
+    int n_pos = 0;
 
     if (refine) {
         // ---- band members in position order ----
-        for (int row = 0; row < n_rows; ++row) {
-            const int j = row * kSelThreads + threadIdx.x;
-            const float v = j < P ? pooled[j] : -1.0f;
+        KVQP_FOR_ROWS(
             const bool inb = v >= lo && v <= hi;
             const unsigned long long bb = __builtin_amdgcn_ballot_w64(inb);
             if (inb) band_idx[tab_b[row * kSelWaves + wave] + __popcll(bb & lt_mask)] = j;
+        )
+        __syncthreads();
+        // ---- the positions whose votes are needed, each once: member c owns those of its pool
+        // window that no earlier member's window covers ----
+        for (int c = threadIdx.x; c < tot_band; c += kSelThreads) {
+            const int jc = band_idx[c];
+            int st = jc - r > 0 ? jc - r : 0;
+            if (c > 0) st = max(st, band_idx[c - 1] + r + 1);
+            const int en = min(jc + r, P - 1);
+            band_start[c] = st;
+            band_off[c] = en >= st ? en - st + 1 : 0;
         }
         __syncthreads();
-        // ---- binary64 re-scoring: one wave per (band member, pool offset) ----
-        const int width = 2 * r + 1;
-        for (int c = threadIdx.x; c < tot_band; c += kSelThreads) band_score[c] = 0.0;   // votes are >= 0
+        if (threadIdx.x == 0) {   // exclusive prefix over at most kMaxBand counts
+            int run = 0;
+            for (int c = 0; c < tot_band; ++c) { const int t = band_off[c]; band_off[c] = run; run += t; }
+            band_off[tot_band] = run;
+        }
         __syncthreads();
-        for (int item = wave; item < tot_band * width; item += kSelWaves) {
-            const int c = item / width, t = item % width - r;
-            const int j = band_idx[c] + t;
-            if (j < 0 || j >= P) continue;
-            const double v = vote_f64(a, head, j);
-            // several waves may hold offsets of the same member: combine with an order-free maximum
-            if (lane == 0) atomicMax(reinterpret_cast<unsigned long long*>(&band_score[c]), (unsigned long long)__double_as_longlong(v));
+        n_pos = band_off[tot_band];
+        refine = n_pos <= kSelThreads && n_pos * n_parts <= kVoteSlots;
+    }
+    if (refine) {
+        // ---- binary64 re-scoring: one wave per (position, 32 window rows) ----
+        for (int item = wave; item < n_pos * n_parts; item += kSelWaves) {
+            const int pos = item / n_parts, part = item % n_parts;
+            int lo_c = 0, hi_c = tot_band - 1;           // owner: last member with band_off <= pos
+            while (lo_c < hi_c) {
+                const int mid = (lo_c + hi_c + 1) >> 1;
+                if (band_off[mid] <= pos) lo_c = mid; else hi_c = mid - 1;
+            }
+            const int j = band_start[lo_c] + (pos - band_off[lo_c]);
+            const double v = vote_f64_part(a, head, j, 32 * part);
+            if (lane == 0) pos_vote[item] = v;
+        }
+        __syncthreads();
+        {   // parts summed in a fixed order, then stored over the parts
+            double sum = 0.0;
+            if ((int)threadIdx.x < n_pos)
+                for (int q = 0; q < n_parts; ++q) sum += pos_vote[threadIdx.x * n_parts + q];
+            __syncthreads();
+            if ((int)threadIdx.x < n_pos) pos_vote[threadIdx.x] = sum;
+        }
+        __syncthreads();
+        // ---- pooled binary64 score of each member ----
+        for (int c = threadIdx.x; c < tot_band; c += kSelThreads) {
+            const int jc = band_idx[c];
+            double best = 0.0;                            // votes are >= 0
+            int o = c;
+            for (int t = r; t >= -r; --t) {               // descending positions: the owner index only falls
+                const int j = jc + t;
+                if (j < 0 || j >= P) continue;
+                while (o > 0 && j < band_start[o]) --o;
+                best = fmax(best, pos_vote[band_off[o] + (j - band_start[o])]);
+            }
+            band_score[c] = best;
         }
         __syncthreads();
         // rank inside the band by (score desc, position asc); band_idx is ascending
@@ -481,16 +587,14 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
             band_take[c] = rank < take;
         }
         __syncthreads();
-        if (threadIdx.x == 0) {   // exclusive prefix over at most 512 flags
+        if (threadIdx.x == 0) {
             int run = 0;
             for (int c = 0; c < tot_band; ++c) { const int t = band_take[c]; band_take[c] = run; run += t; }
             band_take[tot_band] = run;
         }
         __syncthreads();
         // ---- ordered compaction ----
-        for (int row = 0; row < n_rows; ++row) {
-            const int j = row * kSelThreads + threadIdx.x;
-            const float v = j < P ? pooled[j] : -1.0f;
+        KVQP_FOR_ROWS(
             const bool sure = v > hi, inb = v >= lo && v <= hi;
             const unsigned long long bs = __builtin_amdgcn_ballot_w64(sure);
             const unsigned long long bb = __builtin_amdgcn_ballot_w64(inb);
@@ -499,23 +603,19 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
             bool keep = sure;
             if (inb) keep = band_take[band_before + 1] > band_take[band_before];
             if (keep) idx[sure_before + band_take[band_before]] = j;
-        }
+        )
     } else {
         // binary32 decides: everything above the cut, then the first need_at_cut equal to it
-        __syncthreads();
-        for (int row = 0; row < n_rows; ++row) {
-            const int j = row * kSelThreads + threadIdx.x;
-            const float v = j < P ? pooled[j] : -1.0f;
+        KVQP_FOR_ROWS(
             const unsigned long long bs = __builtin_amdgcn_ballot_w64(v > cut);
             const unsigned long long bb = __builtin_amdgcn_ballot_w64(v == cut);
             if (lane == 0) { tab_a[row * kSelWaves + wave] = __popcll(bs); tab_b[row * kSelWaves + wave] = __popcll(bb); }
-        }
+            (void)j;
+        )
         __syncthreads();
         (void)scan_table(tab_a, n_rows * kSelWaves, swave);
         (void)scan_table(tab_b, n_rows * kSelWaves, swave);
-        for (int row = 0; row < n_rows; ++row) {
-            const int j = row * kSelThreads + threadIdx.x;
-            const float v = j < P ? pooled[j] : -1.0f;
+        KVQP_FOR_ROWS(
             const bool above = v > cut, eq = v == cut;
             const unsigned long long bs = __builtin_amdgcn_ballot_w64(above);
             const unsigned long long bb = __builtin_amdgcn_ballot_w64(eq);
@@ -523,9 +623,10 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
             const int eq_before = tab_b[row * kSelWaves + wave] + __popcll(bb & lt_mask);
             if (above) idx[above_before + min(eq_before, need_at_cut)] = j;
             else if (eq && eq_before < need_at_cut) idx[above_before + eq_before] = j;
-        }
+        )
     }
 }
+#undef KVQP_FOR_ROWS
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
