@@ -44,9 +44,9 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kChunk = 64;          // tokens per wave iteration
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f; // finite stand-in for -inf in running maxima
-#ifndef KVQP_PIPE_WAVES
-#define KVQP_PIPE_WAVES 2
-#endif
+// Waves per SIMD the pipelined kernel is compiled for: the 2- and 4-bit variants fit 168 registers
+// (three waves), the 8- and 16-bit ones need more for their wider code words (two waves).
+constexpr int pipe_waves(int bits) { return bits <= 4 ? 3 : 2; }
 constexpr float kLazyLog2 = 8.0f;   // slack of the lazily updated softmax reference
 constexpr int kPartStride = kHeadDim + 2;  // floats per (partial, head): m, l, acc[128]
 
@@ -345,6 +345,118 @@ __device__ void tail_partial(const DecodeArgs& a, int bh, float* smem) {
         if (d == 0) { st_dev(dst + h * kPartStride, M); st_dev(dst + h * kPartStride + 1, L); }
     }
     merge_if_last<GQ>(a, bh);
+}
+
+// Value of lane ^ 16 / lane ^ 32.
+__device__ __forceinline__ float xor16_get(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float((threadIdx.x & 16) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float xor32_get(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+// Sum over the 16 lanes of a DPP row, result in every lane of the row.
+__device__ __forceinline__ float row16_add(float v) {
+    v += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    v += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    v += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x141, 0xF, 0xF, true));   // row_half_mirror
+    v += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x140, 0xF, 0xF, true));   // row_mirror
+    return v;
+}
+
+// Full-precision tail rows [t0, t1) of one KV head, shared by the four waves of a workgroup.  A wave
+// takes four rows per step: lane = 16 * (row in step) + (8-channel segment).  Each wave leaves its
+// softmax state in LDS, sT[wave][head] = {reference m (log2 domain), sum l, unnormalised o[128]}.
+// Heads go in passes of at most four to bound the registers (rows are re-read from cache).
+template <int GQ>
+__device__ void tail_rows(const DecodeArgs& a, int bh, int t0, int t1, float* sT) {
+    constexpr int HB = GQ < 4 ? GQ : 4;
+    const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int seg = lane & 15, rg = lane >> 4;
+    const uint16_t* tk = a.tail_k + (size_t)bh * a.tail_cap * kHeadDim + 8 * seg;
+    const uint16_t* tv = a.tail_v + (size_t)bh * a.tail_cap * kHeadDim + 8 * seg;
+    const bool any = t0 + 4 * wave < t1;   // wave-uniform
+#pragma unroll 1
+    for (int h0 = 0; h0 < GQ; h0 += HB) {
+        float m[HB], l[HB], o[HB][8];
+#pragma unroll
+        for (int h = 0; h < HB; ++h) {
+            m[h] = kNegBig; l[h] = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[h][j] = 0.f;
+        }
+        if (any) {
+            float qf[HB][8];
+#pragma unroll
+            for (int h = 0; h < HB; ++h) {
+                const uint4 u = *reinterpret_cast<const uint4*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + h0 + h) * kHeadDim + 8 * seg);
+                const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const h2v qq = as_h2(w[j]);
+                    qf[h][2 * j] = (float)qq[0] * (a.sm_scale * kLog2e); qf[h][2 * j + 1] = (float)qq[1] * (a.sm_scale * kLog2e);
+                }
+            }
+            for (int r0 = t0 + 4 * wave; r0 < t1; r0 += 4 * kWaves) {
+                const int r = r0 + rg;
+                if (r < t1) {   // whole DPP rows are in or out together
+                    const uint4 ku = *reinterpret_cast<const uint4*>(tk + (size_t)r * kHeadDim);
+                    const uint4 vu = *reinterpret_cast<const uint4*>(tv + (size_t)r * kHeadDim);
+                    const uint32_t kw[4] = {ku.x, ku.y, ku.z, ku.w}, vw[4] = {vu.x, vu.y, vu.z, vu.w};
+                    float kf[8], vf[8];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const h2v kk = as_h2(kw[j]), vv = as_h2(vw[j]);
+                        kf[2 * j] = (float)kk[0]; kf[2 * j + 1] = (float)kk[1];
+                        vf[2 * j] = (float)vv[0]; vf[2 * j + 1] = (float)vv[1];
+                    }
+#pragma unroll
+                    for (int h = 0; h < HB; ++h) {
+                        float sc = 0.f;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) sc = __builtin_fmaf(qf[h][j], kf[j], sc);
+                        sc = row16_add(sc);
+                        const float mn = fmaxf(m[h], sc);
+                        const float alpha = __builtin_amdgcn_exp2f(m[h] - mn), pr = __builtin_amdgcn_exp2f(sc - mn);
+                        l[h] = __builtin_fmaf(l[h], alpha, pr);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) o[h][j] = __builtin_fmaf(o[h][j], alpha, pr * vf[j]);
+                        m[h] = mn;
+                    }
+                }
+            }
+            // merge the four row groups (lanes ^ 16, ^ 32)
+#pragma unroll
+            for (int h = 0; h < HB; ++h) {
+#pragma unroll
+                for (int step = 0; step < 2; ++step) {
+                    const float mo = step ? xor32_get(m[h]) : xor16_get(m[h]);
+                    const float lo = step ? xor32_get(l[h]) : xor16_get(l[h]);
+                    const float mn = fmaxf(m[h], mo);
+                    const float ws = __builtin_amdgcn_exp2f(m[h] - mn), wo = __builtin_amdgcn_exp2f(mo - mn);
+                    l[h] = l[h] * ws + lo * wo;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float oo = step ? xor32_get(o[h][j]) : xor16_get(o[h][j]);
+                        o[h][j] = o[h][j] * ws + oo * wo;
+                    }
+                    m[h] = mn;
+                }
+            }
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int h = 0; h < HB; ++h) {
+                float* row = sT + (wave * GQ + h0 + h) * kPartStride;
+                if (lane == 0) { row[0] = m[h]; row[1] = l[h]; }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) row[2 + 8 * lane + j] = o[h][j];
+            }
+        }
+    }
 }
 
 // BITS: code width; GQ: query heads per kv head (1,2,4 -> two token slots per
@@ -672,7 +784,7 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 //     straight to binary16, and only the lanes that own a lo row compute it.
 // ---------------------------------------------------------------------------
 template <int BITS, int GQ, int NCG>
-__global__ __launch_bounds__(kThreads, KVQP_PIPE_WAVES) void decode_attn_pipe(const DecodeArgs a) {
+__global__ __launch_bounds__(kThreads, pipe_waves(BITS)) void decode_attn_pipe(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int NT = (SLOTS == 2) ? 1 : 2;
     constexpr bool QUANT = BITS != 16;
@@ -690,7 +802,6 @@ __global__ __launch_bounds__(kThreads, KVQP_PIPE_WAVES) void decode_attn_pipe(co
     __shared__ __align__(16) uint16_t sq[8 * kHeadDim];   // the group's query rows (zero rows past GQ), for the z-term product
 
     const int bh = blockIdx.y;
-    if ((int)blockIdx.x == a.n_splits) { tail_partial<GQ>(a, bh, smem); return; }
 
     const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1030,8 +1141,12 @@ __global__ __launch_bounds__(kThreads, KVQP_PIPE_WAVES) void decode_attn_pipe(co
         for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
     }
     __syncthreads();
-    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
-    for (int item = threadIdx.x; item < GQ * kHeadDim; item += kThreads) {
+    // every thread merges the four waves for its outputs (head hh, channel d)
+    constexpr int ITEMS = (GQ * kHeadDim + kThreads - 1) / kThreads;
+    float Mi[ITEMS], Ai[ITEMS], Li[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
         const int hh = item / kHeadDim, d = item % kHeadDim;
         const int cg = d / G;
         float M = kNegBig;
@@ -1051,8 +1166,44 @@ __global__ __launch_bounds__(kThreads, KVQP_PIPE_WAVES) void decode_attn_pipe(co
                 acc = __builtin_fmaf(wgt, o, acc);
                 L = __builtin_fmaf(wgt, st[1], L);
             }
-        st_dev(dst + hh * kPartStride + 2 + d, acc);
-        if (d == 0) { st_dev(dst + hh * kPartStride, M); st_dev(dst + hh * kPartStride + 1, L); }
+        Mi[it] = M; Ai[it] = acc; Li[it] = L;
+    }
+    // this workgroup's share of the full-precision tail rows, then the same merge once more
+    {
+        const int t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
+        const int t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
+        __syncthreads();                               // the wave states above have been read
+        float* sT = smem;                              // [wave][head][m, l, o[128]]
+        tail_rows<GQ>(a, bh, t0, t1, sT);
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
+            const int hh = item / kHeadDim, d = item % kHeadDim;
+            float M = Mi[it];
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sT[(w * GQ + hh) * kPartStride]);
+            const float keep = exp2f(Mi[it] - M);
+            float acc = Ai[it] * keep, L = Li[it] * keep;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float* row = sT + (w * GQ + hh) * kPartStride;
+                const float wgt = exp2f(row[0] - M);
+                acc = __builtin_fmaf(wgt, row[2 + d], acc);
+                L = __builtin_fmaf(wgt, row[1], L);
+            }
+            Mi[it] = M; Ai[it] = acc; Li[it] = L;
+        }
+    }
+    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int item = threadIdx.x + it * kThreads;
+        if (item < GQ * kHeadDim) {
+            const int hh = item / kHeadDim, d = item % kHeadDim;
+            st_dev(dst + hh * kPartStride + 2 + d, Ai[it]);
+            if (d == 0) { st_dev(dst + hh * kPartStride, Mi[it]); st_dev(dst + hh * kPartStride + 1, Li[it]); }
+        }
     }
     merge_if_last<GQ>(a, bh);
 }
@@ -1087,23 +1238,44 @@ hipError_t launch_gq(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t strea
 
 }  // namespace
 
+// The pipelined kernel serves per-channel keys and the 16-bit cache; per-token keys at 2-8 bits
+// run on the plain split-K kernel.
+static bool uses_pipe(const kvqp_cfg& cfg) { return !(cfg.key_axis == KVQP_KEY_PER_TOKEN && cfg.bits != 16); }
+
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
     DecodePlan p;
     const int heads = cfg.batch * cfg.n_kv_heads;
     const int n_chunks = (n_kept + kChunk - 1) / kChunk;
-    int splits = 0;
-    if (n_chunks > 0) {
-        splits = cfg.decode_splits > 0 ? cfg.decode_splits : (1024 + heads - 1) / heads;
+    const int gq = cfg.n_q_heads / cfg.n_kv_heads;
+    if (uses_pipe(cfg)) {
+        // Every workgroup takes a token range and a share of the tail rows.  By default the launch
+        // is one resident round: as many workgroups as the chip holds at the kernel's occupancy.
+        static const int n_cu = [] {
+            int dev = 0, v = 0;
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+            return v;
+        }();
+        int splits = cfg.decode_splits > 0 ? cfg.decode_splits : (n_cu * pipe_waves(cfg.bits)) / heads;
         // at least two 64-token chunks per wave: below that the fixed cost of a workgroup and of the
         // split merge (device-scope round trips) outweighs the extra parallelism
         const int max_splits = cfg.decode_splits > 0 ? n_chunks : (n_chunks + 2 * kWaves - 1) / (2 * kWaves);
         if (splits > max_splits) splits = max_splits;
         if (splits < 1) splits = 1;
+        p.chunks_per_split = (n_chunks + splits - 1) / splits;
+        p.n_splits = p.chunks_per_split ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 1;
+        p.n_partials = p.n_splits;
+    } else {
+        int splits = 0;
+        if (n_chunks > 0) {
+            splits = cfg.decode_splits > 0 ? cfg.decode_splits : (1024 + heads - 1) / heads;
+            const int max_splits = cfg.decode_splits > 0 ? n_chunks : (n_chunks + 2 * kWaves - 1) / (2 * kWaves);
+            if (splits > max_splits) splits = max_splits;
+            if (splits < 1) splits = 1;
+        }
+        p.chunks_per_split = splits ? (n_chunks + splits - 1) / splits : 0;
+        p.n_splits = splits ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 0;
+        p.n_partials = p.n_splits + (tail_len > 0 ? 1 : 0);   // one more workgroup per head for the tail rows
     }
-    p.chunks_per_split = splits ? (n_chunks + splits - 1) / splits : 0;
-    p.n_splits = splits ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 0;
-    p.n_partials = p.n_splits + (tail_len > 0 ? 1 : 0);
-    const int gq = cfg.n_q_heads / cfg.n_kv_heads;
     p.ws_bytes = (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartStride * sizeof(float);
     return p;
 }
