@@ -207,6 +207,7 @@ struct DecodeArgs {
     int n_kept, tail_len, tail_cap;
     int n_q_heads, n_kv_heads;
     int n_splits, chunks_per_split, n_partials;
+    int n_waves;              // waves per workgroup of the pipelined kernel
     int group;                // G
     float sm_scale;
 };
@@ -238,7 +239,7 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
         s_last = last;
     }
     __syncthreads();
-    if (!s_last) return;
+    if (!s_last || threadIdx.x >= kThreads) return;   // (workgroups may be larger than the 256 merging threads)
     const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
     const float* base = a.part + (size_t)bh * a.n_partials * GQ * kPartStride;
     const size_t stride = (size_t)GQ * kPartStride;
@@ -783,28 +784,47 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 //   * hi/lo operand parts are produced with fused multiply-adds that round
 //     straight to binary16, and only the lanes that own a lo row compute it.
 // ---------------------------------------------------------------------------
+// LDS bytes of one wave's staging strip in the pipelined kernel: key scale row | key zero rows |
+// value scales | value zeros of the block in flight.
+template <int BITS, int NCG> struct PipeGeom {
+    static constexpr bool QUANT = BITS != 16;
+    static constexpr int G = kHeadDim / NCG;
+    static constexpr int NGRP = (QUANT && G == 32) ? 2 : 1;   // key groups per 64-token chunk
+    static constexpr int VROW = 64 * NCG;                     // bytes of value scales of one 32-token block
+    static constexpr int OFF_KS = 0, OFF_KZ = 256, OFF_VS = OFF_KZ + 256 * NGRP, OFF_VZ = OFF_VS + VROW;
+    static constexpr int STRIP = QUANT ? OFF_VZ + VROW : 0;
+};
+constexpr int kMergeFloats = kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4);   // wave states of one merge round
+constexpr int kPipeFixedLds = kMergeFloats * 4 + 8 * kHeadDim * 2;             // + the group's query rows
+constexpr int pipe_max_waves(int bits) { return 4 * pipe_waves(bits); }
+
 template <int BITS, int GQ, int NCG>
-__global__ __launch_bounds__(kThreads, pipe_waves(BITS)) void decode_attn_pipe(const DecodeArgs a) {
+__global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int NT = (SLOTS == 2) ? 1 : 2;
     constexpr bool QUANT = BITS != 16;
     constexpr float kCodeUnit = QUANT ? 16777216.0f : 1.0f;
     constexpr int G = kHeadDim / NCG;
     constexpr int NGRP = (QUANT && G == 32) ? 2 : 1;          // key groups per 64-token chunk
-    constexpr int VROW = 64 * NCG;                            // bytes of value scales of one 32-token block
+    using Geo = PipeGeom<BITS, NCG>;
+    constexpr int VROW = Geo::VROW;
     constexpr int VSTRIP = 8 * NCG;                           // bytes of value scales of 4 consecutive tokens
-    // wave-private LDS strip: key scale row | key zero rows | value scales | value zeros
-    constexpr int OFF_KS = 0, OFF_KZ = 256, OFF_VS = OFF_KZ + 256 * NGRP, OFF_VZ = OFF_VS + VROW;
-    constexpr int STRIP = OFF_VZ + VROW;
+    constexpr int OFF_KS = Geo::OFF_KS, OFF_KZ = Geo::OFF_KZ, OFF_VS = Geo::OFF_VS, OFF_VZ = Geo::OFF_VZ;
+    constexpr int STRIP = Geo::STRIP;
 
-    __shared__ __align__(16) float smem[kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4)];
-    __shared__ __align__(16) unsigned char stage_all[QUANT ? kWaves * STRIP : 16];
-    __shared__ __align__(16) uint16_t sq[8 * kHeadDim];   // the group's query rows (zero rows past GQ), for the z-term product
+    // A workgroup is nw = 4, 8 or 12 waves (blockDim.x / 64, a multiple of four): all of them stream
+    // chunks; the merges at the end are done by the first 256 threads, four wave states per round.
+    extern __shared__ __align__(16) unsigned char pipe_lds[];
+    float* smem = reinterpret_cast<float*>(pipe_lds);
+    uint16_t* sq = reinterpret_cast<uint16_t*>(pipe_lds + kMergeFloats * 4);   // the group's query rows (zero rows past GQ), for the z-term product
+    unsigned char* stage_all = pipe_lds + kPipeFixedLds;
+    const int nw = blockDim.x >> 6;
 
     const int bh = blockIdx.y;
 
     const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, kb = lane >> 4;
     const int part = n & 1;
     const int slot = (SLOTS == 2) ? (n >> 3) : 0;
@@ -827,7 +847,7 @@ __global__ __launch_bounds__(kThreads, pipe_waves(BITS)) void decode_attn_pipe(c
     const int n_kgroups = QUANT ? a.n_kept / G : 0;
 
     if constexpr (QUANT) {
-        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += kThreads) {
+        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += blockDim.x) {
             const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
             const uint32_t v = hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
             reinterpret_cast<uint32_t*>(sq)[item] = v;
@@ -1086,7 +1106,7 @@ __global__ __launch_bounds__(kThreads, pipe_waves(BITS)) void decode_attn_pipe(c
     const int c_end = min(n_chunks, c_begin + a.chunks_per_split);
     int chunk = c_begin + wave;
     if (chunk < c_end) load_A(chunk);
-    for (; chunk < c_end; chunk += kWaves) {
+    for (; chunk < c_end; chunk += nw) {
         const int tok0 = chunk * kChunk;
         const bool two = a.n_kept - tok0 >= kChunk;         // n_kept is a multiple of 32
         load_B(chunk, two);
@@ -1120,89 +1140,116 @@ __global__ __launch_bounds__(kThreads, pipe_waves(BITS)) void decode_attn_pipe(c
         }
         compute(ak0, ak1, a_ks, true, bias0, av, 0, a_vs, a_vz);
         if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
-        load_A((chunk + kWaves < c_end) ? chunk + kWaves : chunk);
+        load_A((chunk + nw < c_end) ? chunk + nw : chunk);
         if (two) compute(bk0, bk1, b_ks, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
     }
 
-    // ---- merge the four waves, write the split's partial (same as the plain variant) ----
+    // ---- merge the waves (four states per round through LDS), add the tail rows, write ----
     l_run = quad_rows_add(l_run);
 #pragma unroll
     for (int c = 0; c < NCG; ++c) oz[c] = quad_rows_add(oz[c]);
     float* sO = smem;
     float* sS = smem + kWaves * 16 * kHeadDim;
-#pragma unroll
-    for (int t8 = 0; t8 < 8; ++t8)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sO[(wave * 16 + 4 * kb + i) * kHeadDim + 16 * t8 + n] = O[t8][i];
-    if (kb == 0) {
-        float* st = sS + (wave * 16 + n) * 6;
-        st[0] = m_run; st[1] = l_run;
-#pragma unroll
-        for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
-    }
-    __syncthreads();
-    // every thread merges the four waves for its outputs (head hh, channel d)
-    constexpr int ITEMS = (GQ * kHeadDim + kThreads - 1) / kThreads;
+    constexpr int ITEMS = (GQ * kHeadDim + kThreads - 1) / kThreads;   // outputs (head hh, channel d) per merging thread
+    const bool merger = threadIdx.x < kThreads;
     float Mi[ITEMS], Ai[ITEMS], Li[ITEMS];
 #pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
-        const int hh = item / kHeadDim, d = item % kHeadDim;
-        const int cg = d / G;
-        float M = kNegBig;
+    for (int it = 0; it < ITEMS; ++it) { Mi[it] = kNegBig; Ai[it] = 0.f; Li[it] = 0.f; }
+    for (int w0 = 0; w0 < nw; w0 += kWaves) {
+        if (wave >= w0 && wave < w0 + kWaves) {
+            const int wl = wave - w0;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w)
+            for (int t8 = 0; t8 < 8; ++t8)
 #pragma unroll
-            for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[(w * 16 + sl * 8 + 2 * hh) * 6]);
-        float acc = 0.f, L = 0.f;
+                for (int i = 0; i < 4; ++i) sO[(wl * 16 + 4 * kb + i) * kHeadDim + 16 * t8 + n] = O[t8][i];
+            if (kb == 0) {
+                float* st = sS + (wl * 16 + n) * 6;
+                st[0] = m_run; st[1] = l_run;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w)
-#pragma unroll
-            for (int sl = 0; sl < SLOTS; ++sl) {
-                const int row = sl * 8 + 2 * hh;
-                const float* st = sS + (w * 16 + row) * 6;
-                const float wgt = exp2f(st[0] - M);
-                const float o = (sO[(w * 16 + row) * kHeadDim + d] + sO[(w * 16 + row + 1) * kHeadDim + d]) * kCodeUnit + st[2 + cg];
-                acc = __builtin_fmaf(wgt, o, acc);
-                L = __builtin_fmaf(wgt, st[1], L);
+                for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
             }
-        Mi[it] = M; Ai[it] = acc; Li[it] = L;
+        }
+        __syncthreads();
+        if (merger) {
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it) {
+                const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
+                const int hh = item / kHeadDim, d = item % kHeadDim;
+                const int cg = d / G;
+                float M = Mi[it];
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+                    for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[(w * 16 + sl * 8 + 2 * hh) * 6]);
+                const float keep = exp2f(Mi[it] - M);
+                float acc = Ai[it] * keep, L = Li[it] * keep;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+                    for (int sl = 0; sl < SLOTS; ++sl) {
+                        const int row = sl * 8 + 2 * hh;
+                        const float* st = sS + (w * 16 + row) * 6;
+                        const float wgt = exp2f(st[0] - M);
+                        const float o = (sO[(w * 16 + row) * kHeadDim + d] + sO[(w * 16 + row + 1) * kHeadDim + d]) * kCodeUnit + st[2 + cg];
+                        acc = __builtin_fmaf(wgt, o, acc);
+                        L = __builtin_fmaf(wgt, st[1], L);
+                    }
+                Mi[it] = M; Ai[it] = acc; Li[it] = L;
+            }
+        }
+        __syncthreads();
     }
-    // this workgroup's share of the full-precision tail rows, then the same merge once more
+    // this workgroup's share of the full-precision tail rows (first four waves), merged the same way
     {
         const int t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
         const int t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
-        __syncthreads();                               // the wave states above have been read
         float* sT = smem;                              // [wave][head][m, l, o[128]]
-        tail_rows<GQ>(a, bh, t0, t1, sT);
+        if (wave < kWaves) tail_rows<GQ>(a, bh, t0, t1, sT);
         __syncthreads();
+        if (merger) {
 #pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
-            const int hh = item / kHeadDim, d = item % kHeadDim;
-            float M = Mi[it];
+            for (int it = 0; it < ITEMS; ++it) {
+                const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
+                const int hh = item / kHeadDim, d = item % kHeadDim;
+                float M = Mi[it];
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sT[(w * GQ + hh) * kPartStride]);
-            const float keep = exp2f(Mi[it] - M);
-            float acc = Ai[it] * keep, L = Li[it] * keep;
+                for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sT[(w * GQ + hh) * kPartStride]);
+                const float keep = exp2f(Mi[it] - M);
+                float acc = Ai[it] * keep, L = Li[it] * keep;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                const float* row = sT + (w * GQ + hh) * kPartStride;
-                const float wgt = exp2f(row[0] - M);
-                acc = __builtin_fmaf(wgt, row[2 + d], acc);
-                L = __builtin_fmaf(wgt, row[1], L);
+                for (int w = 0; w < kWaves; ++w) {
+                    const float* row = sT + (w * GQ + hh) * kPartStride;
+                    const float wgt = exp2f(row[0] - M);
+                    acc = __builtin_fmaf(wgt, row[2 + d], acc);
+                    L = __builtin_fmaf(wgt, row[1], L);
+                }
+                Mi[it] = M; Ai[it] = acc; Li[it] = L;
             }
-            Mi[it] = M; Ai[it] = acc; Li[it] = L;
         }
     }
-    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
+    if (a.n_splits == 1) {   // the whole head was here: normalise, round once, done
+        if (merger) {
 #pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const int item = threadIdx.x + it * kThreads;
-        if (item < GQ * kHeadDim) {
-            const int hh = item / kHeadDim, d = item % kHeadDim;
-            st_dev(dst + hh * kPartStride + 2 + d, Ai[it]);
-            if (d == 0) { st_dev(dst + hh * kPartStride, Mi[it]); st_dev(dst + hh * kPartStride + 1, Li[it]); }
+            for (int it = 0; it < ITEMS; ++it) {
+                const int item = threadIdx.x + it * kThreads;
+                if (item < GQ * kHeadDim) {
+                    const int hh = item / kHeadDim, d = item % kHeadDim;
+                    a.out[((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim + d] = __half_as_ushort(__float2half_rn(Ai[it] / Li[it]));
+                }
+            }
+        }
+        return;
+    }
+    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
+    if (merger) {
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const int item = threadIdx.x + it * kThreads;
+            if (item < GQ * kHeadDim) {
+                const int hh = item / kHeadDim, d = item % kHeadDim;
+                st_dev(dst + hh * kPartStride + 2 + d, Ai[it]);
+                if (d == 0) { st_dev(dst + hh * kPartStride, Mi[it]); st_dev(dst + hh * kPartStride + 1, Li[it]); }
+            }
         }
     }
     merge_if_last<GQ>(a, bh);
@@ -1214,7 +1261,11 @@ hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t str
     if (cfg.key_axis == KVQP_KEY_PER_TOKEN && BITS != 16)
         hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 1>), grid, dim3(kThreads), 0, stream, a);
     else
-        hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG>), grid, dim3(kThreads), 0, stream, a);
+    {
+        constexpr int strip = PipeGeom<BITS, NCG>::STRIP;
+        const unsigned lds_bytes = kPipeFixedLds + a.n_waves * strip + 16;
+        hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG>), grid, dim3(64 * a.n_waves), lds_bytes, stream, a);
+    }
     return hipGetLastError();
 }
 template <int BITS, int GQ>
@@ -1255,12 +1306,25 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
             if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
             return v;
         }();
-        int splits = cfg.decode_splits > 0 ? cfg.decode_splits : (n_cu * pipe_waves(cfg.bits)) / heads;
-        // at least two 64-token chunks per wave: below that the fixed cost of a workgroup and of the
-        // split merge (device-scope round trips) outweighs the extra parallelism
-        const int max_splits = cfg.decode_splits > 0 ? n_chunks : (n_chunks + 2 * kWaves - 1) / (2 * kWaves);
-        if (splits > max_splits) splits = max_splits;
+        // Waves a head may use: its share of what the chip holds at this kernel's occupancy, but no
+        // fewer than two 64-token chunks per wave (below that the fixed costs win).
+        const int max_nw = pipe_max_waves(cfg.bits);
+        int waves = (n_cu * max_nw) / heads;
+        if (waves > n_chunks / 2) waves = n_chunks / 2;
+        int splits, nw;
+        if (cfg.decode_splits > 0) {            // caller's choice: that many four-wave workgroups
+            splits = cfg.decode_splits < n_chunks ? cfg.decode_splits : n_chunks;
+            nw = kWaves;
+        } else if (waves <= max_nw) {           // one workgroup per head: no partials, no merge across workgroups
+            splits = 1;
+            nw = waves / kWaves * kWaves;
+        } else {
+            splits = (waves + max_nw - 1) / max_nw;
+            nw = max_nw;
+        }
         if (splits < 1) splits = 1;
+        if (nw < kWaves) nw = kWaves;
+        p.n_waves = nw;
         p.chunks_per_split = (n_chunks + splits - 1) / splits;
         p.n_splits = p.chunks_per_split ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 1;
         p.n_partials = p.n_splits;
@@ -1275,6 +1339,7 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         p.chunks_per_split = splits ? (n_chunks + splits - 1) / splits : 0;
         p.n_splits = splits ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 0;
         p.n_partials = p.n_splits + (tail_len > 0 ? 1 : 0);   // one more workgroup per head for the tail rows
+        p.n_waves = kWaves;
     }
     p.ws_bytes = (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartStride * sizeof(float);
     return p;
@@ -1293,6 +1358,7 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.n_kept = c.n_kept; a.tail_len = c.tail_len; a.tail_cap = c.tail_cap;
     a.n_q_heads = cfg.n_q_heads; a.n_kv_heads = cfg.n_kv_heads;
     a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;
+    a.n_waves = plan.n_waves;
     a.group = cfg.group_size; a.sm_scale = cfg.sm_scale;
     hipError_t e;
     switch (cfg.bits) {

@@ -36,6 +36,7 @@ struct DecodePlan {
     int n_splits;        // token-axis splits of the packed part
     int chunks_per_split;// 64-token chunks handled by one workgroup
     int n_partials;      // n_splits (+1 when a tail partial is written)
+    int n_waves;         // waves per decode workgroup
     size_t ws_bytes;
 };
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len);
