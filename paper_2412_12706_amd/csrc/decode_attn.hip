@@ -76,6 +76,11 @@ __device__ __forceinline__ float pair_other(float v) {
 
 __device__ __forceinline__ h2v as_h2(uint32_t u) { union { uint32_t u; h2v h; } c; c.u = u; return c.h; }
 __device__ __forceinline__ uint32_t as_u32(h2v h) { union { uint32_t u; h2v h; } c; c.h = h; return c.u; }
+// two binary32 values cut (toward zero) to binary16, (lo, hi) half-words
+__device__ __forceinline__ uint32_t pack_rtz(float lo, float hi) {
+    typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+    union { fp16x2 h; uint32_t u; } c; c.h = __builtin_amdgcn_cvt_pkrtz(lo, hi); return c.u;
+}
 
 // ---- key codes: BITS words per lane per 16-token tile (the lane's 32 channels) ----
 template <int BITS> struct KWords { uint32_t w[BITS]; };
@@ -795,7 +800,7 @@ template <int BITS, int NCG> struct PipeGeom {
     static constexpr int STRIP = QUANT ? OFF_VZ + VROW : 0;
 };
 constexpr int kMergeFloats = kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4);   // wave states of one merge round
-constexpr int kPipeFixedLds = kMergeFloats * 4 + 8 * kHeadDim * 2;             // + the group's query rows
+constexpr int kPipeFixedLds = kMergeFloats * 4 + 8 * kHeadDim * 2 + 4 * 64 * 16;   // + the group's query rows, twice (plain, operand layout)
 constexpr int pipe_max_waves(int bits) { return 4 * pipe_waves(bits); }
 
 template <int BITS, int GQ, int NCG>
@@ -817,6 +822,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
     extern __shared__ __align__(16) unsigned char pipe_lds[];
     float* smem = reinterpret_cast<float*>(pipe_lds);
     uint16_t* sq = reinterpret_cast<uint16_t*>(pipe_lds + kMergeFloats * 4);   // the group's query rows (zero rows past GQ), for the z-term product
+    uint4* sqpos = reinterpret_cast<uint4*>(pipe_lds + kMergeFloats * 4 + 8 * kHeadDim * 2);   // [slice s][lane]
     unsigned char* stage_all = pipe_lds + kPipeFixedLds;
     const int nw = blockDim.x >> 6;
 
@@ -846,16 +852,11 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
     const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
     const int n_kgroups = QUANT ? a.n_kept / G : 0;
 
-    if constexpr (QUANT) {
-        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += blockDim.x) {
-            const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
-            const uint32_t v = hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
-            reinterpret_cast<uint32_t*>(sq)[item] = v;
-        }
-        __syncthreads();
-    }
-    h2v qpos[16];
-    {
+    // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
+    // (head row, channel block kb).  The quantized variants park them in LDS (same for every wave)
+    // and re-read them when a key group's scales arrive; that frees 16 registers in the loop.
+    h2v qpos[QUANT ? 1 : 16];
+    if (!QUANT || wave == 0) {
         h2v qn[16];
         const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + 32 * kb;
 #pragma unroll
@@ -865,11 +866,33 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
             qn[4 * i + 2] = as_h2(live_row ? v.z : 0u); qn[4 * i + 3] = as_h2(live_row ? v.w : 0u);
         }
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < 4; ++s) {
+            h2v t[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                qpos[4 * s + r] = qn[4 * s + r] * (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
+            for (int r = 0; r < 4; ++r) t[r] = qn[4 * s + r] * (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
+            if constexpr (QUANT) {
+                sqpos[s * 64 + lane] = make_uint4(as_u32(t[0]), as_u32(t[1]), as_u32(t[2]), as_u32(t[3]));
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) qpos[4 * s + r] = t[r];
+            }
+        }
     }
+    if constexpr (QUANT) {
+        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += blockDim.x) {
+            const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
+            const uint32_t v = hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
+            reinterpret_cast<uint32_t*>(sq)[item] = v;
+        }
+        __syncthreads();
+    }
+    // lane constants of the p*s operand: lo rows subtract the leading bits; a value lands in the
+    // half-word of the lane's token slot (byte selectors for v_perm_b32: 0x0c gives a zero byte)
+    const uint32_t lo_mask = part ? 0xFFFFE000u : 0u;
+    const uint32_t slot_mask = slot ? 0xFFFF0000u : 0x0000FFFFu;
+    const uint32_t sel_even = slot ? 0x01000C0Cu : 0x0C0C0100u;   // low half-word of the pair
+    const uint32_t sel_odd = slot ? 0x03020C0Cu : 0x0C0C0302u;    // high half-word of the pair
+    (void)lo_mask; (void)slot_mask; (void)sel_even; (void)sel_odd;
     const float c_logit = a.sm_scale * kLog2e * kCodeUnit;
     const float c_bias = a.sm_scale * kLog2e;
 
@@ -884,7 +907,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) bq[s].h[r] = part ? (h2v){0, 0} : qpos[4 * s + r];   // 16-bit cache: plain q in the hi rows
+        for (int r = 0; r < 4; ++r) bq[s].h[r] = (QUANT || part) ? (h2v){0, 0} : qpos[QUANT ? 0 : 4 * s + r];   // 16-bit cache: plain q in the hi rows
 
     // ---- the two register sets (codes as MFMA operands; one dword per lane of every scale row) ----
     KWords<BITS> ak0, ak1, bk0, bk1;
@@ -970,18 +993,23 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
             if (new_group) lds_put(OFF_KS, r_ks);
             lds_put_v(OFF_VS, r_vs); lds_put_v(OFF_VZ, r_vz);
             if (new_group) {
-                uint32_t sw[16];
+                uint32_t sw[16], qw[16];
                 lds_get16(OFF_KS + 64 * kb, sw);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const uint4 v = sqpos[s * 64 + lane];
+                    qw[4 * s] = v.x; qw[4 * s + 1] = v.y; qw[4 * s + 2] = v.z; qw[4 * s + 3] = v.w;
+                }
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) bq[s].h[r] = qpos[4 * s + r] * as_h2(sw[4 * s + r]);
+                    for (int r = 0; r < 4; ++r) bq[s].h[r] = as_h2(qw[4 * s + r]) * as_h2(sw[4 * s + r]);
                 if (part) {
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
-                            bq[s].h[r] = __builtin_elementwise_fma(qpos[4 * s + r], as_h2(sw[4 * s + r]), -bq[s].h[r]);
+                            bq[s].h[r] = __builtin_elementwise_fma(as_h2(qw[4 * s + r]), as_h2(sw[4 * s + r]), -bq[s].h[r]);
                 }
             }
 #pragma unroll
@@ -1057,44 +1085,41 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
                 pa[0].u[i] = w;
             }
         } else {
-            _Float16 hv[NT][4][NCG];
+            // x = p * s in binary32; the hi rows take x, the lo rows x minus its leading 11 bits (an
+            // exact difference); both are then cut to binary16 by the same truncating conversion,
+            // so hi + lo reproduces x to ~2^-22.
+            float xv[NT][4][NCG];
 #pragma unroll
             for (int t = 0; t < NT; ++t)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i) {
+                    const float pz = p[t][i] * (float)(1 << v_pos_log2<BITS>(vblk, i));
 #pragma unroll
                     for (int c = 0; c < NCG; ++c) {
                         const int e = i * NCG + c;                       // half index inside the lane's 4-token strip
                         const h2v sv2 = as_h2(vsr[t * 2 * NCG + (e >> 1)]), zv2 = as_h2(vzr[t * 2 * NCG + (e >> 1)]);
-                        const float sv = (float)sv2[e & 1], zv = (float)zv2[e & 1];
-                        hv[t][i][c] = (_Float16)__builtin_fmaf(p[t][i], sv, 0.0f);
-                        oz[c] = __builtin_fmaf(p[t][i] * (float)(1 << v_pos_log2<BITS>(vblk, i)), zv, oz[c]);
+                        const float x = __builtin_fmaf(p[t][i], (float)sv2[e & 1], 0.0f);
+                        xv[t][i][c] = x - __uint_as_float(__float_as_uint(x) & lo_mask);
+                        oz[c] = __builtin_fmaf(pz, (float)zv2[e & 1], oz[c]);
                     }
-            if (part) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-#pragma unroll
-                        for (int c = 0; c < NCG; ++c) {
-                            const int e = i * NCG + c;
-                            const h2v sv2 = as_h2(vsr[t * 2 * NCG + (e >> 1)]);
-                            hv[t][i][c] = (_Float16)__builtin_fmaf(p[t][i], (float)sv2[e & 1], -(float)hv[t][i][c]);
-                        }
-            }
-#pragma unroll
-            for (int c = 0; c < NCG; ++c)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    uint32_t w = 0;
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        union { _Float16 f; uint16_t u; } cv; cv.f = hv[t][i][c];
-                        const int th = (SLOTS == 2) ? slot : t;
-                        w |= (uint32_t)cv.u << (16 * th);
-                    }
-                    pa[c].u[i] = w;
                 }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (SLOTS == 1) {          // both token halves are this lane's: (t = 0 | t = 1)
+#pragma unroll
+                    for (int c = 0; c < NCG; ++c)
+                        pa[c].u[i] = pack_rtz(xv[0][i][c], xv[NT - 1][i][c]);
+                } else if constexpr (NCG == 1) {     // one value, parked in the half of this lane's token slot
+                    pa[0].u[i] = pack_rtz(xv[0][i][0], xv[0][i][0]) & slot_mask;
+                } else {                             // two channel groups per conversion, each moved to the slot's half
+#pragma unroll
+                    for (int c = 0; c < NCG; c += 2) {
+                        const uint32_t pk = pack_rtz(xv[0][i][c], xv[0][i][c + 1]);
+                        pa[c].u[i] = __builtin_amdgcn_perm(pk, pk, sel_even);
+                        pa[c + 1].u[i] = __builtin_amdgcn_perm(pk, pk, sel_odd);
+                    }
+                }
+            }
         }
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8)
