@@ -45,8 +45,8 @@ constexpr int kChunk = 64;          // tokens per wave iteration
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f; // finite stand-in for -inf in running maxima
 // Waves per SIMD the pipelined kernel is compiled for: the 2- and 4-bit variants fit 168 registers
-// (three waves), the 8- and 16-bit ones need more for their wider code words (two waves).
-constexpr int pipe_waves(int bits) { return bits <= 4 ? 3 : 2; }
+// (three waves) up to four query heads per KV head; wider code words or eight heads need more (two waves).
+constexpr int pipe_waves(int bits, int gq) { return (bits <= 4 && gq <= 4) ? 3 : 2; }
 constexpr float kLazyLog2 = 8.0f;   // slack of the lazily updated softmax reference
 constexpr int kPartStride = kHeadDim + 2;  // floats per (partial, head): m, l, acc[128]
 
@@ -801,10 +801,10 @@ template <int BITS, int NCG> struct PipeGeom {
 };
 constexpr int kMergeFloats = kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4);   // wave states of one merge round
 constexpr int kPipeFixedLds = kMergeFloats * 4 + 8 * kHeadDim * 2 + 4 * 64 * 16;   // + the group's query rows, twice (plain, operand layout)
-constexpr int pipe_max_waves(int bits) { return 4 * pipe_waves(bits); }
+constexpr int pipe_max_waves(int bits, int gq) { return 4 * pipe_waves(bits, gq); }
 
 template <int BITS, int GQ, int NCG>
-__global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe(const DecodeArgs a) {
+__global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_pipe(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int NT = (SLOTS == 2) ? 1 : 2;
     constexpr bool QUANT = BITS != 16;
@@ -823,7 +823,11 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
     float* smem = reinterpret_cast<float*>(pipe_lds);
     uint16_t* sq = reinterpret_cast<uint16_t*>(pipe_lds + kMergeFloats * 4);   // the group's query rows (zero rows past GQ), for the z-term product
     uint4* sqpos = reinterpret_cast<uint4*>(pipe_lds + kMergeFloats * 4 + 8 * kHeadDim * 2);   // [slice s][lane]
-    unsigned char* stage_all = pipe_lds + kPipeFixedLds;
+    unsigned char* stage_all = pipe_lds + kPipeFixedLds + (GQ <= 4 ? kWaves * GQ * kPartStride * 4 : 0);
+    // Tail states [wave][head][m, l, o[128]]: a region of their own up to four query heads per KV
+    // head, so that the tail can run first; with eight they share the merge buffer and run last.
+    constexpr bool kTailFirst = GQ <= 4;
+    float* sT = kTailFirst ? reinterpret_cast<float*>(pipe_lds + kPipeFixedLds) : smem;
     const int nw = blockDim.x >> 6;
 
     const int bh = blockIdx.y;
@@ -852,40 +856,6 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
     const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
     const int n_kgroups = QUANT ? a.n_kept / G : 0;
 
-    // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
-    // (head row, channel block kb).  The quantized variants park them in LDS (same for every wave)
-    // and re-read them when a key group's scales arrive; that frees 16 registers in the loop.
-    h2v qpos[QUANT ? 1 : 16];
-    if (!QUANT || wave == 0) {
-        h2v qn[16];
-        const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + 32 * kb;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint4 v = reinterpret_cast<const uint4*>(qp)[i];
-            qn[4 * i] = as_h2(live_row ? v.x : 0u); qn[4 * i + 1] = as_h2(live_row ? v.y : 0u);
-            qn[4 * i + 2] = as_h2(live_row ? v.z : 0u); qn[4 * i + 3] = as_h2(live_row ? v.w : 0u);
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            h2v t[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) t[r] = qn[4 * s + r] * (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
-            if constexpr (QUANT) {
-                sqpos[s * 64 + lane] = make_uint4(as_u32(t[0]), as_u32(t[1]), as_u32(t[2]), as_u32(t[3]));
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) qpos[4 * s + r] = t[r];
-            }
-        }
-    }
-    if constexpr (QUANT) {
-        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += blockDim.x) {
-            const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
-            const uint32_t v = hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
-            reinterpret_cast<uint32_t*>(sq)[item] = v;
-        }
-        __syncthreads();
-    }
     // lane constants of the p*s operand: lo rows subtract the leading bits; a value lands in the
     // half-word of the lane's token slot (byte selectors for v_perm_b32: 0x0c gives a zero byte)
     const uint32_t lo_mask = part ? 0xFFFFE000u : 0u;
@@ -904,10 +874,6 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
     for (int c = 0; c < NCG; ++c) oz[c] = 0.f;
     float m_run = kNegBig, l_run = 0.f;
     Frag bq[4];                       // query-times-scale operand of the current key group
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) bq[s].h[r] = (QUANT || part) ? (h2v){0, 0} : qpos[QUANT ? 0 : 4 * s + r];   // 16-bit cache: plain q in the hi rows
 
     // ---- the two register sets (codes as MFMA operands; one dword per lane of every scale row) ----
     KWords<BITS> ak0, ak1, bk0, bk1;
@@ -1130,7 +1096,51 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
     const int c_begin = blockIdx.x * a.chunks_per_split;
     const int c_end = min(n_chunks, c_begin + a.chunks_per_split);
     int chunk = c_begin + wave;
-    if (chunk < c_end) load_A(chunk);
+    if (chunk < c_end) load_A(chunk);   // issued before anything else waits on memory
+    // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
+    // (head row, channel block kb).  The quantized variants park them in LDS (same for every wave)
+    // and re-read them when a key group's scales arrive; that frees 16 registers in the loop.
+    h2v qpos[QUANT ? 1 : 16];
+    if (!QUANT || wave == 0) {
+        h2v qn[16];
+        const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + 32 * kb;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 v = reinterpret_cast<const uint4*>(qp)[i];
+            qn[4 * i] = as_h2(live_row ? v.x : 0u); qn[4 * i + 1] = as_h2(live_row ? v.y : 0u);
+            qn[4 * i + 2] = as_h2(live_row ? v.z : 0u); qn[4 * i + 3] = as_h2(live_row ? v.w : 0u);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            h2v t[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) t[r] = qn[4 * s + r] * (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
+            if constexpr (QUANT) {
+                sqpos[s * 64 + lane] = make_uint4(as_u32(t[0]), as_u32(t[1]), as_u32(t[2]), as_u32(t[3]));
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) qpos[4 * s + r] = t[r];
+            }
+        }
+    }
+    if constexpr (QUANT) {
+        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += blockDim.x) {
+            const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
+            const uint32_t v = hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
+            reinterpret_cast<uint32_t*>(sq)[item] = v;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bq[s].h[r] = (QUANT || part) ? (h2v){0, 0} : qpos[QUANT ? 0 : 4 * s + r];   // 16-bit cache: plain q in the hi rows
+    // the tail rows go first, while the first blocks are on their way (their state waits in LDS)
+    const int tail_t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
+    const int tail_t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
+    if constexpr (kTailFirst) {
+        if (wave < kWaves) tail_rows<GQ>(a, bh, tail_t0, tail_t1, sT);
+    }
     for (; chunk < c_end; chunk += nw) {
         const int tok0 = chunk * kChunk;
         const bool two = a.n_kept - tok0 >= kChunk;         // n_kept is a multiple of 32
@@ -1226,10 +1236,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS), 1) void decode_attn_pipe
     }
     // this workgroup's share of the full-precision tail rows (first four waves), merged the same way
     {
-        const int t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
-        const int t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
-        float* sT = smem;                              // [wave][head][m, l, o[128]]
-        if (wave < kWaves) tail_rows<GQ>(a, bh, t0, t1, sT);
+        if constexpr (!kTailFirst) {
+            if (wave < kWaves) tail_rows<GQ>(a, bh, tail_t0, tail_t1, sT);
+        }
         __syncthreads();
         if (merger) {
 #pragma unroll
@@ -1288,7 +1297,7 @@ hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t str
     else
     {
         constexpr int strip = PipeGeom<BITS, NCG>::STRIP;
-        const unsigned lds_bytes = kPipeFixedLds + a.n_waves * strip + 16;
+        const unsigned lds_bytes = kPipeFixedLds + (GQ <= 4 ? kWaves * GQ * kPartStride * 4 : 0) + a.n_waves * strip + 16;
         hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG>), grid, dim3(64 * a.n_waves), lds_bytes, stream, a);
     }
     return hipGetLastError();
@@ -1333,7 +1342,7 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         }();
         // Waves a head may use: its share of what the chip holds at this kernel's occupancy, but no
         // fewer than two 64-token chunks per wave (below that the fixed costs win).
-        const int max_nw = pipe_max_waves(cfg.bits);
+        const int max_nw = pipe_max_waves(cfg.bits, gq);
         int waves = (n_cu * max_nw) / heads;
         if (waves > n_chunks / 2) waves = n_chunks / 2;
         int splits, nw;
