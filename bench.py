@@ -216,7 +216,7 @@ def main():
     dom_s, dom_r = settings[dom], sweep[dom]
     tag = f"decode_attn_pipe_{dom_s['bits']}bit_cfg2"
     roofline = {
-        "bound": "hbm", "kernel": f"decode_attn_pipe<{dom_s['bits']} bit> (+ decode_combine, same event window)",
+        "bound": "hbm", "kernel": f"decode_attn_pipe<{dom_s['bits']} bit> (one launch per decode call; HIP events around the {DECODE_STEPS} calls)",
         "achieved": dom_r["decode_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": round(dom_r["decode_gbs"] / PEAK_HBM_GBS, 4), "traffic": read_traffic_note(tag),
         "algorithmic_bytes_per_launch": dom_r["bytes_per_step"], "launch_us": dom_r["decode_us_per_step"],

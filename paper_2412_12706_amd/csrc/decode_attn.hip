@@ -1352,9 +1352,11 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         } else if (waves <= max_nw) {           // one workgroup per head: no partials, no merge across workgroups
             splits = 1;
             nw = waves / kWaves * kWaves;
-        } else {
-            splits = (waves + max_nw - 1) / max_nw;
-            nw = max_nw;
+        } else {                                // several workgroups per head: small ones while CUs are left over
+            nw = (int)((long long)waves * heads / n_cu) / kWaves * kWaves;
+            if (nw > max_nw) nw = max_nw;
+            if (nw < kWaves) nw = kWaves;
+            splits = (waves + nw - 1) / nw;
         }
         if (splits < 1) splits = 1;
         if (nw < kWaves) nw = kWaves;
