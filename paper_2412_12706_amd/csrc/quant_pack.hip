@@ -1,22 +1,44 @@
 // Gather the surviving tokens, quantize them group by group and write the
 // packed cache (paper Section 3, "KV Quantization": z = min, m = max,
 // s = (m - z)/(2^B - 1), Q(G) = round((G - z)/s); grouping axes of Section 2 /
-// Section 5.4).  Memory-bound: every survivor row is read once (2 x 256 B) and
-// k*bpt bytes are written; there is no reuse to exploit, so the kernel's job
-// is coalesced 16-byte row gathers and fully coalesced word stores.
+// Section 5.4).  Memory-bound by design: every survivor row is read once
+// (2 x 256 B) and k*bpt bytes are written; there is no reuse to exploit.
 //
-// One workgroup owns TB consecutive kept tokens of one (batch, kv head):
-// whole key groups (G | TB) and whole value superblocks (SB | TB).
+// One workgroup owns TB consecutive kept tokens of one (batch, kv head): whole
+// key groups (G | TB) and whole value superblocks (SB | TB).  Thread
+// (r = tid / 16, c8 = tid % 16) keeps channels 8 c8 .. 8 c8 + 7 of rows
+// r, r + 16, r + 32, ... in registers from the gather to the packed words:
+//   * minima / maxima are taken on packed 16-bit order keys (two channels per
+//     register), across lanes with DPP / permlane exchanges and across waves
+//     through a few hundred bytes of LDS;
+//   * key words are assembled in registers and stored straight from them
+//     (a word holds consecutive channels of one token);
+//   * value words hold one channel of several tokens (the tile-transposed
+//     layout of kvqp.h): wave kb owns tokens 4 kb + i, lanes OR their fields
+//     together, and the finished superblocks leave through LDS as 16-byte
+//     coalesced stores.
 #include "kvqp_internal.h"
 
 namespace kvqp {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowPad = kHeadDim + 2;  // halves; odd dword stride -> conflict-free column walks
+
+typedef unsigned short us2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {
+    union { uint32_t u; us2v v; } x, y, z; x.u = a; y.u = b; z.v = __builtin_elementwise_min(x.v, y.v); return z.u;
+}
+__device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {
+    union { uint32_t u; us2v v; } x, y, z; x.u = a; y.u = b; z.v = __builtin_elementwise_max(x.v, y.v); return z.u;
+}
 
 // binary16 bit pattern -> key that orders like the value (-0 below +0).
 __device__ __forceinline__ uint32_t order_key(uint16_t h) { return (h & 0x8000u) ? (uint16_t)~h : (uint16_t)(h | 0x8000u); }
+// the same on both halves of a word
+__device__ __forceinline__ uint32_t order_key2(uint32_t w) {
+    const uint32_t neg = (w >> 15) & 0x00010001u;
+    return w ^ (0x80008000u | (neg * 0x7fffu));
+}
 __device__ __forceinline__ uint16_t key_to_half(uint32_t key) { return (key & 0x8000u) ? (uint16_t)(key & 0x7fffu) : (uint16_t)~key; }
 __device__ __forceinline__ float half_bits_to_float(uint16_t h) { return __half2float(__ushort_as_half(h)); }
 
@@ -47,35 +69,87 @@ __device__ __forceinline__ uint32_t encode(uint16_t xh, const GroupParams& g) {
     return (uint32_t)c;
 }
 
-template <int BITS> struct CodeT { using type = uint8_t; };
-template <> struct CodeT<16> { using type = uint16_t; };
+// lane exchanges: partner lane ^ 16 / ^ 32 (both values come back, combine them with any symmetric op)
+#define KVQP_SWAP16(v) __builtin_amdgcn_permlane16_swap((v), (v), false, false)
+#define KVQP_SWAP32(v) __builtin_amdgcn_permlane32_swap((v), (v), false, false)
+template <int CTRL> __device__ __forceinline__ uint32_t dpp(uint32_t v) { return __builtin_amdgcn_update_dpp(0u, v, CTRL, 0xF, 0xF, true); }
+constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E, kRowHalfMirror = 0x141, kRowMirror = 0x140;
 
-// Gather ntok rows (positions sidx[t]) of one head into the LDS tile.
-__device__ __forceinline__ void gather_rows(const uint16_t* __restrict__ src_head, const int* sidx, int ntok,
-                                            uint16_t* tile) {
-    for (int item = threadIdx.x; item < ntok * 16; item += kThreads) {
-        const int t = item >> 4, c = item & 15;
-        const uint4 v = *reinterpret_cast<const uint4*>(src_head + (size_t)sidx[t] * kHeadDim + c * 8);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(tile + t * kRowPad + c * 8);  // 4-byte aligned (kRowPad even)
-        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+// min / max over the LANES consecutive lanes (4, 8 or 16) that share a per-token group
+template <int LANES> __device__ __forceinline__ void group_minmax(uint32_t& mn, uint32_t& mx) {
+    mn = min(mn, dpp<kQuadXor1>(mn)); mx = max(mx, dpp<kQuadXor1>(mx));
+    mn = min(mn, dpp<kQuadXor2>(mn)); mx = max(mx, dpp<kQuadXor2>(mx));
+    if (LANES >= 8) { mn = min(mn, dpp<kRowHalfMirror>(mn)); mx = max(mx, dpp<kRowHalfMirror>(mx)); }
+    if (LANES >= 16) { mn = min(mn, dpp<kRowMirror>(mn)); mx = max(mx, dpp<kRowMirror>(mx)); }
+}
+
+// codes of a thread's eight channels of one row
+template <int BITS>
+__device__ __forceinline__ void encode8(const uint32_t (&w)[4], const float (&zf)[8], const float (&inv)[8], uint32_t (&c)[8]) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        GroupParams g0, g1;
+        g0.zf = zf[2 * q]; g0.inv = inv[2 * q]; g1.zf = zf[2 * q + 1]; g1.inv = inv[2 * q + 1];
+        c[2 * q] = encode<BITS>((uint16_t)(w[q] & 0xffffu), g0);
+        c[2 * q + 1] = encode<BITS>((uint16_t)(w[q] >> 16), g1);
     }
 }
 
-template <int BITS, int TB>
+// Key words of one row from the thread's eight codes (row-major layout of kvqp.h: channel d sits in
+// word d / E at half-word r % 2, field r / 2, r = d % E) and their store.  krow points at the row.
+template <int BITS>
+__device__ __forceinline__ void store_key_words(uint32_t* krow, int c8, const uint32_t (&c)[8]) {
+    constexpr int E = 32 / BITS;
+    if constexpr (E == 8) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int dd = 0; dd < 8; ++dd) w |= c[dd] << (16 * (dd & 1) + BITS * (dd >> 1));
+        krow[c8] = w;
+    } else if constexpr (E == 4) {
+        uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+        for (int dd = 0; dd < 4; ++dd) {
+            w0 |= c[dd] << (16 * (dd & 1) + BITS * (dd >> 1));
+            w1 |= c[4 + dd] << (16 * (dd & 1) + BITS * (dd >> 1));
+        }
+        *reinterpret_cast<uint2*>(krow + 2 * c8) = make_uint2(w0, w1);
+    } else {   // E == 16: the word spans this lane's channels and its neighbour's
+        uint32_t w = 0;
+#pragma unroll
+        for (int dd = 0; dd < 8; ++dd) {
+            const int r = dd;   // position inside the lane's half of the word
+            w |= c[dd] << (16 * (r & 1) + BITS * (r >> 1));
+        }
+        // odd lanes hold channels 8..15 of the word: fields 4..7 of each half-word
+        if (c8 & 1) w <<= 4 * BITS;
+        w |= dpp<kQuadXor1>(w);
+        if (!(c8 & 1)) krow[c8 >> 1] = w;
+    }
+}
+
+template <int BITS, int G>
 __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, const int32_t* __restrict__ idx,
     uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale,
     uint16_t* __restrict__ k_zero, uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero,
-    uint16_t* __restrict__ tail_k, uint16_t* __restrict__ tail_v, int L, int W, int n_kept, int G, int key_axis,
+    uint16_t* __restrict__ tail_k, uint16_t* __restrict__ tail_v, int L, int W, int n_kept, int key_axis,
     int tail_cap, int n_tok_blocks) {
-    using code_t = typename CodeT<BITS>::type;
+    constexpr bool QUANT = BITS != 16;
+    constexpr int TB = (QUANT && G == 128) ? 128 : 64;   // tokens per workgroup
+    constexpr int R = TB / 16;                            // rows per thread
+    constexpr int NG = TB / G > 0 ? TB / G : 1;           // per-channel key groups per workgroup
+    constexpr int JPG = G / 16;                           // a thread's rows per key group
+    constexpr int CPT = kHeadDim / G;                     // per-token groups per row
+    constexpr int GL = G / 8;                             // lanes per per-token group
     constexpr int E = 32 / BITS;
     constexpr int SB = v_superblock(BITS);
     constexpr int WPT = v_words_per_tile(BITS);
     constexpr int SBW = v_superblock_words(BITS);
-    __shared__ __align__(16) uint16_t tile[TB * kRowPad];
-    __shared__ __align__(16) code_t cbuf[TB * kHeadDim];
-    __shared__ int sidx[TB];
+    constexpr int NSB = TB / SB;
+    __shared__ __align__(16) uint32_t s_words[NSB * SBW];                 // finished value superblocks
+    __shared__ __align__(16) uint16_t s_min[QUANT ? 4 * NG * kHeadDim : 8];   // per wave: channel minima / maxima (order keys)
+    __shared__ __align__(16) uint16_t s_max[QUANT ? 4 * NG * kHeadDim : 8];
+    __shared__ __align__(16) float2 s_par[QUANT ? NG * kHeadDim : 1];     // (z, 1/s) per (key group, channel)
 
     const int head = blockIdx.y;
     const uint16_t* kh = k + (size_t)head * L * kHeadDim;
@@ -93,127 +167,227 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         return;
     }
 
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c8 = threadIdx.x & 15, r = threadIdx.x >> 4, i4 = (threadIdx.x >> 4) & 3;
     const int t0 = blockIdx.x * TB;
-    const int ntok = min(TB, n_kept - t0);
-    for (int t = threadIdx.x; t < ntok; t += kThreads) sidx[t] = idx[(size_t)head * n_kept + t0 + t];
-    __syncthreads();
+    const int ntok = min(TB, n_kept - t0);   // a multiple of 32 (and of G for per-channel keys)
+
+    // ---- gather: all of the thread's rows of both tensors are requested before anything is used ----
+    uint32_t kw[R][4], vw[R][4];
+    bool live[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int t = r + 16 * j;
+        live[j] = t < ntok;
+        const int pos = live[j] ? idx[(size_t)head * n_kept + t0 + t] : 0;
+        const uint4 a = live[j] ? *reinterpret_cast<const uint4*>(kh + (size_t)pos * kHeadDim + 8 * c8) : make_uint4(0, 0, 0, 0);
+        const uint4 b = live[j] ? *reinterpret_cast<const uint4*>(vh + (size_t)pos * kHeadDim + 8 * c8) : make_uint4(0, 0, 0, 0);
+        kw[j][0] = a.x; kw[j][1] = a.y; kw[j][2] = a.z; kw[j][3] = a.w;
+        vw[j][0] = b.x; vw[j][1] = b.y; vw[j][2] = b.z; vw[j][3] = b.w;
+    }
+
+    // Per-token groups (values always, keys on that axis): every row is complete inside GL lanes.
+    // Fills the codes of all rows and stores scale / zero.  Lane q of a quad derives the parameters
+    // of rows q, q + 4, ... and hands them to the other three.
+    auto per_token = [&](const uint32_t (&w)[R][4], uint16_t* scale, uint16_t* zero, uint32_t (&codes)[R][8]) {
+        uint32_t mn[R], mx[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            uint32_t a = order_key2(w[j][0]), lo = a, hi = a;
+#pragma unroll
+            for (int q = 1; q < 4; ++q) { a = order_key2(w[j][q]); lo = pk_min(lo, a); hi = pk_max(hi, a); }
+            mn[j] = min(lo & 0xffffu, lo >> 16); mx[j] = max(hi & 0xffffu, hi >> 16);
+            group_minmax<GL>(mn[j], mx[j]);
+        }
+        const int q4 = c8 & 3;
+#pragma unroll
+        for (int jj = 0; jj < R / 4; ++jj) {
+            const uint32_t a = q4 == 0 ? mn[4 * jj] : q4 == 1 ? mn[4 * jj + 1] : q4 == 2 ? mn[4 * jj + 2] : mn[4 * jj + 3];
+            const uint32_t b = q4 == 0 ? mx[4 * jj] : q4 == 1 ? mx[4 * jj + 1] : q4 == 2 ? mx[4 * jj + 2] : mx[4 * jj + 3];
+            const GroupParams gp = group_params<BITS>(a, b);
+            const int t = r + 16 * (4 * jj + q4);
+            if (t < ntok && (c8 & (GL - 1)) < 4) {
+                const size_t m = ((size_t)head * n_kept + t0 + t) * CPT + c8 / GL;
+                scale[m] = gp.scale_h; zero[m] = gp.zero_h;
+            }
+            const uint32_t zb = __float_as_uint(gp.zf), ib = __float_as_uint(gp.inv);
+            const uint32_t zq[4] = {dpp<0x00>(zb), dpp<0x55>(zb), dpp<0xAA>(zb), dpp<0xFF>(zb)};
+            const uint32_t iq[4] = {dpp<0x00>(ib), dpp<0x55>(ib), dpp<0xAA>(ib), dpp<0xFF>(ib)};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float zf[8], inv[8];
+#pragma unroll
+                for (int dd = 0; dd < 8; ++dd) { zf[dd] = __uint_as_float(zq[u]); inv[dd] = __uint_as_float(iq[u]); }
+                encode8<BITS>(w[4 * jj + u], zf, inv, codes[4 * jj + u]);
+            }
+        }
+    };
 
     // ---------------- keys ----------------
-    gather_rows(kh, sidx, ntok, tile);
-    __syncthreads();
     uint32_t* kc_head = k_codes + (size_t)head * ((size_t)n_kept * kHeadDim / E);
-    if constexpr (BITS == 16) {
-        for (int item = threadIdx.x; item < ntok * (kHeadDim / 2); item += kThreads) {
-            const int t = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
-            kc_head[(size_t)(t0 + t) * (kHeadDim / 2) + w] = *reinterpret_cast<const uint32_t*>(tile + t * kRowPad + 2 * w);
-        }
-    } else {
-        if (key_axis == KVQP_KEY_PER_CHANNEL) {
-            const int d = threadIdx.x & (kHeadDim - 1);
-            for (int ug = threadIdx.x / kHeadDim; ug < ntok / G; ug += kThreads / kHeadDim) {
-                uint32_t kmin = 0xffffu, kmax = 0u;
-                for (int e = 0; e < G; ++e) {
-                    const uint32_t key = order_key(tile[(ug * G + e) * kRowPad + d]);
-                    kmin = min(kmin, key); kmax = max(kmax, key);
+    if constexpr (!QUANT) {
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (live[j])
+                *reinterpret_cast<uint4*>(kc_head + (size_t)(t0 + r + 16 * j) * (kHeadDim / 2) + 4 * c8) = make_uint4(kw[j][0], kw[j][1], kw[j][2], kw[j][3]);
+    } else if (key_axis == KVQP_KEY_PER_CHANNEL) {
+        // minima / maxima per channel over the G tokens of a group: own rows, the four row lanes of
+        // the wave (lane ^ 16, ^ 32), then the four waves through LDS
+        uint32_t pmin[NG][4], pmax[NG][4];
+#pragma unroll
+        for (int ug = 0; ug < NG; ++ug)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { pmin[ug][q] = 0xffffffffu; pmax[ug][q] = 0u; }
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (live[j]) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t a = order_key2(kw[j][q]);
+                    pmin[j / JPG][q] = pk_min(pmin[j / JPG][q], a); pmax[j / JPG][q] = pk_max(pmax[j / JPG][q], a);
                 }
-                const GroupParams gp = group_params<BITS>(kmin, kmax);
-                const size_t m = ((size_t)head * (n_kept / G) + (t0 / G + ug)) * kHeadDim + d;
-                k_scale[m] = gp.scale_h; k_zero[m] = gp.zero_h;
-                for (int e = 0; e < G; ++e)
-                    cbuf[(ug * G + e) * kHeadDim + d] = (code_t)encode<BITS>(tile[(ug * G + e) * kRowPad + d], gp);
             }
-        } else {
-            const int cpt = kHeadDim / G;
-            for (int item = threadIdx.x; item < ntok * cpt; item += kThreads) {
-                const int t = item / cpt, cg = item % cpt;
-                uint32_t kmin = 0xffffu, kmax = 0u;
-                for (int e = 0; e < G; ++e) {
-                    const uint32_t key = order_key(tile[t * kRowPad + cg * G + e]);
-                    kmin = min(kmin, key); kmax = max(kmax, key);
-                }
-                const GroupParams gp = group_params<BITS>(kmin, kmax);
-                const size_t m = ((size_t)head * n_kept + t0 + t) * cpt + cg;
-                k_scale[m] = gp.scale_h; k_zero[m] = gp.zero_h;
-                for (int e = 0; e < G; ++e)
-                    cbuf[t * kHeadDim + cg * G + e] = (code_t)encode<BITS>(tile[t * kRowPad + cg * G + e], gp);
+#pragma unroll
+        for (int ug = 0; ug < NG; ++ug)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                auto s1 = KVQP_SWAP16(pmin[ug][q]); uint32_t a = pk_min(s1[0], s1[1]);
+                auto s2 = KVQP_SWAP32(a); pmin[ug][q] = pk_min(s2[0], s2[1]);
+                auto s3 = KVQP_SWAP16(pmax[ug][q]); uint32_t b = pk_max(s3[0], s3[1]);
+                auto s4 = KVQP_SWAP32(b); pmax[ug][q] = pk_max(s4[0], s4[1]);
+            }
+        if (lane < 16) {
+#pragma unroll
+            for (int ug = 0; ug < NG; ++ug) {
+                *reinterpret_cast<uint4*>(s_min + (wave * NG + ug) * kHeadDim + 8 * c8) = make_uint4(pmin[ug][0], pmin[ug][1], pmin[ug][2], pmin[ug][3]);
+                *reinterpret_cast<uint4*>(s_max + (wave * NG + ug) * kHeadDim + 8 * c8) = make_uint4(pmax[ug][0], pmax[ug][1], pmax[ug][2], pmax[ug][3]);
             }
         }
         __syncthreads();
-        constexpr int WPR = kHeadDim / E;  // words per key row
-        for (int item = threadIdx.x; item < ntok * WPR; item += kThreads) {
-            const int t = item / WPR, w = item % WPR;
-            uint32_t word = 0;
+        for (int item = threadIdx.x; item < NG * kHeadDim; item += kThreads) {   // one (group, channel) each
+            const int ug = item / kHeadDim, d = item % kHeadDim;
+            uint32_t a = 0xffffu, b = 0u;
 #pragma unroll
-            for (int r = 0; r < E; ++r)
-                word |= (uint32_t)cbuf[t * kHeadDim + w * E + r] << (16 * (r & 1) + BITS * (r >> 1));
-            kc_head[(size_t)(t0 + t) * WPR + w] = word;
+            for (int w = 0; w < 4; ++w) {
+                a = min(a, (uint32_t)s_min[(w * NG + ug) * kHeadDim + d]);
+                b = max(b, (uint32_t)s_max[(w * NG + ug) * kHeadDim + d]);
+            }
+            const GroupParams gp = group_params<BITS>(a, b);
+            s_par[item] = make_float2(gp.zf, gp.inv);
+            if (ug * G < ntok) {
+                const size_t m = ((size_t)head * (n_kept / G) + (t0 / G + ug)) * kHeadDim + d;
+                k_scale[m] = gp.scale_h; k_zero[m] = gp.zero_h;
+            }
         }
+        __syncthreads();
+#pragma unroll
+        for (int ug = 0; ug < NG; ++ug) {
+            float zf[8], inv[8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 pr = *reinterpret_cast<const float4*>(&s_par[ug * kHeadDim + 8 * c8 + 2 * q]);
+                zf[2 * q] = pr.x; inv[2 * q] = pr.y; zf[2 * q + 1] = pr.z; inv[2 * q + 1] = pr.w;
+            }
+#pragma unroll
+            for (int jl = 0; jl < JPG && ug * JPG + jl < R; ++jl) {
+                const int j = ug * JPG + jl;
+                uint32_t c[8];
+                encode8<BITS>(kw[j], zf, inv, c);
+                if (live[j]) store_key_words<BITS>(kc_head + (size_t)(t0 + r + 16 * j) * (kHeadDim / E), c8, c);
+            }
+        }
+    } else {
+        uint32_t codes[R][8];
+        per_token(kw, k_scale, k_zero, codes);
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (live[j]) store_key_words<BITS>(kc_head + (size_t)(t0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
     }
-    __syncthreads();
 
     // ---------------- values ----------------
-    gather_rows(vh, sidx, ntok, tile);
-    __syncthreads();
-    if constexpr (BITS == 16) {
-        for (int item = threadIdx.x; item < ntok * kHeadDim; item += kThreads)
-            cbuf[item] = tile[(item / kHeadDim) * kRowPad + (item % kHeadDim)];
-    } else {
-        const int cpt = kHeadDim / G;
-        for (int item = threadIdx.x; item < ntok * cpt; item += kThreads) {
-            const int t = item / cpt, cg = item % cpt;
-            uint32_t kmin = 0xffffu, kmax = 0u;
-            for (int e = 0; e < G; ++e) {
-                const uint32_t key = order_key(tile[t * kRowPad + cg * G + e]);
-                kmin = min(kmin, key); kmax = max(kmax, key);
-            }
-            const GroupParams gp = group_params<BITS>(kmin, kmax);
-            const size_t m = ((size_t)head * n_kept + t0 + t) * cpt + cg;
-            v_scale[m] = gp.scale_h; v_zero[m] = gp.zero_h;
-            for (int e = 0; e < G; ++e)
-                cbuf[t * kHeadDim + cg * G + e] = (code_t)encode<BITS>(tile[t * kRowPad + cg * G + e], gp);
-        }
-    }
-    __syncthreads();
+    // Token t = r + 16 j = 32 (j / 2) + 16 (j % 2) + 4 wave + i4: half-word H = j % 2, 32-token block
+    // j / 2, kb = wave, i = i4.  A lane's field of word (superblock, kb, channel, wl) sits at
+    // 16 H + BITS p with run = 4 blk + i4 = wl (E/2) + p; lanes of equal wl OR their fields together.
     {
-        const int n_sb = (ntok + SB - 1) / SB;
-        uint32_t* vc = v_codes + (size_t)head * v_superblock_words(BITS) * ((n_kept + SB - 1) / SB) + (size_t)(t0 / SB) * SBW;
-        for (int item = threadIdx.x; item < n_sb * SBW; item += kThreads) {
-            const int sbl = item / SBW, wsb = item % SBW;
-            const int y = 4 * (wsb >> 8) + (wsb & 3), lane = (wsb >> 2) & 63;
-            const int kb = lane >> 4, n = lane & 15, tl = y / WPT, wl = y % WPT;
-            const int d = 16 * tl + n;
-            uint32_t word = 0;
+        uint32_t part[NSB][8];
 #pragma unroll
-            for (int H = 0; H < 2; ++H)
+        for (int sb = 0; sb < NSB; ++sb)
 #pragma unroll
-                for (int p = 0; p < E / 2; ++p) {
-                    const int run = wl * (E / 2) + p;
-                    const int t = sbl * SB + 32 * (run >> 2) + 16 * H + 4 * kb + (run & 3);
-                    const uint32_t c = (t < ntok) ? (uint32_t)cbuf[t * kHeadDim + d] : 0u;
-                    word |= c << (16 * H + BITS * p);
+            for (int dd = 0; dd < 8; ++dd) part[sb][dd] = 0u;
+        if constexpr (QUANT) {
+            uint32_t codes[R][8];
+            per_token(vw, v_scale, v_zero, codes);
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const int b32 = j >> 1, H = j & 1;
+                const int sb = (32 * b32) / SB, blk = b32 % (SB / 32);
+                const int p = (4 * blk + i4) % (E / 2);
+#pragma unroll
+                for (int dd = 0; dd < 8; ++dd) part[sb][dd] |= live[j] ? codes[j][dd] << (16 * H + BITS * p) : 0u;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const int sb = j >> 1, H = j & 1;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    part[sb][2 * q] |= (vw[j][q] & 0xffffu) << (16 * H);
+                    part[sb][2 * q + 1] |= (vw[j][q] >> 16) << (16 * H);
                 }
-            vc[item] = word;
+            }
         }
+        constexpr int LANES_PER_WORD = (E / 2 >= 4) ? 4 : E / 2;   // row lanes whose fields share a word
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb)
+#pragma unroll
+            for (int dd = 0; dd < 8; ++dd) {
+                if (LANES_PER_WORD >= 2) { auto s1 = KVQP_SWAP16(part[sb][dd]); part[sb][dd] = s1[0] | s1[1]; }
+                if (LANES_PER_WORD >= 4) { auto s2 = KVQP_SWAP32(part[sb][dd]); part[sb][dd] = s2[0] | s2[1]; }
+            }
+        const int wl = (E / 2 >= 4) ? 0 : i4 / (E / 2);          // run / (E/2) with blk = 0 (SB = 32 whenever E/2 < 4)
+        const bool writer = (i4 % LANES_PER_WORD) == 0;
+        if (writer) {
+            const int tile = c8 >> 1, y = tile * WPT + wl;
+#pragma unroll
+            for (int sb = 0; sb < NSB; ++sb)
+#pragma unroll
+                for (int dd = 0; dd < 8; ++dd) {
+                    const int n = 8 * (c8 & 1) + dd;
+                    s_words[sb * SBW + ((y >> 2) * 64 + wave * 16 + n) * 4 + (y & 3)] = part[sb][dd];
+                }
+        }
+        __syncthreads();
+        const int n_sb = (ntok + SB - 1) / SB;
+        uint32_t* vc = v_codes + (size_t)head * SBW * ((n_kept + SB - 1) / SB) + (size_t)(t0 / SB) * SBW;
+        for (int item = threadIdx.x; item < n_sb * SBW / 4; item += kThreads)
+            reinterpret_cast<uint4*>(vc)[item] = reinterpret_cast<const uint4*>(s_words)[item];
     }
 }
+#undef KVQP_SWAP16
+#undef KVQP_SWAP32
 
+template <int BITS, int G>
+hipError_t launch_bits_g(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx, int n_kept,
+                         const kvqp_cache& c, hipStream_t stream) {
+    constexpr int TB = (BITS != 16 && G == 128) ? 128 : 64;
+    const int heads = cfg.batch * cfg.n_kv_heads;
+    const int nblk = (n_kept + TB - 1) / TB;
+    dim3 grid(nblk + 1, heads);
+    hipLaunchKernelGGL((gather_quant_pack<BITS, G>), grid, dim3(kThreads), 0, stream, (const uint16_t*)k,
+                       (const uint16_t*)v, idx, (uint32_t*)c.k_codes, (uint32_t*)c.v_codes, (uint16_t*)c.k_scale,
+                       (uint16_t*)c.k_zero, (uint16_t*)c.v_scale, (uint16_t*)c.v_zero, (uint16_t*)c.tail_k,
+                       (uint16_t*)c.tail_v, cfg.seq_len, cfg.window, n_kept, cfg.key_axis, c.tail_cap, nblk);
+    return hipGetLastError();
+}
 template <int BITS>
 hipError_t launch_bits(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx, int n_kept,
                        const kvqp_cache& c, hipStream_t stream) {
-    const int heads = cfg.batch * cfg.n_kv_heads;
-    auto go = [&](auto tb_tag) {
-        constexpr int TB = decltype(tb_tag)::value;
-        const int nblk = (n_kept + TB - 1) / TB;
-        dim3 grid(nblk + 1, heads);
-        hipLaunchKernelGGL((gather_quant_pack<BITS, TB>), grid, dim3(kThreads), 0, stream, (const uint16_t*)k,
-                           (const uint16_t*)v, idx, (uint32_t*)c.k_codes, (uint32_t*)c.v_codes, (uint16_t*)c.k_scale,
-                           (uint16_t*)c.k_zero, (uint16_t*)c.v_scale, (uint16_t*)c.v_zero, (uint16_t*)c.tail_k,
-                           (uint16_t*)c.tail_v, cfg.seq_len, cfg.window, n_kept, cfg.group_size, cfg.key_axis,
-                           c.tail_cap, nblk);
-    };
-    if (cfg.bits != 16 && cfg.group_size == 128) go(std::integral_constant<int, 128>{});
-    else go(std::integral_constant<int, 64>{});
-    return hipGetLastError();
+    if (BITS == 16) return launch_bits_g<BITS, 32>(cfg, k, v, idx, n_kept, c, stream);
+    switch (cfg.group_size) {
+        case 32: return launch_bits_g<BITS, 32>(cfg, k, v, idx, n_kept, c, stream);
+        case 64: return launch_bits_g<BITS, 64>(cfg, k, v, idx, n_kept, c, stream);
+        default: return launch_bits_g<BITS, 128>(cfg, k, v, idx, n_kept, c, stream);
+    }
 }
 
 }  // namespace
