@@ -32,11 +32,13 @@ union Frag {
 };
 
 constexpr int kThreads = 256;
-constexpr int kRowsPerWave = 64;        // query rows one wave owns (4 MFMA row tiles)
-constexpr int kMT = kRowsPerWave / 16;
+// Query rows one wave owns (its MFMA A operands, register-resident): 32 when the group has up to
+// 128 window rows (small register footprint, four waves per SIMD), else 64.
+constexpr int rows_per_wave(int rows) { return rows <= 128 ? 32 : 64; }
 constexpr int kKeyStride = kHeadDim * 2 + 16;  // LDS bytes per key row; +16 B skews banks
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;
+constexpr float kLazy = 8.0f;           // pass 1 moves a row's reference only when a score beats it by 2^8
 
 enum { PASS_STATS = 0, PASS_VOTES = 1 };
 
@@ -47,7 +49,7 @@ struct ScoreArgs {
     const float2* stats;    // [heads, rows_pad]           (m, 1/Z)
     float* vote;            // [heads, P]
     int L, W, P, gq, n_q_heads, n_kv_heads;
-    int rows, rows_pad;     // Gq*W and its multiple of 64
+    int rows, rows_pad;     // Gq*W and the rows the waves cover (a multiple of 32 or 64)
     int chunks_per_wg, n_chunks, n_parts;
     float scale_log2;       // sm_scale * log2(e)
 };
@@ -59,8 +61,9 @@ template <int NRW> struct ScoreGeom {
     static constexpr int KT = CK / (16 * KS);         // key tiles per wave per chunk
 };
 
-template <int NRW, int PASS>
-__global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
+template <int RPW, int NRW, int PASS>
+__global__ __launch_bounds__(kThreads, RPW == 32 ? 4 : 2) void score_pass(const ScoreArgs a) {
+    constexpr int kRowsPerWave = RPW, kMT = RPW / 16;
     using Gm = ScoreGeom<NRW>;
     constexpr int KS = Gm::KS, CK = Gm::CK, KT = Gm::KT;
     __shared__ __align__(16) unsigned char sk[CK * kKeyStride];
@@ -68,7 +71,8 @@ __global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
 
     const int head = blockIdx.y;
     const int b = head / a.n_kv_heads, g = head % a.n_kv_heads;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tile positions stay uniform
     const int n = lane & 15, kb = lane >> 4;
     const int rw = wave % NRW, ks = wave / NRW;
     const uint16_t* kh = a.k + (size_t)head * a.L * kHeadDim;
@@ -86,17 +90,7 @@ __global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
             qf[mt][s].q = live ? *reinterpret_cast<const uint4*>(qp + 32 * s) : make_uint4(0, 0, 0, 0);
         }
     }
-    // Window position of each accumulator row this lane holds: row 64rw+16mt+4kb+i.
-    int wrow[kMT][4];
-#pragma unroll
-    for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = kRowsPerWave * rw + 16 * mt + 4 * kb + i;
-            wrow[mt][i] = (r < a.rows) ? r % a.W : -1;   // -1: padding row, sees nothing beyond the prefix
-        }
-
-    float m_run[kMT][4], z_run[kMT][4];   // STATS: running max / sum.  VOTES: m and 1/Z of the row.
+    float m_run[kMT][4], z_run[kMT][4];   // STATS: reference (log2 domain) and sum of exp2(score - reference).  VOTES: m and 1/Z of the row.
 #pragma unroll
     for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
@@ -135,66 +129,86 @@ __global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
         const int key0 = chunk * CK;
         KVQP_ISSUE(min(chunk + 1, c_end - 1))
 
-        f4v acc[kMT][KT];
+        // one 16-key tile at a time keeps the accumulators at 16 registers
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
             Frag kf[4];
             const unsigned char* kp = sk + (16 * (ks * KT + kt) + n) * kKeyStride + 16 * kb;
 #pragma unroll
             for (int s = 0; s < 4; ++s) kf[s].q = *reinterpret_cast<const uint4*>(kp + 64 * s);
+            f4v acc[kMT];
 #pragma unroll
             for (int mt = 0; mt < kMT; ++mt) {
                 f4v c = (f4v){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) c = __builtin_amdgcn_mfma_f32_16x16x32_f16(qf[mt][s].v, kf[s].v, c, 0, 0, 0);
-                acc[mt][kt] = c;
+                acc[mt] = c;
             }
-        }
-        // causal mask only where the chunk reaches the window (raw scores; the scale is positive)
-        if (key0 + CK > a.P) {
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int key = key0 + 16 * (ks * KT + kt) + n;
-                        if (key > a.P + wrow[mt][i] || key >= a.L) acc[mt][kt][i] = -INFINITY;
-                    }
-        }
-
-        if (PASS == PASS_STATS) {
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float raw = acc[mt][0][i];
-#pragma unroll
-                    for (int kt = 1; kt < KT; ++kt) raw = fmaxf(raw, acc[mt][kt][i]);
-                    const float mx = fmaxf(m_run[mt][i], raw * a.scale_log2);   // log2-domain running maximum
-                    float z = z_run[mt][i] * __builtin_amdgcn_exp2f(m_run[mt][i] - mx);
-#pragma unroll
-                    for (int kt = 0; kt < KT; ++kt) z += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[mt][kt][i], a.scale_log2, -mx));
-                    m_run[mt][i] = mx; z_run[mt][i] = z;
-                }
-            __syncthreads();                 // all waves are done with this chunk's keys
-        } else {
-            // normalised probabilities summed over this wave's 64 rows, per key
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt) {
-                float col = 0.f;
+            // causal mask only where the tile reaches the window (raw scores; the scale is positive)
+            const int tile0 = key0 + 16 * (ks * KT + kt);
+            if (tile0 + 16 > a.P) {
+                const int key = tile0 + n;
+                int w = a.W;
+                asm volatile("" : "+s"(w));   // keeps the window positions out of the loop's live registers
 #pragma unroll
                 for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        col = __builtin_fmaf(__builtin_amdgcn_exp2f(__builtin_fmaf(acc[mt][kt][i], a.scale_log2, -m_run[mt][i])),
-                                             z_run[mt][i], col);
+                    for (int i = 0; i < 4; ++i) {
+                        const int r = kRowsPerWave * rw + 16 * mt + 4 * kb + i;
+                        const int wr = (r < a.rows) ? r % w : -1;   // padding rows see the prefix only
+                        if (key > a.P + wr || key >= a.L) acc[mt][i] = -INFINITY;
+                    }
+            }
+            if (PASS == PASS_STATS) {
+                // m_run is a reference, not the exact maximum: it moves only when a score beats it
+                // by more than 2^kLazy, so the common path is one fused multiply-add and one exp2
+                float e[kMT][4];
+                float big = -INFINITY;
+#pragma unroll
+                for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        e[mt][i] = __builtin_fmaf(acc[mt][i], a.scale_log2, -m_run[mt][i]);
+                        big = fmaxf(big, e[mt][i]);
+                    }
+                if (__builtin_amdgcn_ballot_w64(big > kLazy) != 0ull) {   // rare after the first tiles
+#pragma unroll
+                    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float sc = acc[mt][i] * a.scale_log2;
+                            if (sc > m_run[mt][i]) {
+                                z_run[mt][i] *= __builtin_amdgcn_exp2f(m_run[mt][i] - sc);
+                                m_run[mt][i] = sc;
+                            }
+                            e[mt][i] = __builtin_fmaf(acc[mt][i], a.scale_log2, -m_run[mt][i]);
+                        }
+                }
+#pragma unroll
+                for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) z_run[mt][i] += __builtin_amdgcn_exp2f(e[mt][i]);
+            } else {
+                // normalised probabilities summed over this wave's 64 rows, per key
+                float c0 = 0.f, c1 = 0.f;
+#pragma unroll
+                for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 4; i += 2) {
+                        c0 = __builtin_fmaf(__builtin_amdgcn_exp2f(__builtin_fmaf(acc[mt][i], a.scale_log2, -m_run[mt][i])),
+                                            z_run[mt][i], c0);
+                        c1 = __builtin_fmaf(__builtin_amdgcn_exp2f(__builtin_fmaf(acc[mt][i + 1], a.scale_log2, -m_run[mt][i + 1])),
+                                            z_run[mt][i + 1], c1);
+                    }
+                float col = c0 + c1;
                 // rows 4kb+i of all four lane quads
                 col += __shfl_xor(col, 16);
                 col += __shfl_xor(col, 32);
                 if (kb == 0) svote[rw * CK + 16 * (ks * KT + kt) + n] = col;
             }
-            __syncthreads();                 // votes of all row slabs parked; keys of this chunk consumed
+        }
+        __syncthreads();                 // all waves are done with this chunk's keys (and votes are parked)
+        if (PASS == PASS_VOTES) {
             for (int kk = threadIdx.x; kk < CK; kk += kThreads) {
                 float v = 0.f;
 #pragma unroll
@@ -230,19 +244,27 @@ __global__ __launch_bounds__(kThreads) void score_pass(const ScoreArgs a) {
     }
 }
 
-// Merge the per-part row statistics; Z is accumulated in binary64.
-__global__ void stats_combine(const float2* __restrict__ part, float2* __restrict__ stats, double* __restrict__ zsum,
-                              int n_parts, int rows_pad) {
+// Merge the per-part row statistics; Z is accumulated in binary64.  One wave per row (four rows
+// per workgroup): lanes stride over the parts, then a fixed-order butterfly.
+__global__ __launch_bounds__(256) void stats_combine(const float2* __restrict__ part, float2* __restrict__ stats,
+                                                     double* __restrict__ zsum, int n_parts, int rows_pad) {
     const int head = blockIdx.x;
-    for (int r = threadIdx.x; r < rows_pad; r += blockDim.x) {
-        const float2* p = part + (size_t)head * n_parts * rows_pad + r;
-        float M = kNegBig;
-        for (int s = 0; s < n_parts; ++s) M = fmaxf(M, p[(size_t)s * rows_pad].x);
-        double Z = 0.0;
-        for (int s = 0; s < n_parts; ++s) {
-            const float2 v = p[(size_t)s * rows_pad];
-            Z += (double)v.y * (double)exp2f(v.x - M);
-        }
+    const int lane = threadIdx.x & 63;
+    const int r = 4 * blockIdx.y + (threadIdx.x >> 6);
+    if (r >= rows_pad) return;
+    const float2* p = part + (size_t)head * n_parts * rows_pad + r;
+    float M = kNegBig;
+    for (int s = lane; s < n_parts; s += 64) M = fmaxf(M, p[(size_t)s * rows_pad].x);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    double Z = 0.0;
+    for (int s = lane; s < n_parts; s += 64) {
+        const float2 v = p[(size_t)s * rows_pad];
+        Z += (double)v.y * (double)exp2f(v.x - M);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) Z += __shfl_xor(Z, off);
+    if (lane == 0) {
         stats[(size_t)head * rows_pad + r] = make_float2(M, Z > 0.0 ? (float)(1.0 / Z) : 0.f);
         zsum[(size_t)head * rows_pad + r] = Z;
     }
@@ -632,17 +654,18 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 int n_row_slabs(const kvqp_cfg& cfg) {
     const int rows = (cfg.n_q_heads / cfg.n_kv_heads) * cfg.window;
-    const int slabs = (rows + kRowsPerWave - 1) / kRowsPerWave;
+    const int rpw = rows_per_wave(rows);
+    const int slabs = (rows + rpw - 1) / rpw;
     return slabs <= 1 ? 1 : slabs == 2 ? 2 : 4;
 }
 
-template <int NRW>
+template <int RPW, int NRW>
 hipError_t launch_scores(const ScoreArgs& a, int n_wg, int heads, hipStream_t stream, float2* stats, double* zsum) {
     ScoreArgs s1 = a;
-    hipLaunchKernelGGL((score_pass<NRW, PASS_STATS>), dim3(n_wg, heads), dim3(kThreads), 0, stream, s1);
-    hipLaunchKernelGGL(stats_combine, dim3(heads), dim3(256), 0, stream, (const float2*)a.stats_part, stats, zsum,
+    hipLaunchKernelGGL((score_pass<RPW, NRW, PASS_STATS>), dim3(n_wg, heads), dim3(kThreads), 0, stream, s1);
+    hipLaunchKernelGGL(stats_combine, dim3(heads, (a.rows_pad + 3) / 4), dim3(256), 0, stream, (const float2*)a.stats_part, stats, zsum,
                        a.n_parts, a.rows_pad);
-    hipLaunchKernelGGL((score_pass<NRW, PASS_VOTES>), dim3(n_wg, heads), dim3(kThreads), 0, stream, s1);
+    hipLaunchKernelGGL((score_pass<RPW, NRW, PASS_VOTES>), dim3(n_wg, heads), dim3(kThreads), 0, stream, s1);
     return hipGetLastError();
 }
 
@@ -654,7 +677,7 @@ CompressPlan plan_compress(const kvqp_cfg& cfg) {
     p.n_kept = cfg.budget < p.P ? cfg.budget : p.P;
     p.rows = (cfg.n_q_heads / cfg.n_kv_heads) * cfg.window;
     const int nrw = n_row_slabs(cfg);
-    const int rows_pad = nrw * kRowsPerWave;
+    const int rows_pad = nrw * rows_per_wave(p.rows);
     const int ks = 4 / nrw, ck = (ks == 1) ? 64 : 128;
     const int heads = cfg.batch * cfg.n_kv_heads;
     p.n_chunks = (cfg.seq_len + ck - 1) / ck;
@@ -689,7 +712,7 @@ hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, 
     a.q_obs = (const uint16_t*)q_obs; a.k = (const uint16_t*)k;
     a.stats_part = reinterpret_cast<float2*>(base + plan.off_stats_part);
     float2* stats = reinterpret_cast<float2*>(base + plan.off_stats);
-    a.rows = plan.rows; a.rows_pad = nrw * kRowsPerWave;
+    a.rows = plan.rows; a.rows_pad = nrw * rows_per_wave(plan.rows);
     double* zsum = reinterpret_cast<double*>(base + plan.off_stats + (size_t)heads * a.rows_pad * sizeof(float2));
     a.stats = stats;
     a.vote = reinterpret_cast<float*>(base + plan.off_vote);
@@ -700,10 +723,14 @@ hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, 
 
     hipError_t e;
     if (plan.n_kept < plan.P) {   // scores are needed only when something is dropped
-        switch (nrw) {
-            case 1: e = launch_scores<1>(a, n_wg, heads, stream, stats, zsum); break;
-            case 2: e = launch_scores<2>(a, n_wg, heads, stream, stats, zsum); break;
-            default: e = launch_scores<4>(a, n_wg, heads, stream, stats, zsum); break;
+        if (rows_per_wave(plan.rows) == 32) {
+            switch (nrw) {
+                case 1: e = launch_scores<32, 1>(a, n_wg, heads, stream, stats, zsum); break;
+                case 2: e = launch_scores<32, 2>(a, n_wg, heads, stream, stats, zsum); break;
+                default: e = launch_scores<32, 4>(a, n_wg, heads, stream, stats, zsum); break;
+            }
+        } else {
+            e = launch_scores<64, 4>(a, n_wg, heads, stream, stats, zsum);   // 129..256 rows: four 64-row slabs
         }
         if (e != hipSuccess) return e;
     }
