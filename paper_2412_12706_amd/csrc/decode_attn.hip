@@ -1095,6 +1095,16 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     const int n_chunks = (a.n_kept + kChunk - 1) / kChunk;
     const int c_begin = blockIdx.x * a.chunks_per_split;
     const int c_end = min(n_chunks, c_begin + a.chunks_per_split);
+    // Chunks are claimed, not dealt: a wave takes its first chunk by index and every later one from
+    // a workgroup counter, so waves that start late (the tail rows) or run slower (the SIMD favours
+    // its oldest wave) simply take fewer and all of them finish together.
+    __shared__ int s_next_chunk;
+    if (threadIdx.x == 0) s_next_chunk = c_begin + nw;
+    auto claim = [&]() {
+        int v = 0;
+        if (lane == 0) v = atomicAdd(&s_next_chunk, 1);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
     int chunk = c_begin + wave;
     if (chunk < c_end) load_A(chunk);   // issued before anything else waits on memory
     // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
@@ -1129,8 +1139,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             const uint32_t v = hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
             reinterpret_cast<uint32_t*>(sq)[item] = v;
         }
-        __syncthreads();
     }
+    __syncthreads();   // query rows staged, chunk counter set
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -1141,10 +1151,11 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     if constexpr (kTailFirst) {
         if (wave < kWaves) tail_rows<GQ>(a, bh, tail_t0, tail_t1, sT);
     }
-    for (; chunk < c_end; chunk += nw) {
+    while (chunk < c_end) {
         const int tok0 = chunk * kChunk;
         const bool two = a.n_kept - tok0 >= kChunk;         // n_kept is a multiple of 32
         load_B(chunk, two);
+        const int next = claim();                            // used half an iteration later
         // key zero-point terms of this chunk's groups: token rows = z rows, unscaled q as the other operand
         float bias0 = 0.f, bias1 = 0.f;
         if constexpr (QUANT) {
@@ -1175,8 +1186,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         }
         compute(ak0, ak1, a_ks, true, bias0, av, 0, a_vs, a_vz);
         if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
-        load_A((chunk + nw < c_end) ? chunk + nw : chunk);
+        load_A(next < c_end ? next : chunk);
         if (two) compute(bk0, bk1, b_ks, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
+        chunk = next;
     }
 
     // ---- merge the waves (four states per round through LDS), add the tail rows, write ----
