@@ -799,8 +799,22 @@ template <int BITS, int NCG> struct PipeGeom {
     static constexpr int OFF_KS = 0, OFF_KZ = 256, OFF_VS = OFF_KZ + 256 * NGRP, OFF_VZ = OFF_VS + VROW;
     static constexpr int STRIP = QUANT ? OFF_VZ + VROW : 0;
 };
-constexpr int kMergeFloats = kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4);   // wave states of one merge round
-constexpr int kPipeFixedLds = kMergeFloats * 4 + 8 * kHeadDim * 2 + 4 * 64 * 16;   // + the group's query rows, twice (plain, operand layout)
+// LDS of the pipelined kernel, bytes.  While the chunks stream: the group's query rows twice
+// (plain for the z-term product, operand layout for the scale fold) and one staging strip per wave.
+// Afterwards the same bytes hold every wave's state for the merge: 8 output rows (hi + lo parts
+// already added) of 128 floats and 16 x (m, l, oz[4]).  The tail rows' states have their own
+// region behind both (they are produced first and merged last).
+constexpr int kPipeQueryLds = 8 * kHeadDim * 2 + 4 * 64 * 16;
+constexpr int kPipeStateLds = 8 * kHeadDim * 4 + 16 * 6 * 4;       // per wave
+constexpr int pipe_tail_lds(int gq) { return kWaves * gq * kPartStride * 4; }
+constexpr int pipe_lds_bytes(int nw, int strip, int gq) {
+    const int loop = kPipeQueryLds + nw * strip, merge = nw * kPipeStateLds;
+    return (loop > merge ? loop : merge) + pipe_tail_lds(gq);
+}
+constexpr int pipe_tail_offset(int nw, int strip) {
+    const int loop = kPipeQueryLds + nw * strip, merge = nw * kPipeStateLds;
+    return loop > merge ? loop : merge;
+}
 constexpr int pipe_max_waves(int bits, int gq) { return 4 * pipe_waves(bits, gq); }
 
 template <int BITS, int GQ, int NCG>
@@ -818,17 +832,15 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     constexpr int STRIP = Geo::STRIP;
 
     // A workgroup is nw = 4, 8 or 12 waves (blockDim.x / 64, a multiple of four): all of them stream
-    // chunks; the merges at the end are done by the first 256 threads, four wave states per round.
+    // chunks; the merge at the end is done by the first 256 threads.
     extern __shared__ __align__(16) unsigned char pipe_lds[];
-    float* smem = reinterpret_cast<float*>(pipe_lds);
-    uint16_t* sq = reinterpret_cast<uint16_t*>(pipe_lds + kMergeFloats * 4);   // the group's query rows (zero rows past GQ), for the z-term product
-    uint4* sqpos = reinterpret_cast<uint4*>(pipe_lds + kMergeFloats * 4 + 8 * kHeadDim * 2);   // [slice s][lane]
-    unsigned char* stage_all = pipe_lds + kPipeFixedLds + (GQ <= 4 ? kWaves * GQ * kPartStride * 4 : 0);
-    // Tail states [wave][head][m, l, o[128]]: a region of their own up to four query heads per KV
-    // head, so that the tail can run first; with eight they share the merge buffer and run last.
-    constexpr bool kTailFirst = GQ <= 4;
-    float* sT = kTailFirst ? reinterpret_cast<float*>(pipe_lds + kPipeFixedLds) : smem;
     const int nw = blockDim.x >> 6;
+    uint16_t* sq = reinterpret_cast<uint16_t*>(pipe_lds);                      // the group's query rows (zero rows past GQ), for the z-term product
+    uint4* sqpos = reinterpret_cast<uint4*>(pipe_lds + 8 * kHeadDim * 2);      // [slice s][lane]
+    unsigned char* stage_all = pipe_lds + kPipeQueryLds;
+    float* sO = reinterpret_cast<float*>(pipe_lds);                            // after the loop: [wave][8 rows][128]
+    float* sS = reinterpret_cast<float*>(pipe_lds + nw * (8 * kHeadDim * 4));  //                 [wave][16 rows][m, l, oz[4]]
+    float* sT = reinterpret_cast<float*>(pipe_lds + pipe_tail_offset(nw, STRIP));   // tail states [wave < 4][head][m, l, o[128]]
 
     const int bh = blockIdx.y;
 
@@ -1106,7 +1118,13 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         return __builtin_amdgcn_readfirstlane(v);
     };
     int chunk = c_begin + wave;
-    if (chunk < c_end) load_A(chunk);   // issued before anything else waits on memory
+    bool two = chunk < c_end && a.n_kept - chunk * kChunk >= kChunk;   // n_kept is a multiple of 32
+    // The second block of a chunk is requested right after the previous chunk's second block has
+    // been consumed (quantized variants: more bytes in flight, and the first chunk's blocks are both
+    // on their way before anything waits); the 16-bit variant, whose blocks are four times larger,
+    // runs faster when it asks at the top of the chunk's own iteration.
+    constexpr bool kEarlyB = QUANT;
+    if (chunk < c_end) { load_A(chunk); if (kEarlyB) load_B(chunk, two); }   // issued before anything else waits on memory
     // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
     // (head row, channel block kb).  The quantized variants park them in LDS (same for every wave)
     // and re-read them when a key group's scales arrive; that frees 16 registers in the loop.
@@ -1148,13 +1166,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     // the tail rows go first, while the first blocks are on their way (their state waits in LDS)
     const int tail_t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
     const int tail_t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
-    if constexpr (kTailFirst) {
-        if (wave < kWaves) tail_rows<GQ>(a, bh, tail_t0, tail_t1, sT);
-    }
+    if (wave < kWaves) tail_rows<GQ>(a, bh, tail_t0, tail_t1, sT);
     while (chunk < c_end) {
-        const int tok0 = chunk * kChunk;
-        const bool two = a.n_kept - tok0 >= kChunk;         // n_kept is a multiple of 32
-        load_B(chunk, two);
+        if (!kEarlyB) load_B(chunk, two);
         const int next = claim();                            // used half an iteration later
         // key zero-point terms of this chunk's groups: token rows = z rows, unscaled q as the other operand
         float bias0 = 0.f, bias1 = 0.f;
@@ -1186,72 +1200,61 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         }
         compute(ak0, ak1, a_ks, true, bias0, av, 0, a_vs, a_vz);
         if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
-        load_A(next < c_end ? next : chunk);
+        // both blocks of the wave's next chunk are requested while this chunk's second block is computed
+        const int nx = next < c_end ? next : chunk;
+        const bool two_nx = a.n_kept - nx * kChunk >= kChunk;
+        load_A(nx);
         if (two) compute(bk0, bk1, b_ks, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
-        chunk = next;
+        if (kEarlyB) load_B(nx, two_nx);
+        chunk = next; two = two_nx;
     }
 
-    // ---- merge the waves (four states per round through LDS), add the tail rows, write ----
+    // ---- merge the waves through LDS (one round), add the tail rows, write ----
     l_run = quad_rows_add(l_run);
 #pragma unroll
     for (int c = 0; c < NCG; ++c) oz[c] = quad_rows_add(oz[c]);
-    float* sO = smem;
-    float* sS = smem + kWaves * 16 * kHeadDim;
     constexpr int ITEMS = (GQ * kHeadDim + kThreads - 1) / kThreads;   // outputs (head hh, channel d) per merging thread
     const bool merger = threadIdx.x < kThreads;
+    __syncthreads();                     // every wave has left the loop: its LDS is free for the states
+    // rows 4kb+i come in (hi, lo) pairs i = (0,1), (2,3) with a common reference: add them here
+#pragma unroll
+    for (int t8 = 0; t8 < 8; ++t8) {
+        sO[(wave * 8 + 2 * kb) * kHeadDim + 16 * t8 + n] = O[t8][0] + O[t8][1];
+        sO[(wave * 8 + 2 * kb + 1) * kHeadDim + 16 * t8 + n] = O[t8][2] + O[t8][3];
+    }
+    if (kb == 0) {
+        float* st = sS + (wave * 16 + n) * 6;
+        st[0] = m_run; st[1] = l_run;
+#pragma unroll
+        for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
+    }
+    __syncthreads();
     float Mi[ITEMS], Ai[ITEMS], Li[ITEMS];
+    if (merger) {
 #pragma unroll
-    for (int it = 0; it < ITEMS; ++it) { Mi[it] = kNegBig; Ai[it] = 0.f; Li[it] = 0.f; }
-    for (int w0 = 0; w0 < nw; w0 += kWaves) {
-        if (wave >= w0 && wave < w0 + kWaves) {
-            const int wl = wave - w0;
+        for (int it = 0; it < ITEMS; ++it) {
+            const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
+            const int hh = item / kHeadDim, d = item % kHeadDim;
+            const int cg = d / G;
+            float M = kNegBig;
+            for (int w = 0; w < nw; ++w)
 #pragma unroll
-            for (int t8 = 0; t8 < 8; ++t8)
+                for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[(w * 16 + sl * 8 + 2 * hh) * 6]);
+            float acc = 0.f, L = 0.f;
+            for (int w = 0; w < nw; ++w)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) sO[(wl * 16 + 4 * kb + i) * kHeadDim + 16 * t8 + n] = O[t8][i];
-            if (kb == 0) {
-                float* st = sS + (wl * 16 + n) * 6;
-                st[0] = m_run; st[1] = l_run;
-#pragma unroll
-                for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
-            }
+                for (int sl = 0; sl < SLOTS; ++sl) {
+                    const float* st = sS + (w * 16 + sl * 8 + 2 * hh) * 6;
+                    const float wgt = exp2f(st[0] - M);
+                    const float o = sO[(w * 8 + sl * 4 + hh) * kHeadDim + d] * kCodeUnit + st[2 + cg];
+                    acc = __builtin_fmaf(wgt, o, acc);
+                    L = __builtin_fmaf(wgt, st[1], L);
+                }
+            Mi[it] = M; Ai[it] = acc; Li[it] = L;
         }
-        __syncthreads();
-        if (merger) {
-#pragma unroll
-            for (int it = 0; it < ITEMS; ++it) {
-                const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
-                const int hh = item / kHeadDim, d = item % kHeadDim;
-                const int cg = d / G;
-                float M = Mi[it];
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w)
-#pragma unroll
-                    for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[(w * 16 + sl * 8 + 2 * hh) * 6]);
-                const float keep = exp2f(Mi[it] - M);
-                float acc = Ai[it] * keep, L = Li[it] * keep;
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w)
-#pragma unroll
-                    for (int sl = 0; sl < SLOTS; ++sl) {
-                        const int row = sl * 8 + 2 * hh;
-                        const float* st = sS + (w * 16 + row) * 6;
-                        const float wgt = exp2f(st[0] - M);
-                        const float o = (sO[(w * 16 + row) * kHeadDim + d] + sO[(w * 16 + row + 1) * kHeadDim + d]) * kCodeUnit + st[2 + cg];
-                        acc = __builtin_fmaf(wgt, o, acc);
-                        L = __builtin_fmaf(wgt, st[1], L);
-                    }
-                Mi[it] = M; Ai[it] = acc; Li[it] = L;
-            }
-        }
-        __syncthreads();
     }
     // this workgroup's share of the full-precision tail rows (first four waves), merged the same way
     {
-        if constexpr (!kTailFirst) {
-            if (wave < kWaves) tail_rows<GQ>(a, bh, tail_t0, tail_t1, sT);
-        }
-        __syncthreads();
         if (merger) {
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
@@ -1309,7 +1312,7 @@ hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t str
     else
     {
         constexpr int strip = PipeGeom<BITS, NCG>::STRIP;
-        const unsigned lds_bytes = kPipeFixedLds + (GQ <= 4 ? kWaves * GQ * kPartStride * 4 : 0) + a.n_waves * strip + 16;
+        const unsigned lds_bytes = pipe_lds_bytes(a.n_waves, strip, GQ) + 16;
         hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG>), grid, dim3(64 * a.n_waves), lds_bytes, stream, a);
     }
     return hipGetLastError();
