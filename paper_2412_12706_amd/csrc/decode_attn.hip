@@ -867,6 +867,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     const uint32_t row_lane = (uint32_t)lane * 4;                                     // dword of a 256-byte scale row
     const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
     const int n_kgroups = QUANT ? a.n_kept / G : 0;
+    // The loads of the pipeline are unconditional; when a wave has no further chunk they are pointed
+    // at one 16-byte spot (lane offsets zeroed) instead of re-reading a whole chunk.
+    uint32_t k_off = k_lane, v_off = v_lane, row_off = row_lane, vrow_off = vrow_lane;
 
     // lane constants of the p*s operand: lo rows subtract the leading bits; a value lands in the
     // half-word of the lane's token slot (byte selectors for v_perm_b32: 0x0c gives a zero byte)
@@ -895,7 +898,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     for (int i = 0; i < NGRP; ++i) a_kz[i] = 0;
 
     auto load_k = [&](int tok, KWords<BITS>& dst) {
-        const char* p = kc + (size_t)tok * (16 * BITS) + k_lane;
+        const char* p = kc + (size_t)tok * (16 * BITS) + k_off;
         if constexpr (BITS == 2) {
             const uint2 v = *reinterpret_cast<const uint2*>(p);
             dst.w[0] = v.x; dst.w[1] = v.y;
@@ -908,7 +911,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         }
     };
     auto load_v = [&](int sb, VWords<BITS>& dst) {
-        const char* p = vc + (size_t)sb * (v_superblock_words(BITS) * 4) + v_lane;
+        const char* p = vc + (size_t)sb * (v_superblock_words(BITS) * 4) + v_off;
 #pragma unroll
         for (int q = 0; q < VGeom<BITS>::kWordsPerLoad / 4; ++q) {
             const uint4 v = *reinterpret_cast<const uint4*>(p + q * 1024);
@@ -923,11 +926,11 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         load_k(tb + 0, ak0); load_k(tb + 16, ak1);
         if constexpr (QUANT) {
             const int u = tb / G;
-            a_ks = dword_at(ks, (uint32_t)u * 256 + row_lane);
+            a_ks = dword_at(ks, (uint32_t)u * 256 + row_off);
 #pragma unroll
-            for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_lane);
-            a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_lane);
-            a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_lane);
+            for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_off);
+            a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off);
+            a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off);
         }
         load_v((BITS == 2) ? chunk : 2 * chunk, av);
     };
@@ -935,9 +938,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         const int tb = chunk * kChunk + (two ? 32 : 0);
         load_k(tb + 0, bk0); load_k(tb + 16, bk1);
         if constexpr (QUANT) {
-            if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_lane);
-            b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_lane);
-            b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_lane);
+            if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_off);
+            b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off);
+            b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off);
         }
         if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv);
     };
@@ -1201,8 +1204,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         compute(ak0, ak1, a_ks, true, bias0, av, 0, a_vs, a_vz);
         if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
         // both blocks of the wave's next chunk are requested while this chunk's second block is computed
-        const int nx = next < c_end ? next : chunk;
+        const bool has_next = next < c_end;
+        const int nx = has_next ? next : chunk;
         const bool two_nx = a.n_kept - nx * kChunk >= kChunk;
+        if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; }   // (wave-uniform; the loop ends after this pass)
         load_A(nx);
         if (two) compute(bk0, bk1, b_ks, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
         if (kEarlyB) load_B(nx, two_nx);
