@@ -91,3 +91,54 @@ def test_per_layer_calls_agree_with_the_batched_call(workload):
         # split counts differ between the two launch shapes, so sums are reassociated
         assert (o1.float() - out[layer:layer + 1].float()).abs().max().item() <= 2e-3
     torch.cuda.synchronize()
+
+
+def test_longest_context_shape(orc):
+    """The long-context configuration of the benchmark spec at its real size, one
+    layer: L = 131072 (the library's longest prefix), window 64 (256 query rows
+    per KV head: the 64-rows-per-wave scoring variant), 16384 tokens kept at
+    2 bits in groups of 64, key outlier channels x20.  Two KV heads are checked
+    against the CPU checker."""
+    Lc, Wc, Gc, n_kept, bits = 131072, 64, 64, 16384, 2
+    print(f"case L={Lc} W={Wc} G={Gc} tokens={n_kept} bits={bits}", flush=True)
+    q_obs, k, v = synth.prompt_device(1, HQ, HKV, Lc, Wc, D, outlier=20.0, config=4, device="cuda:0")
+    sm = float(np.float32(D ** -0.5))
+    cfg = kvqp.Cfg(batch=1, n_q_heads=HQ, n_kv_heads=HKV, seq_len=Lc, window=Wc, pool_kernel=POOL, budget=n_kept,
+                   bits=bits, group_size=Gc, sm_scale=sm)
+    cache = kvqp.alloc_cache(cfg, device="cuda:0")
+    idx_dev = torch.empty((1, HKV, n_kept), dtype=torch.int32, device="cuda:0")
+    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev)
+    q = synth.decode_query_device(1, HQ, D, config=4, step=0, device="cuda:0")
+    out = kvqp.decode_attn(cfg, q, cache)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    idx_all = idx_dev.cpu().numpy()
+    assert np.all(np.diff(idx_all, axis=-1) > 0) and idx_all.min() >= 0 and idx_all.max() < Lc - Wc
+    heads = [1, 6]
+    qs = np.concatenate([q_obs[:, g * GQ:(g + 1) * GQ].cpu().numpy() for g in heads], axis=1)
+    ks = np.concatenate([k[:, g:g + 1].cpu().numpy() for g in heads], axis=1)
+    vs = np.concatenate([v[:, g:g + 1].cpu().numpy() for g in heads], axis=1)
+    print("  checker: 2 KV heads", flush=True)
+    oc, idx_ref, pooled = orc.compress(qs, ks, vs, window=Wc, pool=POOL, budget=n_kept, bits=bits, G=Gc, sm_scale=sm)
+    got = idx_all[0, heads]
+    if not np.array_equal(got, idx_ref[0]):
+        for i in range(len(heads)):
+            kth = np.sort(pooled[0, i])[-n_kept]
+            diff = np.setxor1d(got[i], idx_ref[0, i])
+            if diff.size:
+                rel = np.abs(pooled[0, i][diff] - kth) / kth
+                assert np.all(rel <= 1e-6), f"head {heads[i]}: {diff.size} indices differ, worst relative gap {rel.max():.3e}"
+                print(f"    head {heads[i]}: {diff.size} index differences inside the 1e-6 tie band", flush=True)
+        oc = orc.quantize_selected(ks, vs, got.reshape(1, len(heads), -1), W=Wc, bits=bits, G=Gc)
+    for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
+        t = cache.buffers[name]
+        per = t.numel() // HKV
+        ref = np.ascontiguousarray(getattr(oc, name)).view(np.uint8).reshape(len(heads), -1)
+        for i, g in enumerate(heads):
+            assert np.array_equal(t[g * per:(g + 1) * per].cpu().numpy(), ref[i]), f"{name} differs at head {g}"
+    qd = np.concatenate([q[:, g * GQ:(g + 1) * GQ].cpu().numpy() for g in heads], axis=1)
+    ref = orc.decode_attn(qd, oc, sm)
+    gpu = np.concatenate([out[:, g * GQ:(g + 1) * GQ].cpu().numpy() for g in heads], axis=1).astype(np.float64)
+    err = np.abs(gpu - ref).max()
+    print(f"    decode max-abs error {err:.2e}", flush=True)
+    assert err <= 2e-3
