@@ -109,3 +109,31 @@ def test_single_token_cache(orc):
     out = kvqp.decode_attn(cfg, dev(q), upload_cache(oc))
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy()[0], np.broadcast_to(v[0, 0, 1], (4, 128)))
+
+
+@pytest.mark.parametrize("bits,Gq,splits", [(4, 4, 0), (4, 4, 3), (2, 8, 0), (16, 2, 5)])
+def test_tail_grown_by_decoded_tokens(orc, bits, Gq, splits):
+    """The caller appends decoded tokens' K/V rows to the full-precision tail
+    (the cache update of Eq. (2)): 517 valid rows of 600, many more than the
+    window, shared between the workgroups of a head."""
+    B, Hkv, n_kept, W, cap, grown = 1, 2, 384, 32, 600, 517
+    L = n_kept + W + 57
+    Hq = Hkv * Gq
+    _, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, config=70 + bits)
+    rng = np.random.default_rng(bits + Gq)
+    idx = np.stack([np.sort(rng.choice(L - W, n_kept, replace=False)) for _ in range(B * Hkv)]).astype(np.int32).reshape(B, Hkv, n_kept)
+    oc = orc.quantize_selected(k, v, idx, W=W, bits=bits, G=32, tail_cap=cap)
+    extra_k = rng.standard_normal((B, Hkv, grown - W, 128)).astype(np.float16)
+    extra_v = rng.standard_normal((B, Hkv, grown - W, 128)).astype(np.float16)
+    oc.tail_k[:, :, W:grown] = extra_k.view(np.uint16)
+    oc.tail_v[:, :, W:grown] = extra_v.view(np.uint16)
+    oc.tail_len = grown
+    cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, budget=n_kept, bits=bits, group_size=32,
+                   decode_splits=splits)
+    q = synth.decode_query_host(B, Hq, 128, config=70)
+    ref = orc.decode_attn(q, oc, cfg.sm_scale)
+    out = kvqp.decode_attn(cfg, dev(q), upload_cache(oc))
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref).max()
+    print(f"  bits={bits} Gq={Gq} splits={splits} max-abs error {err:.3e}", flush=True)
+    assert err <= TOL
