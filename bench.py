@@ -35,6 +35,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, HERE)
 
 PEAK_HBM_GBS = 8000.0
+PEAK_FP32_VECTOR_TFLOPS = 157.3
 LAYERS, HQ, HKV, D, L, W, POOL, G = 32, 32, 8, 128, 32768, 32, 7, 32
 SWEEP = [(2048, 16), (4096, 8), (8192, 4), (16384, 2)]
 DECODE_STEPS = 128
@@ -173,9 +174,16 @@ def main():
         us_call = s["t_decode_ms"] * 1e3 / n_calls
         gbs = b / (us_call * 1e-6) / 1e9
         c_ms = s["t_compress_ms"] / args.steps
+        # two lower bounds of one decode launch: its bytes at the HBM peak, and its multiply-adds
+        # (Gq per stored code, keys and values) at the plain fp32 vector peak -- what a kernel
+        # that dequantizes with ordinary ALU instructions would be held to
+        t_hbm_us = b / (PEAK_HBM_GBS * 1e9) * 1e6
+        macs = LAYERS * HKV * s["n_kept"] * 2 * (HQ // HKV) * D
+        t_alu_us = 2 * macs / (PEAK_FP32_VECTOR_TFLOPS * 1e12) * 1e6
         sweep.append({
             "tokens": s["n_kept"], "bits": s["bits"], "decode_us_per_step": round(us_call, 2),
             "decode_gbs": round(gbs, 1), "pct_of_8TBs": round(100 * gbs / PEAK_HBM_GBS, 1),
+            "t_hbm_us": round(t_hbm_us, 1), "t_plain_alu_us": round(t_alu_us, 1),
             "bytes_per_step": b, "compress_ms_32_layers": round(c_ms, 3),
             "compress_mtok_s": round(L / (c_ms * 1e-3) / 1e6, 2),
             "compress_gbs": round(compress_bytes(LAYERS, s["n_kept"], s["bits"], G) / (c_ms * 1e-3) / 1e9, 1),
@@ -220,6 +228,9 @@ def main():
         "achieved": dom_r["decode_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": round(dom_r["decode_gbs"] / PEAK_HBM_GBS, 4), "traffic": read_traffic_note(tag),
         "algorithmic_bytes_per_launch": dom_r["bytes_per_step"], "launch_us": dom_r["decode_us_per_step"],
+        "roofline_time_us": max(dom_r["t_hbm_us"], dom_r["t_plain_alu_us"]),
+        "note": "the products run on the matrix cores with the codes as operands, so the plain-ALU bound does not "
+                "apply; at 2 bits the measured limit is vector-instruction issue for operand preparation (DESIGN.md 5.1)",
     }
 
     if args.calibrate_copy:

@@ -21,9 +21,12 @@
 // The value codes are stored tile-transposed (kvqp.h) so that the lane that
 // holds probabilities of tokens {4kb+i} after the QK product is the lane that
 // needs them as the P operand: nothing moves between lanes or through LDS
-// inside the token loop.  One workgroup = 4 waves streams a contiguous token
-// range (split-K); waves own interleaved 64-token chunks; partial (m, l, O)
-// go to the workspace and a second small kernel merges the splits.
+// inside the token loop.  A workgroup streams a contiguous token range in
+// 64-token chunks.  When the launch has enough (batch, kv head) pairs to fill
+// the chip, a head is one workgroup of 8 or 12 waves that merges through LDS
+// and writes the output itself; otherwise a head is split over several
+// workgroups whose partial (m, l, O) go to the workspace, and the last one to
+// arrive merges them (no second kernel).
 #include "kvqp_internal.h"
 
 namespace kvqp {
@@ -776,8 +779,12 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 // Software-pipelined variant for per-channel keys (the default axes) and for
 // the 16-bit cache.  Same arithmetic as above; differences are all about
 // keeping HBM, the texture-address path and the vector ALU busy at once:
-//   * every global load of a 32-token block is issued one block ahead into a
-//     second register set (A = first block of a 64-token chunk, B = second);
+//   * every global load of a 32-token block is issued ahead into a second
+//     register set (A = first block of a 64-token chunk, B = second): the next
+//     chunk's blocks are requested while the current chunk's second block is
+//     computed;
+//   * waves claim chunks from a workgroup counter instead of owning a fixed
+//     interleave, so late or slower waves take fewer and all finish together;
 //   * scales and zero-points are needed replicated (every row lane of a quad
 //     multiplies by the same 32 key scales; every row lane of a slot by the same
 //     token scales).  Loading them replicated costs a full 1 KB trip through the
@@ -786,8 +793,9 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 //     it back with broadcast ds_read_b128;
 //   * the key zero-point term sum_d q[d] z[group, d] of a chunk's groups comes
 //     from one extra MFMA whose token rows are the z rows themselves;
-//   * hi/lo operand parts are produced with fused multiply-adds that round
-//     straight to binary16, and only the lanes that own a lo row compute it.
+//   * the hi/lo parts of q*s come from a packed binary16 multiply and a fused
+//     multiply-add of the residual; those of p*s from one binary32 product,
+//     a mask, an exact subtraction and a truncating pack.
 // ---------------------------------------------------------------------------
 // LDS bytes of one wave's staging strip in the pipelined kernel: key scale row | key zero rows |
 // value scales | value zeros of the block in flight.
