@@ -813,7 +813,7 @@ template <int BITS, int NCG> struct PipeGeom {
 // already added) of 128 floats and 16 x (m, l, oz[4]).  The tail rows' states have their own
 // region behind both (they are produced first and merged last).
 constexpr int kPipeQueryLds = 8 * kHeadDim * 2 + 4 * 64 * 16;
-constexpr int kPipeStateLds = 8 * kHeadDim * 4 + 16 * 6 * 4;       // per wave
+constexpr int kPipeStateLds = 8 * kHeadDim * 4 + 16 * 6 * 4 + 2 * 8 * 4 + 8 * 4;   // per wave: rows, stats, merge weights (+ references)
 constexpr int pipe_tail_lds(int gq) { return kWaves * gq * kPartStride * 4; }
 constexpr int pipe_lds_bytes(int nw, int strip, int gq) {
     const int loop = kPipeQueryLds + nw * strip, merge = nw * kPipeStateLds;
@@ -1242,6 +1242,17 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
     }
     __syncthreads();
+    // the merge weights exp2(m - M) are shared by all channels of a head: one thread per
+    // (wave, slot, head) derives its weight, then every merging thread reads them back
+    float* sW = sS + nw * 16 * 6;                 // [wave * SLOTS + slot][head] weights, then [head] references
+    if ((int)threadIdx.x < nw * SLOTS * GQ) {
+        const int hh = threadIdx.x % GQ, ws = threadIdx.x / GQ;
+        float M = kNegBig;
+        for (int u = 0; u < nw * SLOTS; ++u) M = fmaxf(M, sS[((u / SLOTS) * 16 + (u % SLOTS) * 8 + 2 * hh) * 6]);
+        sW[ws * GQ + hh] = exp2f(sS[((ws / SLOTS) * 16 + (ws % SLOTS) * 8 + 2 * hh) * 6] - M);
+        if (ws == 0) sW[nw * SLOTS * GQ + hh] = M;
+    }
+    __syncthreads();
     float Mi[ITEMS], Ai[ITEMS], Li[ITEMS];
     if (merger) {
 #pragma unroll
@@ -1249,21 +1260,17 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
             const int hh = item / kHeadDim, d = item % kHeadDim;
             const int cg = d / G;
-            float M = kNegBig;
-            for (int w = 0; w < nw; ++w)
-#pragma unroll
-                for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[(w * 16 + sl * 8 + 2 * hh) * 6]);
             float acc = 0.f, L = 0.f;
             for (int w = 0; w < nw; ++w)
 #pragma unroll
                 for (int sl = 0; sl < SLOTS; ++sl) {
                     const float* st = sS + (w * 16 + sl * 8 + 2 * hh) * 6;
-                    const float wgt = exp2f(st[0] - M);
+                    const float wgt = sW[(w * SLOTS + sl) * GQ + hh];
                     const float o = sO[(w * 8 + sl * 4 + hh) * kHeadDim + d] * kCodeUnit + st[2 + cg];
                     acc = __builtin_fmaf(wgt, o, acc);
                     L = __builtin_fmaf(wgt, st[1], L);
                 }
-            Mi[it] = M; Ai[it] = acc; Li[it] = L;
+            Mi[it] = sW[nw * SLOTS * GQ + hh]; Ai[it] = acc; Li[it] = L;
         }
     }
     // this workgroup's share of the full-precision tail rows (first four waves), merged the same way
