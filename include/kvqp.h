@@ -119,11 +119,21 @@ typedef struct kvqp_cache {
     int32_t n_kept;   /* kept low-precision tokens; set by compress / quantize_selected */
     int32_t tail_len; /* valid tail rows                                                */
     int32_t tail_cap; /* allocated tail rows, >= window                                 */
+    int32_t n_cap;    /* tokens the six packed buffers are laid out for: every "n_kept"
+                         in the buffer shapes above is n_cap (the stride of the
+                         [batch, Hkv] axes); 0 means n_kept, the compact layout of
+                         kvqp_cache_sizes.  A larger n_cap (a multiple of 64 and of G,
+                         sizes from kvqp_cache_sizes_cap) leaves room for
+                         kvqp_append_tail.  Set by the caller, never changed.           */
 } kvqp_cache;
 
 /* Bytes of the eight cache buffers (order of the struct) for n_kept =
  * min(budget, L - W) and the given tail capacity.  Host only. */
 int kvqp_cache_sizes(const kvqp_cfg *cfg, int32_t tail_cap, size_t sizes_out[8]);
+
+/* The same for buffers laid out for n_cap tokens per head (n_cap a multiple of 64 and of
+ * group_size, >= 0); cfg->seq_len, window and budget are not read.  Host only. */
+int kvqp_cache_sizes_cap(const kvqp_cfg *cfg, int32_t n_cap, int32_t tail_cap, size_t sizes_out[8]);
 
 /* Workspace bytes needed by kvqp_compress and kvqp_decode_attn for this cfg
  * (either pointer may be NULL).  Host only. */
@@ -184,6 +194,24 @@ int kvqp_quantize_selected(const kvqp_cfg *cfg, const void *k, const void *v, co
  */
 int kvqp_decode_attn(const kvqp_cfg *cfg, const void *q, const kvqp_cache *cache, void *out,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Decode-time cache update (Section 3, Eq. (2): the new token's key and value
+ * are concatenated to the cache; the paper's quantizer, KIVI, keeps the most
+ * recent tokens in full precision and quantizes them group by group).  The
+ * caller appends each decoded token's K/V row to the tail and raises tail_len;
+ * this call moves the n_tokens OLDEST tail rows into the low-precision part:
+ * they are quantized and packed exactly as kvqp_quantize_selected would have
+ * done had they been survivors n_kept .. n_kept + n_tokens - 1, the remaining
+ * tail rows move down, and n_kept / tail_len are updated.
+ *   n_tokens  > 0, <= tail_len, and a multiple of q; n_kept must be a multiple
+ *             of q too and n_kept + n_tokens <= n_cap, where q is 32, raised to
+ *             64 for 2-bit caches and to a multiple of group_size for
+ *             per-channel keys (whole key groups, whole value superblocks).
+ * cfg fields used: batch, heads, head_dim, bits, group_size, key_axis.
+ * Errors: INVALID_ARG when the counts do not fit the rules above.
+ */
+int kvqp_append_tail(const kvqp_cfg *cfg, kvqp_cache *cache, int32_t n_tokens, void *hip_stream);
 
 /* Static string for a return code. */
 const char *kvqp_strerror(int code);

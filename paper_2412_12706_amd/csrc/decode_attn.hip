@@ -213,6 +213,7 @@ struct DecodeArgs {
     float* part;              // [B*Hkv, n_partials, GQ, D+2]
     uint16_t* out;            // [B, Hq, D]
     int n_kept, tail_len, tail_cap;
+    int n_cap;                // tokens the packed buffers are laid out for (head strides); >= n_kept
     int n_q_heads, n_kv_heads;
     int n_splits, chunks_per_split, n_partials;
     int n_waves;              // waves per workgroup of the pipelined kernel
@@ -492,13 +493,14 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
     const int h = (SLOTS == 2) ? ((n & 7) >> 1) : (n >> 1);
     const bool live_row = h < GQ;
 
-    const uint32_t* kc = a.k_codes + (size_t)bh * ((size_t)a.n_kept * kHeadDim * BITS / 32);
-    const uint32_t* vc = a.v_codes + (size_t)bh * v_superblock_words(BITS) * ((a.n_kept + v_superblock(BITS) - 1) / v_superblock(BITS));
+    const uint32_t* kc = a.k_codes + (size_t)bh * ((size_t)a.n_cap * kHeadDim * BITS / 32);
+    const uint32_t* vc = a.v_codes + (size_t)bh * v_superblock_words(BITS) * ((a.n_cap + v_superblock(BITS) - 1) / v_superblock(BITS));
     const int n_kgroups = (AXIS == KVQP_KEY_PER_CHANNEL) ? a.n_kept / G : a.n_kept;
-    const uint16_t* ks = QUANT ? a.k_scale + (size_t)bh * n_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
-    const uint16_t* kz = QUANT ? a.k_zero + (size_t)bh * n_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
-    const uint16_t* vs = QUANT ? a.v_scale + (size_t)bh * a.n_kept * NCG : nullptr;
-    const uint16_t* vz = QUANT ? a.v_zero + (size_t)bh * a.n_kept * NCG : nullptr;
+    const int cap_kgroups = (AXIS == KVQP_KEY_PER_CHANNEL) ? a.n_cap / G : a.n_cap;   // head stride of the key scales
+    const uint16_t* ks = QUANT ? a.k_scale + (size_t)bh * cap_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
+    const uint16_t* kz = QUANT ? a.k_zero + (size_t)bh * cap_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
+    const uint16_t* vs = QUANT ? a.v_scale + (size_t)bh * a.n_cap * NCG : nullptr;
+    const uint16_t* vz = QUANT ? a.v_zero + (size_t)bh * a.n_cap * NCG : nullptr;
 
     // The lane's 32 query channels [32kb, 32kb+32) of its head, as natural pairs.
     h2v qn[16];
@@ -863,13 +865,13 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     unsigned char* stage = stage_all + (QUANT ? wave * STRIP : 0);
 
     // head bases (wave-uniform) and per-lane 32-bit byte offsets
-    const char* kc = reinterpret_cast<const char*>(a.k_codes) + (size_t)bh * ((size_t)a.n_kept * kHeadDim * BITS / 8);
+    const char* kc = reinterpret_cast<const char*>(a.k_codes) + (size_t)bh * ((size_t)a.n_cap * kHeadDim * BITS / 8);
     const char* vc = reinterpret_cast<const char*>(a.v_codes) +
-                     (size_t)bh * v_superblock_words(BITS) * 4 * ((a.n_kept + v_superblock(BITS) - 1) / v_superblock(BITS));
-    const char* ks = QUANT ? reinterpret_cast<const char*>(a.k_scale) + (size_t)bh * (a.n_kept / G) * kHeadDim * 2 : nullptr;
-    const char* kz = QUANT ? reinterpret_cast<const char*>(a.k_zero) + (size_t)bh * (a.n_kept / G) * kHeadDim * 2 : nullptr;
-    const char* vs = QUANT ? reinterpret_cast<const char*>(a.v_scale) + (size_t)bh * a.n_kept * NCG * 2 : nullptr;
-    const char* vz = QUANT ? reinterpret_cast<const char*>(a.v_zero) + (size_t)bh * a.n_kept * NCG * 2 : nullptr;
+                     (size_t)bh * v_superblock_words(BITS) * 4 * ((a.n_cap + v_superblock(BITS) - 1) / v_superblock(BITS));
+    const char* ks = QUANT ? reinterpret_cast<const char*>(a.k_scale) + (size_t)bh * (a.n_cap / G) * kHeadDim * 2 : nullptr;
+    const char* kz = QUANT ? reinterpret_cast<const char*>(a.k_zero) + (size_t)bh * (a.n_cap / G) * kHeadDim * 2 : nullptr;
+    const char* vs = QUANT ? reinterpret_cast<const char*>(a.v_scale) + (size_t)bh * a.n_cap * NCG * 2 : nullptr;
+    const char* vz = QUANT ? reinterpret_cast<const char*>(a.v_zero) + (size_t)bh * a.n_cap * NCG * 2 : nullptr;
     const uint32_t k_lane = (uint32_t)n * (16 * BITS) + (uint32_t)kb * (4 * BITS);   // within a 16-token key tile
     const uint32_t v_lane = (uint32_t)lane * 16;
     const uint32_t row_lane = (uint32_t)lane * 4;                                     // dword of a 256-byte scale row
@@ -1427,6 +1429,7 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.part = (float*)ws;
     a.out = (uint16_t*)out;
     a.n_kept = c.n_kept; a.tail_len = c.tail_len; a.tail_cap = c.tail_cap;
+    a.n_cap = c.n_cap > 0 ? c.n_cap : c.n_kept;
     a.n_q_heads = cfg.n_q_heads; a.n_kv_heads = cfg.n_kv_heads;
     a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;
     a.n_waves = plan.n_waves;

@@ -53,8 +53,30 @@ int check_n_kept(const kvqp_cfg* c, int n_kept) {
     return KVQP_OK;
 }
 
+// A non-zero capacity must hold the tokens and keep every head's buffers aligned.
+int check_cap(const kvqp_cfg* c, int n_cap, int n_kept) {
+    if (n_cap == 0) return KVQP_OK;
+    if (n_cap < n_kept || n_cap % 64) return KVQP_ERR_INVALID_ARG;
+    if (c->bits != 16 && n_cap % c->group_size) return KVQP_ERR_INVALID_ARG;
+    return KVQP_OK;
+}
+
+int fill_sizes(const kvqp_cfg* cfg, int n_tok, int32_t tail_cap, size_t sizes_out[8]) {
+    const size_t heads = (size_t)cfg->batch * cfg->n_kv_heads;
+    const size_t km = k_meta_elems(n_tok, cfg->bits, cfg->group_size, cfg->key_axis) * 2 * heads;
+    const size_t vm = v_meta_elems(n_tok, cfg->bits, cfg->group_size) * 2 * heads;
+    const size_t tail = heads * (size_t)tail_cap * kHeadDim * 2;
+    sizes_out[0] = k_code_words(n_tok, cfg->bits) * 4 * heads;
+    sizes_out[1] = v_code_words(n_tok, cfg->bits) * 4 * heads;
+    sizes_out[2] = km; sizes_out[3] = km;
+    sizes_out[4] = vm; sizes_out[5] = vm;
+    sizes_out[6] = tail; sizes_out[7] = tail;
+    return KVQP_OK;
+}
+
 int check_cache_ptrs(const kvqp_cfg* c, const kvqp_cache* cache, int n_kept, bool need_tail) {
     if (!cache) return KVQP_ERR_INVALID_ARG;
+    if (check_cap(c, cache->n_cap, n_kept)) return KVQP_ERR_INVALID_ARG;
     if (n_kept > 0) {
         if (!cache->k_codes || !cache->v_codes) return KVQP_ERR_INVALID_ARG;
         if (c->bits != 16 && (!cache->k_scale || !cache->k_zero || !cache->v_scale || !cache->v_zero))
@@ -71,7 +93,7 @@ using namespace kvqp;
 
 extern "C" {
 
-int kvqp_version(void) { return 100; }
+int kvqp_version(void) { return 200; }
 
 const char* kvqp_strerror(int code) {
     switch (code) {
@@ -91,16 +113,15 @@ int kvqp_cache_sizes(const kvqp_cfg* cfg, int32_t tail_cap, size_t sizes_out[8])
     if (!sizes_out || tail_cap < cfg->window) return KVQP_ERR_INVALID_ARG;
     const int n_kept = n_kept_of(cfg);
     if ((rc = check_n_kept(cfg, n_kept))) return rc;
-    const size_t heads = (size_t)cfg->batch * cfg->n_kv_heads;
-    const size_t km = k_meta_elems(n_kept, cfg->bits, cfg->group_size, cfg->key_axis) * 2 * heads;
-    const size_t vm = v_meta_elems(n_kept, cfg->bits, cfg->group_size) * 2 * heads;
-    const size_t tail = heads * (size_t)tail_cap * kHeadDim * 2;
-    sizes_out[0] = k_code_words(n_kept, cfg->bits) * 4 * heads;
-    sizes_out[1] = v_code_words(n_kept, cfg->bits) * 4 * heads;
-    sizes_out[2] = km; sizes_out[3] = km;
-    sizes_out[4] = vm; sizes_out[5] = vm;
-    sizes_out[6] = tail; sizes_out[7] = tail;
-    return KVQP_OK;
+    return fill_sizes(cfg, n_kept, tail_cap, sizes_out);
+}
+
+int kvqp_cache_sizes_cap(const kvqp_cfg* cfg, int32_t n_cap, int32_t tail_cap, size_t sizes_out[8]) {
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if (!sizes_out || tail_cap < 0 || n_cap < 0) return KVQP_ERR_INVALID_ARG;
+    if (n_cap > 0 && (rc = check_cap(cfg, n_cap, 0))) return rc;
+    return fill_sizes(cfg, n_cap, tail_cap, sizes_out);
 }
 
 int kvqp_workspace_bytes(const kvqp_cfg* cfg, size_t* compress_bytes, size_t* decode_bytes) {
@@ -156,6 +177,25 @@ int kvqp_compress(const kvqp_cfg* cfg, const void* q_obs, const void* k, const v
     if (launch_quant_pack(*cfg, k, v, idx, n_kept, *cache, stream) != hipSuccess) return KVQP_ERR_HIP;
     cache->n_kept = n_kept;
     cache->tail_len = cfg->window;
+    return KVQP_OK;
+}
+
+int kvqp_append_tail(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_tokens, void* hip_stream) {
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if (!cache || n_tokens < 1) return KVQP_ERR_INVALID_ARG;
+    if (cache->n_kept < 0 || cache->tail_len < 0 || cache->tail_len > cache->tail_cap) return KVQP_ERR_INVALID_ARG;
+    if (n_tokens > cache->tail_len) return KVQP_ERR_INVALID_ARG;
+    // whole value superblocks and, for per-channel keys, whole key groups
+    int quantum = cfg->bits == 2 ? 64 : 32;
+    if (cfg->bits != 16 && cfg->key_axis == KVQP_KEY_PER_CHANNEL && cfg->group_size > quantum) quantum = cfg->group_size;
+    if (n_tokens % quantum || cache->n_kept % quantum) return KVQP_ERR_INVALID_ARG;
+    const int cap = cache->n_cap > 0 ? cache->n_cap : cache->n_kept;
+    if (cache->n_kept + n_tokens > cap) return KVQP_ERR_INVALID_ARG;
+    if ((rc = check_cache_ptrs(cfg, cache, cache->n_kept + n_tokens, true))) return rc;
+    if (launch_append_tail(*cfg, *cache, n_tokens, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    cache->n_kept += n_tokens;
+    cache->tail_len -= n_tokens;
     return KVQP_OK;
 }
 

@@ -55,6 +55,7 @@ hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, 
                              int n_kept, const kvqp_cache& cache, hipStream_t stream);
 hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& cache, void* out,
                          void* ws, const DecodePlan& plan, hipStream_t stream);
+hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, hipStream_t stream);
 hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx,
                          void* ws, const CompressPlan& plan, hipStream_t stream);
 

@@ -24,6 +24,15 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// One launch of the quantize-and-pack kernel: n_tok rows per head of (k, v) -- rows idx[...] or, with
+// idx == NULL, rows 0 .. n_tok-1 -- land at tokens dst_base .. of a cache laid out for n_cap tokens.
+struct QuantPackJob {
+    const kvqp_cache& c;
+    const void* k; const void* v; const int32_t* idx;
+    int heads, src_rows, window, n_tok, dst_base, n_cap, bits, group_size, key_axis;
+    bool copy_tail;
+};
+
 typedef unsigned short us2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {
     union { uint32_t u; us2v v; } x, y, z; x.u = a; y.u = b; z.v = __builtin_elementwise_min(x.v, y.v); return z.u;
@@ -133,7 +142,10 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale,
     uint16_t* __restrict__ k_zero, uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero,
     uint16_t* __restrict__ tail_k, uint16_t* __restrict__ tail_v, int L, int W, int n_kept, int key_axis,
-    int tail_cap, int n_tok_blocks) {
+    int tail_cap, int n_tok_blocks, int n_cap, int dst_base) {
+    // L: rows per head of the source tensors.  idx: source row of every token of this call
+    // ([heads, n_kept]), or NULL for rows 0 .. n_kept-1.  The tokens land at positions dst_base ..
+    // dst_base + n_kept - 1 of a cache whose buffers are laid out for n_cap tokens per head.
     constexpr bool QUANT = BITS != 16;
     constexpr int TB = (QUANT && G == 128) ? 128 : 64;   // tokens per workgroup
     constexpr int R = TB / 16;                            // rows per thread
@@ -170,6 +182,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c8 = threadIdx.x & 15, r = threadIdx.x >> 4, i4 = (threadIdx.x >> 4) & 3;
     const int t0 = blockIdx.x * TB;
+    const int d0 = dst_base + t0;            // first destination token: a multiple of the group and superblock sizes
     const int ntok = min(TB, n_kept - t0);   // a multiple of 32 (and of G for per-channel keys)
 
     // ---- gather: all of the thread's rows of both tensors are requested before anything is used ----
@@ -179,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     for (int j = 0; j < R; ++j) {
         const int t = r + 16 * j;
         live[j] = t < ntok;
-        const int pos = live[j] ? idx[(size_t)head * n_kept + t0 + t] : 0;
+        const int pos = !live[j] ? 0 : idx ? idx[(size_t)head * n_kept + t0 + t] : t0 + t;
         const uint4 a = live[j] ? *reinterpret_cast<const uint4*>(kh + (size_t)pos * kHeadDim + 8 * c8) : make_uint4(0, 0, 0, 0);
         const uint4 b = live[j] ? *reinterpret_cast<const uint4*>(vh + (size_t)pos * kHeadDim + 8 * c8) : make_uint4(0, 0, 0, 0);
         kw[j][0] = a.x; kw[j][1] = a.y; kw[j][2] = a.z; kw[j][3] = a.w;
@@ -207,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             const GroupParams gp = group_params<BITS>(a, b);
             const int t = r + 16 * (4 * jj + q4);
             if (t < ntok && (c8 & (GL - 1)) < 4) {
-                const size_t m = ((size_t)head * n_kept + t0 + t) * CPT + c8 / GL;
+                const size_t m = ((size_t)head * n_cap + d0 + t) * CPT + c8 / GL;
                 scale[m] = gp.scale_h; zero[m] = gp.zero_h;
             }
             const uint32_t zb = __float_as_uint(gp.zf), ib = __float_as_uint(gp.inv);
@@ -224,12 +237,12 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     };
 
     // ---------------- keys ----------------
-    uint32_t* kc_head = k_codes + (size_t)head * ((size_t)n_kept * kHeadDim / E);
+    uint32_t* kc_head = k_codes + (size_t)head * ((size_t)n_cap * kHeadDim / E);
     if constexpr (!QUANT) {
 #pragma unroll
         for (int j = 0; j < R; ++j)
             if (live[j])
-                *reinterpret_cast<uint4*>(kc_head + (size_t)(t0 + r + 16 * j) * (kHeadDim / 2) + 4 * c8) = make_uint4(kw[j][0], kw[j][1], kw[j][2], kw[j][3]);
+                *reinterpret_cast<uint4*>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / 2) + 4 * c8) = make_uint4(kw[j][0], kw[j][1], kw[j][2], kw[j][3]);
     } else if (key_axis == KVQP_KEY_PER_CHANNEL) {
         // minima / maxima per channel over the G tokens of a group: own rows, the four row lanes of
         // the wave (lane ^ 16, ^ 32), then the four waves through LDS
@@ -275,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             const GroupParams gp = group_params<BITS>(a, b);
             s_par[item] = make_float2(gp.zf, gp.inv);
             if (ug * G < ntok) {
-                const size_t m = ((size_t)head * (n_kept / G) + (t0 / G + ug)) * kHeadDim + d;
+                const size_t m = ((size_t)head * (n_cap / G) + (d0 / G + ug)) * kHeadDim + d;
                 k_scale[m] = gp.scale_h; k_zero[m] = gp.zero_h;
             }
         }
@@ -293,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
                 const int j = ug * JPG + jl;
                 uint32_t c[8];
                 encode8<BITS>(kw[j], zf, inv, c);
-                if (live[j]) store_key_words<BITS>(kc_head + (size_t)(t0 + r + 16 * j) * (kHeadDim / E), c8, c);
+                if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, c);
             }
         }
     } else {
@@ -301,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         per_token(kw, k_scale, k_zero, codes);
 #pragma unroll
         for (int j = 0; j < R; ++j)
-            if (live[j]) store_key_words<BITS>(kc_head + (size_t)(t0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
+            if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
     }
 
     // ---------------- values ----------------
@@ -358,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         }
         __syncthreads();
         const int n_sb = (ntok + SB - 1) / SB;
-        uint32_t* vc = v_codes + (size_t)head * SBW * ((n_kept + SB - 1) / SB) + (size_t)(t0 / SB) * SBW;
+        uint32_t* vc = v_codes + (size_t)head * SBW * ((n_cap + SB - 1) / SB) + (size_t)(d0 / SB) * SBW;
         for (int item = threadIdx.x; item < n_sb * SBW / 4; item += kThreads)
             reinterpret_cast<uint4*>(vc)[item] = reinterpret_cast<const uint4*>(s_words)[item];
     }
@@ -367,26 +380,60 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
 #undef KVQP_SWAP32
 
 template <int BITS, int G>
-hipError_t launch_bits_g(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx, int n_kept,
-                         const kvqp_cache& c, hipStream_t stream) {
+hipError_t launch_bits_g(const QuantPackJob& j, hipStream_t stream) {
     constexpr int TB = (BITS != 16 && G == 128) ? 128 : 64;
-    const int heads = cfg.batch * cfg.n_kv_heads;
-    const int nblk = (n_kept + TB - 1) / TB;
-    dim3 grid(nblk + 1, heads);
-    hipLaunchKernelGGL((gather_quant_pack<BITS, G>), grid, dim3(kThreads), 0, stream, (const uint16_t*)k,
-                       (const uint16_t*)v, idx, (uint32_t*)c.k_codes, (uint32_t*)c.v_codes, (uint16_t*)c.k_scale,
-                       (uint16_t*)c.k_zero, (uint16_t*)c.v_scale, (uint16_t*)c.v_zero, (uint16_t*)c.tail_k,
-                       (uint16_t*)c.tail_v, cfg.seq_len, cfg.window, n_kept, cfg.key_axis, c.tail_cap, nblk);
+    const int nblk = (j.n_tok + TB - 1) / TB;
+    dim3 grid(nblk + (j.copy_tail ? 1 : 0), j.heads);
+    if (grid.x == 0) return hipSuccess;
+    hipLaunchKernelGGL((gather_quant_pack<BITS, G>), grid, dim3(kThreads), 0, stream, (const uint16_t*)j.k,
+                       (const uint16_t*)j.v, j.idx, (uint32_t*)j.c.k_codes, (uint32_t*)j.c.v_codes, (uint16_t*)j.c.k_scale,
+                       (uint16_t*)j.c.k_zero, (uint16_t*)j.c.v_scale, (uint16_t*)j.c.v_zero, (uint16_t*)j.c.tail_k,
+                       (uint16_t*)j.c.tail_v, j.src_rows, j.window, j.n_tok, j.key_axis, j.c.tail_cap, nblk, j.n_cap,
+                       j.dst_base);
     return hipGetLastError();
 }
 template <int BITS>
-hipError_t launch_bits(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx, int n_kept,
-                       const kvqp_cache& c, hipStream_t stream) {
-    if (BITS == 16) return launch_bits_g<BITS, 32>(cfg, k, v, idx, n_kept, c, stream);
-    switch (cfg.group_size) {
-        case 32: return launch_bits_g<BITS, 32>(cfg, k, v, idx, n_kept, c, stream);
-        case 64: return launch_bits_g<BITS, 64>(cfg, k, v, idx, n_kept, c, stream);
-        default: return launch_bits_g<BITS, 128>(cfg, k, v, idx, n_kept, c, stream);
+hipError_t launch_bits(const QuantPackJob& j, hipStream_t stream) {
+    if (BITS == 16) return launch_bits_g<BITS, 32>(j, stream);
+    switch (j.group_size) {
+        case 32: return launch_bits_g<BITS, 32>(j, stream);
+        case 64: return launch_bits_g<BITS, 64>(j, stream);
+        default: return launch_bits_g<BITS, 128>(j, stream);
+    }
+}
+
+// Rows [n_shift, tail_len) of both tail tensors move down to [0, tail_len - n_shift).  One workgroup
+// per head; 16 rows per round go through registers (all reads of a round before its writes, rounds
+// in ascending order, so overlapping ranges are safe).
+__global__ __launch_bounds__(kThreads) void tail_shift(uint16_t* __restrict__ tail_k, uint16_t* __restrict__ tail_v,
+                                                       int tail_cap, int n_shift, int tail_len) {
+    const int head = blockIdx.x;
+    uint16_t* tk = tail_k + (size_t)head * tail_cap * kHeadDim;
+    uint16_t* tv = tail_v + (size_t)head * tail_cap * kHeadDim;
+    const int r = threadIdx.x >> 4, c8 = threadIdx.x & 15;
+    for (int r0 = n_shift; r0 < tail_len; r0 += 16) {
+        const int row = r0 + r;
+        const bool live = row < tail_len;
+        uint4 a = make_uint4(0, 0, 0, 0), b = a;
+        if (live) {
+            a = *reinterpret_cast<const uint4*>(tk + (size_t)row * kHeadDim + 8 * c8);
+            b = *reinterpret_cast<const uint4*>(tv + (size_t)row * kHeadDim + 8 * c8);
+        }
+        __syncthreads();
+        if (live) {
+            *reinterpret_cast<uint4*>(tk + (size_t)(row - n_shift) * kHeadDim + 8 * c8) = a;
+            *reinterpret_cast<uint4*>(tv + (size_t)(row - n_shift) * kHeadDim + 8 * c8) = b;
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_job(const QuantPackJob& j, hipStream_t stream) {
+    switch (j.bits) {
+        case 2: return launch_bits<2>(j, stream);
+        case 4: return launch_bits<4>(j, stream);
+        case 8: return launch_bits<8>(j, stream);
+        default: return launch_bits<16>(j, stream);
     }
 }
 
@@ -394,12 +441,26 @@ hipError_t launch_bits(const kvqp_cfg& cfg, const void* k, const void* v, const 
 
 hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx, int n_kept,
                              const kvqp_cache& cache, hipStream_t stream) {
-    switch (cfg.bits) {
-        case 2: return launch_bits<2>(cfg, k, v, idx, n_kept, cache, stream);
-        case 4: return launch_bits<4>(cfg, k, v, idx, n_kept, cache, stream);
-        case 8: return launch_bits<8>(cfg, k, v, idx, n_kept, cache, stream);
-        default: return launch_bits<16>(cfg, k, v, idx, n_kept, cache, stream);
-    }
+    QuantPackJob j{cache};
+    j.k = k; j.v = v; j.idx = idx;
+    j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cfg.seq_len; j.window = cfg.window;
+    j.n_tok = n_kept; j.dst_base = 0; j.n_cap = cache.n_cap > 0 ? cache.n_cap : n_kept;
+    j.bits = cfg.bits; j.group_size = cfg.group_size; j.key_axis = cfg.key_axis; j.copy_tail = true;
+    return launch_job(j, stream);
+}
+
+// The n_tokens oldest tail rows are quantized onto the end of the packed part, then the tail closes up.
+hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, hipStream_t stream) {
+    QuantPackJob j{cache};
+    j.k = cache.tail_k; j.v = cache.tail_v; j.idx = nullptr;
+    j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cache.tail_cap; j.window = 0;
+    j.n_tok = n_tokens; j.dst_base = cache.n_kept; j.n_cap = cache.n_cap > 0 ? cache.n_cap : cache.n_kept;
+    j.bits = cfg.bits; j.group_size = cfg.group_size; j.key_axis = cfg.key_axis; j.copy_tail = false;
+    hipError_t e = launch_job(j, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(tail_shift, dim3(j.heads), dim3(kThreads), 0, stream, (uint16_t*)cache.tail_k, (uint16_t*)cache.tail_v,
+                       cache.tail_cap, n_tokens, cache.tail_len);
+    return hipGetLastError();
 }
 
 }  // namespace kvqp

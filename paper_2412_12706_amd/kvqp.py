@@ -16,8 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libkvqp.so")
 KVQP_OK = 0
 KEY_PER_CHANNEL = 0
 KEY_PER_TOKEN = 1
-EXPORTS = ["kvqp_cache_sizes", "kvqp_workspace_bytes", "kvqp_compress", "kvqp_quantize_selected",
-           "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
+EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_workspace_bytes", "kvqp_compress",
+           "kvqp_quantize_selected", "kvqp_append_tail", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
 
 
 class KvqpError(RuntimeError):
@@ -35,7 +35,7 @@ class CfgStruct(C.Structure):
 class CacheStruct(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero",
                                           "tail_k", "tail_v")] + [(n, C.c_int32) for n in
-                                                                  ("n_kept", "tail_len", "tail_cap")]
+                                                                  ("n_kept", "tail_len", "tail_cap", "n_cap")]
 
 
 _lib = None
@@ -51,6 +51,8 @@ def lib():
         L.kvqp_strerror.restype = C.c_char_p
         L.kvqp_strerror.argtypes = [C.c_int]
         L.kvqp_cache_sizes.argtypes = [C.POINTER(CfgStruct), C.c_int32, C.POINTER(C.c_size_t)]
+        L.kvqp_cache_sizes_cap.argtypes = [C.POINTER(CfgStruct), C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        L.kvqp_append_tail.argtypes = [C.POINTER(CfgStruct), C.POINTER(CacheStruct), C.c_int32, C.c_void_p]
         L.kvqp_workspace_bytes.argtypes = [C.POINTER(CfgStruct), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.kvqp_compress.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(CacheStruct),
                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -104,6 +106,14 @@ def cache_sizes(cfg: Cfg, tail_cap: int):
     return list(out)
 
 
+def cache_sizes_cap(cfg: Cfg, n_cap: int, tail_cap: int):
+    out = (C.c_size_t * 8)()
+    rc = lib().kvqp_cache_sizes_cap(C.byref(cfg.struct()), n_cap, tail_cap, out)
+    if rc:
+        raise KvqpError(rc, "kvqp_cache_sizes_cap")
+    return list(out)
+
+
 def workspace_bytes(cfg: Cfg):
     a, b = C.c_size_t(), C.c_size_t()
     rc = lib().kvqp_workspace_bytes(C.byref(cfg.struct()), C.byref(a), C.byref(b))
@@ -122,22 +132,24 @@ class Cache:
     n_kept: int = 0
     tail_len: int = 0
     tail_cap: int = 0
+    n_cap: int = 0      # tokens the packed buffers are laid out for; 0 = n_kept (compact)
     _keep: list = field(default_factory=list)
 
     def struct(self) -> CacheStruct:
         ptrs = [self.buffers[n].data_ptr() if self.buffers[n].numel() else None for n in _NAMES]
-        return CacheStruct(*ptrs, self.n_kept, self.tail_len, self.tail_cap)
+        return CacheStruct(*ptrs, self.n_kept, self.tail_len, self.tail_cap, self.n_cap)
 
     def nbytes(self) -> int:
         return sum(t.numel() for t in self.buffers.values())
 
 
-def alloc_cache(cfg: Cfg, tail_cap: int | None = None, device="cuda") -> Cache:
+def alloc_cache(cfg: Cfg, tail_cap: int | None = None, device="cuda", n_cap: int = 0) -> Cache:
+    """Buffers for cfg's budget (compact) or, with n_cap, laid out for n_cap tokens per head."""
     import torch
     tail_cap = cfg.window if tail_cap is None else tail_cap
-    sizes = cache_sizes(cfg, tail_cap)
+    sizes = cache_sizes_cap(cfg, n_cap, tail_cap) if n_cap else cache_sizes(cfg, tail_cap)
     bufs = {n: torch.empty(max(s, 0), dtype=torch.uint8, device=device) for n, s in zip(_NAMES, sizes)}
-    return Cache(bufs, 0, 0, tail_cap)
+    return Cache(bufs, 0, 0, tail_cap, n_cap)
 
 
 def _stream_ptr(stream):
@@ -176,6 +188,16 @@ def quantize_selected(cfg: Cfg, k, v, idx, cache: Cache, stream=None):
                                       C.byref(cs), _stream_ptr(stream))
     if rc:
         raise KvqpError(rc, "kvqp_quantize_selected")
+    cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
+    return cache
+
+
+def append_tail(cfg: Cfg, cache: Cache, n_tokens: int, stream=None):
+    """kvqp_append_tail: the n_tokens oldest tail rows join the low-precision part."""
+    cs = cache.struct()
+    rc = lib().kvqp_append_tail(C.byref(cfg.struct()), C.byref(cs), n_tokens, _stream_ptr(stream))
+    if rc:
+        raise KvqpError(rc, "kvqp_append_tail")
     cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
     return cache
 

@@ -110,6 +110,35 @@ def test_entry_points_reject_null_pointers_without_touching_the_device(lib):
     assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1
 
 
+def test_capacity_sizes_and_append_argument_checks(lib):
+    """Buffers laid out for n_cap tokens are sized like a compact cache of n_cap
+    tokens; kvqp_append_tail validates counts on the host before any launch."""
+    cfg = kvqp.Cfg(batch=2, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024, bits=4, group_size=32)
+    compact = kvqp.cache_sizes(cfg, 40)
+    same = kvqp.cache_sizes_cap(cfg, 1024, 40)
+    assert compact == same
+    big = kvqp.cache_sizes_cap(cfg, 2048, 40)
+    assert all(b == 2 * a for a, b in zip(compact[:6], big[:6])) and big[6:] == compact[6:]
+    for bad in (1000, 1040, -64):         # not a multiple of 64 / negative
+        with pytest.raises(kvqp.KvqpError):
+            kvqp.cache_sizes_cap(cfg, bad, 40)
+    st = cfg.struct()
+    cs = kvqp.CacheStruct()
+    for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
+        setattr(cs, name, 0x1000)
+    cs.n_kept, cs.tail_len, cs.tail_cap, cs.n_cap = 1024, 64, 96, 1088
+    assert lib.kvqp_append_tail(None, C.byref(cs), 32, None) == -1
+    assert lib.kvqp_append_tail(C.byref(st), None, 32, None) == -1
+    assert lib.kvqp_append_tail(C.byref(st), C.byref(cs), 0, None) == -1       # nothing to move
+    assert lib.kvqp_append_tail(C.byref(st), C.byref(cs), 48, None) == -1      # not whole groups
+    assert lib.kvqp_append_tail(C.byref(st), C.byref(cs), 96, None) == -1      # more than the tail holds
+    cs.tail_len = 96
+    assert lib.kvqp_append_tail(C.byref(st), C.byref(cs), 96, None) == -1      # beyond the capacity
+    cs.n_cap = 1000
+    assert lib.kvqp_append_tail(C.byref(st), C.byref(cs), 32, None) == -1      # capacity below n_kept / misaligned
+    assert (cs.n_kept, cs.tail_len) == (1024, 96)                               # untouched by rejected calls
+
+
 def test_binding_raises_with_the_library_message(lib):
     cfg = kvqp.Cfg(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024, bits=5)
     with pytest.raises(kvqp.KvqpError) as e:
