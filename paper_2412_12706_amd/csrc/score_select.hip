@@ -11,14 +11,14 @@
 // Kernels.  The score matrix is a dense [Gq*W x D] x [D x L] contraction per
 // KV head, so it runs on the matrix cores (v_mfma_f32_16x16x32_f16, binary32
 // accumulation); everything after it is a bandwidth- or latency-bound sweep.
-//   score_pass<STATS>  row maxima and exp-sums of every window row (pass 1)
-//   stats_combine      merges the per-workgroup row statistics
+//   score_pass<STATS>  a reference and the exp-sum of every window row (pass 1)
+//   stats_combine      merges the per-wave row statistics
 //   score_pass<VOTES>  recomputes the tiles, normalises, sums columns (pass 2)
 //   select_topk        pool, radix-select the cut, ordered compaction; scores
-//                      within a relative 1e-4 of the cut are first re-scored in
+//                      within a relative 2e-5 of the cut are first re-scored in
 //                      binary64 so that binary32 rounding cannot move the cut
-// Keys stream through LDS once per pass in 128-key chunks shared by the four
-// waves of a workgroup; query rows stay in registers as MFMA operands.
+// Keys stream through LDS once per pass in 64- or 128-key chunks shared by the
+// four waves of a workgroup; query rows stay in registers as MFMA operands.
 #include "kvqp_internal.h"
 
 namespace kvqp {
@@ -54,7 +54,7 @@ struct ScoreArgs {
     float scale_log2;       // sm_scale * log2(e)
 };
 
-// NRW = number of 64-row slabs (1, 2, 4); the 4 waves are NRW row slabs x KS key strips.
+// NRW = number of row slabs (1, 2, 4) of RPW rows; the 4 waves are NRW row slabs x KS key strips.
 template <int NRW> struct ScoreGeom {
     static constexpr int KS = 4 / NRW;
     static constexpr int CK = (KS == 1) ? 64 : 128;   // keys per chunk
