@@ -137,3 +137,42 @@ def test_tail_grown_by_decoded_tokens(orc, bits, Gq, splits):
     err = np.abs(out.cpu().numpy().astype(np.float64) - ref).max()
     print(f"  bits={bits} Gq={Gq} splits={splits} max-abs error {err:.3e}", flush=True)
     assert err <= TOL
+
+
+def test_seeded_random_shapes(orc):
+    """Shapes drawn from a fixed seed across the supported space (bits, group,
+    key axis, heads per KV head, kept tokens, tail rows, splits): whatever
+    launch shape the library picks, the result must match the checker."""
+    rng = np.random.default_rng(20241212)
+    worst = 0.0
+    for case in range(24):
+        bits = int(rng.choice([2, 4, 8, 16]))
+        G = int(rng.choice([32, 64, 128]))
+        axis = int(rng.choice([0, 1])) if bits != 16 else 0
+        Gq = int(rng.choice([1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        B = int(rng.choice([1, 2]))
+        unit = 32 if (axis == 1 or bits == 16) else max(32, G)
+        n_kept = unit * int(rng.integers(0, 1 + 1536 // unit))
+        W = int(rng.integers(1, 1 + 256 // Gq)) if n_kept else int(rng.integers(1, 40))
+        W = min(W, 64)
+        splits = int(rng.choice([0, 0, 1, 2, 7]))
+        print(f"case {case}: bits={bits} G={G} axis={axis} Gq={Gq} Hkv={Hkv} B={B} n_kept={n_kept} W={W} splits={splits}", flush=True)
+        L = n_kept + W + 23
+        Hq = Hkv * Gq
+        _, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, config=300 + case)
+        idx = np.stack([np.sort(rng.choice(L - W, n_kept, replace=False)) for _ in range(B * Hkv)]).astype(np.int32).reshape(B, Hkv, n_kept)
+        oc = orc.quantize_selected(k, v, idx, W=W, bits=bits, G=G, key_axis=axis)
+        cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, budget=n_kept, bits=bits, group_size=G,
+                       key_axis=axis, decode_splits=splits)
+        q = synth.decode_query_host(B, Hq, 128, config=300 + case)
+        ref = orc.decode_attn(q, oc, cfg.sm_scale)
+        out = kvqp.decode_attn(cfg, dev(q), upload_cache(oc))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got))
+        err = np.abs(got - ref).max()
+        worst = max(worst, err)
+        print(f"    max-abs error {err:.3e}", flush=True)
+        assert err <= TOL, f"case {case}: max-abs error {err:.3e}"
+    print(f"  worst max-abs error {worst:.3e}", flush=True)
