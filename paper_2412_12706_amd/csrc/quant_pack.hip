@@ -72,7 +72,7 @@ __device__ __forceinline__ GroupParams group_params(uint32_t kmin, uint32_t kmax
 }
 template <int BITS>
 __device__ __forceinline__ uint32_t encode(uint16_t xh, const GroupParams& g) {
-    if (g.inv == 0.0f) return 0u;
+    // a degenerate group needs no branch: (x - z) * 0 rounds and clamps to code 0
     float c = rintf(__fmul_rn(__fsub_rn(half_bits_to_float(xh), g.zf), g.inv));
     c = fminf(fmaxf(c, 0.0f), (float)((1 << BITS) - 1));
     return (uint32_t)c;
@@ -101,6 +101,17 @@ __device__ __forceinline__ void encode8(const uint32_t (&w)[4], const float (&zf
         g0.zf = zf[2 * q]; g0.inv = inv[2 * q]; g1.zf = zf[2 * q + 1]; g1.inv = inv[2 * q + 1];
         c[2 * q] = encode<BITS>((uint16_t)(w[q] & 0xffffu), g0);
         c[2 * q + 1] = encode<BITS>((uint16_t)(w[q] >> 16), g1);
+    }
+}
+
+// the same when all eight channels share one group
+template <int BITS>
+__device__ __forceinline__ void encode8(const uint32_t (&w)[4], float zf, float inv, uint32_t (&c)[8]) {
+    GroupParams g; g.zf = zf; g.inv = inv;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        c[2 * q] = encode<BITS>((uint16_t)(w[q] & 0xffffu), g);
+        c[2 * q + 1] = encode<BITS>((uint16_t)(w[q] >> 16), g);
     }
 }
 
@@ -191,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const int t = r + 16 * j;
-        live[j] = t < ntok;
+        live[j] = 32 * (j >> 1) < ntok;   // ntok is a multiple of 32: the same for the whole workgroup
         const int pos = !live[j] ? 0 : idx ? idx[(size_t)head * n_kept + t0 + t] : t0 + t;
         const uint4 a = live[j] ? *reinterpret_cast<const uint4*>(kh + (size_t)pos * kHeadDim + 8 * c8) : make_uint4(0, 0, 0, 0);
         const uint4 b = live[j] ? *reinterpret_cast<const uint4*>(vh + (size_t)pos * kHeadDim + 8 * c8) : make_uint4(0, 0, 0, 0);
@@ -227,12 +238,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             const uint32_t zq[4] = {dpp<0x00>(zb), dpp<0x55>(zb), dpp<0xAA>(zb), dpp<0xFF>(zb)};
             const uint32_t iq[4] = {dpp<0x00>(ib), dpp<0x55>(ib), dpp<0xAA>(ib), dpp<0xFF>(ib)};
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                float zf[8], inv[8];
-#pragma unroll
-                for (int dd = 0; dd < 8; ++dd) { zf[dd] = __uint_as_float(zq[u]); inv[dd] = __uint_as_float(iq[u]); }
-                encode8<BITS>(w[4 * jj + u], zf, inv, codes[4 * jj + u]);
-            }
+            for (int u = 0; u < 4; ++u) encode8<BITS>(w[4 * jj + u], __uint_as_float(zq[u]), __uint_as_float(iq[u]), codes[4 * jj + u]);
         }
     };
 
