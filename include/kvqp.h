@@ -7,7 +7,7 @@
  * ("KV Quantization": z = min, m = max, s = (m - z)/(2^B - 1),
  * Q(G) = round((G - z)/s)); at decode the attention of Eq. (3),
  * Softmax(h_Q X_K^T) X_V, runs on the dequantized survivors G' = Q(G) s + z
- * ("Quantized Pruning").  Grouping axes follow Section 2 / Section 5.4: keys
+ * ("Quantized Pruning").  Grouping axes follow Section 2 / Section 6.3: keys
  * per channel, values per token (KIVI), or keys per token as the ablation
  * (FlexGen).  The paper's Limitations section names the missing piece this
  * library supplies: dequantization fused into the attention products.
@@ -125,6 +125,10 @@ typedef struct kvqp_cache {
                          kvqp_cache_sizes.  A larger n_cap (a multiple of 64 and of G,
                          sizes from kvqp_cache_sizes_cap) leaves room for
                          kvqp_append_tail.  Set by the caller, never changed.           */
+    int32_t *head_n_kept; /* DEVICE int32 [batch * Hkv] or NULL.  Non-NULL marks a cache with
+                         head-level token counts (kvqp_compress_ragged fills it): head h holds
+                         head_n_kept[h] <= n_kept tokens at the start of its share of every
+                         buffer, and n_kept is only the bound the counts stay under.       */
 } kvqp_cache;
 
 /* Bytes of the eight cache buffers (order of the struct) for n_kept =
@@ -170,6 +174,31 @@ int kvqp_compress(const kvqp_cfg *cfg, const void *q_obs, const void *k, const v
                   void *hip_stream);
 
 /*
+ * Compression with a token count of its own for every KV head (Section 5, Q1, and
+ * Table 1 evaluate head-level allocation, Ada-KV and HeadKV, which the paper
+ * pairs with per-token key groups because the heads keep different numbers of
+ * tokens, and PyramidKV, whose count varies by layer; Appendix B gives them a
+ * window of 8).  The allocation rule itself is the caller's: this call takes
+ * its result.  Scoring, the cut and the quantizer are those of kvqp_compress,
+ * applied to head h with head_budget[h] in place of n_kept.
+ *   head_budget  HOST int32 [batch * Hkv]; every entry a multiple of 32 (of
+ *                group_size for per-channel keys), >= 0 and
+ *                <= min(cfg->budget, L - W).  Read before the call returns.
+ *   cache        as for kvqp_compress with n_kept = min(cfg->budget, L - W) in
+ *                every shape (or n_cap); head_n_kept must point to device memory
+ *                and receives the counts (a copy enqueued on the stream);
+ *                n_kept is set to the bound, tail_len to W.
+ *   idx_out      int32 [batch, Hkv, n_kept] or NULL: the first head_budget[h]
+ *                entries of head h are its survivors, the rest is unspecified.
+ * kvqp_decode_attn reads such a cache through head_n_kept (tail_len must be
+ * >= 1); kvqp_append_tail does not take one (UNSUPPORTED), and kvqp_compress
+ * and kvqp_quantize_selected want head_n_kept == NULL (INVALID_ARG).
+ */
+int kvqp_compress_ragged(const kvqp_cfg *cfg, const void *q_obs, const void *k, const void *v,
+                         const int32_t *head_budget, kvqp_cache *cache, int32_t *idx_out,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The quantization half alone (Section 3 "KV Quantization" applied to given
  * survivors): idx int32 [batch, Hkv, n_kept] ascending positions < L - W
  * chosen by any pruning method; cfg->budget is ignored and n_kept is taken
@@ -187,7 +216,11 @@ int kvqp_quantize_selected(const kvqp_cfg *cfg, const void *k, const void *v, co
  *   q   half [batch, Hq, D]
  *   out half [batch, Hq, D]   binary32 accumulation, rounded once at the end
  * cfg fields used: batch, heads, head_dim, bits, group_size, key_axis,
- * decode_splits, sm_scale.  n_kept + tail_len must be >= 1.
+ * decode_splits, sm_scale.  n_kept + tail_len must be >= 1.  With head-level
+ * counts (cache->head_n_kept non-NULL) head h attends its first
+ * head_n_kept[h] tokens; the counts are read on the device, where a count
+ * above n_kept is cut to n_kept and rounded down to a multiple of 32
+ * (group_size for per-channel keys).
  * Calls of kvqp_decode_attn must not overlap in time on one device: the merge of the
  * token-axis splits uses device-wide arrival counters owned by the library (calls
  * issued on one stream never overlap).

@@ -214,12 +214,27 @@ struct DecodeArgs {
     uint16_t* out;            // [B, Hq, D]
     int n_kept, tail_len, tail_cap;
     int n_cap;                // tokens the packed buffers are laid out for (head strides); >= n_kept
+    const int32_t* head_n_kept;   // per (batch, kv head) token counts under the bound n_kept, or NULL
+    int quantum;              // a head's count is a multiple of this power of two (32, or G for per-channel keys)
     int n_q_heads, n_kv_heads;
     int n_splits, chunks_per_split, n_partials;
     int n_waves;              // waves per workgroup of the pipelined kernel
     int group;                // G
     float sm_scale;
 };
+
+// Tokens of one head: the launch's count, or the head's own, cut to the bound and to whole groups
+// so that no value found in memory can lead a load past the buffers.  Uniform over the workgroup.
+__device__ __forceinline__ int head_tokens(const DecodeArgs& a, int bh) {
+    if (!a.head_n_kept) return a.n_kept;
+    int n = a.head_n_kept[bh];
+    n = n < 0 ? 0 : (n > a.n_kept ? a.n_kept : n);
+    return n & ~(a.quantum - 1);
+}
+// 64-token chunks a split workgroup takes: the plan's share, or an even share of the head's own chunks
+__device__ __forceinline__ int head_chunks_per_split(const DecodeArgs& a, int n_chunks) {
+    return a.head_n_kept ? (n_chunks + a.n_splits - 1) / a.n_splits : a.chunks_per_split;
+}
 
 // Partials cross workgroups (and XCDs, whose L2 caches are not coherent with each other inside a
 // kernel) without device-wide fences, which would write back / invalidate whole L2s: they are
@@ -495,7 +510,8 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 
     const uint32_t* kc = a.k_codes + (size_t)bh * ((size_t)a.n_cap * kHeadDim * BITS / 32);
     const uint32_t* vc = a.v_codes + (size_t)bh * v_superblock_words(BITS) * ((a.n_cap + v_superblock(BITS) - 1) / v_superblock(BITS));
-    const int n_kgroups = (AXIS == KVQP_KEY_PER_CHANNEL) ? a.n_kept / G : a.n_kept;
+    const int n_kept = head_tokens(a, bh);
+    const int n_kgroups = (AXIS == KVQP_KEY_PER_CHANNEL) ? n_kept / G : n_kept;
     const int cap_kgroups = (AXIS == KVQP_KEY_PER_CHANNEL) ? a.n_cap / G : a.n_cap;   // head stride of the key scales
     const uint16_t* ks = QUANT ? a.k_scale + (size_t)bh * cap_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
     const uint16_t* kz = QUANT ? a.k_zero + (size_t)bh * cap_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
@@ -541,13 +557,14 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
     for (int c = 0; c < NCG; ++c) oz[c] = 0.f;
     float m_run = kNegBig, l_run = 0.f;
 
-    const int n_chunks = (a.n_kept + kChunk - 1) / kChunk;
-    const int c_begin = blockIdx.x * a.chunks_per_split;
-    const int c_end = min(n_chunks, c_begin + a.chunks_per_split);
+    const int n_chunks = (n_kept + kChunk - 1) / kChunk;
+    const int cps = head_chunks_per_split(a, n_chunks);
+    const int c_begin = blockIdx.x * cps;
+    const int c_end = min(n_chunks, c_begin + cps);
 
     for (int chunk = c_begin + wave; chunk < c_end; chunk += kWaves) {
         const int tok0 = chunk * kChunk;
-        const int nblk = (a.n_kept - tok0 >= kChunk) ? 2 : 1;  // n_kept is a multiple of 32
+        const int nblk = (n_kept - tok0 >= kChunk) ? 2 : 1;  // n_kept is a multiple of 32
 
         // ---------------- logits of the lane's tokens ----------------
         float logit[2][NT][4];
@@ -876,7 +893,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     const uint32_t v_lane = (uint32_t)lane * 16;
     const uint32_t row_lane = (uint32_t)lane * 4;                                     // dword of a 256-byte scale row
     const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
-    const int n_kgroups = QUANT ? a.n_kept / G : 0;
+    const int n_kept = head_tokens(a, bh);
+    const int n_kgroups = QUANT ? max(n_kept / G, 1) : 0;
     // The loads of the pipeline are unconditional; when a wave has no further chunk they are pointed
     // at one 16-byte spot (lane offsets zeroed) instead of re-reading a whole chunk.
     uint32_t k_off = k_lane, v_off = v_lane, row_off = row_lane, vrow_off = vrow_lane;
@@ -1117,9 +1135,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             O[t8] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[(t8 * 16) / G].v, v_frag<BITS>(vv, vblk, t8).v, O[t8], 0, 0, 0);
     };
 
-    const int n_chunks = (a.n_kept + kChunk - 1) / kChunk;
-    const int c_begin = blockIdx.x * a.chunks_per_split;
-    const int c_end = min(n_chunks, c_begin + a.chunks_per_split);
+    const int n_chunks = (n_kept + kChunk - 1) / kChunk;
+    const int cps = head_chunks_per_split(a, n_chunks);
+    const int c_begin = blockIdx.x * cps;
+    const int c_end = min(n_chunks, c_begin + cps);
     // Chunks are claimed, not dealt: a wave takes its first chunk by index and every later one from
     // a workgroup counter, so waves that start late (the tail rows) or run slower (the SIMD favours
     // its oldest wave) simply take fewer and all of them finish together.
@@ -1131,7 +1150,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         return __builtin_amdgcn_readfirstlane(v);
     };
     int chunk = c_begin + wave;
-    bool two = chunk < c_end && a.n_kept - chunk * kChunk >= kChunk;   // n_kept is a multiple of 32
+    bool two = chunk < c_end && n_kept - chunk * kChunk >= kChunk;   // n_kept is a multiple of 32
     // The second block of a chunk is requested right after the previous chunk's second block has
     // been consumed (quantized variants: more bytes in flight, and the first chunk's blocks are both
     // on their way before anything waits); the 16-bit variant, whose blocks are four times larger,
@@ -1216,7 +1235,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         // both blocks of the wave's next chunk are requested while this chunk's second block is computed
         const bool has_next = next < c_end;
         const int nx = has_next ? next : chunk;
-        const bool two_nx = a.n_kept - nx * kChunk >= kChunk;
+        const bool two_nx = n_kept - nx * kChunk >= kChunk;
         if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; }   // (wave-uniform; the loop ends after this pass)
         load_A(nx);
         if (two) compute(bk0, bk1, b_ks, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
@@ -1430,6 +1449,8 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.out = (uint16_t*)out;
     a.n_kept = c.n_kept; a.tail_len = c.tail_len; a.tail_cap = c.tail_cap;
     a.n_cap = c.n_cap > 0 ? c.n_cap : c.n_kept;
+    a.head_n_kept = c.head_n_kept;
+    a.quantum = (cfg.bits != 16 && cfg.key_axis == KVQP_KEY_PER_CHANNEL) ? cfg.group_size : 32;
     a.n_q_heads = cfg.n_q_heads; a.n_kv_heads = cfg.n_kv_heads;
     a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;
     a.n_waves = plan.n_waves;

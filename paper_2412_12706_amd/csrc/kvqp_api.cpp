@@ -74,6 +74,11 @@ int fill_sizes(const kvqp_cfg* cfg, int n_tok, int32_t tail_cap, size_t sizes_ou
     return KVQP_OK;
 }
 
+// Smallest step of a head-level token count: whole value blocks and, for per-channel keys, whole key groups.
+int head_quantum(const kvqp_cfg* c) {
+    return (c->bits != 16 && c->key_axis == KVQP_KEY_PER_CHANNEL && c->group_size > 32) ? c->group_size : 32;
+}
+
 int check_cache_ptrs(const kvqp_cfg* c, const kvqp_cache* cache, int n_kept, bool need_tail) {
     if (!cache) return KVQP_ERR_INVALID_ARG;
     if (check_cap(c, cache->n_cap, n_kept)) return KVQP_ERR_INVALID_ARG;
@@ -93,7 +98,7 @@ using namespace kvqp;
 
 extern "C" {
 
-int kvqp_version(void) { return 200; }
+int kvqp_version(void) { return 300; }
 
 const char* kvqp_strerror(int code) {
     switch (code) {
@@ -145,15 +150,16 @@ int kvqp_quantize_selected(const kvqp_cfg* cfg, const void* k, const void* v, co
     if (!k || !v || (n_kept > 0 && !idx)) return KVQP_ERR_INVALID_ARG;
     if (n_kept > cfg->seq_len - cfg->window) return KVQP_ERR_INVALID_ARG;
     if ((rc = check_cache_ptrs(cfg, cache, n_kept, true))) return rc;
-    if (cache->tail_cap < cfg->window) return KVQP_ERR_INVALID_ARG;
-    if (launch_quant_pack(*cfg, k, v, idx, n_kept, *cache, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    if (cache->tail_cap < cfg->window || cache->head_n_kept) return KVQP_ERR_INVALID_ARG;
+    if (launch_quant_pack(*cfg, k, v, idx, n_kept, nullptr, *cache, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
     cache->n_kept = n_kept;
     cache->tail_len = cfg->window;
     return KVQP_OK;
 }
 
-int kvqp_compress(const kvqp_cfg* cfg, const void* q_obs, const void* k, const void* v, kvqp_cache* cache,
-                  int32_t* idx_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+// Both forms of compression: head_budget == NULL is the uniform one.
+static int compress_impl(const kvqp_cfg* cfg, const void* q_obs, const void* k, const void* v, const int32_t* head_budget,
+                         kvqp_cache* cache, int32_t* idx_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
     int rc = check_common(cfg);
     if (rc) return rc;
     if ((rc = check_prompt(cfg))) return rc;
@@ -162,28 +168,54 @@ int kvqp_compress(const kvqp_cfg* cfg, const void* q_obs, const void* k, const v
     if (!q_obs || !k || !v) return KVQP_ERR_INVALID_ARG;
     if ((rc = check_cache_ptrs(cfg, cache, n_kept, true))) return rc;
     if (cache->tail_cap < cfg->window) return KVQP_ERR_INVALID_ARG;
+    if ((head_budget != nullptr) != (cache->head_n_kept != nullptr)) return KVQP_ERR_INVALID_ARG;
+    const int heads = cfg->batch * cfg->n_kv_heads;
+    bool score = n_kept < cfg->seq_len - cfg->window;
+    if (head_budget) {
+        const int quantum = head_quantum(cfg);
+        score = false;
+        for (int h = 0; h < heads; ++h) {
+            if (head_budget[h] < 0 || head_budget[h] > n_kept || head_budget[h] % quantum) return KVQP_ERR_INVALID_ARG;
+            if (head_budget[h] > 0 && head_budget[h] < cfg->seq_len - cfg->window) score = true;
+        }
+    }
     const CompressPlan plan = plan_compress(*cfg);
     if (!workspace || workspace_bytes < plan.total) return KVQP_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 15) != 0) return KVQP_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
     int32_t* idx = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.off_idx);
+    if (head_budget &&
+        hipMemcpyAsync(cache->head_n_kept, head_budget, (size_t)heads * sizeof(int32_t), hipMemcpyHostToDevice, stream) != hipSuccess)
+        return KVQP_ERR_HIP;
     if (n_kept > 0) {
-        if (launch_select(*cfg, q_obs, k, idx, workspace, plan, stream) != hipSuccess) return KVQP_ERR_HIP;
+        if (launch_select(*cfg, q_obs, k, idx, workspace, plan, cache->head_n_kept, score, stream) != hipSuccess) return KVQP_ERR_HIP;
         if (idx_out) {
-            const size_t bytes = (size_t)cfg->batch * cfg->n_kv_heads * n_kept * sizeof(int32_t);
+            const size_t bytes = (size_t)heads * n_kept * sizeof(int32_t);
             if (hipMemcpyAsync(idx_out, idx, bytes, hipMemcpyDeviceToDevice, stream) != hipSuccess) return KVQP_ERR_HIP;
         }
     }
-    if (launch_quant_pack(*cfg, k, v, idx, n_kept, *cache, stream) != hipSuccess) return KVQP_ERR_HIP;
+    if (launch_quant_pack(*cfg, k, v, idx, n_kept, cache->head_n_kept, *cache, stream) != hipSuccess) return KVQP_ERR_HIP;
     cache->n_kept = n_kept;
     cache->tail_len = cfg->window;
     return KVQP_OK;
+}
+
+int kvqp_compress(const kvqp_cfg* cfg, const void* q_obs, const void* k, const void* v, kvqp_cache* cache,
+                  int32_t* idx_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return compress_impl(cfg, q_obs, k, v, nullptr, cache, idx_out, workspace, workspace_bytes, hip_stream);
+}
+
+int kvqp_compress_ragged(const kvqp_cfg* cfg, const void* q_obs, const void* k, const void* v, const int32_t* head_budget,
+                         kvqp_cache* cache, int32_t* idx_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!head_budget) return KVQP_ERR_INVALID_ARG;
+    return compress_impl(cfg, q_obs, k, v, head_budget, cache, idx_out, workspace, workspace_bytes, hip_stream);
 }
 
 int kvqp_append_tail(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_tokens, void* hip_stream) {
     int rc = check_common(cfg);
     if (rc) return rc;
     if (!cache || n_tokens < 1) return KVQP_ERR_INVALID_ARG;
+    if (cache->head_n_kept) return KVQP_ERR_UNSUPPORTED;   // head-level counts: the heads would need their own steps
     if (cache->n_kept < 0 || cache->tail_len < 0 || cache->tail_len > cache->tail_cap) return KVQP_ERR_INVALID_ARG;
     if (n_tokens > cache->tail_len) return KVQP_ERR_INVALID_ARG;
     // whole value superblocks and, for per-channel keys, whole key groups
@@ -206,6 +238,7 @@ int kvqp_decode_attn(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache
     if (!q || !out || !cache) return KVQP_ERR_INVALID_ARG;
     if (cache->n_kept < 0 || cache->tail_len < 0 || cache->tail_len > cache->tail_cap) return KVQP_ERR_INVALID_ARG;
     if (cache->n_kept + cache->tail_len < 1) return KVQP_ERR_INVALID_ARG;
+    if (cache->head_n_kept && cache->tail_len < 1) return KVQP_ERR_INVALID_ARG;   // a head may hold no packed token at all
     if ((rc = check_n_kept(cfg, cache->n_kept))) return rc;
     if ((rc = check_cache_ptrs(cfg, cache, cache->n_kept, cache->tail_len > 0))) return rc;
     const DecodePlan plan = plan_decode(*cfg, cache->n_kept, cache->tail_len);

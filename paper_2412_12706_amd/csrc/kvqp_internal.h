@@ -51,12 +51,14 @@ struct CompressPlan {
 };
 CompressPlan plan_compress(const kvqp_cfg& cfg);
 
+// head_n (device, or NULL): every head's own token count under n_kept
 hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx,
-                             int n_kept, const kvqp_cache& cache, hipStream_t stream);
+                             int n_kept, const int32_t* head_n, const kvqp_cache& cache, hipStream_t stream);
 hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& cache, void* out,
                          void* ws, const DecodePlan& plan, hipStream_t stream);
 hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, hipStream_t stream);
+// head_n (device, or NULL): every head's own cut under plan.n_kept; score says whether any head drops a token
 hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx,
-                         void* ws, const CompressPlan& plan, hipStream_t stream);
+                         void* ws, const CompressPlan& plan, const int32_t* head_n, bool score, hipStream_t stream);
 
 }  // namespace kvqp

@@ -1,7 +1,7 @@
 // Gather the surviving tokens, quantize them group by group and write the
 // packed cache (paper Section 3, "KV Quantization": z = min, m = max,
 // s = (m - z)/(2^B - 1), Q(G) = round((G - z)/s); grouping axes of Section 2 /
-// Section 5.4).  Memory-bound by design: every survivor row is read once
+// Section 6.3).  Memory-bound by design: every survivor row is read once
 // (2 x 256 B) and k*bpt bytes are written; there is no reuse to exploit.
 //
 // One workgroup owns TB consecutive kept tokens of one (batch, kv head): whole
@@ -29,6 +29,7 @@ constexpr int kThreads = 256;
 struct QuantPackJob {
     const kvqp_cache& c;
     const void* k; const void* v; const int32_t* idx;
+    const int32_t* head_n;   // device: rows of each head (<= n_tok, whole groups), or NULL for n_tok everywhere
     int heads, src_rows, window, n_tok, dst_base, n_cap, bits, group_size, key_axis;
     bool copy_tail;
 };
@@ -153,10 +154,11 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale,
     uint16_t* __restrict__ k_zero, uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero,
     uint16_t* __restrict__ tail_k, uint16_t* __restrict__ tail_v, int L, int W, int n_kept, int key_axis,
-    int tail_cap, int n_tok_blocks, int n_cap, int dst_base) {
+    int tail_cap, int n_tok_blocks, int n_cap, int dst_base, const int32_t* __restrict__ head_n) {
     // L: rows per head of the source tensors.  idx: source row of every token of this call
     // ([heads, n_kept]), or NULL for rows 0 .. n_kept-1.  The tokens land at positions dst_base ..
     // dst_base + n_kept - 1 of a cache whose buffers are laid out for n_cap tokens per head.
+    // head_n: a head's own token count in place of n_kept (idx keeps its stride of n_kept), or NULL.
     constexpr bool QUANT = BITS != 16;
     constexpr int TB = (QUANT && G == 128) ? 128 : 64;   // tokens per workgroup
     constexpr int R = TB / 16;                            // rows per thread
@@ -194,7 +196,9 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     const int c8 = threadIdx.x & 15, r = threadIdx.x >> 4, i4 = (threadIdx.x >> 4) & 3;
     const int t0 = blockIdx.x * TB;
     const int d0 = dst_base + t0;            // first destination token: a multiple of the group and superblock sizes
-    const int ntok = min(TB, n_kept - t0);   // a multiple of 32 (and of G for per-channel keys)
+    const int n_head = head_n ? head_n[head] : n_kept;
+    if (t0 >= n_head) return;                // (the whole workgroup: nothing of this head left)
+    const int ntok = min(TB, n_head - t0);   // a multiple of 32 (and of G for per-channel keys)
 
     // ---- gather: all of the thread's rows of both tensors are requested before anything is used ----
     uint32_t kw[R][4], vw[R][4];
@@ -395,7 +399,7 @@ hipError_t launch_bits_g(const QuantPackJob& j, hipStream_t stream) {
                        (const uint16_t*)j.v, j.idx, (uint32_t*)j.c.k_codes, (uint32_t*)j.c.v_codes, (uint16_t*)j.c.k_scale,
                        (uint16_t*)j.c.k_zero, (uint16_t*)j.c.v_scale, (uint16_t*)j.c.v_zero, (uint16_t*)j.c.tail_k,
                        (uint16_t*)j.c.tail_v, j.src_rows, j.window, j.n_tok, j.key_axis, j.c.tail_cap, nblk, j.n_cap,
-                       j.dst_base);
+                       j.dst_base, j.head_n);
     return hipGetLastError();
 }
 template <int BITS>
@@ -446,9 +450,9 @@ hipError_t launch_job(const QuantPackJob& j, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx, int n_kept,
-                             const kvqp_cache& cache, hipStream_t stream) {
+                             const int32_t* head_n, const kvqp_cache& cache, hipStream_t stream) {
     QuantPackJob j{cache};
-    j.k = k; j.v = v; j.idx = idx;
+    j.k = k; j.v = v; j.idx = idx; j.head_n = head_n;
     j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cfg.seq_len; j.window = cfg.window;
     j.n_tok = n_kept; j.dst_base = 0; j.n_cap = cache.n_cap > 0 ? cache.n_cap : n_kept;
     j.bits = cfg.bits; j.group_size = cfg.group_size; j.key_axis = cfg.key_axis; j.copy_tail = true;
@@ -458,7 +462,7 @@ hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, 
 // The n_tokens oldest tail rows are quantized onto the end of the packed part, then the tail closes up.
 hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, hipStream_t stream) {
     QuantPackJob j{cache};
-    j.k = cache.tail_k; j.v = cache.tail_v; j.idx = nullptr;
+    j.k = cache.tail_k; j.v = cache.tail_v; j.idx = nullptr; j.head_n = nullptr;
     j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cache.tail_cap; j.window = 0;
     j.n_tok = n_tokens; j.dst_base = cache.n_kept; j.n_cap = cache.n_cap > 0 ? cache.n_cap : cache.n_kept;
     j.bits = cfg.bits; j.group_size = cfg.group_size; j.key_axis = cfg.key_axis; j.copy_tail = false;

@@ -290,6 +290,7 @@ struct SelectArgs {
     const float* vote;      // [heads, P]
     float* pooled;          // [heads, P]
     int32_t* idx;           // [heads, n_kept]
+    const int32_t* head_n;  // a head's own cut (<= n_kept), or NULL for n_kept everywhere
     const uint16_t* q_obs;
     const uint16_t* k;
     const float2* stats;    // (m, 1/Z) binary32
@@ -407,15 +408,16 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
     __shared__ float stage[kStageRows * kSelThreads + 2 * kMaxPoolRadius];   // votes of a few rows plus halo
 
     const int head = blockIdx.x;
-    const int P = a.P, k = a.n_kept;
+    const int P = a.P, k = a.head_n ? a.head_n[head] : a.n_kept;
     const float* vote = a.vote + (size_t)head * P;
     float* pooled = a.pooled + (size_t)head * P;
-    int32_t* idx = a.idx + (size_t)head * k;
+    int32_t* idx = a.idx + (size_t)head * a.n_kept;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n_rows = (P + kSelThreads - 1) / kSelThreads;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
-    if (k >= P) {  // budget covers the prefix: identity, no scores were computed
+    if (k <= 0) return;   // (a head-level count may be zero)
+    if (k >= P) {  // budget covers the prefix: identity, the scores are not looked at
         for (int j = threadIdx.x; j < k; j += kSelThreads) idx[j] = j;
         return;
     }
@@ -701,7 +703,7 @@ CompressPlan plan_compress(const kvqp_cfg& cfg) {
 }
 
 hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx, void* ws,
-                         const CompressPlan& plan, hipStream_t stream) {
+                         const CompressPlan& plan, const int32_t* head_n, bool score, hipStream_t stream) {
     char* base = static_cast<char*>(ws);
     const int heads = cfg.batch * cfg.n_kv_heads;
     const int nrw = plan.n_row_slabs;
@@ -722,7 +724,7 @@ hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, 
     a.scale_log2 = cfg.sm_scale * kLog2e;
 
     hipError_t e;
-    if (plan.n_kept < plan.P) {   // scores are needed only when something is dropped
+    if (score) {   // scores are needed only when something is dropped
         if (rows_per_wave(plan.rows) == 32) {
             switch (nrw) {
                 case 1: e = launch_scores<32, 1>(a, n_wg, heads, stream, stats, zsum); break;
@@ -735,7 +737,7 @@ hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, 
         if (e != hipSuccess) return e;
     }
     SelectArgs s;
-    s.vote = a.vote; s.pooled = reinterpret_cast<float*>(base + plan.off_pooled); s.idx = idx;
+    s.vote = a.vote; s.pooled = reinterpret_cast<float*>(base + plan.off_pooled); s.idx = idx; s.head_n = head_n;
     s.q_obs = a.q_obs; s.k = a.k; s.stats = stats; s.zsum = zsum;
     s.P = plan.P; s.L = cfg.seq_len; s.W = cfg.window; s.n_kept = plan.n_kept; s.pool = cfg.pool_kernel;
     s.gq = a.gq; s.n_q_heads = cfg.n_q_heads; s.n_kv_heads = cfg.n_kv_heads; s.rows = a.rows; s.rows_pad = a.rows_pad;

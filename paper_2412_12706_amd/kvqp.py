@@ -17,7 +17,7 @@ KVQP_OK = 0
 KEY_PER_CHANNEL = 0
 KEY_PER_TOKEN = 1
 EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_workspace_bytes", "kvqp_compress",
-           "kvqp_quantize_selected", "kvqp_append_tail", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
+           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_append_tail", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
 
 
 class KvqpError(RuntimeError):
@@ -35,7 +35,8 @@ class CfgStruct(C.Structure):
 class CacheStruct(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero",
                                           "tail_k", "tail_v")] + [(n, C.c_int32) for n in
-                                                                  ("n_kept", "tail_len", "tail_cap", "n_cap")]
+                                                                  ("n_kept", "tail_len", "tail_cap", "n_cap")] + [
+        ("head_n_kept", C.c_void_p)]
 
 
 _lib = None
@@ -56,6 +57,9 @@ def lib():
         L.kvqp_workspace_bytes.argtypes = [C.POINTER(CfgStruct), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.kvqp_compress.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(CacheStruct),
                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.kvqp_compress_ragged.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.POINTER(C.c_int32), C.POINTER(CacheStruct), C.c_void_p, C.c_void_p,
+                                           C.c_size_t, C.c_void_p]
         L.kvqp_quantize_selected.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                              C.POINTER(CacheStruct), C.c_void_p]
         L.kvqp_decode_attn.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.POINTER(CacheStruct), C.c_void_p,
@@ -133,23 +137,27 @@ class Cache:
     tail_len: int = 0
     tail_cap: int = 0
     n_cap: int = 0      # tokens the packed buffers are laid out for; 0 = n_kept (compact)
+    head_n_kept: object = None   # int32 device tensor [batch * Hkv] of a cache with head-level counts
     _keep: list = field(default_factory=list)
 
     def struct(self) -> CacheStruct:
         ptrs = [self.buffers[n].data_ptr() if self.buffers[n].numel() else None for n in _NAMES]
-        return CacheStruct(*ptrs, self.n_kept, self.tail_len, self.tail_cap, self.n_cap)
+        return CacheStruct(*ptrs, self.n_kept, self.tail_len, self.tail_cap, self.n_cap,
+                           None if self.head_n_kept is None else self.head_n_kept.data_ptr())
 
     def nbytes(self) -> int:
         return sum(t.numel() for t in self.buffers.values())
 
 
-def alloc_cache(cfg: Cfg, tail_cap: int | None = None, device="cuda", n_cap: int = 0) -> Cache:
-    """Buffers for cfg's budget (compact) or, with n_cap, laid out for n_cap tokens per head."""
+def alloc_cache(cfg: Cfg, tail_cap: int | None = None, device="cuda", n_cap: int = 0, ragged: bool = False) -> Cache:
+    """Buffers for cfg's budget (compact) or, with n_cap, laid out for n_cap tokens per head;
+    ragged adds the device array of head-level token counts."""
     import torch
     tail_cap = cfg.window if tail_cap is None else tail_cap
     sizes = cache_sizes_cap(cfg, n_cap, tail_cap) if n_cap else cache_sizes(cfg, tail_cap)
     bufs = {n: torch.empty(max(s, 0), dtype=torch.uint8, device=device) for n, s in zip(_NAMES, sizes)}
-    return Cache(bufs, 0, 0, tail_cap, n_cap)
+    counts = torch.zeros(cfg.batch * cfg.n_kv_heads, dtype=torch.int32, device=device) if ragged else None
+    return Cache(bufs, 0, 0, tail_cap, n_cap, counts)
 
 
 def _stream_ptr(stream):
@@ -176,6 +184,23 @@ def compress(cfg: Cfg, q_obs, k, v, cache: Cache, idx_out=None, workspace=None, 
                              _ptr(workspace), workspace.numel(), _stream_ptr(stream))
     if rc:
         raise KvqpError(rc, "kvqp_compress")
+    cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
+    return cache
+
+
+def compress_ragged(cfg: Cfg, q_obs, k, v, head_budget, cache: Cache, idx_out=None, workspace=None, stream=None):
+    """kvqp_compress_ragged: head_budget is a host sequence of batch * Hkv token counts."""
+    if workspace is None:
+        workspace = alloc_workspace(workspace_bytes(cfg)[0], k.device)
+    n = cfg.batch * cfg.n_kv_heads
+    if len(head_budget) != n:
+        raise ValueError(f"head_budget needs {n} entries")
+    hb = (C.c_int32 * n)(*[int(x) for x in head_budget])
+    cs = cache.struct()
+    rc = lib().kvqp_compress_ragged(C.byref(cfg.struct()), _ptr(q_obs), _ptr(k), _ptr(v), hb, C.byref(cs),
+                                    _ptr(idx_out), _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if rc:
+        raise KvqpError(rc, "kvqp_compress_ragged")
     cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
     return cache
 

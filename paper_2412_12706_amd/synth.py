@@ -5,7 +5,7 @@ The paper evaluates on long prompts run through Llama/Mistral checkpoints
 the tests and the benchmark use tensors with the same shapes and the one
 structural property the paper's quantization study leans on: a few key
 channels carry outliers, which is why keys are quantized per channel
-(Section 2 "KV Quantization", Section 5.4).
+(Section 2 "KV Quantization", Section 6.3).
 
 This module contains no arithmetic of the method itself.  Both the HIP path
 and the CPU checker receive the bytes produced here.

@@ -139,6 +139,35 @@ def test_capacity_sizes_and_append_argument_checks(lib):
     assert (cs.n_kept, cs.tail_len) == (1024, 96)                               # untouched by rejected calls
 
 
+def test_head_level_count_argument_checks(lib):
+    """kvqp_compress_ragged validates every head's count on the host before anything is enqueued;
+    the calls that do not take head-level counts say so."""
+    cfg = kvqp.Cfg(batch=1, n_q_heads=8, n_kv_heads=2, seq_len=800, window=32, budget=256, bits=4, group_size=64)
+    st = cfg.struct()
+    cs = kvqp.CacheStruct()
+    for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v", "head_n_kept"):
+        setattr(cs, name, 0x1000)
+    cs.tail_cap = 32
+    fake = C.c_void_p(0x1000)
+    call = lambda counts, cache=cs: lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(*counts),
+                                                             C.byref(cache), None, fake, 1 << 30, None)
+    assert call([256, 96]) == -1          # per-channel keys: whole groups of 64
+    assert call([256, 320]) == -1         # above the bound
+    assert call([-64, 64]) == -1
+    assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, None, C.byref(cs), None, fake, 1 << 30, None) == -1
+    no_counts = kvqp.CacheStruct.from_buffer_copy(cs)
+    no_counts.head_n_kept = None
+    assert call([256, 64], no_counts) == -1
+    assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(256, 64), C.byref(cs), None, fake,
+                                    16, None) == -3      # counts fine, workspace too small: still nothing launched
+    # uniform calls refuse a cache that carries head-level counts
+    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, fake, 1 << 30, None) == -1
+    cs.n_kept, cs.tail_len, cs.n_cap = 256, 32, 320
+    assert lib.kvqp_append_tail(C.byref(st), C.byref(cs), 64, None) == -2
+    cs.tail_len = 0
+    assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1   # a head may be empty
+
+
 def test_binding_raises_with_the_library_message(lib):
     cfg = kvqp.Cfg(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024, bits=5)
     with pytest.raises(kvqp.KvqpError) as e:

@@ -1,6 +1,6 @@
 """GPU parity of the quantize-and-pack step against the CPU checker: every
 code word, scale, zero and tail row must match bit for bit (paper Section 3,
-"KV Quantization"; grouping axes of Section 5.4)."""
+"KV Quantization"; grouping axes of Section 6.3)."""
 import numpy as np
 import pytest
 import torch

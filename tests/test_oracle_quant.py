@@ -169,7 +169,7 @@ def test_key_layout_16bit_is_plain_little_endian_half(orc):
 def test_cache_groups_follow_the_stated_axes(orc, bits, G, axis):
     """Keys per channel over G consecutive *kept* tokens (axis 0) or per token
     over G consecutive channels (axis 1); values always per token (paper,
-    Section 2 "KV Quantization" and Section 5.4)."""
+    Section 2 "KV Quantization" and Section 6.3)."""
     B, Hkv, L, W, D = 1, 2, 300, 8, 128
     _, k, v = synth.prompt_host(B, 4, Hkv, L, W, D, config=80)
     rng = np.random.default_rng(bits * G)
@@ -209,7 +209,7 @@ def test_cache_groups_follow_the_stated_axes(orc, bits, G, axis):
 
 
 def test_per_channel_keys_beat_per_token_keys_with_outlier_channels(orc):
-    # qualitative agreement with the paper's ablation (Section 5.4): with a few
+    # qualitative agreement with the paper's ablation (Section 6.3): with a few
     # large key channels, grouping keys along the channel axis loses less
     B, Hkv, L, W, D = 1, 2, 600, 8, 128
     _, k, v = synth.prompt_host(B, 4, Hkv, L, W, D, config=81)
