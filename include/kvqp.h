@@ -209,6 +209,17 @@ int kvqp_quantize_selected(const kvqp_cfg *cfg, const void *k, const void *v, co
                            int32_t n_kept, kvqp_cache *cache, void *hip_stream);
 
 /*
+ * The same with a count of its own per KV head (survivors chosen by a
+ * head-level method of the caller's): idx int32 [batch, Hkv, n_kept], of which
+ * head h uses its first head_count[h] entries; head_count is a HOST array
+ * under the rules of kvqp_compress_ragged with n_kept as the bound, and
+ * cache->head_n_kept receives it.
+ */
+int kvqp_quantize_selected_ragged(const kvqp_cfg *cfg, const void *k, const void *v, const int32_t *idx,
+                                  int32_t n_kept, const int32_t *head_count, kvqp_cache *cache,
+                                  void *hip_stream);
+
+/*
  * One decode step of attention over the compressed cache (Section 3, Eq. (3)
  * on G' = Q(G) s + z): for every query head, softmax over the n_kept
  * dequantized tokens followed by tail_len full-precision rows, no mask.

@@ -141,8 +141,16 @@ int kvqp_workspace_bytes(const kvqp_cfg* cfg, size_t* compress_bytes, size_t* de
     return KVQP_OK;
 }
 
-int kvqp_quantize_selected(const kvqp_cfg* cfg, const void* k, const void* v, const int32_t* idx, int32_t n_kept,
-                           kvqp_cache* cache, void* hip_stream) {
+// Host check of head-level counts against their bound.
+static int check_head_counts(const kvqp_cfg* cfg, const int32_t* counts, int bound) {
+    const int heads = cfg->batch * cfg->n_kv_heads, quantum = head_quantum(cfg);
+    for (int h = 0; h < heads; ++h)
+        if (counts[h] < 0 || counts[h] > bound || counts[h] % quantum) return KVQP_ERR_INVALID_ARG;
+    return KVQP_OK;
+}
+
+static int quantize_selected_impl(const kvqp_cfg* cfg, const void* k, const void* v, const int32_t* idx, int32_t n_kept,
+                                  const int32_t* head_count, kvqp_cache* cache, void* hip_stream) {
     int rc = check_common(cfg);
     if (rc) return rc;
     if ((rc = check_prompt(cfg))) return rc;
@@ -150,11 +158,28 @@ int kvqp_quantize_selected(const kvqp_cfg* cfg, const void* k, const void* v, co
     if (!k || !v || (n_kept > 0 && !idx)) return KVQP_ERR_INVALID_ARG;
     if (n_kept > cfg->seq_len - cfg->window) return KVQP_ERR_INVALID_ARG;
     if ((rc = check_cache_ptrs(cfg, cache, n_kept, true))) return rc;
-    if (cache->tail_cap < cfg->window || cache->head_n_kept) return KVQP_ERR_INVALID_ARG;
-    if (launch_quant_pack(*cfg, k, v, idx, n_kept, nullptr, *cache, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    if (cache->tail_cap < cfg->window) return KVQP_ERR_INVALID_ARG;
+    if ((head_count != nullptr) != (cache->head_n_kept != nullptr)) return KVQP_ERR_INVALID_ARG;
+    if (head_count && (rc = check_head_counts(cfg, head_count, n_kept))) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (head_count && hipMemcpyAsync(cache->head_n_kept, head_count, (size_t)cfg->batch * cfg->n_kv_heads * sizeof(int32_t),
+                                     hipMemcpyHostToDevice, stream) != hipSuccess)
+        return KVQP_ERR_HIP;
+    if (launch_quant_pack(*cfg, k, v, idx, n_kept, cache->head_n_kept, *cache, stream) != hipSuccess) return KVQP_ERR_HIP;
     cache->n_kept = n_kept;
     cache->tail_len = cfg->window;
     return KVQP_OK;
+}
+
+int kvqp_quantize_selected(const kvqp_cfg* cfg, const void* k, const void* v, const int32_t* idx, int32_t n_kept,
+                           kvqp_cache* cache, void* hip_stream) {
+    return quantize_selected_impl(cfg, k, v, idx, n_kept, nullptr, cache, hip_stream);
+}
+
+int kvqp_quantize_selected_ragged(const kvqp_cfg* cfg, const void* k, const void* v, const int32_t* idx, int32_t n_kept,
+                                  const int32_t* head_count, kvqp_cache* cache, void* hip_stream) {
+    if (!head_count) return KVQP_ERR_INVALID_ARG;
+    return quantize_selected_impl(cfg, k, v, idx, n_kept, head_count, cache, hip_stream);
 }
 
 // Both forms of compression: head_budget == NULL is the uniform one.
@@ -172,12 +197,10 @@ static int compress_impl(const kvqp_cfg* cfg, const void* q_obs, const void* k, 
     const int heads = cfg->batch * cfg->n_kv_heads;
     bool score = n_kept < cfg->seq_len - cfg->window;
     if (head_budget) {
-        const int quantum = head_quantum(cfg);
+        if ((rc = check_head_counts(cfg, head_budget, n_kept))) return rc;
         score = false;
-        for (int h = 0; h < heads; ++h) {
-            if (head_budget[h] < 0 || head_budget[h] > n_kept || head_budget[h] % quantum) return KVQP_ERR_INVALID_ARG;
+        for (int h = 0; h < heads; ++h)
             if (head_budget[h] > 0 && head_budget[h] < cfg->seq_len - cfg->window) score = true;
-        }
     }
     const CompressPlan plan = plan_compress(*cfg);
     if (!workspace || workspace_bytes < plan.total) return KVQP_ERR_WORKSPACE;

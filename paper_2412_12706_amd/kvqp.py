@@ -17,7 +17,7 @@ KVQP_OK = 0
 KEY_PER_CHANNEL = 0
 KEY_PER_TOKEN = 1
 EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_workspace_bytes", "kvqp_compress",
-           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_append_tail", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
+           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
 
 
 class KvqpError(RuntimeError):
@@ -62,6 +62,8 @@ def lib():
                                            C.c_size_t, C.c_void_p]
         L.kvqp_quantize_selected.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                              C.POINTER(CacheStruct), C.c_void_p]
+        L.kvqp_quantize_selected_ragged.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                                    C.POINTER(C.c_int32), C.POINTER(CacheStruct), C.c_void_p]
         L.kvqp_decode_attn.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.POINTER(CacheStruct), C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
@@ -213,6 +215,22 @@ def quantize_selected(cfg: Cfg, k, v, idx, cache: Cache, stream=None):
                                       C.byref(cs), _stream_ptr(stream))
     if rc:
         raise KvqpError(rc, "kvqp_quantize_selected")
+    cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
+    return cache
+
+
+def quantize_selected_ragged(cfg: Cfg, k, v, idx, head_count, cache: Cache, stream=None):
+    """kvqp_quantize_selected_ragged: idx int32 [B,Hkv,n_kept]; head h uses its first head_count[h] entries."""
+    n_kept = int(idx.shape[-1])
+    n = cfg.batch * cfg.n_kv_heads
+    if len(head_count) != n:
+        raise ValueError(f"head_count needs {n} entries")
+    hc = (C.c_int32 * n)(*[int(x) for x in head_count])
+    cs = cache.struct()
+    rc = lib().kvqp_quantize_selected_ragged(C.byref(cfg.struct()), _ptr(k), _ptr(v), _ptr(idx) if n_kept else None,
+                                             n_kept, hc, C.byref(cs), _stream_ptr(stream))
+    if rc:
+        raise KvqpError(rc, "kvqp_quantize_selected_ragged")
     cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
     return cache
 

@@ -160,6 +160,10 @@ def test_head_level_count_argument_checks(lib):
     assert call([256, 64], no_counts) == -1
     assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(256, 64), C.byref(cs), None, fake,
                                     16, None) == -3      # counts fine, workspace too small: still nothing launched
+    assert lib.kvqp_quantize_selected_ragged(C.byref(st), fake, fake, fake, 256, (C.c_int32 * 2)(256, 96), C.byref(cs),
+                                             None) == -1
+    assert lib.kvqp_quantize_selected_ragged(C.byref(st), fake, fake, fake, 256, None, C.byref(cs), None) == -1
+    assert lib.kvqp_quantize_selected(C.byref(st), fake, fake, fake, 256, C.byref(cs), None) == -1
     # uniform calls refuse a cache that carries head-level counts
     assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, fake, 1 << 30, None) == -1
     cs.n_kept, cs.tail_len, cs.n_cap = 256, 32, 320

@@ -166,3 +166,44 @@ def test_calls_that_do_not_take_head_level_counts(orc):
         kvqp.append_tail(cfg, gc, 32)
     assert e.value.code == -2
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("bits,G,key_axis", [(4, 64, kvqp.KEY_PER_TOKEN), (2, 32, kvqp.KEY_PER_CHANNEL),
+                                             (8, 128, kvqp.KEY_PER_CHANNEL), (16, 32, kvqp.KEY_PER_CHANNEL)])
+def test_quantize_given_survivors_with_head_level_counts(orc, bits, G, key_axis):
+    """Survivors from a head-level method of the caller's (here: seeded random positions): every
+    head's share equals the checker's quantization of that head's own list."""
+    print(f"case given survivors bits={bits} G={G} axis={key_axis}", flush=True)
+    B, Hq, Hkv, L, W, bound = 2, 8, 2, 900, 8, 512
+    q_obs, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, config=68)
+    counts = [512, 128, 0, 384]
+    rng = np.random.default_rng(68)
+    idx = np.zeros((B, Hkv, bound), np.int32)
+    for h, n in enumerate(counts):
+        idx[h // Hkv, h % Hkv, :n] = np.sort(rng.choice(L - W, n, replace=False))
+    cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, budget=bound, bits=bits, group_size=G,
+                   key_axis=key_axis)
+    gc = kvqp.alloc_cache(cfg, ragged=True)
+    for t in gc.buffers.values():
+        t.fill_(0x5A)
+    kvqp.quantize_selected_ragged(cfg, dev(k), dev(v), dev(idx), counts, gc)
+    torch.cuda.synchronize()
+    assert gc.head_n_kept.cpu().tolist() == counts and gc.n_kept == bound and gc.tail_len == W
+    heads, E, sm = B * Hkv, 32 // bits, float(np.float32(cfg.sm_scale))
+    q = synth.decode_query_host(B, Hq, 128, config=68, step=0)
+    out = kvqp.decode_attn(cfg, dev(q), gc)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy().astype(np.float64)
+    gq = Hq // Hkv
+    for h, n in enumerate(counts):
+        b, g = h // Hkv, h % Hkv
+        oc = orc.quantize_selected(k[b:b + 1, g:g + 1], v[b:b + 1, g:g + 1], idx[b:b + 1, g:g + 1, :n], W=W, bits=bits,
+                                   G=G, key_axis=key_axis)
+        assert np.array_equal(head_share(gc, "k_codes", np.uint32, heads, h, n * 128 // E), oc.k_codes.reshape(-1))
+        assert np.array_equal(head_share(gc, "v_codes", np.uint32, heads, h, oc.v_codes.size), oc.v_codes.reshape(-1))
+        if bits != 16:
+            for nm in ("k_scale", "k_zero", "v_scale", "v_zero"):
+                ref = getattr(oc, nm).reshape(-1)
+                assert np.array_equal(head_share(gc, nm, np.uint16, heads, h, ref.size), ref), nm
+        ref = orc.decode_attn(q[b:b + 1, g * gq:(g + 1) * gq], oc, sm)
+        assert np.abs(out[b, g * gq:(g + 1) * gq] - ref[0]).max() <= 2e-3
