@@ -240,6 +240,40 @@ def main():
     append_us = a0.elapsed_time(a1) * 1e3 / reps
     del grow
 
+    # ---- layer-wise token counts (outside the timed steps): the 4-bit setting's memory spread over the
+    # layers as a falling schedule, 1.5x the mean in the first layer down to 0.5x in the last, one batch ----
+    mean = s4["n_kept"]
+    counts = [int(round(mean * (1.5 - l / (LAYERS - 1)) / 64)) * 64 for l in range(LAYERS)]
+    cfg_r = kvqp.Cfg(**{**s4["cfg"].__dict__, "budget": max(counts)})
+    rag = kvqp.alloc_cache(cfg_r, device=dev, ragged=True)
+    ws_rc, ws_rd = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_r))
+    head_counts = [counts[h // HKV] for h in range(LAYERS * HKV)]
+    reps = 3
+    for rep in range(reps + 1):
+        if rep == 1:
+            torch.cuda.synchronize()
+            r0, r1 = ev(), ev()
+            r0.record()
+        kvqp.compress_ragged(cfg_r, q_obs, k, v, head_counts, rag, workspace=ws_rc)
+    r1.record()
+    for t in range(8):
+        kvqp.decode_attn(cfg_r, queries[t], rag, out, ws_rd)
+    torch.cuda.synchronize()
+    r2, r3 = ev(), ev()
+    r2.record()
+    for t in range(DECODE_STEPS):
+        kvqp.decode_attn(cfg_r, queries[t], rag, out, ws_rd)
+    r3.record()
+    torch.cuda.synchronize()
+    rag_bytes = sum(decode_bytes(1, n, 4, G, W) for n in counts)
+    rag_us = r2.elapsed_time(r3) * 1e3 / DECODE_STEPS
+    layer_wise = {
+        "counts": f"{counts[0]} .. {counts[-1]} tokens per layer (mean {sum(counts) // LAYERS}), 4 bit",
+        "compress_ms_32_layers": round(r0.elapsed_time(r1) / reps, 3), "decode_us_per_step": round(rag_us, 2),
+        "decode_gbs": round(rag_bytes / (rag_us * 1e-6) / 1e9, 1), "bytes_per_step": rag_bytes,
+    }
+    del rag
+
     # ---- roofline of the dominant kernel: the decode launch that takes most of the step ----
     dom = max(range(len(settings)), key=lambda i: settings[i]["t_decode_ms"])
     dom_s, dom_r = settings[dom], sweep[dom]
@@ -291,6 +325,7 @@ def main():
         "compress_note": "prompt tokens/s through all 32 layers at the (8192 tok, 4 bit) setting",
         "append_tail_us": round(append_us, 2),
         "append_note": f"kvqp_append_tail of {G} tokens per cache, 32 layers as one batch, 4-bit setting",
+        "layer_wise_counts": layer_wise,
         "sweep": sweep, "per_layer_calls": per_layer,
         "roofline": roofline, "cpu_baseline": cpu,
     }
