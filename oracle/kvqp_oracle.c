@@ -246,14 +246,22 @@ int orc_topk(int P, int k, const double *pooled, int32_t *idx)
  * Ties in rint go to even.  When the group holds both -0 and +0 as extremes
  * the minimum is -0 (IEEE minimum ordering).
  */
-int orc_quantize_group(const uint16_t *x, int n, int stride, int bits, uint16_t *scale,
-                       uint16_t *zero, uint8_t *codes)
+static int quantize_group_excl(const uint16_t *x, int n, int stride, int bits, const uint8_t *excl,
+                               int excl_stride, uint16_t *scale, uint16_t *zero, uint8_t *codes)
 {
     if (n < 1 || !(bits == 2 || bits == 4 || bits == 8))
         return -1;
-    uint16_t zb = x[0], mb = x[0];
-    for (int i = 1; i < n; ++i) {
+    int have = 0;
+    uint16_t zb = 0, mb = 0; /* +0: what a group with nothing left to quantize stores */
+    for (int i = 0; i < n; ++i) {
+        if (excl && excl[(size_t)i * excl_stride])
+            continue;
         uint16_t xb = x[(size_t)i * stride];
+        if (!have) {
+            zb = mb = xb;
+            have = 1;
+            continue;
+        }
         double v = orc_half_to_double(xb), lo = orc_half_to_double(zb), hi = orc_half_to_double(mb);
         if (v < lo || (v == lo && (xb & 0x8000) && !(zb & 0x8000)))
             zb = xb;
@@ -275,6 +283,10 @@ int orc_quantize_group(const uint16_t *x, int n, int stride, int bits, uint16_t 
     }
     volatile float inv = 1.0f / sf;
     for (int i = 0; i < n; ++i) {
+        if (excl && excl[(size_t)i * excl_stride]) {
+            codes[i] = 0;
+            continue;
+        }
         volatile float diff = half_to_float(x[(size_t)i * stride]) - zf;
         volatile float scaled = diff * inv;
         float c = rintf(scaled);
@@ -285,6 +297,76 @@ int orc_quantize_group(const uint16_t *x, int n, int stride, int bits, uint16_t 
         codes[i] = (uint8_t)c;
     }
     return 0;
+}
+
+int orc_quantize_group(const uint16_t *x, int n, int stride, int bits, uint16_t *scale,
+                       uint16_t *zero, uint8_t *codes)
+{
+    return quantize_group_excl(x, n, stride, bits, NULL, 0, scale, zero, codes);
+}
+
+/* ------------------------------------------------------------------ */
+/* Outlier filtering (Section 6.3, item (1); Appendix B "KV             */
+/* quantization": numbers whose absolute value exceeds a threshold, 6   */
+/* in the paper, about 1 % of them, are excluded from quantization).    */
+/* Reading used here, bounded per token so that storage is fixed: in    */
+/* every kept token's key row and value row, the elements with          */
+/* |x| > tau are candidates; the ORC_OUT_SLOTS candidates of largest    */
+/* magnitude (equal magnitudes: lower channel first) are the row's      */
+/* outliers.  An outlier takes no part in its group's min / max, gets   */
+/* code 0, and is kept at full precision beside the codes: a slot word  */
+/* holds the top 24 bits of the binary32 difference float(x) - float(z) */
+/* (z the stored zero-point of the element's group), a valid bit (bit   */
+/* 7) and the channel (bits 0-6); the element dequantizes to            */
+/* float(z) + difference.  A row's slots are ordered by channel, unused */
+/* slots are 0.  A group left with no element stores scale 0, zero +0.  */
+/* Candidates beyond the ORC_OUT_SLOTS largest are quantized like any   */
+/* other element.                                                       */
+/* ------------------------------------------------------------------ */
+#define ORC_OUT_SLOTS 4
+
+/* is_out[d] = 1 for the row's outliers.  Returns how many there are. */
+int orc_mark_outliers(const uint16_t *row, int D, double tau, uint8_t *is_out)
+{
+    int n = 0;
+    memset(is_out, 0, (size_t)D);
+    for (int s = 0; s < ORC_OUT_SLOTS; ++s) {
+        int best = -1;
+        double best_mag = 0.0;
+        for (int d = 0; d < D; ++d) {
+            if (is_out[d])
+                continue;
+            double mag = fabs(orc_half_to_double(row[d]));
+            if (mag > tau && (best < 0 || mag > best_mag)) { /* strict: the lower channel keeps a tie */
+                best = d;
+                best_mag = mag;
+            }
+        }
+        if (best < 0)
+            break;
+        is_out[best] = 1;
+        ++n;
+    }
+    return n;
+}
+
+/* Slot word of an outlier x in channel d whose group stores zero-point zb. */
+uint32_t orc_outlier_slot(uint16_t x, uint16_t zb, int d)
+{
+    volatile float diff = half_to_float(x) - half_to_float(zb);
+    float f = diff;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return (u & 0xFFFFFF00u) | 0x80u | (uint32_t)d;
+}
+
+/* The value a slot word stands for, given its group's zero-point. */
+double orc_outlier_value(uint32_t slot, uint16_t zb)
+{
+    uint32_t u = slot & 0xFFFFFF00u;
+    float f;
+    memcpy(&f, &u, 4);
+    return orc_half_to_double(zb) + (double)f;
 }
 
 /* ------------------------------------------------------------------ */
@@ -396,21 +478,33 @@ static void v_code_put(uint32_t *codes, int D, int bits, int t, int d, uint32_t 
 /*   v_scale/v_zero: [B,Hkv,n_kept,D/G]                                 */
 /*   tail_k/tail_v : [B,Hkv,tail_cap,D], first W rows written           */
 /* ------------------------------------------------------------------ */
-int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int bits, int G,
-                          int key_axis, int tail_cap, const uint16_t *k, const uint16_t *v,
-                          const int32_t *idx, uint32_t *k_codes, uint32_t *v_codes,
-                          uint16_t *k_scale, uint16_t *k_zero, uint16_t *v_scale,
-                          uint16_t *v_zero, uint16_t *tail_k, uint16_t *tail_v)
+/* tau < 0: no outlier filtering (k_out, v_out unused).  Otherwise k_out, v_out
+ * [B,Hkv,n_kept,ORC_OUT_SLOTS] receive the slot words (bits 2, 4, 8 only). */
+static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kept, int bits, int G,
+                                  int key_axis, int tail_cap, const uint16_t *k, const uint16_t *v,
+                                  const int32_t *idx, uint32_t *k_codes, uint32_t *v_codes,
+                                  uint16_t *k_scale, uint16_t *k_zero, uint16_t *v_scale,
+                                  uint16_t *v_zero, uint16_t *tail_k, uint16_t *tail_v, double tau,
+                                  uint32_t *k_out, uint32_t *v_out)
 {
     if (!(bits == 2 || bits == 4 || bits == 8 || bits == 16) || D % 64 || W > tail_cap || W > L)
+        return -1;
+    const int filt = tau >= 0.0;
+    if (filt && (bits == 16 || !k_out || !v_out || D > 128))
         return -1;
     if (bits != 16 && (G < 1 || D % G || (key_axis == 0 && n_kept % G)))
         return -1;
     const int P = L - W;
     const size_t kw = orc_k_words(n_kept, D, bits), vw = orc_v_words(n_kept, D, bits);
     uint8_t *codes = (uint8_t *)malloc((size_t)(G > D ? G : D) + 1);
-    if (!codes)
+    uint8_t *kmask = filt ? (uint8_t *)malloc((size_t)(n_kept > 0 ? n_kept : 1) * D) : NULL;
+    uint8_t *vmask = filt ? (uint8_t *)malloc((size_t)(n_kept > 0 ? n_kept : 1) * D) : NULL;
+    if (!codes || (filt && (!kmask || !vmask))) {
+        free(codes);
+        free(kmask);
+        free(vmask);
         return -2;
+    }
     for (int b = 0; b < B; ++b)
         for (int g = 0; g < Hkv; ++g) {
             const size_t head = (size_t)b * Hkv + g;
@@ -422,7 +516,14 @@ int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int b
             for (int t = 0; t < n_kept; ++t)
                 if (id[t] < 0 || id[t] >= P) {
                     free(codes);
+                    free(kmask);
+                    free(vmask);
                     return -3;
+                }
+            if (filt)
+                for (int t = 0; t < n_kept; ++t) {
+                    orc_mark_outliers(kh + (size_t)id[t] * D, D, tau, kmask + (size_t)t * D);
+                    orc_mark_outliers(vh + (size_t)id[t] * D, D, tau, vmask + (size_t)t * D);
                 }
             if (bits == 16) {
                 for (int t = 0; t < n_kept; ++t)
@@ -438,7 +539,9 @@ int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int b
                             for (int e = 0; e < G; ++e)
                                 gath[e] = kh[(size_t)id[u * G + e] * D + d];
                             size_t m = (head * (size_t)(n_kept / G) + u) * D + d;
-                            orc_quantize_group(gath, G, 1, bits, &k_scale[m], &k_zero[m], codes);
+                            quantize_group_excl(gath, G, 1, bits,
+                                                filt ? kmask + (size_t)u * G * D + d : NULL, D,
+                                                &k_scale[m], &k_zero[m], codes);
                             for (int e = 0; e < G; ++e)
                                 k_code_put(kc, D, bits, u * G + e, d, codes[e]);
                         }
@@ -447,8 +550,9 @@ int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int b
                     for (int t = 0; t < n_kept; ++t)
                         for (int c = 0; c < D / G; ++c) {
                             size_t m = (head * (size_t)n_kept + t) * (D / G) + c;
-                            orc_quantize_group(kh + (size_t)id[t] * D + c * G, G, 1, bits,
-                                               &k_scale[m], &k_zero[m], codes);
+                            quantize_group_excl(kh + (size_t)id[t] * D + c * G, G, 1, bits,
+                                                filt ? kmask + (size_t)t * D + c * G : NULL, 1,
+                                                &k_scale[m], &k_zero[m], codes);
                             for (int e = 0; e < G; ++e)
                                 k_code_put(kc, D, bits, t, c * G + e, codes[e]);
                         }
@@ -456,12 +560,30 @@ int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int b
                 for (int t = 0; t < n_kept; ++t)
                     for (int c = 0; c < D / G; ++c) {
                         size_t m = (head * (size_t)n_kept + t) * (D / G) + c;
-                        orc_quantize_group(vh + (size_t)id[t] * D + c * G, G, 1, bits, &v_scale[m],
-                                           &v_zero[m], codes);
+                        quantize_group_excl(vh + (size_t)id[t] * D + c * G, G, 1, bits,
+                                            filt ? vmask + (size_t)t * D + c * G : NULL, 1,
+                                            &v_scale[m], &v_zero[m], codes);
                         for (int e = 0; e < G; ++e)
                             v_code_put(vc, D, bits, t, c * G + e, codes[e]);
                     }
             }
+            if (filt)
+                for (int t = 0; t < n_kept; ++t) {
+                    uint32_t *ko = k_out + (head * (size_t)n_kept + t) * ORC_OUT_SLOTS;
+                    uint32_t *vo = v_out + (head * (size_t)n_kept + t) * ORC_OUT_SLOTS;
+                    int nk = 0, nv = 0;
+                    memset(ko, 0, sizeof(uint32_t) * ORC_OUT_SLOTS);
+                    memset(vo, 0, sizeof(uint32_t) * ORC_OUT_SLOTS);
+                    for (int d = 0; d < D; ++d) { /* ascending channel */
+                        size_t mk = key_axis == 0 ? (head * (size_t)(n_kept / G) + t / G) * D + d
+                                                  : (head * (size_t)n_kept + t) * (D / G) + d / G;
+                        size_t mv = (head * (size_t)n_kept + t) * (D / G) + d / G;
+                        if (kmask[(size_t)t * D + d])
+                            ko[nk++] = orc_outlier_slot(kh[(size_t)id[t] * D + d], k_zero[mk], d);
+                        if (vmask[(size_t)t * D + d])
+                            vo[nv++] = orc_outlier_slot(vh[(size_t)id[t] * D + d], v_zero[mv], d);
+                    }
+                }
             for (int i = 0; i < W; ++i) {
                 memcpy(tail_k + (head * tail_cap + i) * (size_t)D, kh + (size_t)(P + i) * D,
                        sizeof(uint16_t) * (size_t)D);
@@ -470,7 +592,36 @@ int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int b
             }
         }
     free(codes);
+    free(kmask);
+    free(vmask);
     return 0;
+}
+
+int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int bits, int G,
+                          int key_axis, int tail_cap, const uint16_t *k, const uint16_t *v,
+                          const int32_t *idx, uint32_t *k_codes, uint32_t *v_codes,
+                          uint16_t *k_scale, uint16_t *k_zero, uint16_t *v_scale,
+                          uint16_t *v_zero, uint16_t *tail_k, uint16_t *tail_v)
+{
+    return quantize_selected_impl(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap, k, v, idx,
+                                  k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k,
+                                  tail_v, -1.0, NULL, NULL);
+}
+
+/* The same with outlier filtering at threshold tau >= 0. */
+int orc_quantize_selected_outliers(int B, int Hkv, int D, int L, int W, int n_kept, int bits,
+                                   int G, int key_axis, int tail_cap, double tau,
+                                   const uint16_t *k, const uint16_t *v, const int32_t *idx,
+                                   uint32_t *k_codes, uint32_t *v_codes, uint16_t *k_scale,
+                                   uint16_t *k_zero, uint16_t *v_scale, uint16_t *v_zero,
+                                   uint16_t *tail_k, uint16_t *tail_v, uint32_t *k_out,
+                                   uint32_t *v_out)
+{
+    if (tau < 0.0)
+        return -1;
+    return quantize_selected_impl(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap, k, v, idx,
+                                  k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k,
+                                  tail_v, tau, k_out, v_out);
 }
 
 /*
@@ -520,10 +671,12 @@ int orc_compress(int B, int Hq, int Hkv, int D, int L, int W, int pool, int budg
 /* ------------------------------------------------------------------ */
 
 /* Dequantize one head into dense rows: Kd, Vd [n_kept + tail_len, D]. */
+/* ko, vo: the head's outlier slots [n_kept, ORC_OUT_SLOTS], or NULL. */
 static void dequantize_head(int D, int n_kept, int bits, int G, int key_axis, int tail_len,
                             const uint32_t *kc, const uint32_t *vc, const uint16_t *ks,
                             const uint16_t *kz, const uint16_t *vs, const uint16_t *vz,
-                            const uint16_t *tk, const uint16_t *tv, double *Kd, double *Vd)
+                            const uint16_t *tk, const uint16_t *tv, const uint32_t *ko,
+                            const uint32_t *vo, double *Kd, double *Vd)
 {
     for (int t = 0; t < n_kept; ++t)
         for (int d = 0; d < D; ++d) {
@@ -540,6 +693,19 @@ static void dequantize_head(int D, int n_kept, int bits, int G, int key_axis, in
                     (double)cv * orc_half_to_double(vs[mv]) + orc_half_to_double(vz[mv]);
             }
         }
+    for (int t = 0; t < n_kept && ko && vo; ++t)
+        for (int j = 0; j < ORC_OUT_SLOTS; ++j) {
+            uint32_t a = ko[(size_t)t * ORC_OUT_SLOTS + j], c = vo[(size_t)t * ORC_OUT_SLOTS + j];
+            if (a & 0x80u) {
+                int d = (int)(a & 0x7Fu);
+                size_t mk = key_axis == 0 ? (size_t)(t / G) * D + d : (size_t)t * (D / G) + d / G;
+                Kd[(size_t)t * D + d] = orc_outlier_value(a, kz[mk]);
+            }
+            if (c & 0x80u) {
+                int d = (int)(c & 0x7Fu);
+                Vd[(size_t)t * D + d] = orc_outlier_value(c, vz[(size_t)t * (D / G) + d / G]);
+            }
+        }
     for (int t = 0; t < tail_len; ++t)
         for (int d = 0; d < D; ++d) {
             Kd[(size_t)(n_kept + t) * D + d] = orc_half_to_double(tk[(size_t)t * D + d]);
@@ -548,11 +714,13 @@ static void dequantize_head(int D, int n_kept, int bits, int G, int key_axis, in
 }
 
 /* q [B,Hq,D] half -> out [B,Hq,D] double.  Query head h reads KV head h/Gq. */
-int orc_decode_attn(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G, int key_axis,
-                    double sm_scale, int tail_len, int tail_cap, const uint16_t *q,
-                    const uint32_t *k_codes, const uint32_t *v_codes, const uint16_t *k_scale,
-                    const uint16_t *k_zero, const uint16_t *v_scale, const uint16_t *v_zero,
-                    const uint16_t *tail_k, const uint16_t *tail_v, double *out)
+static int decode_attn_impl(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G, int key_axis,
+                            double sm_scale, int tail_len, int tail_cap, const uint16_t *q,
+                            const uint32_t *k_codes, const uint32_t *v_codes,
+                            const uint16_t *k_scale, const uint16_t *k_zero,
+                            const uint16_t *v_scale, const uint16_t *v_zero, const uint16_t *tail_k,
+                            const uint16_t *tail_v, const uint32_t *k_out, const uint32_t *v_out,
+                            double *out)
 {
     if (Hq % Hkv || tail_len > tail_cap || n_kept + tail_len < 1)
         return -1;
@@ -581,7 +749,9 @@ int orc_decode_attn(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G, 
                             v_codes + head * vw, k_scale + head * kmeta, k_zero + head * kmeta,
                             v_scale + head * vmeta, v_zero + head * vmeta,
                             tail_k + head * (size_t)tail_cap * D,
-                            tail_v + head * (size_t)tail_cap * D, Kd, Vd);
+                            tail_v + head * (size_t)tail_cap * D,
+                            k_out ? k_out + head * (size_t)n_kept * ORC_OUT_SLOTS : NULL,
+                            v_out ? v_out + head * (size_t)n_kept * ORC_OUT_SLOTS : NULL, Kd, Vd);
             for (int h = g * Gq; h < (g + 1) * Gq; ++h) {
                 const uint16_t *qr = q + ((size_t)b * Hq + h) * (size_t)D;
                 double mx = -INFINITY;
@@ -613,12 +783,51 @@ int orc_decode_attn(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G, 
     return status;
 }
 
-/* Dense dequantized K', V' of one head, for tests of the error bound. */
+int orc_decode_attn(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G, int key_axis,
+                    double sm_scale, int tail_len, int tail_cap, const uint16_t *q,
+                    const uint32_t *k_codes, const uint32_t *v_codes, const uint16_t *k_scale,
+                    const uint16_t *k_zero, const uint16_t *v_scale, const uint16_t *v_zero,
+                    const uint16_t *tail_k, const uint16_t *tail_v, double *out)
+{
+    return decode_attn_impl(B, Hq, Hkv, D, n_kept, bits, G, key_axis, sm_scale, tail_len, tail_cap,
+                            q, k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k, tail_v,
+                            NULL, NULL, out);
+}
+
+/* The same over a cache with outlier slots k_out, v_out [B,Hkv,n_kept,ORC_OUT_SLOTS]. */
+int orc_decode_attn_outliers(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G,
+                             int key_axis, double sm_scale, int tail_len, int tail_cap,
+                             const uint16_t *q, const uint32_t *k_codes, const uint32_t *v_codes,
+                             const uint16_t *k_scale, const uint16_t *k_zero,
+                             const uint16_t *v_scale, const uint16_t *v_zero,
+                             const uint16_t *tail_k, const uint16_t *tail_v, const uint32_t *k_out,
+                             const uint32_t *v_out, double *out)
+{
+    if (!k_out || !v_out)
+        return -1;
+    return decode_attn_impl(B, Hq, Hkv, D, n_kept, bits, G, key_axis, sm_scale, tail_len, tail_cap,
+                            q, k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k, tail_v,
+                            k_out, v_out, out);
+}
+
+/* Dense dequantized K', V' of one head, for tests of the error bound
+ * (ko, vo: the head's outlier slots or NULL). */
 int orc_dequantize_head(int D, int n_kept, int bits, int G, int key_axis, const uint32_t *kc,
                         const uint32_t *vc, const uint16_t *ks, const uint16_t *kz,
                         const uint16_t *vs, const uint16_t *vz, double *Kd, double *Vd)
 {
-    dequantize_head(D, n_kept, bits, G, key_axis, 0, kc, vc, ks, kz, vs, vz, NULL, NULL, Kd, Vd);
+    dequantize_head(D, n_kept, bits, G, key_axis, 0, kc, vc, ks, kz, vs, vz, NULL, NULL, NULL, NULL,
+                    Kd, Vd);
+    return 0;
+}
+
+int orc_dequantize_head_outliers(int D, int n_kept, int bits, int G, int key_axis,
+                                 const uint32_t *kc, const uint32_t *vc, const uint16_t *ks,
+                                 const uint16_t *kz, const uint16_t *vs, const uint16_t *vz,
+                                 const uint32_t *ko, const uint32_t *vo, double *Kd, double *Vd)
+{
+    dequantize_head(D, n_kept, bits, G, key_axis, 0, kc, vc, ks, kz, vs, vz, NULL, NULL, ko, vo, Kd,
+                    Vd);
     return 0;
 }
 

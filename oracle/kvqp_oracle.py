@@ -51,6 +51,11 @@ def lib():
         L.orc_k_code_get.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
         L.orc_v_code_get.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
         L.orc_threads.restype = C.c_int
+        L.orc_mark_outliers.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_void_p]
+        L.orc_outlier_slot.restype = C.c_uint32
+        L.orc_outlier_slot.argtypes = [C.c_uint16, C.c_uint16, C.c_int]
+        L.orc_outlier_value.restype = C.c_double
+        L.orc_outlier_value.argtypes = [C.c_uint32, C.c_uint16]
         _lib = L
     return _lib
 
@@ -128,6 +133,25 @@ def quantize_group(x, bits):
     return s.value, z.value, codes
 
 
+OUT_SLOTS = 4
+
+
+def mark_outliers(row, tau):
+    """row: 1-D float16 token row -> uint8 mask of its outliers at threshold tau."""
+    row = _u16(row)
+    mask = np.zeros(row.size, np.uint8)
+    lib().orc_mark_outliers(_p(row), row.size, C.c_double(tau), _p(mask))
+    return mask
+
+
+def outlier_slot(x_bits, zero_bits, d):
+    return int(lib().orc_outlier_slot(int(x_bits), int(zero_bits), int(d)))
+
+
+def outlier_value(slot, zero_bits):
+    return float(lib().orc_outlier_value(int(slot), int(zero_bits)))
+
+
 def k_code_at(words, D, bits, t, d):
     """Field (t, d) of a key-code buffer of one head (uint32 array)."""
     return int(lib().orc_k_code_get(_p(words), D, bits, t, d))
@@ -166,6 +190,8 @@ class Cache:
     v_zero: np.ndarray
     tail_k: np.ndarray  # uint16 [B,Hkv,tail_cap,D]
     tail_v: np.ndarray
+    k_out: np.ndarray = None  # uint32 [B,Hkv,n_kept,OUT_SLOTS] outlier slots, or None (no filtering)
+    v_out: np.ndarray = None
 
     def k_code(self, b, g, t, d):
         return k_code_at(self.k_codes[b, g], self.D, self.bits, t, d)
@@ -189,25 +215,39 @@ def _alloc_cache(B, Hkv, D, n_kept, bits, G, key_axis, W, tail_cap):
                  np.zeros((B, Hkv, tail_cap, D), np.uint16), np.zeros((B, Hkv, tail_cap, D), np.uint16))
 
 
-def quantize_selected(k, v, idx, W, bits, G, key_axis=0, tail_cap=None):
-    """Quantize the survivors listed in idx [B,Hkv,n_kept] (ascending)."""
+def quantize_selected(k, v, idx, W, bits, G, key_axis=0, tail_cap=None, tau=None):
+    """Quantize the survivors listed in idx [B,Hkv,n_kept] (ascending); tau: outlier threshold or None."""
     k, v = _u16(k), _u16(v)
     B, Hkv, L, D = k.shape
     idx = np.ascontiguousarray(idx, np.int32)
     n_kept = idx.shape[-1]
     tail_cap = W if tail_cap is None else tail_cap
     c = _alloc_cache(B, Hkv, D, n_kept, bits, G, key_axis, W, tail_cap)
-    rc = lib().orc_quantize_selected(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap, _p(k), _p(v),
-                                     _p(idx), _p(c.k_codes), _p(c.v_codes), _p(c.k_scale), _p(c.k_zero),
-                                     _p(c.v_scale), _p(c.v_zero), _p(c.tail_k), _p(c.tail_v))
+    if tau is None:
+        rc = lib().orc_quantize_selected(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap, _p(k), _p(v),
+                                         _p(idx), _p(c.k_codes), _p(c.v_codes), _p(c.k_scale), _p(c.k_zero),
+                                         _p(c.v_scale), _p(c.v_zero), _p(c.tail_k), _p(c.tail_v))
+    else:
+        c.k_out = np.zeros((B, Hkv, n_kept, OUT_SLOTS), np.uint32)
+        c.v_out = np.zeros((B, Hkv, n_kept, OUT_SLOTS), np.uint32)
+        rc = lib().orc_quantize_selected_outliers(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap,
+                                                  C.c_double(tau), _p(k), _p(v), _p(idx), _p(c.k_codes),
+                                                  _p(c.v_codes), _p(c.k_scale), _p(c.k_zero), _p(c.v_scale),
+                                                  _p(c.v_zero), _p(c.tail_k), _p(c.tail_v), _p(c.k_out), _p(c.v_out))
     if rc:
         raise ValueError(f"orc_quantize_selected rc={rc}")
     return c
 
 
 def compress(q_obs, k, v, *, window, pool, budget, bits, G, sm_scale, key_axis=0, tail_cap=None,
-             want_pooled=True):
-    """Whole prefill-time compression.  Returns (cache, idx, pooled)."""
+             want_pooled=True, tau=None):
+    """Whole prefill-time compression.  Returns (cache, idx, pooled).  With an outlier threshold
+    the survivors are the same (selection looks at the unquantized keys) and only their
+    quantization differs."""
+    if tau is not None:
+        _, idx, pooled = compress(q_obs, k, v, window=window, pool=pool, budget=budget, bits=bits, G=G,
+                                  sm_scale=sm_scale, key_axis=key_axis, tail_cap=tail_cap, want_pooled=want_pooled)
+        return quantize_selected(k, v, idx, window, bits, G, key_axis, tail_cap, tau), idx, pooled
     q_obs, k, v = _u16(q_obs), _u16(k), _u16(v)
     B, Hq, W, D = q_obs.shape
     assert W == window
@@ -233,9 +273,16 @@ def decode_attn(q, cache: Cache, sm_scale, n_q_heads=None):
     B, Hq, D = q.shape
     out = np.empty((B, Hq, D), np.float64)
     c = cache
-    rc = lib().orc_decode_attn(B, Hq, c.Hkv, D, c.n_kept, c.bits, c.G, c.key_axis, C.c_double(sm_scale),
-                               c.tail_len, c.tail_cap, _p(q), _p(c.k_codes), _p(c.v_codes), _p(c.k_scale),
-                               _p(c.k_zero), _p(c.v_scale), _p(c.v_zero), _p(c.tail_k), _p(c.tail_v), _p(out))
+    if c.k_out is None:
+        rc = lib().orc_decode_attn(B, Hq, c.Hkv, D, c.n_kept, c.bits, c.G, c.key_axis, C.c_double(sm_scale),
+                                   c.tail_len, c.tail_cap, _p(q), _p(c.k_codes), _p(c.v_codes), _p(c.k_scale),
+                                   _p(c.k_zero), _p(c.v_scale), _p(c.v_zero), _p(c.tail_k), _p(c.tail_v), _p(out))
+    else:
+        rc = lib().orc_decode_attn_outliers(B, Hq, c.Hkv, D, c.n_kept, c.bits, c.G, c.key_axis,
+                                            C.c_double(sm_scale), c.tail_len, c.tail_cap, _p(q), _p(c.k_codes),
+                                            _p(c.v_codes), _p(c.k_scale), _p(c.k_zero), _p(c.v_scale),
+                                            _p(c.v_zero), _p(c.tail_k), _p(c.tail_v), _p(c.k_out), _p(c.v_out),
+                                            _p(out))
     if rc:
         raise ValueError(f"orc_decode_attn rc={rc}")
     return out
@@ -246,7 +293,14 @@ def dequantize_head(cache: Cache, b, g):
     c = cache
     Kd = np.empty((c.n_kept, c.D), np.float64)
     Vd = np.empty((c.n_kept, c.D), np.float64)
-    lib().orc_dequantize_head(c.D, c.n_kept, c.bits, c.G, c.key_axis, _p(c.k_codes[b, g]), _p(c.v_codes[b, g]),
-                              _p(c.k_scale[b, g]), _p(c.k_zero[b, g]), _p(c.v_scale[b, g]), _p(c.v_zero[b, g]),
-                              _p(Kd), _p(Vd))
+    if c.k_out is None:
+        lib().orc_dequantize_head(c.D, c.n_kept, c.bits, c.G, c.key_axis, _p(c.k_codes[b, g]), _p(c.v_codes[b, g]),
+                                  _p(c.k_scale[b, g]), _p(c.k_zero[b, g]), _p(c.v_scale[b, g]), _p(c.v_zero[b, g]),
+                                  _p(Kd), _p(Vd))
+    else:
+        lib().orc_dequantize_head_outliers(c.D, c.n_kept, c.bits, c.G, c.key_axis, _p(c.k_codes[b, g]),
+                                           _p(c.v_codes[b, g]), _p(c.k_scale[b, g]), _p(c.k_zero[b, g]),
+                                           _p(c.v_scale[b, g]), _p(c.v_zero[b, g]),
+                                           _p(np.ascontiguousarray(c.k_out[b, g])),
+                                           _p(np.ascontiguousarray(c.v_out[b, g])), _p(Kd), _p(Vd))
     return Kd, Vd
