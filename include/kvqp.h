@@ -54,6 +54,7 @@ extern "C" {
  * and pool_kernel belong to the attention-score pruning rule below).
  * Supported in this build: head_dim == 128; n_q_heads / n_kv_heads in
  * {1,2,4,8}; bits in {2,4,8,16}; group_size in {32,64,128};
+ * outlier_threshold 0, or > 0 with bits in {2,4,8};
  * window * (n_q_heads/n_kv_heads) <= 256; pool_kernel odd, <= 63;
  * seq_len - window <= 131072.
  */
@@ -71,6 +72,7 @@ typedef struct kvqp_cfg {
     int32_t key_axis;     /* KVQP_KEY_PER_CHANNEL or KVQP_KEY_PER_TOKEN                  */
     int32_t decode_splits;/* token-axis splits of decode attention; 0 = library chooses  */
     float sm_scale;       /* logit scale > 0, e.g. 1/sqrt(D) (Eq. (3) omits it)          */
+    float outlier_threshold; /* tau; > 0 turns outlier filtering on (below), 0 = off     */
 } kvqp_cfg;
 
 /*
@@ -110,7 +112,25 @@ typedef struct kvqp_cfg {
  *   s == 0  ->  all codes 0;  else inv = 1.0f / float(s),
  *   code = clamp(rint((float(x) - float(z)) * inv), 0, 2^bits - 1).
  * NaN inputs are not supported.
+ *
+ * Outlier filtering (Section 6.3, item (1); Appendix B: numbers whose absolute
+ * value exceeds 6, about 1 %, are excluded from quantization).  With
+ * cfg->outlier_threshold = tau > 0 (bits 2, 4, 8): in every kept token's key
+ * row and value row the elements with |x| > tau are candidates and the
+ * KVQP_OUTLIER_SLOTS candidates of largest magnitude (equal magnitudes: lower
+ * channel first) are the row's outliers -- a bound per token, so that storage
+ * is fixed; further candidates are quantized like any other element.  An
+ * outlier takes no part in its group's min / max and gets code 0; a group left
+ * with no element stores scale 0, zero +0.  The outlier is kept beside the
+ * codes in a slot word: bits 31..8 the top 24 bits of the binary32 difference
+ * float(x) - float(z), z the stored zero of the element's group, bit 7 set,
+ * bits 6..0 the channel; it dequantizes to float(z) + that difference (within
+ * 2^-15 of |x - z|, finer than a binary16 step of x).  A row's slots are in
+ * order of selection, unused slots are 0.
+ *   k_out, v_out  uint32 [batch, Hkv, n_kept, KVQP_OUTLIER_SLOTS]
+ *   (sizes from kvqp_outlier_sizes; NULL when filtering is off)
  */
+#define KVQP_OUTLIER_SLOTS 4
 typedef struct kvqp_cache {
     void *k_codes, *v_codes;
     void *k_scale, *k_zero;
@@ -129,6 +149,7 @@ typedef struct kvqp_cache {
                          head-level token counts (kvqp_compress_ragged fills it): head h holds
                          head_n_kept[h] <= n_kept tokens at the start of its share of every
                          buffer, and n_kept is only the bound the counts stay under.       */
+    void *k_out, *v_out;  /* outlier slots when cfg->outlier_threshold > 0, else unused (NULL) */
 } kvqp_cache;
 
 /* Bytes of the eight cache buffers (order of the struct) for n_kept =
@@ -138,6 +159,11 @@ int kvqp_cache_sizes(const kvqp_cfg *cfg, int32_t tail_cap, size_t sizes_out[8])
 /* The same for buffers laid out for n_cap tokens per head (n_cap a multiple of 64 and of
  * group_size, >= 0); cfg->seq_len, window and budget are not read.  Host only. */
 int kvqp_cache_sizes_cap(const kvqp_cfg *cfg, int32_t n_cap, int32_t tail_cap, size_t sizes_out[8]);
+
+/* Bytes of k_out and v_out for buffers laid out for n_cap tokens per head
+ * (n_cap = 0: for n_kept = min(budget, L - W)); both 0 when cfg->outlier_threshold
+ * is 0.  Host only. */
+int kvqp_outlier_sizes(const kvqp_cfg *cfg, int32_t n_cap, size_t sizes_out[2]);
 
 /* Workspace bytes needed by kvqp_compress and kvqp_decode_attn for this cfg
  * (either pointer may be NULL).  Host only. */

@@ -215,6 +215,8 @@ struct DecodeArgs {
     int n_kept, tail_len, tail_cap;
     int n_cap;                // tokens the packed buffers are laid out for (head strides); >= n_kept
     const int32_t* head_n_kept;   // per (batch, kv head) token counts under the bound n_kept, or NULL
+    const uint32_t* k_out;        // outlier slots [B*Hkv, n_cap, 4] (filtering on), else NULL
+    const uint32_t* v_out;
     int quantum;              // a head's count is a multiple of this power of two (32, or G for per-channel keys)
     int n_q_heads, n_kv_heads;
     int n_splits, chunks_per_split, n_partials;
@@ -484,9 +486,18 @@ __device__ void tail_rows(const DecodeArgs& a, int bh, int t0, int t1, float* sT
     }
 }
 
+// the binary32 difference an outlier slot word carries (0 for an unused slot)
+__device__ __forceinline__ float slot_delta(uint32_t w) { return __uint_as_float(w & 0xFFFFFF00u); }
+
 // BITS: code width; GQ: query heads per kv head (1,2,4 -> two token slots per
 // MFMA tile; 8 -> one); NCG = D / G value channel groups; AXIS: key grouping.
-template <int BITS, int GQ, int NCG, int AXIS>
+// OUT: the cache carries outlier slots.  An outlier has code 0, so the products above see its
+// group's zero; what is missing, q[ch] * delta in the logit of its token and p * delta in channel
+// ch of the output, is added outside the matrix products: the logit term by the lanes that hold
+// the token's logit (two slots each for the hi / lo lane pair, looked up in a copy of q in LDS),
+// the output term into a per-wave [8 rows][128] binary32 array in LDS with LDS float atomics,
+// rescaled whenever the running maximum of its row moves and folded in at the merge.
+template <int BITS, int GQ, int NCG, int AXIS, bool OUT>
 __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int GQP = (GQ <= 4) ? 4 : 8;        // heads per slot incl. padding
@@ -496,6 +507,8 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
     constexpr int G = kHeadDim / NCG;
 
     __shared__ __align__(16) float smem[kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4)];
+    __shared__ __align__(16) uint16_t s_q[OUT ? 8 * kHeadDim : 8];            // the group's query rows (zero rows past GQ)
+    __shared__ __align__(16) float s_oc[OUT ? kWaves * 8 * kHeadDim : 4];     // per wave: outlier terms of the outputs
 
     const int bh = blockIdx.y;
     if ((int)blockIdx.x == a.n_splits) { tail_partial<GQ>(a, bh, smem); return; }
@@ -538,6 +551,20 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
             const _Float16 f = (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
             qpos[4 * s + r] = qn[4 * s + r] * f;
         }
+
+    const int row8 = (SLOTS == 2) ? slot * 4 + h : h;                       // the lane's row of the wave's outlier terms
+    float* oc = s_oc + (OUT ? wave * 8 * kHeadDim : 0);
+    const uint32_t* ko = OUT ? a.k_out + (size_t)bh * a.n_cap * 4 : nullptr;
+    const uint32_t* vo = OUT ? a.v_out + (size_t)bh * a.n_cap * 4 : nullptr;
+    if constexpr (OUT) {
+        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += kThreads) {
+            const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
+            reinterpret_cast<uint32_t*>(s_q)[item] =
+                hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
+        }
+        for (int item = threadIdx.x; item < kWaves * 8 * kHeadDim; item += kThreads) s_oc[item] = 0.f;
+        __syncthreads();
+    }
 
     // Per-token keys: the query operand is constant; per-channel-group sums of q.
     float qsum_cg = 0.f;  // sum of the lane's own 32 channels (all inside one channel group)
@@ -667,6 +694,23 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                     logit[blk][1][i] = __builtin_fmaf(s1, c_logit, bias * c_bias);
                 }
             }
+            if constexpr (OUT) {
+                // key outliers of the lane's tokens: this lane takes slots 2 part, 2 part + 1, its pair the other two
+                const uint16_t* qrow = s_q + (size_t)h * kHeadDim;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int tile_h = (SLOTS == 2) ? slot : t;
+                    const uint2* sp = reinterpret_cast<const uint2*>(ko + (size_t)(tb + 16 * tile_h + 4 * kb) * 4) + part;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint2 w = sp[2 * i];
+                        float c = slot_delta(w.x) * __half2float(__ushort_as_half(qrow[w.x & 127u]));
+                        c = __builtin_fmaf(slot_delta(w.y), __half2float(__ushort_as_half(qrow[w.y & 127u])), c);
+                        c += pair_other(c);
+                        logit[blk][t][i] = __builtin_fmaf(c, c_bias, logit[blk][t][i]);
+                    }
+                }
+            }
         }
 
         // ---------------- online softmax bookkeeping ----------------
@@ -692,6 +736,19 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 #pragma unroll
                 for (int i = 0; i < 4; ++i) O[t][i] *= ar[i];
             m_run = m_new;
+            if constexpr (OUT) {
+                // the eight lanes of a row (hi / lo pair x four kb) rescale 16 channels each of its outlier terms
+                if (live_row && alpha != 1.0f) {
+                    float* p16 = oc + row8 * kHeadDim + (part * 4 + kb) * 16;
+#pragma unroll
+                    for (int c = 0; c < 16; c += 4) {
+                        float4 v = *reinterpret_cast<float4*>(p16 + c);
+                        v.x *= alpha; v.y *= alpha; v.z *= alpha; v.w *= alpha;
+                        *reinterpret_cast<float4*>(p16 + c) = v;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // (LDS serves a wave in order; this only pins the compiler)
+            }
         }
 
         // ---------------- probabilities, P.V ----------------
@@ -716,6 +773,24 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                     p[t][i] = exp2f(logit[blk][t][i] - (m_run + (float)e));
                     l_run = __builtin_fmaf(p[t][i], (float)(1 << e), l_run);
                 }
+            if constexpr (OUT) {
+                // value outliers of the lane's tokens: weight x delta into channel ch of the lane's row
+                if (live_row) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const int tile_h = (SLOTS == 2) ? slot : t;
+                        const uint2* sp = reinterpret_cast<const uint2*>(vo + (size_t)(tb + 16 * tile_h + 4 * kb) * 4) + part;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const uint2 w = sp[2 * i];
+                            const float pw = p[t][i] * (float)(1 << v_pos_log2<BITS>(blk, i));
+                            if (w.x) atomicAdd(oc + row8 * kHeadDim + (w.x & 127u), pw * slot_delta(w.x));
+                            if (w.y) atomicAdd(oc + row8 * kHeadDim + (w.y & 127u), pw * slot_delta(w.y));
+                        }
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            }
             // scale / zero of the lane's tokens: 4 consecutive tokens x NCG, per tile
             Frag pa[NCG];
 #pragma unroll
@@ -784,7 +859,8 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                 const int row = sl * 8 + 2 * hh;  // hi row; lo row is row + 1
                 const float* st = sS + (w * 16 + row) * 6;
                 const float wgt = exp2f(st[0] - M);
-                const float o = (sO[(w * 16 + row) * kHeadDim + d] + sO[(w * 16 + row + 1) * kHeadDim + d]) * kCodeUnit + st[2 + cg];
+                float o = (sO[(w * 16 + row) * kHeadDim + d] + sO[(w * 16 + row + 1) * kHeadDim + d]) * kCodeUnit + st[2 + cg];
+                if constexpr (OUT) o += s_oc[(w * 8 + ((SLOTS == 2) ? sl * 4 + hh : hh)) * kHeadDim + d];
                 acc = __builtin_fmaf(wgt, o, acc);
                 L = __builtin_fmaf(wgt, st[1], L);
             }
@@ -1348,8 +1424,15 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
 template <int BITS, int GQ, int NCG>
 hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t stream) {
     const dim3 grid(a.n_partials, cfg.batch * cfg.n_kv_heads);
-    if (cfg.key_axis == KVQP_KEY_PER_TOKEN && BITS != 16)
-        hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 1>), grid, dim3(kThreads), 0, stream, a);
+    if (BITS != 16 && a.k_out != nullptr) {          // outlier slots: the plain split-K kernel serves both key axes
+        if constexpr (BITS != 16) {
+            if (cfg.key_axis == KVQP_KEY_PER_TOKEN)
+                hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 1, true>), grid, dim3(kThreads), 0, stream, a);
+            else
+                hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 0, true>), grid, dim3(kThreads), 0, stream, a);
+        }
+    } else if (cfg.key_axis == KVQP_KEY_PER_TOKEN && BITS != 16)
+        hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 1, false>), grid, dim3(kThreads), 0, stream, a);
     else
     {
         constexpr int strip = PipeGeom<BITS, NCG>::STRIP;
@@ -1381,7 +1464,7 @@ hipError_t launch_gq(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t strea
 
 // The pipelined kernel serves per-channel keys and the 16-bit cache; per-token keys at 2-8 bits
 // run on the plain split-K kernel.
-static bool uses_pipe(const kvqp_cfg& cfg) { return !(cfg.key_axis == KVQP_KEY_PER_TOKEN && cfg.bits != 16); }
+static bool uses_pipe(const kvqp_cfg& cfg) { return !(cfg.key_axis == KVQP_KEY_PER_TOKEN && cfg.bits != 16) && !outliers_on(cfg); }
 
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
     DecodePlan p;
@@ -1450,6 +1533,8 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.n_kept = c.n_kept; a.tail_len = c.tail_len; a.tail_cap = c.tail_cap;
     a.n_cap = c.n_cap > 0 ? c.n_cap : c.n_kept;
     a.head_n_kept = c.head_n_kept;
+    a.k_out = outliers_on(cfg) ? (const uint32_t*)c.k_out : nullptr;
+    a.v_out = outliers_on(cfg) ? (const uint32_t*)c.v_out : nullptr;
     a.quantum = (cfg.bits != 16 && cfg.key_axis == KVQP_KEY_PER_CHANNEL) ? cfg.group_size : 32;
     a.n_q_heads = cfg.n_q_heads; a.n_kv_heads = cfg.n_kv_heads;
     a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;

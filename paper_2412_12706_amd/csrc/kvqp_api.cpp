@@ -22,6 +22,8 @@ int check_common(const kvqp_cfg* c) {
         if (c->group_size < 1 || c->head_dim % c->group_size) return KVQP_ERR_INVALID_ARG;
     }
     if (!(c->sm_scale > 0.0f) || c->sm_scale > 3.0e38f) return KVQP_ERR_INVALID_ARG;   /* positive and finite */
+    if (!(c->outlier_threshold >= 0.0f) || c->outlier_threshold > 3.0e38f) return KVQP_ERR_INVALID_ARG;
+    if (c->outlier_threshold > 0.0f && c->bits == 16) return KVQP_ERR_INVALID_ARG;   /* nothing is quantized at 16 bits */
     const int gq = c->n_q_heads / c->n_kv_heads;
     if (c->head_dim != kHeadDim) return KVQP_ERR_UNSUPPORTED;
     if (!(gq == 1 || gq == 2 || gq == 4 || gq == 8)) return KVQP_ERR_UNSUPPORTED;
@@ -86,6 +88,7 @@ int check_cache_ptrs(const kvqp_cfg* c, const kvqp_cache* cache, int n_kept, boo
         if (!cache->k_codes || !cache->v_codes) return KVQP_ERR_INVALID_ARG;
         if (c->bits != 16 && (!cache->k_scale || !cache->k_zero || !cache->v_scale || !cache->v_zero))
             return KVQP_ERR_INVALID_ARG;
+        if (outliers_on(*c) && (!cache->k_out || !cache->v_out)) return KVQP_ERR_INVALID_ARG;
     }
     if (need_tail && (!cache->tail_k || !cache->tail_v)) return KVQP_ERR_INVALID_ARG;
     return KVQP_OK;
@@ -127,6 +130,20 @@ int kvqp_cache_sizes_cap(const kvqp_cfg* cfg, int32_t n_cap, int32_t tail_cap, s
     if (!sizes_out || tail_cap < 0 || n_cap < 0) return KVQP_ERR_INVALID_ARG;
     if (n_cap > 0 && (rc = check_cap(cfg, n_cap, 0))) return rc;
     return fill_sizes(cfg, n_cap, tail_cap, sizes_out);
+}
+
+int kvqp_outlier_sizes(const kvqp_cfg* cfg, int32_t n_cap, size_t sizes_out[2]) {
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if (!sizes_out || n_cap < 0) return KVQP_ERR_INVALID_ARG;
+    int n = n_cap;
+    if (n == 0) {
+        if ((rc = check_prompt(cfg))) return rc;
+        n = n_kept_of(cfg);
+    }
+    const size_t bytes = outliers_on(*cfg) ? (size_t)cfg->batch * cfg->n_kv_heads * (size_t)n * KVQP_OUTLIER_SLOTS * sizeof(uint32_t) : 0;
+    sizes_out[0] = bytes; sizes_out[1] = bytes;
+    return KVQP_OK;
 }
 
 int kvqp_workspace_bytes(const kvqp_cfg* cfg, size_t* compress_bytes, size_t* decode_bytes) {

@@ -17,6 +17,9 @@ __host__ __device__ constexpr int v_superblock(int bits) { return bits == 2 ? 64
 __host__ __device__ constexpr int v_words_per_tile(int bits) { return bits == 16 ? 4 : bits == 8 ? 2 : 1; }
 __host__ __device__ constexpr int v_superblock_words(int bits) { return 64 * (kHeadDim / 16) * v_words_per_tile(bits); }
 
+// Outlier filtering is on (format statement in kvqp.h, "Outlier filtering").
+inline bool outliers_on(const kvqp_cfg& c) { return c.outlier_threshold > 0.0f; }
+
 inline size_t k_code_words(int n_kept, int bits) { return (size_t)n_kept * kHeadDim * bits / 32; }
 inline size_t v_code_words(int n_kept, int bits) {
     const int sb = v_superblock(bits);

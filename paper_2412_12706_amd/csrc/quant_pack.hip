@@ -30,6 +30,8 @@ struct QuantPackJob {
     const kvqp_cache& c;
     const void* k; const void* v; const int32_t* idx;
     const int32_t* head_n;   // device: rows of each head (<= n_tok, whole groups), or NULL for n_tok everywhere
+    uint32_t tau_bits;       // outlier filtering: |x| is above the threshold iff its binary16 pattern exceeds this
+    bool outliers;
     int heads, src_rows, window, n_tok, dst_base, n_cap, bits, group_size, key_axis;
     bool copy_tail;
 };
@@ -148,17 +150,28 @@ __device__ __forceinline__ void store_key_words(uint32_t* krow, int c8, const ui
     }
 }
 
-template <int BITS, int G>
+// all 16 lanes of a row of lanes (one token row) get the largest value among them
+__device__ __forceinline__ uint32_t row16_max(uint32_t v) {
+    v = max(v, dpp<kQuadXor1>(v)); v = max(v, dpp<kQuadXor2>(v));
+    v = max(v, dpp<kRowHalfMirror>(v)); v = max(v, dpp<kRowMirror>(v));
+    return v;
+}
+// 0xFFFF in the half-words whose bit (bit 0: low half, bit 1: high half) is set
+__device__ __forceinline__ uint32_t half_mask(uint32_t b) { return ((0u - (b & 1u)) & 0xFFFFu) | ((0u - ((b >> 1) & 1u)) << 16); }
+
+template <int BITS, int G, bool OUT>
 __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, const int32_t* __restrict__ idx,
     uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale,
     uint16_t* __restrict__ k_zero, uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero,
     uint16_t* __restrict__ tail_k, uint16_t* __restrict__ tail_v, int L, int W, int n_kept, int key_axis,
-    int tail_cap, int n_tok_blocks, int n_cap, int dst_base, const int32_t* __restrict__ head_n) {
+    int tail_cap, int n_tok_blocks, int n_cap, int dst_base, const int32_t* __restrict__ head_n,
+    uint32_t* __restrict__ k_out, uint32_t* __restrict__ v_out, uint32_t tau_bits) {
     // L: rows per head of the source tensors.  idx: source row of every token of this call
     // ([heads, n_kept]), or NULL for rows 0 .. n_kept-1.  The tokens land at positions dst_base ..
     // dst_base + n_kept - 1 of a cache whose buffers are laid out for n_cap tokens per head.
     // head_n: a head's own token count in place of n_kept (idx keeps its stride of n_kept), or NULL.
+    // OUT: outlier filtering; k_out / v_out receive four slot words per token row.
     constexpr bool QUANT = BITS != 16;
     constexpr int TB = (QUANT && G == 128) ? 128 : 64;   // tokens per workgroup
     constexpr int R = TB / 16;                            // rows per thread
@@ -214,18 +227,63 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         vw[j][0] = b.x; vw[j][1] = b.y; vw[j][2] = b.z; vw[j][3] = b.w;
     }
 
+    // Outlier marking (OUT): per token row, the elements with |x| above the threshold compete by
+    // magnitude (then lower channel) in up to four rounds over the row's 16 lanes; om gets a bit per
+    // own element that won, win the winners in order (0 = none) as |x| bits << 8 | (127 - channel)
+    // << 1 | sign, known to every lane of the row.
+    auto mark = [&](const uint32_t (&w)[R][4], uint32_t (&om)[R], uint32_t (&win)[R][4]) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            uint32_t key[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t hbits = (w[j][e >> 1] >> (16 * (e & 1))) & 0xffffu, mag = hbits & 0x7fffu;
+                key[e] = mag > tau_bits ? (mag << 8) | ((uint32_t)(127 - (8 * c8 + e)) << 1) | (hbits >> 15) : 0u;
+            }
+            om[j] = 0u;
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) win[j][sl] = 0u;
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+                uint32_t m = max(max(max(key[0], key[1]), max(key[2], key[3])), max(max(key[4], key[5]), max(key[6], key[7])));
+                m = row16_max(m);
+                if (__builtin_amdgcn_ballot_w64(m != 0u) == 0ull) break;   // no row of this wave has a candidate left
+                win[j][sl] = m;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool mine = m != 0u && key[e] == m;
+                    om[j] |= mine ? (1u << e) : 0u;
+                    key[e] = mine ? 0u : key[e];
+                }
+            }
+        }
+    };
+    // slot word of a winner given the float bits of its group's zero
+    auto slot_word = [](uint32_t win, float zf) -> uint32_t {
+        const uint32_t xh = (win >> 8) | ((win & 1u) << 15), ch = 127u - ((win >> 1) & 127u);
+        const float diff = __fsub_rn(half_bits_to_float((uint16_t)xh), zf);
+        return win ? ((__float_as_uint(diff) & 0xFFFFFF00u) | 0x80u | ch) : 0u;
+    };
+
     // Per-token groups (values always, keys on that axis): every row is complete inside GL lanes.
     // Fills the codes of all rows and stores scale / zero.  Lane q of a quad derives the parameters
-    // of rows q, q + 4, ... and hands them to the other three.
-    auto per_token = [&](const uint32_t (&w)[R][4], uint16_t* scale, uint16_t* zero, uint32_t (&codes)[R][8]) {
+    // of rows q, q + 4, ... and hands them to the other three.  om: outlier bits (OUT); zrow: float
+    // bits of the zero of the lane's own group, per row.
+    auto per_token = [&](const uint32_t (&w)[R][4], uint16_t* scale, uint16_t* zero, uint32_t (&codes)[R][8],
+                         const uint32_t (&om)[R], uint32_t (&zrow)[R]) {
         uint32_t mn[R], mx[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            uint32_t a = order_key2(w[j][0]), lo = a, hi = a;
+            uint32_t lo = 0xffffffffu, hi = 0u;
 #pragma unroll
-            for (int q = 1; q < 4; ++q) { a = order_key2(w[j][q]); lo = pk_min(lo, a); hi = pk_max(hi, a); }
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t a = order_key2(w[j][q]);
+                const uint32_t ex = OUT ? half_mask(om[j] >> (2 * q)) : 0u;   // excluded halves: neutral for min and max
+                lo = pk_min(lo, a | ex); hi = pk_max(hi, a & ~ex);
+            }
             mn[j] = min(lo & 0xffffu, lo >> 16); mx[j] = max(hi & 0xffffu, hi >> 16);
             group_minmax<GL>(mn[j], mx[j]);
+            if (OUT && mn[j] > mx[j]) { mn[j] = 0x8000u; mx[j] = 0x8000u; }   // nothing left in the group: zero +0, scale 0
         }
         const int q4 = c8 & 3;
 #pragma unroll
@@ -242,12 +300,39 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             const uint32_t zq[4] = {dpp<0x00>(zb), dpp<0x55>(zb), dpp<0xAA>(zb), dpp<0xFF>(zb)};
             const uint32_t iq[4] = {dpp<0x00>(ib), dpp<0x55>(ib), dpp<0xAA>(ib), dpp<0xFF>(ib)};
 #pragma unroll
-            for (int u = 0; u < 4; ++u) encode8<BITS>(w[4 * jj + u], __uint_as_float(zq[u]), __uint_as_float(iq[u]), codes[4 * jj + u]);
+            for (int u = 0; u < 4; ++u) {
+                encode8<BITS>(w[4 * jj + u], __uint_as_float(zq[u]), __uint_as_float(iq[u]), codes[4 * jj + u]);
+                zrow[4 * jj + u] = zq[u];
+                if constexpr (OUT) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) codes[4 * jj + u][e] &= ((om[4 * jj + u] >> e) & 1u) - 1u;   // outliers: code 0
+                }
+            }
+        }
+    };
+    // Slots of rows whose groups lie along the row: the zero of channel ch's group sits in lane ch / 8 of the row.
+    auto store_slots_per_token = [&](uint32_t* out, const uint32_t (&win)[R][4], const uint32_t (&zrow)[R]) {
+        const int row_lane0 = lane & ~15;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            uint32_t sw[4];
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+                const uint32_t ch = 127u - ((win[j][sl] >> 1) & 127u);
+                const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute((row_lane0 + (int)(ch >> 3)) << 2, (int)zrow[j]);
+                sw[sl] = slot_word(win[j][sl], __uint_as_float(zb));
+            }
+            if (c8 == 0 && live[j])
+                *reinterpret_cast<uint4*>(out + ((size_t)head * n_cap + d0 + r + 16 * j) * 4) = make_uint4(sw[0], sw[1], sw[2], sw[3]);
         }
     };
 
     // ---------------- keys ----------------
     uint32_t* kc_head = k_codes + (size_t)head * ((size_t)n_cap * kHeadDim / E);
+    uint32_t om[R], win[R][4], zrow[R];   // outlier bits and winners of the tensor at hand (OUT)
+#pragma unroll
+    for (int j = 0; j < R; ++j) om[j] = 0u;
+    if constexpr (OUT) mark(kw, om, win);
     if constexpr (!QUANT) {
 #pragma unroll
         for (int j = 0; j < R; ++j)
@@ -267,7 +352,8 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const uint32_t a = order_key2(kw[j][q]);
-                    pmin[j / JPG][q] = pk_min(pmin[j / JPG][q], a); pmax[j / JPG][q] = pk_max(pmax[j / JPG][q], a);
+                    const uint32_t ex = OUT ? half_mask(om[j] >> (2 * q)) : 0u;
+                    pmin[j / JPG][q] = pk_min(pmin[j / JPG][q], a | ex); pmax[j / JPG][q] = pk_max(pmax[j / JPG][q], a & ~ex);
                 }
             }
 #pragma unroll
@@ -295,6 +381,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
                 a = min(a, (uint32_t)s_min[(w * NG + ug) * kHeadDim + d]);
                 b = max(b, (uint32_t)s_max[(w * NG + ug) * kHeadDim + d]);
             }
+            if (OUT && a > b) { a = 0x8000u; b = 0x8000u; }   // every token of the group is an outlier here: zero +0, scale 0
             const GroupParams gp = group_params<BITS>(a, b);
             s_par[item] = make_float2(gp.zf, gp.inv);
             if (ug * G < ntok) {
@@ -316,12 +403,25 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
                 const int j = ug * JPG + jl;
                 uint32_t c[8];
                 encode8<BITS>(kw[j], zf, inv, c);
+                if constexpr (OUT) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) c[e] &= ((om[j] >> e) & 1u) - 1u;
+                    uint32_t sw[4];
+#pragma unroll
+                    for (int sl = 0; sl < 4; ++sl) {
+                        const uint32_t ch = 127u - ((win[j][sl] >> 1) & 127u);
+                        sw[sl] = slot_word(win[j][sl], s_par[ug * kHeadDim + ch].x);
+                    }
+                    if (c8 == 0 && live[j])
+                        *reinterpret_cast<uint4*>(k_out + ((size_t)head * n_cap + d0 + r + 16 * j) * 4) = make_uint4(sw[0], sw[1], sw[2], sw[3]);
+                }
                 if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, c);
             }
         }
     } else {
         uint32_t codes[R][8];
-        per_token(kw, k_scale, k_zero, codes);
+        per_token(kw, k_scale, k_zero, codes, om, zrow);
+        if constexpr (OUT) store_slots_per_token(k_out, win, zrow);
 #pragma unroll
         for (int j = 0; j < R; ++j)
             if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
@@ -339,7 +439,9 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             for (int dd = 0; dd < 8; ++dd) part[sb][dd] = 0u;
         if constexpr (QUANT) {
             uint32_t codes[R][8];
-            per_token(vw, v_scale, v_zero, codes);
+            if constexpr (OUT) mark(vw, om, win);
+            per_token(vw, v_scale, v_zero, codes, om, zrow);
+            if constexpr (OUT) store_slots_per_token(v_out, win, zrow);
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const int b32 = j >> 1, H = j & 1;
@@ -389,26 +491,36 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
 #undef KVQP_SWAP16
 #undef KVQP_SWAP32
 
-template <int BITS, int G>
+template <int BITS, int G, bool OUT>
 hipError_t launch_bits_g(const QuantPackJob& j, hipStream_t stream) {
     constexpr int TB = (BITS != 16 && G == 128) ? 128 : 64;
     const int nblk = (j.n_tok + TB - 1) / TB;
     dim3 grid(nblk + (j.copy_tail ? 1 : 0), j.heads);
     if (grid.x == 0) return hipSuccess;
-    hipLaunchKernelGGL((gather_quant_pack<BITS, G>), grid, dim3(kThreads), 0, stream, (const uint16_t*)j.k,
+    hipLaunchKernelGGL((gather_quant_pack<BITS, G, OUT>), grid, dim3(kThreads), 0, stream, (const uint16_t*)j.k,
                        (const uint16_t*)j.v, j.idx, (uint32_t*)j.c.k_codes, (uint32_t*)j.c.v_codes, (uint16_t*)j.c.k_scale,
                        (uint16_t*)j.c.k_zero, (uint16_t*)j.c.v_scale, (uint16_t*)j.c.v_zero, (uint16_t*)j.c.tail_k,
                        (uint16_t*)j.c.tail_v, j.src_rows, j.window, j.n_tok, j.key_axis, j.c.tail_cap, nblk, j.n_cap,
-                       j.dst_base, j.head_n);
+                       j.dst_base, j.head_n, (uint32_t*)j.c.k_out, (uint32_t*)j.c.v_out, j.tau_bits);
     return hipGetLastError();
 }
 template <int BITS>
 hipError_t launch_bits(const QuantPackJob& j, hipStream_t stream) {
-    if (BITS == 16) return launch_bits_g<BITS, 32>(j, stream);
-    switch (j.group_size) {
-        case 32: return launch_bits_g<BITS, 32>(j, stream);
-        case 64: return launch_bits_g<BITS, 64>(j, stream);
-        default: return launch_bits_g<BITS, 128>(j, stream);
+    if constexpr (BITS == 16) {
+        return launch_bits_g<BITS, 32, false>(j, stream);
+    } else {
+        if (j.outliers) {
+            switch (j.group_size) {
+                case 32: return launch_bits_g<BITS, 32, true>(j, stream);
+                case 64: return launch_bits_g<BITS, 64, true>(j, stream);
+                default: return launch_bits_g<BITS, 128, true>(j, stream);
+            }
+        }
+        switch (j.group_size) {
+            case 32: return launch_bits_g<BITS, 32, false>(j, stream);
+            case 64: return launch_bits_g<BITS, 64, false>(j, stream);
+            default: return launch_bits_g<BITS, 128, false>(j, stream);
+        }
     }
 }
 
@@ -449,9 +561,29 @@ hipError_t launch_job(const QuantPackJob& j, hipStream_t stream) {
 
 }  // namespace
 
+// Largest binary16 magnitude pattern whose value does not exceed tau (> 0): |x| > tau iff the
+// pattern of |x| is greater (patterns of non-negative halves order like their values).
+static uint32_t threshold_bits(float tau) {
+    auto value = [](uint32_t h) -> double {   // finite non-negative binary16 pattern -> value
+        const int e = (int)(h >> 10), m = (int)(h & 0x3ff);
+        return e == 0 ? m * (1.0 / 16777216.0) : (double)(1024 + m) * (e >= 25 ? (double)(1 << (e - 25)) : 1.0 / (double)(1 << (25 - e)));
+    };
+    uint32_t lo = 0, hi = 0x7BFF;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) / 2;
+        if (value(mid) <= (double)tau) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+static void set_outliers(QuantPackJob& j, const kvqp_cfg& cfg) {
+    j.outliers = outliers_on(cfg);
+    j.tau_bits = j.outliers ? threshold_bits(cfg.outlier_threshold) : 0x7fffu;
+}
+
 hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, const int32_t* idx, int n_kept,
                              const int32_t* head_n, const kvqp_cache& cache, hipStream_t stream) {
     QuantPackJob j{cache};
+    set_outliers(j, cfg);
     j.k = k; j.v = v; j.idx = idx; j.head_n = head_n;
     j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cfg.seq_len; j.window = cfg.window;
     j.n_tok = n_kept; j.dst_base = 0; j.n_cap = cache.n_cap > 0 ? cache.n_cap : n_kept;
@@ -462,6 +594,7 @@ hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, 
 // The n_tokens oldest tail rows are quantized onto the end of the packed part, then the tail closes up.
 hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, hipStream_t stream) {
     QuantPackJob j{cache};
+    set_outliers(j, cfg);
     j.k = cache.tail_k; j.v = cache.tail_v; j.idx = nullptr; j.head_n = nullptr;
     j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cache.tail_cap; j.window = 0;
     j.n_tok = n_tokens; j.dst_base = cache.n_kept; j.n_cap = cache.n_cap > 0 ? cache.n_cap : cache.n_kept;

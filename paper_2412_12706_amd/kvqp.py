@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libkvqp.so")
 KVQP_OK = 0
 KEY_PER_CHANNEL = 0
 KEY_PER_TOKEN = 1
-EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_workspace_bytes", "kvqp_compress",
+EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_outlier_sizes", "kvqp_workspace_bytes", "kvqp_compress",
            "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
 
 
@@ -29,14 +29,14 @@ class KvqpError(RuntimeError):
 class CfgStruct(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "seq_len", "window",
                                          "pool_kernel", "budget", "bits", "group_size", "key_axis",
-                                         "decode_splits")] + [("sm_scale", C.c_float)]
+                                         "decode_splits")] + [("sm_scale", C.c_float), ("outlier_threshold", C.c_float)]
 
 
 class CacheStruct(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero",
                                           "tail_k", "tail_v")] + [(n, C.c_int32) for n in
                                                                   ("n_kept", "tail_len", "tail_cap", "n_cap")] + [
-        ("head_n_kept", C.c_void_p)]
+        ("head_n_kept", C.c_void_p), ("k_out", C.c_void_p), ("v_out", C.c_void_p)]
 
 
 _lib = None
@@ -53,6 +53,7 @@ def lib():
         L.kvqp_strerror.argtypes = [C.c_int]
         L.kvqp_cache_sizes.argtypes = [C.POINTER(CfgStruct), C.c_int32, C.POINTER(C.c_size_t)]
         L.kvqp_cache_sizes_cap.argtypes = [C.POINTER(CfgStruct), C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        L.kvqp_outlier_sizes.argtypes = [C.POINTER(CfgStruct), C.c_int32, C.POINTER(C.c_size_t)]
         L.kvqp_append_tail.argtypes = [C.POINTER(CfgStruct), C.POINTER(CacheStruct), C.c_int32, C.c_void_p]
         L.kvqp_workspace_bytes.argtypes = [C.POINTER(CfgStruct), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.kvqp_compress.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(CacheStruct),
@@ -93,11 +94,12 @@ class Cfg:
     key_axis: int = KEY_PER_CHANNEL
     decode_splits: int = 0
     sm_scale: float = 128 ** -0.5
+    outlier_threshold: float = 0.0
 
     def struct(self) -> CfgStruct:
         return CfgStruct(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.seq_len, self.window,
                          self.pool_kernel, self.budget, self.bits, self.group_size, self.key_axis,
-                         self.decode_splits, self.sm_scale)
+                         self.decode_splits, self.sm_scale, self.outlier_threshold)
 
     @property
     def n_kept(self) -> int:
@@ -117,6 +119,14 @@ def cache_sizes_cap(cfg: Cfg, n_cap: int, tail_cap: int):
     rc = lib().kvqp_cache_sizes_cap(C.byref(cfg.struct()), n_cap, tail_cap, out)
     if rc:
         raise KvqpError(rc, "kvqp_cache_sizes_cap")
+    return list(out)
+
+
+def outlier_sizes(cfg: Cfg, n_cap: int = 0):
+    out = (C.c_size_t * 2)()
+    rc = lib().kvqp_outlier_sizes(C.byref(cfg.struct()), n_cap, out)
+    if rc:
+        raise KvqpError(rc, "kvqp_outlier_sizes")
     return list(out)
 
 
@@ -144,8 +154,10 @@ class Cache:
 
     def struct(self) -> CacheStruct:
         ptrs = [self.buffers[n].data_ptr() if self.buffers[n].numel() else None for n in _NAMES]
+        outs = [self.buffers[n].data_ptr() if n in self.buffers and self.buffers[n].numel() else None
+                for n in ("k_out", "v_out")]
         return CacheStruct(*ptrs, self.n_kept, self.tail_len, self.tail_cap, self.n_cap,
-                           None if self.head_n_kept is None else self.head_n_kept.data_ptr())
+                           None if self.head_n_kept is None else self.head_n_kept.data_ptr(), *outs)
 
     def nbytes(self) -> int:
         return sum(t.numel() for t in self.buffers.values())
@@ -158,6 +170,9 @@ def alloc_cache(cfg: Cfg, tail_cap: int | None = None, device="cuda", n_cap: int
     tail_cap = cfg.window if tail_cap is None else tail_cap
     sizes = cache_sizes_cap(cfg, n_cap, tail_cap) if n_cap else cache_sizes(cfg, tail_cap)
     bufs = {n: torch.empty(max(s, 0), dtype=torch.uint8, device=device) for n, s in zip(_NAMES, sizes)}
+    if cfg.outlier_threshold > 0:
+        for n, s in zip(("k_out", "v_out"), outlier_sizes(cfg, n_cap)):
+            bufs[n] = torch.empty(s, dtype=torch.uint8, device=device)
     counts = torch.zeros(cfg.batch * cfg.n_kv_heads, dtype=torch.int32, device=device) if ragged else None
     return Cache(bufs, 0, 0, tail_cap, n_cap, counts)
 

@@ -18,6 +18,9 @@ def upload_cache(oc, device="cuda"):
     for n in NAMES:
         arr = np.ascontiguousarray(getattr(oc, n))
         bufs[n] = torch.from_numpy(arr.view(np.uint8).reshape(-1).copy()).to(device)
+    if getattr(oc, "k_out", None) is not None:        # outlier slots
+        for n in ("k_out", "v_out"):
+            bufs[n] = torch.from_numpy(np.ascontiguousarray(getattr(oc, n)).view(np.uint8).reshape(-1).copy()).to(device)
     return kvqp.Cache(bufs, oc.n_kept, oc.tail_len, oc.tail_cap)
 
 
@@ -28,7 +31,8 @@ def download(cache, name, dtype):
 def assert_cache_equal(gc, oc):
     """Every buffer of the device cache equals the checker's, bit for bit."""
     assert gc.n_kept == oc.n_kept and gc.tail_len == oc.tail_len
-    for n in NAMES:
+    names = NAMES + (("k_out", "v_out") if getattr(oc, "k_out", None) is not None else ())
+    for n in names:
         ref = np.ascontiguousarray(getattr(oc, n))
         got = download(gc, n, ref.dtype)
         if n.startswith("tail"):

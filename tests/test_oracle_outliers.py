@@ -1,7 +1,7 @@
 """Pins for the CPU checker's outlier filtering (paper, Section 6.3 item (1) and
 Appendix B "KV quantization": numbers with |x| > 6, about 1 %, are excluded from
 quantization).  The bounded-per-token reading (at most four outliers per token row
-per tensor, largest magnitudes first) and the slot format are this build's; the
+per tensor, largest magnitudes first, stored in that order) and the slot format are this build's; the
 pins below fix them with hand-worked values, closed forms and properties that do
 not go through the checker's own arithmetic."""
 import numpy as np
@@ -78,7 +78,7 @@ def test_which_elements_are_outliers(orc):
         cand = [d for d in range(128) if a[d] > 6.0]
         cand.sort(key=lambda d: (-a[d], d))
         want = np.zeros(128, np.uint8)
-        want[cand[:4]] = 1
+        want[cand[:4]] = np.arange(1, len(cand[:4]) + 1)          # 1 + rank of selection
         assert np.array_equal(mask, want)
 
 
@@ -115,12 +115,14 @@ def test_group_ranges_exclude_outliers_and_errors_stay_bounded(orc, bits, G, axi
                                                  ("v", v, Vd, c.v_scale, c.v_zero, c.v_out, 1)):
         rows = src[0, 0][idx[0, 0]]                                  # [n, 128] float16
         x = rows.astype(np.float64)
-        mask = np.stack([orc.mark_outliers(r, 6.0) for r in rows]).astype(bool)
+        rank = np.stack([orc.mark_outliers(r, 6.0) for r in rows])
+        mask = rank.astype(bool)
         assert mask.sum() > 0.003 * mask.size                        # the case does contain outliers
-        # slots list exactly the masked channels, ascending, zeros after
+        # slots list exactly the marked channels in order of selection, zeros after
         for t in range(n):
             chans = [int(s & 0x7F) for s in out[0, 0, t] if s & 0x80]
-            assert chans == sorted(np.flatnonzero(mask[t]).tolist())
+            marked = np.flatnonzero(mask[t])
+            assert chans == sorted(marked.tolist(), key=lambda d: rank[t][d])
             assert all(s == 0 for s in out[0, 0, t][len(chans):])
         if ax == 0:    # groups of G tokens per channel
             xs = x.reshape(n // G, G, 128).transpose(0, 2, 1)        # [group, channel, member]
