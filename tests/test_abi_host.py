@@ -172,6 +172,29 @@ def test_head_level_count_argument_checks(lib):
     assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1   # a head may be empty
 
 
+def test_outlier_filtering_argument_checks(lib):
+    """Slot buffer sizes and the host-side rejects of the outlier-filtering mode."""
+    base = dict(batch=2, n_q_heads=8, n_kv_heads=2, seq_len=800, window=32, budget=256, bits=4, group_size=32)
+    on = kvqp.Cfg(**base, outlier_threshold=6.0)
+    assert kvqp.outlier_sizes(on) == [2 * 2 * 256 * 4 * 4] * 2              # heads x tokens x 4 slots x 4 bytes
+    assert kvqp.outlier_sizes(on, 320) == [2 * 2 * 320 * 4 * 4] * 2
+    assert kvqp.outlier_sizes(kvqp.Cfg(**base)) == [0, 0]
+    for bad in (-1.0, float("nan"), float("inf")):
+        with pytest.raises(kvqp.KvqpError):
+            kvqp.outlier_sizes(kvqp.Cfg(**base, outlier_threshold=bad))
+    with pytest.raises(kvqp.KvqpError):                                      # nothing is quantized at 16 bits
+        kvqp.cache_sizes(kvqp.Cfg(**{**base, "bits": 16}, outlier_threshold=6.0), 32)
+    st = on.struct()
+    cs = kvqp.CacheStruct()
+    for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
+        setattr(cs, name, 0x1000)
+    cs.tail_cap = 32
+    fake = C.c_void_p(0x1000)
+    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, fake, 1 << 30, None) == -1   # no slot buffers
+    cs.n_kept, cs.tail_len = 256, 32
+    assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1
+
+
 def test_binding_raises_with_the_library_message(lib):
     cfg = kvqp.Cfg(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024, bits=5)
     with pytest.raises(kvqp.KvqpError) as e:
