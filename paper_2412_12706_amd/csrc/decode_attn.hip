@@ -486,6 +486,28 @@ __device__ void tail_rows(const DecodeArgs& a, int bh, int t0, int t1, float* sT
     }
 }
 
+// The per-token scales (or zeros) of four consecutive tokens, NCG halves each: 2 NCG words in one or
+// two wide loads; element (token i, group c) is half i * NCG + c.
+template <int NCG>
+__device__ __forceinline__ void load_tok4(const uint16_t* __restrict__ base, int tok, uint32_t (&w)[2 * NCG]) {
+    const uint16_t* p = base + (size_t)tok * NCG;
+    if constexpr (NCG == 4) {
+        const uint4 x = reinterpret_cast<const uint4*>(p)[0], y = reinterpret_cast<const uint4*>(p)[1];
+        w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w; w[4] = y.x; w[5] = y.y; w[6] = y.z; w[7] = y.w;
+    } else if constexpr (NCG == 2) {
+        const uint4 x = *reinterpret_cast<const uint4*>(p);
+        w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
+    } else {
+        const uint2 x = *reinterpret_cast<const uint2*>(p);
+        w[0] = x.x; w[1] = x.y;
+    }
+}
+template <int NCG>
+__device__ __forceinline__ float tok4_at(const uint32_t (&w)[2 * NCG], int i, int c) {
+    const int e = i * NCG + c;
+    return __half2float(__ushort_as_half((uint16_t)(w[e >> 1] >> (16 * (e & 1)))));
+}
+
 // the binary32 difference an outlier slot word carries (0 for an unused slot)
 __device__ __forceinline__ float slot_delta(uint32_t w) { return __uint_as_float(w & 0xFFFFFF00u); }
 
@@ -649,6 +671,9 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                 // per-token keys: one masked product per channel group, scaled per token afterwards
                 constexpr int LPG = 4 / NCG;  // lane quads (kb values) per channel group
                 f4v sum0 = acc0, sum1 = acc0;
+                uint32_t ks0[2 * NCG], kz0[2 * NCG], ks1[2 * NCG], kz1[2 * NCG];   // tokens tb + 4kb + i and 16 further
+                load_tok4<NCG>(ks, tb + 4 * kb, ks0); load_tok4<NCG>(kz, tb + 4 * kb, kz0);
+                load_tok4<NCG>(ks, tb + 16 + 4 * kb, ks1); load_tok4<NCG>(kz, tb + 16 + 4 * kb, kz1);
 #pragma unroll
                 for (int c = 0; c < NCG; ++c) {
                     const bool mine = (kb / LPG) == c;
@@ -665,11 +690,8 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                     const float qs_c = quad_rows_add(mine ? qsum_cg : 0.f);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const int t0i = tb + 4 * kb + i, t1i = t0i + 16;
-                        const float s0 = __half2float(__ushort_as_half(ks[(size_t)t0i * NCG + c]));
-                        const float z0 = __half2float(__ushort_as_half(kz[(size_t)t0i * NCG + c]));
-                        const float s1 = __half2float(__ushort_as_half(ks[(size_t)t1i * NCG + c]));
-                        const float z1 = __half2float(__ushort_as_half(kz[(size_t)t1i * NCG + c]));
+                        const float s0 = tok4_at<NCG>(ks0, i, c), z0 = tok4_at<NCG>(kz0, i, c);
+                        const float s1 = tok4_at<NCG>(ks1, i, c), z1 = tok4_at<NCG>(kz1, i, c);
                         // fold 1/kCodeUnit of the bias in, since the sum is scaled by c_logit later
                         sum0[i] = __builtin_fmaf(p0[i], s0, sum0[i]) + (part ? 0.f : z0 * qs_c * (1.0f / kCodeUnit));
                         sum1[i] = __builtin_fmaf(p1[i], s1, sum1[i]) + (part ? 0.f : z1 * qs_c * (1.0f / kCodeUnit));
@@ -801,14 +823,15 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
             for (int t = 0; t < NT; ++t) {
                 const int tile_h = (SLOTS == 2) ? slot : t;          // 0: tokens 4kb+i, 1: tokens 16+4kb+i
                 const int tokb = tb + 16 * tile_h + 4 * kb;
+                uint32_t vsw[2 * NCG], vzw[2 * NCG];
+                if constexpr (QUANT) { load_tok4<NCG>(vs, tokb, vsw); load_tok4<NCG>(vz, tokb, vzw); }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
 #pragma unroll
                     for (int c = 0; c < NCG; ++c) {
                         float ps = p[t][i];
                         if constexpr (QUANT) {
-                            const float sv = __half2float(__ushort_as_half(vs[(size_t)(tokb + i) * NCG + c]));
-                            const float zv = __half2float(__ushort_as_half(vz[(size_t)(tokb + i) * NCG + c]));
+                            const float sv = tok4_at<NCG>(vsw, i, c), zv = tok4_at<NCG>(vzw, i, c);
                             ps *= sv;
                             oz[c] = __builtin_fmaf(p[t][i] * (float)(1 << v_pos_log2<BITS>(blk, i)), zv, oz[c]);
                         }
