@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the quantized-pruned KV cache hot path on one MI355X.
 
-Workload (benchmark configs[1]): Llama-3-8B-shaped KV cache -- 32 layers,
+Workload (the headline configuration, configs[1]): Llama-3-8B-shaped KV cache -- 32 layers,
 32 query / 8 KV heads, head_dim 128, half precision, batch 1, prompt L = 32768,
 synthetic N(0,1) data with four x10 outlier key channels per head -- swept over
 the equal-memory settings (tokens, bits) in {(2048,16), (4096,8), (8192,4),
@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-only", action="store_true",
+                    help="only the timed sweep (used by the profiling commands so that their per-kernel averages "
+                         "cover exactly the timed launches)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="kept for the profiling commands: the plain 1 GiB device copy (known size) that scales profiler "
                          "byte counters is always run")
@@ -193,121 +196,127 @@ def main():
         tot_ms += s["t_decode_ms"]
     value = tot_bytes / (tot_ms * 1e-3) / 1e9
 
-    # ---- the same decode bytes issued as 32 per-layer calls (outside the timed steps) ----
-    per_layer = []
-    for s in settings:
-        cfg1 = kvqp.Cfg(**{**s["cfg"].__dict__, "batch": 1})
-        caches = []
-        for l in range(LAYERS):
-            bufs = {}
-            for name, t in s["cache"].buffers.items():
-                per = t.numel() // LAYERS
-                bufs[name] = t[l * per:(l + 1) * per]
-            caches.append(kvqp.Cache(bufs, s["cache"].n_kept, s["cache"].tail_len, s["cache"].tail_cap))
-        ws1 = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg1)[1], dev)
-        reps = 8
+    def extra_legs():
+        """Measurements outside the timed steps: per-layer calls, cache update, layer-wise counts, outlier filtering."""
+        # ---- the same decode bytes issued as 32 per-layer calls (outside the timed steps) ----
+        per_layer = []
+        for s in settings:
+            cfg1 = kvqp.Cfg(**{**s["cfg"].__dict__, "batch": 1})
+            caches = []
+            for l in range(LAYERS):
+                bufs = {}
+                for name, t in s["cache"].buffers.items():
+                    per = t.numel() // LAYERS
+                    bufs[name] = t[l * per:(l + 1) * per]
+                caches.append(kvqp.Cache(bufs, s["cache"].n_kept, s["cache"].tail_len, s["cache"].tail_cap))
+            ws1 = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg1)[1], dev)
+            reps = 8
+            for rep in range(reps + 1):
+                if rep == 1:
+                    torch.cuda.synchronize()
+                    a, bq = ev(), ev()
+                    a.record()
+                for l in range(LAYERS):
+                    kvqp.decode_attn(cfg1, queries[rep][l:l + 1], caches[l], out[l:l + 1], ws1)
+            bq.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(bq) * 1e3 / reps
+            b = decode_bytes(LAYERS, s["n_kept"], s["bits"], G, W)
+            per_layer.append({"tokens": s["n_kept"], "bits": s["bits"], "decode_us_per_step": round(us, 1),
+                              "decode_gbs": round(b / (us * 1e-6) / 1e9, 1)})
+
+        # ---- decode-time cache update (outside the timed steps): 32 decoded tokens per layer move from the
+        # full-precision tail into the 4-bit part of a cache laid out with room to grow ----
+        s4 = next(s for s in settings if s["bits"] == 4)
+        grow = kvqp.alloc_cache(s4["cfg"], tail_cap=W + G, device=dev, n_cap=s4["n_kept"] + 64)
+        kvqp.compress(s4["cfg"], q_obs, k, v, grow, workspace=s4["ws_c"])
+        grow.buffers["tail_k"].view(torch.float16).normal_()
+        grow.buffers["tail_v"].view(torch.float16).normal_()
+        reps = 20
+        for rep in range(reps + 2):
+            if rep == 2:
+                torch.cuda.synchronize()
+                a0, a1 = ev(), ev()
+                a0.record()
+            grow.n_kept, grow.tail_len = s4["n_kept"], W + G      # (the counts live on the host; the rows are re-quantized)
+            kvqp.append_tail(s4["cfg"], grow, G)
+        a1.record()
+        torch.cuda.synchronize()
+        append_us = a0.elapsed_time(a1) * 1e3 / reps
+        del grow
+
+        # ---- layer-wise token counts (outside the timed steps): the 4-bit setting's memory spread over the
+        # layers as a falling schedule, 1.5x the mean in the first layer down to 0.5x in the last, one batch ----
+        mean = s4["n_kept"]
+        counts = [int(round(mean * (1.5 - l / (LAYERS - 1)) / 64)) * 64 for l in range(LAYERS)]
+        cfg_r = kvqp.Cfg(**{**s4["cfg"].__dict__, "budget": max(counts)})
+        rag = kvqp.alloc_cache(cfg_r, device=dev, ragged=True)
+        ws_rc, ws_rd = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_r))
+        head_counts = [counts[h // HKV] for h in range(LAYERS * HKV)]
+        reps = 3
         for rep in range(reps + 1):
             if rep == 1:
                 torch.cuda.synchronize()
-                a, bq = ev(), ev()
-                a.record()
-            for l in range(LAYERS):
-                kvqp.decode_attn(cfg1, queries[rep][l:l + 1], caches[l], out[l:l + 1], ws1)
-        bq.record()
+                r0, r1 = ev(), ev()
+                r0.record()
+            kvqp.compress_ragged(cfg_r, q_obs, k, v, head_counts, rag, workspace=ws_rc)
+        r1.record()
+        for t in range(8):
+            kvqp.decode_attn(cfg_r, queries[t], rag, out, ws_rd)
         torch.cuda.synchronize()
-        us = a.elapsed_time(bq) * 1e3 / reps
-        b = decode_bytes(LAYERS, s["n_kept"], s["bits"], G, W)
-        per_layer.append({"tokens": s["n_kept"], "bits": s["bits"], "decode_us_per_step": round(us, 1),
-                          "decode_gbs": round(b / (us * 1e-6) / 1e9, 1)})
+        r2, r3 = ev(), ev()
+        r2.record()
+        for t in range(DECODE_STEPS):
+            kvqp.decode_attn(cfg_r, queries[t], rag, out, ws_rd)
+        r3.record()
+        torch.cuda.synchronize()
+        rag_bytes = sum(decode_bytes(1, n, 4, G, W) for n in counts)
+        rag_us = r2.elapsed_time(r3) * 1e3 / DECODE_STEPS
+        layer_wise = {
+            "counts": f"{counts[0]} .. {counts[-1]} tokens per layer (mean {sum(counts) // LAYERS}), 4 bit",
+            "compress_ms_32_layers": round(r0.elapsed_time(r1) / reps, 3), "decode_us_per_step": round(rag_us, 2),
+            "decode_gbs": round(rag_bytes / (rag_us * 1e-6) / 1e9, 1), "bytes_per_step": rag_bytes,
+        }
+        del rag
 
-    # ---- decode-time cache update (outside the timed steps): 32 decoded tokens per layer move from the
-    # full-precision tail into the 4-bit part of a cache laid out with room to grow ----
-    s4 = next(s for s in settings if s["bits"] == 4)
-    grow = kvqp.alloc_cache(s4["cfg"], tail_cap=W + G, device=dev, n_cap=s4["n_kept"] + 64)
-    kvqp.compress(s4["cfg"], q_obs, k, v, grow, workspace=s4["ws_c"])
-    grow.buffers["tail_k"].view(torch.float16).normal_()
-    grow.buffers["tail_v"].view(torch.float16).normal_()
-    reps = 20
-    for rep in range(reps + 2):
-        if rep == 2:
-            torch.cuda.synchronize()
-            a0, a1 = ev(), ev()
-            a0.record()
-        grow.n_kept, grow.tail_len = s4["n_kept"], W + G      # (the counts live on the host; the rows are re-quantized)
-        kvqp.append_tail(s4["cfg"], grow, G)
-    a1.record()
-    torch.cuda.synchronize()
-    append_us = a0.elapsed_time(a1) * 1e3 / reps
-    del grow
+        # ---- outlier filtering at the paper's threshold (outside the timed steps): the 4-bit setting with
+        # |x| > 6 kept beside the codes, four slot words per token row and tensor ----
+        cfg_o = kvqp.Cfg(**{**s4["cfg"].__dict__, "outlier_threshold": 6.0})
+        oc_cache = kvqp.alloc_cache(cfg_o, device=dev)
+        ws_oc, ws_od = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_o))
+        reps = 3
+        for rep in range(reps + 1):
+            if rep == 1:
+                torch.cuda.synchronize()
+                o0, o1 = ev(), ev()
+                o0.record()
+            kvqp.compress(cfg_o, q_obs, k, v, oc_cache, workspace=ws_oc)
+        o1.record()
+        for t in range(8):
+            kvqp.decode_attn(cfg_o, queries[t], oc_cache, out, ws_od)
+        torch.cuda.synchronize()
+        o2, o3 = ev(), ev()
+        o2.record()
+        for t in range(DECODE_STEPS):
+            kvqp.decode_attn(cfg_o, queries[t], oc_cache, out, ws_od)
+        o3.record()
+        torch.cuda.synchronize()
+        slot_bytes = LAYERS * HKV * s4["n_kept"] * 2 * 16
+        o_bytes = decode_bytes(LAYERS, s4["n_kept"], 4, G, W) + slot_bytes
+        o_us = o2.elapsed_time(o3) * 1e3 / DECODE_STEPS
+        n_slots = int((oc_cache.buffers["k_out"].view(torch.int32) != 0).sum().item())
+        outlier_leg = {
+            "threshold": 6.0, "bits": 4, "tokens": s4["n_kept"],
+            "key_outliers_per_row": round(n_slots / (LAYERS * HKV * s4["n_kept"]), 2),
+            "compress_ms_32_layers": round(o0.elapsed_time(o1) / reps, 3), "decode_us_per_step": round(o_us, 2),
+            "decode_gbs": round(o_bytes / (o_us * 1e-6) / 1e9, 1), "bytes_per_step": o_bytes,
+            "note": "decode runs on the plain split-K kernel when a cache carries outlier slots",
+        }
+        del oc_cache
 
-    # ---- layer-wise token counts (outside the timed steps): the 4-bit setting's memory spread over the
-    # layers as a falling schedule, 1.5x the mean in the first layer down to 0.5x in the last, one batch ----
-    mean = s4["n_kept"]
-    counts = [int(round(mean * (1.5 - l / (LAYERS - 1)) / 64)) * 64 for l in range(LAYERS)]
-    cfg_r = kvqp.Cfg(**{**s4["cfg"].__dict__, "budget": max(counts)})
-    rag = kvqp.alloc_cache(cfg_r, device=dev, ragged=True)
-    ws_rc, ws_rd = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_r))
-    head_counts = [counts[h // HKV] for h in range(LAYERS * HKV)]
-    reps = 3
-    for rep in range(reps + 1):
-        if rep == 1:
-            torch.cuda.synchronize()
-            r0, r1 = ev(), ev()
-            r0.record()
-        kvqp.compress_ragged(cfg_r, q_obs, k, v, head_counts, rag, workspace=ws_rc)
-    r1.record()
-    for t in range(8):
-        kvqp.decode_attn(cfg_r, queries[t], rag, out, ws_rd)
-    torch.cuda.synchronize()
-    r2, r3 = ev(), ev()
-    r2.record()
-    for t in range(DECODE_STEPS):
-        kvqp.decode_attn(cfg_r, queries[t], rag, out, ws_rd)
-    r3.record()
-    torch.cuda.synchronize()
-    rag_bytes = sum(decode_bytes(1, n, 4, G, W) for n in counts)
-    rag_us = r2.elapsed_time(r3) * 1e3 / DECODE_STEPS
-    layer_wise = {
-        "counts": f"{counts[0]} .. {counts[-1]} tokens per layer (mean {sum(counts) // LAYERS}), 4 bit",
-        "compress_ms_32_layers": round(r0.elapsed_time(r1) / reps, 3), "decode_us_per_step": round(rag_us, 2),
-        "decode_gbs": round(rag_bytes / (rag_us * 1e-6) / 1e9, 1), "bytes_per_step": rag_bytes,
-    }
-    del rag
+        return per_layer, append_us, layer_wise, outlier_leg
 
-    # ---- outlier filtering at the paper's threshold (outside the timed steps): the 4-bit setting with
-    # |x| > 6 kept beside the codes, four slot words per token row and tensor ----
-    cfg_o = kvqp.Cfg(**{**s4["cfg"].__dict__, "outlier_threshold": 6.0})
-    oc_cache = kvqp.alloc_cache(cfg_o, device=dev)
-    ws_oc, ws_od = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_o))
-    reps = 3
-    for rep in range(reps + 1):
-        if rep == 1:
-            torch.cuda.synchronize()
-            o0, o1 = ev(), ev()
-            o0.record()
-        kvqp.compress(cfg_o, q_obs, k, v, oc_cache, workspace=ws_oc)
-    o1.record()
-    for t in range(8):
-        kvqp.decode_attn(cfg_o, queries[t], oc_cache, out, ws_od)
-    torch.cuda.synchronize()
-    o2, o3 = ev(), ev()
-    o2.record()
-    for t in range(DECODE_STEPS):
-        kvqp.decode_attn(cfg_o, queries[t], oc_cache, out, ws_od)
-    o3.record()
-    torch.cuda.synchronize()
-    slot_bytes = LAYERS * HKV * s4["n_kept"] * 2 * 16
-    o_bytes = decode_bytes(LAYERS, s4["n_kept"], 4, G, W) + slot_bytes
-    o_us = o2.elapsed_time(o3) * 1e3 / DECODE_STEPS
-    n_slots = int((oc_cache.buffers["k_out"].view(torch.int32) != 0).sum().item())
-    outlier_leg = {
-        "threshold": 6.0, "bits": 4, "tokens": s4["n_kept"],
-        "key_outliers_per_row": round(n_slots / (LAYERS * HKV * s4["n_kept"]), 2),
-        "compress_ms_32_layers": round(o0.elapsed_time(o1) / reps, 3), "decode_us_per_step": round(o_us, 2),
-        "decode_gbs": round(o_bytes / (o_us * 1e-6) / 1e9, 1), "bytes_per_step": o_bytes,
-        "note": "decode runs on the plain split-K kernel when a cache carries outlier slots",
-    }
-    del oc_cache
+    per_layer, append_us, layer_wise, outlier_leg = (None, None, None, None) if args.sweep_only else extra_legs()
 
     # ---- roofline of the dominant kernel: the decode launch that takes most of the step ----
     dom = max(range(len(settings)), key=lambda i: settings[i]["t_decode_ms"])
@@ -320,7 +329,7 @@ def main():
         "algorithmic_bytes_per_launch": dom_r["bytes_per_step"], "launch_us": dom_r["decode_us_per_step"],
         "roofline_time_us": max(dom_r["t_hbm_us"], dom_r["t_plain_alu_us"]),
         "note": "the products run on the matrix cores with the codes as operands, so the plain-ALU bound does not "
-                "apply; at 2 bits the measured limit is vector-instruction issue for operand preparation (DESIGN.md 5.1)",
+                "apply; at 2 bits the measured limit is vector-instruction issue for operand preparation",
     }
 
     # ---- what a plain device copy reaches on this machine (1 GiB read + 1 GiB written per copy) ----
@@ -358,7 +367,7 @@ def main():
         "device_copy_gbs": round(copy_gbs, 1), "pct_of_device_copy": round(100 * value / copy_gbs, 1),
         "compress_mtok_s": c4["compress_mtok_s"],
         "compress_note": "prompt tokens/s through all 32 layers at the (8192 tok, 4 bit) setting",
-        "append_tail_us": round(append_us, 2),
+        "append_tail_us": None if append_us is None else round(append_us, 2),
         "append_note": f"kvqp_append_tail of {G} tokens per cache, 32 layers as one batch, 4-bit setting",
         "layer_wise_counts": layer_wise, "outlier_filtering": outlier_leg,
         "sweep": sweep, "per_layer_calls": per_layer,
