@@ -668,33 +668,41 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                     acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq.v, acc1, 0, 0, 0);
                 }
             } else {
-                // per-token keys: one masked product per channel group, scaled per token afterwards
+                // per-token keys: masked products, scaled per token afterwards.  A pass serves two channel
+                // groups at once: q needs no hi / lo split here, so the hi rows take group 2 c2 and the lo
+                // rows group 2 c2 + 1; the sum of the row pair below then adds the groups instead.
                 constexpr int LPG = 4 / NCG;  // lane quads (kb values) per channel group
+                constexpr int NP = (NCG + 1) / 2;
                 f4v sum0 = acc0, sum1 = acc0;
                 uint32_t ks0[2 * NCG], kz0[2 * NCG], ks1[2 * NCG], kz1[2 * NCG];   // tokens tb + 4kb + i and 16 further
                 load_tok4<NCG>(ks, tb + 4 * kb, ks0); load_tok4<NCG>(kz, tb + 4 * kb, kz0);
                 load_tok4<NCG>(ks, tb + 16 + 4 * kb, ks1); load_tok4<NCG>(kz, tb + 16 + 4 * kb, kz1);
 #pragma unroll
-                for (int c = 0; c < NCG; ++c) {
-                    const bool mine = (kb / LPG) == c;
+                for (int c2 = 0; c2 < NP; ++c2) {
+                    constexpr int kLast = NCG - 1;
+                    const int c_lo = 2 * c2, c_hi = (2 * c2 + 1 < NCG) ? 2 * c2 + 1 : kLast;
+                    const bool has = !part || 2 * c2 + 1 < NCG;            // (one group in all: the lo rows stay empty)
+                    const bool mine = has && (kb / LPG) == (part ? c_hi : c_lo);
                     f4v p0 = (f4v){0.f, 0.f, 0.f, 0.f}, p1 = p0;
 #pragma unroll
                     for (int s = 0; s < 4; ++s) {
                         Frag bq;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) bq.h[r] = (mine && !part) ? qpos[4 * s + r] : (h2v){0, 0};
+                        for (int r = 0; r < 4; ++r) bq.h[r] = mine ? qpos[4 * s + r] : (h2v){0, 0};
                         p0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq.v, p0, 0, 0, 0);
                         p1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq.v, p1, 0, 0, 0);
                     }
-                    // sum over the group's channels of q, broadcast to all lanes of the row
+                    // sum over the group's channels of q, broadcast to all lanes of the row (0 where the row has no group)
                     const float qs_c = quad_rows_add(mine ? qsum_cg : 0.f);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float s0 = tok4_at<NCG>(ks0, i, c), z0 = tok4_at<NCG>(kz0, i, c);
-                        const float s1 = tok4_at<NCG>(ks1, i, c), z1 = tok4_at<NCG>(kz1, i, c);
+                        const float s0 = part ? tok4_at<NCG>(ks0, i, c_hi) : tok4_at<NCG>(ks0, i, c_lo);
+                        const float z0 = part ? tok4_at<NCG>(kz0, i, c_hi) : tok4_at<NCG>(kz0, i, c_lo);
+                        const float s1 = part ? tok4_at<NCG>(ks1, i, c_hi) : tok4_at<NCG>(ks1, i, c_lo);
+                        const float z1 = part ? tok4_at<NCG>(kz1, i, c_hi) : tok4_at<NCG>(kz1, i, c_lo);
                         // fold 1/kCodeUnit of the bias in, since the sum is scaled by c_logit later
-                        sum0[i] = __builtin_fmaf(p0[i], s0, sum0[i]) + (part ? 0.f : z0 * qs_c * (1.0f / kCodeUnit));
-                        sum1[i] = __builtin_fmaf(p1[i], s1, sum1[i]) + (part ? 0.f : z1 * qs_c * (1.0f / kCodeUnit));
+                        sum0[i] = __builtin_fmaf(p0[i], s0, sum0[i]) + z0 * qs_c * (1.0f / kCodeUnit);
+                        sum1[i] = __builtin_fmaf(p1[i], s1, sum1[i]) + z1 * qs_c * (1.0f / kCodeUnit);
                     }
                 }
                 acc0 = sum0; acc1 = sum1;
