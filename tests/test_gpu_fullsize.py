@@ -142,3 +142,65 @@ def test_longest_context_shape(orc):
     err = np.abs(gpu - ref).max()
     print(f"    decode max-abs error {err:.2e}", flush=True)
     assert err <= 2e-3
+
+
+def check_one_layer(orc, *, B, Hq, Hkv, Lc, Wc, n_kept, bits, Gc, axis, config, samples, outlier=10.0):
+    """One layer of a configuration at its real shape: compress and one decode step on the device,
+    the sampled (sequence, KV head) slices against the CPU checker on the same bytes."""
+    gq = Hq // Hkv
+    q_obs, k, v = synth.prompt_device(B, Hq, Hkv, Lc, Wc, D, outlier=outlier, config=config, device="cuda:0")
+    sm = float(np.float32(D ** -0.5))
+    cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=Lc, window=Wc, pool_kernel=POOL, budget=n_kept,
+                   bits=bits, group_size=Gc, key_axis=axis, sm_scale=sm)
+    cache = kvqp.alloc_cache(cfg, device="cuda:0")
+    idx_dev = torch.empty((B, Hkv, n_kept), dtype=torch.int32, device="cuda:0")
+    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev)
+    q = synth.decode_query_device(B, Hq, D, config=config, step=0, device="cuda:0")
+    out = kvqp.decode_attn(cfg, q, cache)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    idx_all = idx_dev.cpu().numpy()
+    assert np.all(np.diff(idx_all, axis=-1) > 0) and idx_all.min() >= 0 and idx_all.max() < Lc - Wc
+    for b, g in samples:
+        print(f"  slice sequence={b} kv_head={g}", flush=True)
+        qs = q_obs[b:b + 1, g * gq:(g + 1) * gq].cpu().numpy()
+        ks, vs = k[b:b + 1, g:g + 1].cpu().numpy(), v[b:b + 1, g:g + 1].cpu().numpy()
+        oc, idx_ref, pooled = orc.compress(qs, ks, vs, window=Wc, pool=POOL, budget=n_kept, bits=bits, G=Gc, sm_scale=sm,
+                                           key_axis=axis)
+        got = idx_all[b, g]
+        if not np.array_equal(got, idx_ref[0, 0]):
+            kth = np.sort(pooled[0, 0])[-n_kept]
+            diff = np.setxor1d(got, idx_ref[0, 0])
+            rel = np.abs(pooled[0, 0][diff] - kth) / kth
+            assert np.all(rel <= 1e-6), f"{diff.size} indices differ, worst relative gap {rel.max():.3e}"
+            print(f"    {diff.size} index differences inside the 1e-6 tie band", flush=True)
+            oc = orc.quantize_selected(ks, vs, got.reshape(1, 1, -1), W=Wc, bits=bits, G=Gc, key_axis=axis)
+        for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
+            t = cache.buffers[name]
+            per = t.numel() // (B * Hkv)
+            i = b * Hkv + g
+            ref = np.ascontiguousarray(getattr(oc, name)).view(np.uint8).reshape(-1)
+            assert np.array_equal(t[i * per:(i + 1) * per].cpu().numpy(), ref), f"{name} differs at sequence {b}, head {g}"
+        qd = q[b:b + 1, g * gq:(g + 1) * gq].cpu().numpy()
+        ref = orc.decode_attn(qd, oc, sm)
+        err = np.abs(out[b, g * gq:(g + 1) * gq].cpu().numpy().astype(np.float64) - ref[0]).max()
+        print(f"    decode max-abs error {err:.2e}", flush=True)
+        assert err <= 2e-3
+
+
+def test_batched_sequences_shape(orc):
+    """The batched-decode configuration, one layer at its real shape: 16 sequences of L = 16384,
+    4096 tokens kept at 4 bits."""
+    print("case batch 16, L=16384, 4096 tokens at 4 bits", flush=True)
+    check_one_layer(orc, B=16, Hq=HQ, Hkv=HKV, Lc=16384, Wc=32, n_kept=4096, bits=4, Gc=32, axis=kvqp.KEY_PER_CHANNEL,
+                    config=3, samples=[(0, 2), (15, 7)])
+
+
+@pytest.mark.parametrize("axis", [kvqp.KEY_PER_CHANNEL, kvqp.KEY_PER_TOKEN])
+def test_seventy_b_shape(orc, axis):
+    """The 70B-shaped configuration, one layer at its real shape: 64 query / 8 KV heads (eight query
+    heads per KV head: 256 window rows per head), 8 sequences of L = 32768, 8192 tokens kept at
+    4 bits; per-channel keys and the per-token-key ablation."""
+    print(f"case 64/8 heads, batch 8, L=32768, 8192 tokens at 4 bits, key axis {axis}", flush=True)
+    check_one_layer(orc, B=8, Hq=64, Hkv=8, Lc=32768, Wc=32, n_kept=8192, bits=4, Gc=32, axis=axis, config=5,
+                    samples=[(0, 0), (7, 5)])
