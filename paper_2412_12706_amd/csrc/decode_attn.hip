@@ -77,6 +77,11 @@ __device__ __forceinline__ float pair_other(float v) {
     return __uint_as_float(__builtin_amdgcn_mov_dpp(__float_as_uint(v), 0xB1 /*quad_perm [1,0,3,2]*/, 0xf, 0xf, true));
 }
 
+// value of the lane eight further round the row of 16 (lane ^ 8)
+__device__ __forceinline__ float row_ror8(float v) {
+    return __uint_as_float(__builtin_amdgcn_mov_dpp(__float_as_uint(v), 0x128 /*row_ror:8*/, 0xf, 0xf, true));
+}
+
 __device__ __forceinline__ h2v as_h2(uint32_t u) { union { uint32_t u; h2v h; } c; c.u = u; return c.h; }
 __device__ __forceinline__ uint32_t as_u32(h2v h) { union { uint32_t u; h2v h; } c; c.h = h; return c.u; }
 // two binary32 values cut (toward zero) to binary16, (lo, hi) half-words
@@ -902,8 +907,8 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 }
 
 // ---------------------------------------------------------------------------
-// Software-pipelined variant for per-channel keys (the default axes) and for
-// the 16-bit cache.  Same arithmetic as above; differences are all about
+// Software-pipelined kernel: every cache without outlier slots.  Same
+// arithmetic as above; differences are all about
 // keeping HBM, the texture-address path and the vector ALU busy at once:
 //   * every global load of a 32-token block is issued ahead into a second
 //     register set (A = first block of a 64-token chunk, B = second): the next
@@ -938,7 +943,7 @@ template <int BITS, int NCG> struct PipeGeom {
 // Afterwards the same bytes hold every wave's state for the merge: 8 output rows (hi + lo parts
 // already added) of 128 floats and 16 x (m, l, oz[4]).  The tail rows' states have their own
 // region behind both (they are produced first and merged last).
-constexpr int kPipeQueryLds = 8 * kHeadDim * 2 + 4 * 64 * 16;
+constexpr int kPipeQueryLds = 8 * kHeadDim * 2 + 2 * 4 * 64 * 16;   // plain rows + up to two operand-layout copies
 constexpr int kPipeStateLds = 8 * kHeadDim * 4 + 16 * 6 * 4 + 2 * 8 * 4 + 8 * 4;   // per wave: rows, stats, merge weights (+ references)
 constexpr int pipe_tail_lds(int gq) { return kWaves * gq * kPartStride * 4; }
 constexpr int pipe_lds_bytes(int nw, int strip, int gq) {
@@ -951,14 +956,25 @@ constexpr int pipe_tail_offset(int nw, int strip) {
 }
 constexpr int pipe_max_waves(int bits, int gq) { return 4 * pipe_waves(bits, gq); }
 
-template <int BITS, int GQ, int NCG>
+// KT (per-token key groups, AXIS = 1): the key scales have the shape of the value scales, [token][NCG],
+// and travel the same way (one dword per lane per block, parked in the strip, read back as the
+// scales of four consecutive tokens).  The query operand is then the same for every block: column
+// n of the product holds q masked to ONE channel group -- the columns of a head, (slot, hi/lo),
+// are free for that because q needs no scale folded in and so no hi/lo split: group 2 slot + hi/lo
+// at four groups, hi/lo at two -- so one pass of the usual eight matrix instructions yields every
+// group's partial sum; each lane scales its own by the token's scale, adds zero x sum(q of the
+// group), and two DPP exchanges add the columns of the head up.  With eight query heads per KV head
+// a head has only its hi / lo columns, and four groups take two passes.
+template <int BITS, int GQ, int NCG, int AXIS>
 __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_pipe(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int NT = (SLOTS == 2) ? 1 : 2;
     constexpr bool QUANT = BITS != 16;
+    constexpr bool KT = QUANT && AXIS == KVQP_KEY_PER_TOKEN;
+    constexpr int KP = (KT && SLOTS == 1 && NCG == 4) ? 2 : 1;   // passes of the key product: eight heads leave two columns per head, four groups take two passes
     constexpr float kCodeUnit = QUANT ? 16777216.0f : 1.0f;
     constexpr int G = kHeadDim / NCG;
-    constexpr int NGRP = (QUANT && G == 32) ? 2 : 1;          // key groups per 64-token chunk
+    constexpr int NGRP = (QUANT && !KT && G == 32) ? 2 : 1;   // key groups per 64-token chunk
     using Geo = PipeGeom<BITS, NCG>;
     constexpr int VROW = Geo::VROW;
     constexpr int VSTRIP = 8 * NCG;                           // bytes of value scales of 4 consecutive tokens
@@ -992,8 +1008,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     const char* kc = reinterpret_cast<const char*>(a.k_codes) + (size_t)bh * ((size_t)a.n_cap * kHeadDim * BITS / 8);
     const char* vc = reinterpret_cast<const char*>(a.v_codes) +
                      (size_t)bh * v_superblock_words(BITS) * 4 * ((a.n_cap + v_superblock(BITS) - 1) / v_superblock(BITS));
-    const char* ks = QUANT ? reinterpret_cast<const char*>(a.k_scale) + (size_t)bh * (a.n_cap / G) * kHeadDim * 2 : nullptr;
-    const char* kz = QUANT ? reinterpret_cast<const char*>(a.k_zero) + (size_t)bh * (a.n_cap / G) * kHeadDim * 2 : nullptr;
+    const size_t k_meta_head = KT ? (size_t)a.n_cap * NCG * 2 : (size_t)(a.n_cap / G) * kHeadDim * 2;   // bytes per head
+    const char* ks = QUANT ? reinterpret_cast<const char*>(a.k_scale) + (size_t)bh * k_meta_head : nullptr;
+    const char* kz = QUANT ? reinterpret_cast<const char*>(a.k_zero) + (size_t)bh * k_meta_head : nullptr;
     const char* vs = QUANT ? reinterpret_cast<const char*>(a.v_scale) + (size_t)bh * a.n_cap * NCG * 2 : nullptr;
     const char* vz = QUANT ? reinterpret_cast<const char*>(a.v_zero) + (size_t)bh * a.n_cap * NCG * 2 : nullptr;
     const uint32_t k_lane = (uint32_t)n * (16 * BITS) + (uint32_t)kb * (4 * BITS);   // within a 16-token key tile
@@ -1015,6 +1032,22 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     (void)lo_mask; (void)slot_mask; (void)sel_even; (void)sel_odd;
     const float c_logit = a.sm_scale * kLog2e * kCodeUnit;
     const float c_bias = a.sm_scale * kLog2e;
+    // per-token keys: the channel group of the lane's column, whether the lane's 32 channels lie in
+    // it, the byte selector that picks that group's half out of a pair of strip words, and (set once
+    // q is staged) the sum of q over the group, in code units
+    // (per pass where the product takes two)
+    bool kt_mine[KP];
+    uint32_t kt_sel[KP];
+    float kt_qs[KP];
+#pragma unroll
+    for (int ps = 0; ps < KP; ++ps) {
+        const int c = (NCG == 4) ? ((SLOTS == 2) ? 2 * slot + part : 2 * ps + part) : (NCG == 2 ? part : 0);
+        kt_mine[ps] = (NCG > 1 || part == 0) && (kb / (4 / NCG)) == c;
+        const uint32_t bsel = (NCG == 4) ? 4u * (c >> 1) + 2u * (c & 1) : 2u * (uint32_t)c;
+        kt_sel[ps] = 0x0C0C0000u | ((bsel + 1u) << 8) | bsel;
+        kt_qs[ps] = 0.f;
+    }
+    (void)kt_mine; (void)kt_sel;
 
     f4v O[8];
 #pragma unroll
@@ -1023,12 +1056,12 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
 #pragma unroll
     for (int c = 0; c < NCG; ++c) oz[c] = 0.f;
     float m_run = kNegBig, l_run = 0.f;
-    Frag bq[4];                       // query-times-scale operand of the current key group
+    Frag bq[4];                       // query-times-scale operand of the current key group (KT: masked q, set once)
 
     // ---- the two register sets (codes as MFMA operands; one dword per lane of every scale row) ----
     KWords<BITS> ak0, ak1, bk0, bk1;
     VWords<BITS> av, bv;
-    uint32_t a_ks = 0, a_kz[NGRP], a_vs = 0, a_vz = 0, b_ks = 0, b_vs = 0, b_vz = 0;
+    uint32_t a_ks = 0, a_kz[NGRP], a_vs = 0, a_vz = 0, b_ks = 0, b_kz = 0, b_vs = 0, b_vz = 0;
 #pragma unroll
     for (int i = 0; i < NGRP; ++i) a_kz[i] = 0;
 
@@ -1060,10 +1093,15 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         const int tb = chunk * kChunk;
         load_k(tb + 0, ak0); load_k(tb + 16, ak1);
         if constexpr (QUANT) {
-            const int u = tb / G;
-            a_ks = dword_at(ks, (uint32_t)u * 256 + row_off);
+            if constexpr (KT) {
+                a_ks = dword_at(ks, (uint32_t)tb * (2 * NCG) + vrow_off);
+                a_kz[0] = dword_at(kz, (uint32_t)tb * (2 * NCG) + vrow_off);
+            } else {
+                const int u = tb / G;
+                a_ks = dword_at(ks, (uint32_t)u * 256 + row_off);
 #pragma unroll
-            for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_off);
+                for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_off);
+            }
             a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off);
             a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off);
         }
@@ -1073,7 +1111,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         const int tb = chunk * kChunk + (two ? 32 : 0);
         load_k(tb + 0, bk0); load_k(tb + 16, bk1);
         if constexpr (QUANT) {
-            if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_off);
+            if constexpr (KT) {
+                b_ks = dword_at(ks, (uint32_t)tb * (2 * NCG) + vrow_off);
+                b_kz = dword_at(kz, (uint32_t)tb * (2 * NCG) + vrow_off);
+            } else if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_off);
             b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off);
             b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off);
         }
@@ -1102,13 +1143,16 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     };
 
     // one 32-token block: QK product, online softmax update, PV product
-    auto compute = [&](const KWords<BITS>& k0, const KWords<BITS>& k1, uint32_t r_ks, bool new_group, float bias,
+    auto compute = [&](const KWords<BITS>& k0, const KWords<BITS>& k1, uint32_t r_ks, uint32_t r_kz, bool new_group, float bias,
                        const VWords<BITS>& vv, int vblk, uint32_t r_vs, uint32_t r_vz) {
         uint32_t vsr[QUANT ? NT * 2 * NCG : 1], vzr[QUANT ? NT * 2 * NCG : 1];
         if constexpr (QUANT) {
-            if (new_group) lds_put(OFF_KS, r_ks);
+            if constexpr (KT) { lds_put_v(OFF_KS, r_ks); lds_put_v(OFF_KZ, r_kz); }
+            else if (new_group) lds_put(OFF_KS, r_ks);
             lds_put_v(OFF_VS, r_vs); lds_put_v(OFF_VZ, r_vz);
-            if (new_group) {
+            if constexpr (KT) {
+                // (the masked query operand is re-read from LDS inside the pass loop below)
+            } else if (new_group) {
                 uint32_t sw[16], qw[16];
                 lds_get16(OFF_KS + 64 * kb, sw);
 #pragma unroll
@@ -1136,13 +1180,78 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             }
         }
         f4v acc0 = (f4v){0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+        if constexpr (!KT) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq[s].v, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq[s].v, acc1, 0, 0, 0);
+            for (int s = 0; s < 4; ++s) {
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq[s].v, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq[s].v, acc1, 0, 0, 0);
+            }
         }
         const float bias_l2 = bias * c_bias;
         float lg[NT][4];
+        if constexpr (KT) {
+            // The lane's column holds one channel group (per pass): the product with the masked query,
+            // re-read from LDS rather than kept (16 registers), then scale by the token's scale of that
+            // group and add its zero term.  One tile's strips at a time (16 registers), and only the
+            // slot's own tile where the other one is not needed.
+            constexpr bool kBothTiles = SLOTS == 1 || NCG == 4;
+            float tt[2][4];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) tt[t][i] = 0.f;
+#pragma unroll
+            for (int ps = 0; ps < KP; ++ps) {
+                acc0 = (f4v){0.f, 0.f, 0.f, 0.f}; acc1 = acc0;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const uint4 v = sqpos[(ps * 4 + s) * 64 + lane];
+                    Frag bqs;
+                    bqs.u[0] = v.x; bqs.u[1] = v.y; bqs.u[2] = v.z; bqs.u[3] = v.w;
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bqs.v, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bqs.v, acc1, 0, 0, 0);
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    if (!kBothTiles && t != 0) continue;
+                    const int tile = kBothTiles ? t : slot;
+                    uint32_t ksr[2 * NCG], kzr[2 * NCG];
+                    lds_get_strip(OFF_KS + (16 * tile + 4 * kb) * (2 * NCG), ksr);
+                    lds_get_strip(OFF_KZ + (16 * tile + 4 * kb) * (2 * NCG), kzr);
+                    auto at = [&](const uint32_t* w, int i) -> float {   // half (token i, the column's group) of the strip
+                        if constexpr (NCG == 4) {
+                            return (float)as_h2(__builtin_amdgcn_perm(w[2 * i + 1], w[2 * i], kt_sel[ps]))[0];
+                        } else if constexpr (NCG == 2) {
+                            return (float)as_h2(__builtin_amdgcn_perm(w[i], w[i], kt_sel[ps]))[0];
+                        } else {
+                            return (float)as_h2(w[i >> 1])[i & 1];
+                        }
+                    };
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float acc = kBothTiles ? (t ? acc1[i] : acc0[i]) : (slot ? acc1[i] : acc0[i]);
+                        tt[t][i] += __builtin_fmaf(acc, at(ksr, i), at(kzr, i) * kt_qs[ps]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (SLOTS == 2 && NCG == 4) {          // four columns per head: both tiles are summed, then the slot's is kept
+                    float t0 = tt[0][i], t1 = tt[1][i];
+                    t0 += pair_other(t0); t1 += pair_other(t1);
+                    t0 += row_ror8(t0); t1 += row_ror8(t1);
+                    lg[0][i] = (slot ? t1 : t0) * c_logit;
+                } else if constexpr (SLOTS == 2) {
+                    float s = tt[0][i];
+                    s += pair_other(s);
+                    lg[0][i] = s * c_logit;
+                } else {
+                    float t0 = tt[0][i], t1 = tt[1][i];
+                    t0 += pair_other(t0); t1 += pair_other(t1);
+                    lg[0][i] = t0 * c_logit; lg[NT - 1][i] = t1 * c_logit;
+                }
+            }
+        } else
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if constexpr (SLOTS == 2) {
@@ -1283,7 +1392,12 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
 #pragma unroll
             for (int r = 0; r < 4; ++r) t[r] = qn[4 * s + r] * (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
             if constexpr (QUANT) {
-                sqpos[s * 64 + lane] = make_uint4(as_u32(t[0]), as_u32(t[1]), as_u32(t[2]), as_u32(t[3]));
+                // (per-token keys: the operand is q masked to the channel group of the lane's column, per pass)
+#pragma unroll
+                for (int ps = 0; ps < KP; ++ps) {
+                    const bool keep = !KT || kt_mine[ps];
+                    sqpos[(ps * 4 + s) * 64 + lane] = keep ? make_uint4(as_u32(t[0]), as_u32(t[1]), as_u32(t[2]), as_u32(t[3])) : make_uint4(0u, 0u, 0u, 0u);
+                }
             } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) qpos[4 * s + r] = t[r];
@@ -1302,6 +1416,18 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int r = 0; r < 4; ++r) bq[s].h[r] = (QUANT || part) ? (h2v){0, 0} : qpos[QUANT ? 0 : 4 * s + r];   // 16-bit cache: plain q in the hi rows
+    if constexpr (KT) {
+        float own = 0.f;                                  // sum of q over the lane's 32 channels
+        const uint16_t* qrow = sq + h * kHeadDim + 32 * kb;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint4 w = *reinterpret_cast<const uint4*>(qrow + 8 * s);
+            const h2v a0 = as_h2(w.x), a1 = as_h2(w.y), a2 = as_h2(w.z), a3 = as_h2(w.w);
+            own += ((float)a0[0] + (float)a0[1]) + ((float)a1[0] + (float)a1[1]) + ((float)a2[0] + (float)a2[1]) + ((float)a3[0] + (float)a3[1]);
+        }
+#pragma unroll
+        for (int ps = 0; ps < KP; ++ps) kt_qs[ps] = quad_rows_add(kt_mine[ps] ? own : 0.f) * (1.0f / kCodeUnit);
+    }
     // the tail rows go first, while the first blocks are on their way (their state waits in LDS)
     const int tail_t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
     const int tail_t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
@@ -1311,7 +1437,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         const int next = claim();                            // used half an iteration later
         // key zero-point terms of this chunk's groups: token rows = z rows, unscaled q as the other operand
         float bias0 = 0.f, bias1 = 0.f;
-        if constexpr (QUANT) {
+        if constexpr (QUANT && !KT) {
 #pragma unroll
             for (int i = 0; i < NGRP; ++i) lds_put(OFF_KZ + 256 * i, a_kz[i]);
             uint32_t zw[16], qw[16];
@@ -1337,7 +1463,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             bias0 = quad_rows_add(zc[0]);                     // rows >= NGRP are zero, so the sum is a broadcast
             if constexpr (NGRP == 2) bias1 = quad_rows_add(zc[1]);
         }
-        compute(ak0, ak1, a_ks, true, bias0, av, 0, a_vs, a_vz);
+        compute(ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, a_vs, a_vz);
         if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
         // both blocks of the wave's next chunk are requested while this chunk's second block is computed
         const bool has_next = next < c_end;
@@ -1345,7 +1471,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
         const bool two_nx = n_kept - nx * kChunk >= kChunk;
         if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; }   // (wave-uniform; the loop ends after this pass)
         load_A(nx);
-        if (two) compute(bk0, bk1, b_ks, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
+        if (two) compute(bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
         if (kEarlyB) load_B(nx, two_nx);
         chunk = next; two = two_nx;
     }
@@ -1462,13 +1588,16 @@ hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t str
             else
                 hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 0, true>), grid, dim3(kThreads), 0, stream, a);
         }
-    } else if (cfg.key_axis == KVQP_KEY_PER_TOKEN && BITS != 16)
-        hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 1, false>), grid, dim3(kThreads), 0, stream, a);
-    else
-    {
+    } else if (cfg.key_axis == KVQP_KEY_PER_TOKEN && BITS != 16) {
+        if constexpr (BITS != 16) {
+            constexpr int strip = PipeGeom<BITS, NCG>::STRIP;
+            const unsigned lds_bytes = pipe_lds_bytes(a.n_waves, strip, GQ) + 16;
+            hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG, 1>), grid, dim3(64 * a.n_waves), lds_bytes, stream, a);
+        }
+    } else {
         constexpr int strip = PipeGeom<BITS, NCG>::STRIP;
         const unsigned lds_bytes = pipe_lds_bytes(a.n_waves, strip, GQ) + 16;
-        hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG>), grid, dim3(64 * a.n_waves), lds_bytes, stream, a);
+        hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG, 0>), grid, dim3(64 * a.n_waves), lds_bytes, stream, a);
     }
     return hipGetLastError();
 }
@@ -1493,9 +1622,9 @@ hipError_t launch_gq(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t strea
 
 }  // namespace
 
-// The pipelined kernel serves per-channel keys and the 16-bit cache; per-token keys at 2-8 bits
-// run on the plain split-K kernel.
-static bool uses_pipe(const kvqp_cfg& cfg) { return !(cfg.key_axis == KVQP_KEY_PER_TOKEN && cfg.bits != 16) && !outliers_on(cfg); }
+// The pipelined kernel serves everything but caches with outlier slots, which run on the plain
+// split-K kernel.
+static bool uses_pipe(const kvqp_cfg& cfg) { return !outliers_on(cfg); }
 
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
     DecodePlan p;

@@ -31,6 +31,15 @@ CASES = [
     (4, 64, 1, 8, 192, 32, 1, 1),
     (2, 128, 1, 4, 256, 32, 1, 1),
     (8, 32, 1, 4, 160, 32, 1, 1),
+    # per-token keys on the pipelined kernel: every (groups per row, heads per KV head) pairing it serves
+    (4, 64, 1, 4, 352, 32, 1, 2),
+    (2, 32, 1, 2, 608, 16, 2, 1),
+    (8, 64, 1, 1, 224, 8, 1, 3),
+    (2, 64, 1, 8, 448, 32, 1, 1),
+    (8, 128, 1, 8, 160, 16, 1, 2),
+    (4, 128, 1, 1, 96, 4, 1, 2),
+    (2, 32, 1, 4, 1056, 32, 1, 2),
+    (4, 32, 1, 8, 288, 32, 1, 1),        # four groups and eight heads: the plain kernel
     (4, 32, 0, 4, 0, 32, 1, 2),          # tail only
 ]
 
