@@ -314,9 +314,37 @@ def main():
         }
         del oc_cache
 
-        return per_layer, append_us, layer_wise, outlier_leg
+        # ---- per-token key groups (the FlexGen axis of the paper's ablation and of its head-level methods) ----
+        cfg_t = kvqp.Cfg(**{**s4["cfg"].__dict__, "key_axis": kvqp.KEY_PER_TOKEN})
+        tc = kvqp.alloc_cache(cfg_t, device=dev)
+        ws_tc, ws_td = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_t))
+        for rep in range(reps + 1):
+            if rep == 1:
+                torch.cuda.synchronize()
+                t0_, t1_ = ev(), ev()
+                t0_.record()
+            kvqp.compress(cfg_t, q_obs, k, v, tc, workspace=ws_tc)
+        t1_.record()
+        for t in range(DECODE_STEPS):
+            kvqp.decode_attn(cfg_t, queries[t], tc, out, ws_td)
+        torch.cuda.synchronize()
+        t2_, t3_ = ev(), ev()
+        t2_.record()
+        for t in range(DECODE_STEPS):
+            kvqp.decode_attn(cfg_t, queries[t], tc, out, ws_td)
+        t3_.record()
+        torch.cuda.synchronize()
+        t_bytes = decode_bytes(LAYERS, s4["n_kept"], 4, G, W)      # same count: a scale and a zero per 32 elements either way
+        t_us = t2_.elapsed_time(t3_) * 1e3 / DECODE_STEPS
+        token_keys = {
+            "bits": 4, "tokens": s4["n_kept"], "compress_ms_32_layers": round(t0_.elapsed_time(t1_) / reps, 3),
+            "decode_us_per_step": round(t_us, 2), "decode_gbs": round(t_bytes / (t_us * 1e-6) / 1e9, 1),
+            "bytes_per_step": t_bytes,
+        }
+        del tc
+        return per_layer, append_us, layer_wise, outlier_leg, token_keys
 
-    per_layer, append_us, layer_wise, outlier_leg = (None, None, None, None) if args.sweep_only else extra_legs()
+    per_layer, append_us, layer_wise, outlier_leg, token_keys = (None,) * 5 if args.sweep_only else extra_legs()
 
     # ---- roofline of the dominant kernel: the decode launch that takes most of the step ----
     dom = max(range(len(settings)), key=lambda i: settings[i]["t_decode_ms"])
@@ -369,7 +397,7 @@ def main():
         "compress_note": "prompt tokens/s through all 32 layers at the (8192 tok, 4 bit) setting",
         "append_tail_us": None if append_us is None else round(append_us, 2),
         "append_note": f"kvqp_append_tail of {G} tokens per cache, 32 layers as one batch, 4-bit setting",
-        "layer_wise_counts": layer_wise, "outlier_filtering": outlier_leg,
+        "layer_wise_counts": layer_wise, "outlier_filtering": outlier_leg, "per_token_keys": token_keys,
         "sweep": sweep, "per_layer_calls": per_layer,
         "roofline": roofline, "cpu_baseline": cpu,
     }
