@@ -634,6 +634,18 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
             const int tb = tok0 + 32 * blk;
             const KWords<BITS> k0 = load_k_tile<BITS>(kc, tb + n, kb);
             const KWords<BITS> k1 = load_k_tile<BITS>(kc, tb + 16 + n, kb);
+            // key outlier slots of the lane's tokens, requested together with the tiles: this lane takes
+            // slots 2 part, 2 part + 1 of each token, its hi / lo pair the other two
+            uint2 kslot[OUT ? NT : 1][4];
+            if constexpr (OUT) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int tile_h = (SLOTS == 2) ? slot : t;
+                    const uint2* sp = reinterpret_cast<const uint2*>(ko + (size_t)(tb + 16 * tile_h + 4 * kb) * 4) + part;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) kslot[t][i] = sp[2 * i];
+                }
+            }
             f4v acc0 = (f4v){0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
             float bias = 0.f;
             if constexpr (!QUANT) {
@@ -730,15 +742,12 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                 }
             }
             if constexpr (OUT) {
-                // key outliers of the lane's tokens: this lane takes slots 2 part, 2 part + 1, its pair the other two
                 const uint16_t* qrow = s_q + (size_t)h * kHeadDim;
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    const int tile_h = (SLOTS == 2) ? slot : t;
-                    const uint2* sp = reinterpret_cast<const uint2*>(ko + (size_t)(tb + 16 * tile_h + 4 * kb) * 4) + part;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const uint2 w = sp[2 * i];
+                        const uint2 w = kslot[t][i];
                         float c = slot_delta(w.x) * __half2float(__ushort_as_half(qrow[w.x & 127u]));
                         c = __builtin_fmaf(slot_delta(w.y), __half2float(__ushort_as_half(qrow[w.y & 127u])), c);
                         c += pair_other(c);
@@ -794,6 +803,19 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
             vw[0] = load_v_superblock<BITS>(vc, 2 * chunk, lane);
             if (nblk == 2) vw[1] = load_v_superblock<BITS>(vc, 2 * chunk + 1, lane);
         }
+        uint2 vslot[OUT ? 2 : 1][OUT ? NT : 1][4];   // value outlier slots of both blocks, requested with the value words
+        if constexpr (OUT) {
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int tile_h = (SLOTS == 2) ? slot : t;
+                    const int tokb = tok0 + 32 * (blk < nblk ? blk : 0) + 16 * tile_h + 4 * kb;
+                    const uint2* sp = reinterpret_cast<const uint2*>(vo + (size_t)tokb * 4) + part;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) vslot[blk][t][i] = sp[2 * i];
+                }
+        }
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
             if (blk >= nblk) continue;
@@ -813,11 +835,9 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
                 if (live_row) {
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
-                        const int tile_h = (SLOTS == 2) ? slot : t;
-                        const uint2* sp = reinterpret_cast<const uint2*>(vo + (size_t)(tb + 16 * tile_h + 4 * kb) * 4) + part;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            const uint2 w = sp[2 * i];
+                            const uint2 w = vslot[blk][t][i];
                             const float pw = p[t][i] * (float)(1 << v_pos_log2<BITS>(blk, i));
                             if (w.x) atomicAdd(oc + row8 * kHeadDim + (w.x & 127u), pw * slot_delta(w.x));
                             if (w.y) atomicAdd(oc + row8 * kHeadDim + (w.y & 127u), pw * slot_delta(w.y));
