@@ -310,7 +310,7 @@ def main():
             "key_outliers_per_row": round(n_slots / (LAYERS * HKV * s4["n_kept"]), 2),
             "compress_ms_32_layers": round(o0.elapsed_time(o1) / reps, 3), "decode_us_per_step": round(o_us, 2),
             "decode_gbs": round(o_bytes / (o_us * 1e-6) / 1e9, 1), "bytes_per_step": o_bytes,
-            "note": "decode runs on the plain split-K kernel when a cache carries outlier slots",
+            "note": "the decode kernel's outlier variant runs two waves per SIMD (eight per workgroup) instead of three",
         }
         del oc_cache
 

@@ -49,7 +49,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f; // finite stand-in for -inf in running maxima
 // Waves per SIMD the pipelined kernel is compiled for: the 2- and 4-bit variants fit 168 registers
 // (three waves) up to four query heads per KV head; wider code words or eight heads need more (two waves).
-constexpr int pipe_waves(int bits, int gq) { return (bits <= 4 && gq <= 4) ? 3 : 2; }
+constexpr int pipe_waves(int bits, int gq, bool out = false) { return (bits <= 4 && gq <= 4 && !out) ? 3 : 2; }
 constexpr float kLazyLog2 = 8.0f;   // slack of the lazily updated softmax reference
 constexpr int kPartStride = kHeadDim + 2;  // floats per (partial, head): m, l, acc[128]
 
@@ -93,23 +93,6 @@ __device__ __forceinline__ uint32_t pack_rtz(float lo, float hi) {
 // ---- key codes: BITS words per lane per 16-token tile (the lane's 32 channels) ----
 template <int BITS> struct KWords { uint32_t w[BITS]; };
 
-template <int BITS>
-__device__ __forceinline__ KWords<BITS> load_k_tile(const uint32_t* __restrict__ kc_head, int tok, int kb) {
-    KWords<BITS> r;
-    const uint32_t* p = kc_head + (size_t)tok * (4 * BITS) + kb * BITS;
-    if constexpr (BITS == 2) {
-        const uint2 v = *reinterpret_cast<const uint2*>(p);
-        r.w[0] = v.x; r.w[1] = v.y;
-    } else {
-#pragma unroll
-        for (int i = 0; i < BITS / 4; ++i) {
-            const uint4 v = reinterpret_cast<const uint4*>(p)[i];
-            r.w[4 * i] = v.x; r.w[4 * i + 1] = v.y; r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
-        }
-    }
-    return r;
-}
-
 // MFMA operand for contraction step s (8 of the lane's 32 channels, natural order).
 // Fields are left in place; their power-of-two position factor is KPosLog2.
 template <int BITS>
@@ -152,17 +135,6 @@ template <int BITS> struct VGeom {
 };
 template <int BITS> struct VWords { uint32_t w[VGeom<BITS>::kWordsPerLoad]; };
 
-template <int BITS>
-__device__ __forceinline__ VWords<BITS> load_v_superblock(const uint32_t* __restrict__ vc_head, int sb, int lane) {
-    VWords<BITS> r;
-    const uint32_t* p = vc_head + (size_t)sb * v_superblock_words(BITS);
-#pragma unroll
-    for (int q = 0; q < VGeom<BITS>::kWordsPerLoad / 4; ++q) {
-        const uint4 v = reinterpret_cast<const uint4*>(p)[q * 64 + lane];
-        r.w[4 * q] = v.x; r.w[4 * q + 1] = v.y; r.w[4 * q + 2] = v.z; r.w[4 * q + 3] = v.w;
-    }
-    return r;
-}
 // MFMA operand of (block-in-superblock, channel tile): registers i = 0..3 hold
 // the token pairs (16H + 4kb + i, H = 0/1) in the (low, high) halves.
 template <int BITS>
@@ -319,66 +291,6 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
     }
 }
 
-// Full-precision tail rows: a short plain loop, one wave per row at a time.
-template <int GQ>
-__device__ void tail_partial(const DecodeArgs& a, int bh, float* smem) {
-    const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint16_t* tk = a.tail_k + (size_t)bh * a.tail_cap * kHeadDim;
-    const uint16_t* tv = a.tail_v + (size_t)bh * a.tail_cap * kHeadDim;
-    float qa[GQ], qb[GQ], m[GQ], l[GQ], oa[GQ], ob[GQ];
-#pragma unroll
-    for (int h = 0; h < GQ; ++h) {
-        const uint32_t u = *reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + h) * kHeadDim + 2 * lane);
-        const h2v qq = as_h2(u);
-        qa[h] = (float)qq[0] * (a.sm_scale * kLog2e); qb[h] = (float)qq[1] * (a.sm_scale * kLog2e);
-        m[h] = kNegBig; l[h] = 0.f; oa[h] = 0.f; ob[h] = 0.f;
-    }
-    for (int t = wave; t < a.tail_len; t += kWaves) {
-        const h2v kk = as_h2(*reinterpret_cast<const uint32_t*>(tk + (size_t)t * kHeadDim + 2 * lane));
-        const h2v vv = as_h2(*reinterpret_cast<const uint32_t*>(tv + (size_t)t * kHeadDim + 2 * lane));
-#pragma unroll
-        for (int h = 0; h < GQ; ++h) {
-            float s = __builtin_fmaf(qa[h], (float)kk[0], qb[h] * (float)kk[1]);
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-            const float mn = fmaxf(m[h], s);
-            const float alpha = exp2f(m[h] - mn), p = exp2f(s - mn);
-            l[h] = __builtin_fmaf(l[h], alpha, p);
-            oa[h] = __builtin_fmaf(oa[h], alpha, p * (float)vv[0]);
-            ob[h] = __builtin_fmaf(ob[h], alpha, p * (float)vv[1]);
-            m[h] = mn;
-        }
-    }
-    // merge the four waves through LDS: layout [wave][h][130]
-    float* sm = smem;
-#pragma unroll
-    for (int h = 0; h < GQ; ++h) {
-        float* row = sm + (wave * GQ + h) * kPartStride;
-        row[2 + 2 * lane] = oa[h]; row[3 + 2 * lane] = ob[h];
-        if (lane == 0) { row[0] = m[h]; row[1] = l[h]; }
-    }
-    __syncthreads();
-    float* dst = a.part + ((size_t)bh * a.n_partials + a.n_splits) * GQ * kPartStride;
-    for (int item = threadIdx.x; item < GQ * kHeadDim; item += kThreads) {
-        const int h = item / kHeadDim, d = item % kHeadDim;
-        float M = kNegBig;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm[(w * GQ + h) * kPartStride]);
-        float acc = 0.f, L = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float* row = sm + (w * GQ + h) * kPartStride;
-            const float wgt = exp2f(row[0] - M);
-            acc = __builtin_fmaf(wgt, row[2 + d], acc);
-            L = __builtin_fmaf(wgt, row[1], L);
-        }
-        st_dev(dst + h * kPartStride + 2 + d, acc);
-        if (d == 0) { st_dev(dst + h * kPartStride, M); st_dev(dst + h * kPartStride + 1, L); }
-    }
-    merge_if_last<GQ>(a, bh);
-}
-
 // Value of lane ^ 16 / lane ^ 32.
 __device__ __forceinline__ float xor16_get(float v) {
     const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
@@ -491,445 +403,13 @@ __device__ void tail_rows(const DecodeArgs& a, int bh, int t0, int t1, float* sT
     }
 }
 
-// The per-token scales (or zeros) of four consecutive tokens, NCG halves each: 2 NCG words in one or
-// two wide loads; element (token i, group c) is half i * NCG + c.
-template <int NCG>
-__device__ __forceinline__ void load_tok4(const uint16_t* __restrict__ base, int tok, uint32_t (&w)[2 * NCG]) {
-    const uint16_t* p = base + (size_t)tok * NCG;
-    if constexpr (NCG == 4) {
-        const uint4 x = reinterpret_cast<const uint4*>(p)[0], y = reinterpret_cast<const uint4*>(p)[1];
-        w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w; w[4] = y.x; w[5] = y.y; w[6] = y.z; w[7] = y.w;
-    } else if constexpr (NCG == 2) {
-        const uint4 x = *reinterpret_cast<const uint4*>(p);
-        w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
-    } else {
-        const uint2 x = *reinterpret_cast<const uint2*>(p);
-        w[0] = x.x; w[1] = x.y;
-    }
-}
-template <int NCG>
-__device__ __forceinline__ float tok4_at(const uint32_t (&w)[2 * NCG], int i, int c) {
-    const int e = i * NCG + c;
-    return __half2float(__ushort_as_half((uint16_t)(w[e >> 1] >> (16 * (e & 1)))));
-}
-
 // the binary32 difference an outlier slot word carries (0 for an unused slot)
 __device__ __forceinline__ float slot_delta(uint32_t w) { return __uint_as_float(w & 0xFFFFFF00u); }
 
-// BITS: code width; GQ: query heads per kv head (1,2,4 -> two token slots per
-// MFMA tile; 8 -> one); NCG = D / G value channel groups; AXIS: key grouping.
-// OUT: the cache carries outlier slots.  An outlier has code 0, so the products above see its
-// group's zero; what is missing, q[ch] * delta in the logit of its token and p * delta in channel
-// ch of the output, is added outside the matrix products: the logit term by the lanes that hold
-// the token's logit (two slots each for the hi / lo lane pair, looked up in a copy of q in LDS),
-// the output term into a per-wave [8 rows][128] binary32 array in LDS with LDS float atomics,
-// rescaled whenever the running maximum of its row moves and folded in at the merge.
-template <int BITS, int GQ, int NCG, int AXIS, bool OUT>
-__global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs a) {
-    constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
-    constexpr int GQP = (GQ <= 4) ? 4 : 8;        // heads per slot incl. padding
-    constexpr int NT = (SLOTS == 2) ? 1 : 2;      // QK tiles a lane keeps per 32-token block
-    constexpr bool QUANT = BITS != 16;
-    constexpr float kCodeUnit = QUANT ? 16777216.0f : 1.0f;  // 2^24: undo the subnormal reading of codes
-    constexpr int G = kHeadDim / NCG;
-
-    __shared__ __align__(16) float smem[kWaves * 16 * kHeadDim + kWaves * 16 * (2 + 4)];
-    __shared__ __align__(16) uint16_t s_q[OUT ? 8 * kHeadDim : 8];            // the group's query rows (zero rows past GQ)
-    __shared__ __align__(16) float s_oc[OUT ? kWaves * 8 * kHeadDim : 4];     // per wave: outlier terms of the outputs
-
-    const int bh = blockIdx.y;
-    if ((int)blockIdx.x == a.n_splits) { tail_partial<GQ>(a, bh, smem); return; }
-
-    const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n = lane & 15, kb = lane >> 4;
-    const int part = n & 1;
-    const int slot = (SLOTS == 2) ? (n >> 3) : 0;
-    const int h = (SLOTS == 2) ? ((n & 7) >> 1) : (n >> 1);
-    const bool live_row = h < GQ;
-
-    const uint32_t* kc = a.k_codes + (size_t)bh * ((size_t)a.n_cap * kHeadDim * BITS / 32);
-    const uint32_t* vc = a.v_codes + (size_t)bh * v_superblock_words(BITS) * ((a.n_cap + v_superblock(BITS) - 1) / v_superblock(BITS));
-    const int n_kept = head_tokens(a, bh);
-    const int n_kgroups = (AXIS == KVQP_KEY_PER_CHANNEL) ? n_kept / G : n_kept;
-    const int cap_kgroups = (AXIS == KVQP_KEY_PER_CHANNEL) ? a.n_cap / G : a.n_cap;   // head stride of the key scales
-    const uint16_t* ks = QUANT ? a.k_scale + (size_t)bh * cap_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
-    const uint16_t* kz = QUANT ? a.k_zero + (size_t)bh * cap_kgroups * (AXIS == 0 ? kHeadDim : NCG) : nullptr;
-    const uint16_t* vs = QUANT ? a.v_scale + (size_t)bh * a.n_cap * NCG : nullptr;
-    const uint16_t* vz = QUANT ? a.v_zero + (size_t)bh * a.n_cap * NCG : nullptr;
-
-    // The lane's 32 query channels [32kb, 32kb+32) of its head, as natural pairs.
-    h2v qn[16];
-    {
-        const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + 32 * kb;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint4 v = reinterpret_cast<const uint4*>(qp)[i];
-            qn[4 * i] = as_h2(live_row ? v.x : 0u); qn[4 * i + 1] = as_h2(live_row ? v.y : 0u);
-            qn[4 * i + 2] = as_h2(live_row ? v.z : 0u); qn[4 * i + 3] = as_h2(live_row ? v.w : 0u);
-        }
-    }
-    // Query pre-divided by the position factor of the code it will meet.
-    h2v qpos[16];
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const _Float16 f = (_Float16)(1.0f / (float)(1 << k_pos_log2<BITS>(s, r)));
-            qpos[4 * s + r] = qn[4 * s + r] * f;
-        }
-
-    const int row8 = (SLOTS == 2) ? slot * 4 + h : h;                       // the lane's row of the wave's outlier terms
-    float* oc = s_oc + (OUT ? wave * 8 * kHeadDim : 0);
-    const uint32_t* ko = OUT ? a.k_out + (size_t)bh * a.n_cap * 4 : nullptr;
-    const uint32_t* vo = OUT ? a.v_out + (size_t)bh * a.n_cap * 4 : nullptr;
-    if constexpr (OUT) {
-        for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += kThreads) {
-            const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
-            reinterpret_cast<uint32_t*>(s_q)[item] =
-                hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
-        }
-        for (int item = threadIdx.x; item < kWaves * 8 * kHeadDim; item += kThreads) s_oc[item] = 0.f;
-        __syncthreads();
-    }
-
-    // Per-token keys: the query operand is constant; per-channel-group sums of q.
-    float qsum_cg = 0.f;  // sum of the lane's own 32 channels (all inside one channel group)
-    if constexpr (QUANT && AXIS == KVQP_KEY_PER_TOKEN) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) qsum_cg += (float)qn[i][0] + (float)qn[i][1];
-    }
-
-    const float c_logit = a.sm_scale * kLog2e * kCodeUnit;  // MFMA sum -> log2-domain logit
-    const float c_bias = a.sm_scale * kLog2e;
-
-    f4v O[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) O[t] = (f4v){0.f, 0.f, 0.f, 0.f};
-    float oz[NCG];
-#pragma unroll
-    for (int c = 0; c < NCG; ++c) oz[c] = 0.f;
-    float m_run = kNegBig, l_run = 0.f;
-
-    const int n_chunks = (n_kept + kChunk - 1) / kChunk;
-    const int cps = head_chunks_per_split(a, n_chunks);
-    const int c_begin = blockIdx.x * cps;
-    const int c_end = min(n_chunks, c_begin + cps);
-
-    for (int chunk = c_begin + wave; chunk < c_end; chunk += kWaves) {
-        const int tok0 = chunk * kChunk;
-        const int nblk = (n_kept - tok0 >= kChunk) ? 2 : 1;  // n_kept is a multiple of 32
-
-        // ---------------- logits of the lane's tokens ----------------
-        float logit[2][NT][4];
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            if (blk >= nblk) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) logit[blk][t][i] = kNegBig;
-                continue;
-            }
-            const int tb = tok0 + 32 * blk;
-            const KWords<BITS> k0 = load_k_tile<BITS>(kc, tb + n, kb);
-            const KWords<BITS> k1 = load_k_tile<BITS>(kc, tb + 16 + n, kb);
-            // key outlier slots of the lane's tokens, requested together with the tiles: this lane takes
-            // slots 2 part, 2 part + 1 of each token, its hi / lo pair the other two
-            uint2 kslot[OUT ? NT : 1][4];
-            if constexpr (OUT) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const int tile_h = (SLOTS == 2) ? slot : t;
-                    const uint2* sp = reinterpret_cast<const uint2*>(ko + (size_t)(tb + 16 * tile_h + 4 * kb) * 4) + part;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) kslot[t][i] = sp[2 * i];
-                }
-            }
-            f4v acc0 = (f4v){0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
-            float bias = 0.f;
-            if constexpr (!QUANT) {
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    Frag bq;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) bq.h[r] = part ? (h2v){0, 0} : qn[4 * s + r];
-                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq.v, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq.v, acc1, 0, 0, 0);
-                }
-            } else if constexpr (AXIS == KVQP_KEY_PER_CHANNEL) {
-                const int u = tb / G;
-                const uint4* sp = reinterpret_cast<const uint4*>(ks + (size_t)u * kHeadDim + 32 * kb);
-                const uint4* zp = reinterpret_cast<const uint4*>(kz + (size_t)u * kHeadDim + 32 * kb);
-                uint32_t sw[16], zw[16];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint4 sv = sp[i], zv = zp[i];
-                    sw[4 * i] = sv.x; sw[4 * i + 1] = sv.y; sw[4 * i + 2] = sv.z; sw[4 * i + 3] = sv.w;
-                    zw[4 * i] = zv.x; zw[4 * i + 1] = zv.y; zw[4 * i + 2] = zv.z; zw[4 * i + 3] = zv.w;
-                }
-#pragma unroll
-                for (int i = 0; i < 16; ++i) bias = __builtin_amdgcn_fdot2(qn[i], as_h2(zw[i]), bias, false);
-                bias = quad_rows_add(bias);
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    Frag bq;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const h2v sc = as_h2(sw[4 * s + r]);
-                        const h2v hi = qpos[4 * s + r] * sc;
-                        const h2v lo = __builtin_elementwise_fma(qpos[4 * s + r], sc, -hi);
-                        bq.h[r] = part ? lo : hi;
-                    }
-                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq.v, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq.v, acc1, 0, 0, 0);
-                }
-            } else {
-                // per-token keys: masked products, scaled per token afterwards.  A pass serves two channel
-                // groups at once: q needs no hi / lo split here, so the hi rows take group 2 c2 and the lo
-                // rows group 2 c2 + 1; the sum of the row pair below then adds the groups instead.
-                constexpr int LPG = 4 / NCG;  // lane quads (kb values) per channel group
-                constexpr int NP = (NCG + 1) / 2;
-                f4v sum0 = acc0, sum1 = acc0;
-                uint32_t ks0[2 * NCG], kz0[2 * NCG], ks1[2 * NCG], kz1[2 * NCG];   // tokens tb + 4kb + i and 16 further
-                load_tok4<NCG>(ks, tb + 4 * kb, ks0); load_tok4<NCG>(kz, tb + 4 * kb, kz0);
-                load_tok4<NCG>(ks, tb + 16 + 4 * kb, ks1); load_tok4<NCG>(kz, tb + 16 + 4 * kb, kz1);
-#pragma unroll
-                for (int c2 = 0; c2 < NP; ++c2) {
-                    constexpr int kLast = NCG - 1;
-                    const int c_lo = 2 * c2, c_hi = (2 * c2 + 1 < NCG) ? 2 * c2 + 1 : kLast;
-                    const bool has = !part || 2 * c2 + 1 < NCG;            // (one group in all: the lo rows stay empty)
-                    const bool mine = has && (kb / LPG) == (part ? c_hi : c_lo);
-                    f4v p0 = (f4v){0.f, 0.f, 0.f, 0.f}, p1 = p0;
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) {
-                        Frag bq;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) bq.h[r] = mine ? qpos[4 * s + r] : (h2v){0, 0};
-                        p0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq.v, p0, 0, 0, 0);
-                        p1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq.v, p1, 0, 0, 0);
-                    }
-                    // sum over the group's channels of q, broadcast to all lanes of the row (0 where the row has no group)
-                    const float qs_c = quad_rows_add(mine ? qsum_cg : 0.f);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float s0 = part ? tok4_at<NCG>(ks0, i, c_hi) : tok4_at<NCG>(ks0, i, c_lo);
-                        const float z0 = part ? tok4_at<NCG>(kz0, i, c_hi) : tok4_at<NCG>(kz0, i, c_lo);
-                        const float s1 = part ? tok4_at<NCG>(ks1, i, c_hi) : tok4_at<NCG>(ks1, i, c_lo);
-                        const float z1 = part ? tok4_at<NCG>(kz1, i, c_hi) : tok4_at<NCG>(kz1, i, c_lo);
-                        // fold 1/kCodeUnit of the bias in, since the sum is scaled by c_logit later
-                        sum0[i] = __builtin_fmaf(p0[i], s0, sum0[i]) + z0 * qs_c * (1.0f / kCodeUnit);
-                        sum1[i] = __builtin_fmaf(p1[i], s1, sum1[i]) + z1 * qs_c * (1.0f / kCodeUnit);
-                    }
-                }
-                acc0 = sum0; acc1 = sum1;
-            }
-            // keep the slot's tile, add the hi and lo rows, scale into the log2 domain
-            if constexpr (SLOTS == 2) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float s = slot ? acc1[i] : acc0[i];
-                    s += pair_other(s);
-                    logit[blk][0][i] = __builtin_fmaf(s, c_logit, bias * c_bias);
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float s0 = acc0[i], s1 = acc1[i];
-                    s0 += pair_other(s0); s1 += pair_other(s1);
-                    logit[blk][0][i] = __builtin_fmaf(s0, c_logit, bias * c_bias);
-                    logit[blk][1][i] = __builtin_fmaf(s1, c_logit, bias * c_bias);
-                }
-            }
-            if constexpr (OUT) {
-                const uint16_t* qrow = s_q + (size_t)h * kHeadDim;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const uint2 w = kslot[t][i];
-                        float c = slot_delta(w.x) * __half2float(__ushort_as_half(qrow[w.x & 127u]));
-                        c = __builtin_fmaf(slot_delta(w.y), __half2float(__ushort_as_half(qrow[w.y & 127u])), c);
-                        c += pair_other(c);
-                        logit[blk][t][i] = __builtin_fmaf(c, c_bias, logit[blk][t][i]);
-                    }
-                }
-            }
-        }
-
-        // ---------------- online softmax bookkeeping ----------------
-        float mx = kNegBig;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) mx = fmaxf(mx, logit[blk][t][i]);
-        mx = quad_rows_max(mx);
-        const float m_new = fmaxf(m_run, mx);
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
-            const float alpha = exp2f(m_run - m_new);
-            l_run *= alpha;
-#pragma unroll
-            for (int c = 0; c < NCG; ++c) oz[c] *= alpha;
-            float ar[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) ar[i] = __shfl(alpha, 4 * kb + i);  // row 4kb+i lives in lanes with n = 4kb+i
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) O[t][i] *= ar[i];
-            m_run = m_new;
-            if constexpr (OUT) {
-                // the eight lanes of a row (hi / lo pair x four kb) rescale 16 channels each of its outlier terms
-                if (live_row && alpha != 1.0f) {
-                    float* p16 = oc + row8 * kHeadDim + (part * 4 + kb) * 16;
-#pragma unroll
-                    for (int c = 0; c < 16; c += 4) {
-                        float4 v = *reinterpret_cast<float4*>(p16 + c);
-                        v.x *= alpha; v.y *= alpha; v.z *= alpha; v.w *= alpha;
-                        *reinterpret_cast<float4*>(p16 + c) = v;
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // (LDS serves a wave in order; this only pins the compiler)
-            }
-        }
-
-        // ---------------- probabilities, P.V ----------------
-        VWords<BITS> vw[VGeom<BITS>::kLoadsPerChunk];
-        if constexpr (BITS == 2) {
-            vw[0] = load_v_superblock<BITS>(vc, chunk, lane);
-        } else {
-            vw[0] = load_v_superblock<BITS>(vc, 2 * chunk, lane);
-            if (nblk == 2) vw[1] = load_v_superblock<BITS>(vc, 2 * chunk + 1, lane);
-        }
-        uint2 vslot[OUT ? 2 : 1][OUT ? NT : 1][4];   // value outlier slots of both blocks, requested with the value words
-        if constexpr (OUT) {
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const int tile_h = (SLOTS == 2) ? slot : t;
-                    const int tokb = tok0 + 32 * (blk < nblk ? blk : 0) + 16 * tile_h + 4 * kb;
-                    const uint2* sp = reinterpret_cast<const uint2*>(vo + (size_t)tokb * 4) + part;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) vslot[blk][t][i] = sp[2 * i];
-                }
-        }
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            if (blk >= nblk) continue;
-            const int tb = tok0 + 32 * blk;
-            // p[t][i] already divided by the position factor of the value code it meets
-            float p[NT][4];
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int e = v_pos_log2<BITS>(blk, i);
-                    p[t][i] = exp2f(logit[blk][t][i] - (m_run + (float)e));
-                    l_run = __builtin_fmaf(p[t][i], (float)(1 << e), l_run);
-                }
-            if constexpr (OUT) {
-                // value outliers of the lane's tokens: weight x delta into channel ch of the lane's row
-                if (live_row) {
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const uint2 w = vslot[blk][t][i];
-                            const float pw = p[t][i] * (float)(1 << v_pos_log2<BITS>(blk, i));
-                            if (w.x) atomicAdd(oc + row8 * kHeadDim + (w.x & 127u), pw * slot_delta(w.x));
-                            if (w.y) atomicAdd(oc + row8 * kHeadDim + (w.y & 127u), pw * slot_delta(w.y));
-                        }
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            }
-            // scale / zero of the lane's tokens: 4 consecutive tokens x NCG, per tile
-            Frag pa[NCG];
-#pragma unroll
-            for (int c = 0; c < NCG; ++c)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pa[c].u[i] = 0u;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int tile_h = (SLOTS == 2) ? slot : t;          // 0: tokens 4kb+i, 1: tokens 16+4kb+i
-                const int tokb = tb + 16 * tile_h + 4 * kb;
-                uint32_t vsw[2 * NCG], vzw[2 * NCG];
-                if constexpr (QUANT) { load_tok4<NCG>(vs, tokb, vsw); load_tok4<NCG>(vz, tokb, vzw); }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                    for (int c = 0; c < NCG; ++c) {
-                        float ps = p[t][i];
-                        if constexpr (QUANT) {
-                            const float sv = tok4_at<NCG>(vsw, i, c), zv = tok4_at<NCG>(vzw, i, c);
-                            ps *= sv;
-                            oz[c] = __builtin_fmaf(p[t][i] * (float)(1 << v_pos_log2<BITS>(blk, i)), zv, oz[c]);
-                        }
-                        pa[c].u[i] |= split_half(ps, part) << (16 * tile_h);
-                    }
-                }
-            }
-            const VWords<BITS>& vv = vw[(BITS == 2) ? 0 : blk];
-#pragma unroll
-            for (int t8 = 0; t8 < 8; ++t8) {
-                const int c = (t8 * 16) / G;
-                O[t8] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[c].v, v_frag<BITS>(vv, (BITS == 2) ? blk : 0, t8).v, O[t8], 0, 0, 0);
-            }
-        }
-    }
-
-    // ---------------- merge the four waves, write the split's partial ----------------
-    l_run = quad_rows_add(l_run);
-#pragma unroll
-    for (int c = 0; c < NCG; ++c) oz[c] = quad_rows_add(oz[c]);
-    float* sO = smem;                                  // [wave][row 16][128]
-    float* sS = smem + kWaves * 16 * kHeadDim;         // [wave][row 16][m, l, oz0..3]
-#pragma unroll
-    for (int t8 = 0; t8 < 8; ++t8)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sO[(wave * 16 + 4 * kb + i) * kHeadDim + 16 * t8 + n] = O[t8][i];
-    if (kb == 0) {
-        float* st = sS + (wave * 16 + n) * 6;
-        st[0] = m_run; st[1] = l_run;
-#pragma unroll
-        for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
-    }
-    __syncthreads();
-    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
-    for (int item = threadIdx.x; item < GQ * kHeadDim; item += kThreads) {
-        const int hh = item / kHeadDim, d = item % kHeadDim;
-        const int cg = d / G;
-        float M = kNegBig;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w)
-#pragma unroll
-            for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[(w * 16 + sl * 8 + 2 * hh) * 6]);
-        float acc = 0.f, L = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w)
-#pragma unroll
-            for (int sl = 0; sl < SLOTS; ++sl) {
-                const int row = sl * 8 + 2 * hh;  // hi row; lo row is row + 1
-                const float* st = sS + (w * 16 + row) * 6;
-                const float wgt = exp2f(st[0] - M);
-                float o = (sO[(w * 16 + row) * kHeadDim + d] + sO[(w * 16 + row + 1) * kHeadDim + d]) * kCodeUnit + st[2 + cg];
-                if constexpr (OUT) o += s_oc[(w * 8 + ((SLOTS == 2) ? sl * 4 + hh : hh)) * kHeadDim + d];
-                acc = __builtin_fmaf(wgt, o, acc);
-                L = __builtin_fmaf(wgt, st[1], L);
-            }
-        st_dev(dst + hh * kPartStride + 2 + d, acc);
-        if (d == 0) { st_dev(dst + hh * kPartStride, M); st_dev(dst + hh * kPartStride + 1, L); }
-    }
-    merge_if_last<GQ>(a, bh);
-}
-
 // ---------------------------------------------------------------------------
-// Software-pipelined kernel: every cache without outlier slots.  Same
-// arithmetic as above; differences are all about
-// keeping HBM, the texture-address path and the vector ALU busy at once:
+// The decode kernel.  Beyond the arithmetic described at the top of the file,
+// its structure is all about keeping HBM, the texture-address path and the
+// vector ALU busy at once:
 //   * every global load of a 32-token block is issued ahead into a second
 //     register set (A = first block of a 64-token chunk, B = second): the next
 //     chunk's blocks are requested while the current chunk's second block is
@@ -950,13 +430,15 @@ __global__ __launch_bounds__(kThreads) void decode_attn_splitk(const DecodeArgs 
 // ---------------------------------------------------------------------------
 // LDS bytes of one wave's staging strip in the pipelined kernel: key scale row | key zero rows |
 // value scales | value zeros of the block in flight.
-template <int BITS, int NCG> struct PipeGeom {
+// (with outlier slots: also the block's key and value slot words, 512 bytes each)
+template <int BITS, int NCG, bool OUT = false> struct PipeGeom {
     static constexpr bool QUANT = BITS != 16;
     static constexpr int G = kHeadDim / NCG;
     static constexpr int NGRP = (QUANT && G == 32) ? 2 : 1;   // key groups per 64-token chunk
     static constexpr int VROW = 64 * NCG;                     // bytes of value scales of one 32-token block
     static constexpr int OFF_KS = 0, OFF_KZ = 256, OFF_VS = OFF_KZ + 256 * NGRP, OFF_VZ = OFF_VS + VROW;
-    static constexpr int STRIP = QUANT ? OFF_VZ + VROW : 0;
+    static constexpr int OFF_KO = OFF_VZ + VROW, OFF_VO = OFF_KO + 512;
+    static constexpr int STRIP = QUANT ? (OUT ? OFF_VO + 512 : OFF_VZ + VROW) : 0;
 };
 // LDS of the pipelined kernel, bytes.  While the chunks stream: the group's query rows twice
 // (plain for the z-term product, operand layout for the scale fold) and one staging strip per wave.
@@ -966,15 +448,15 @@ template <int BITS, int NCG> struct PipeGeom {
 constexpr int kPipeQueryLds = 8 * kHeadDim * 2 + 2 * 4 * 64 * 16;   // plain rows + up to two operand-layout copies
 constexpr int kPipeStateLds = 8 * kHeadDim * 4 + 16 * 6 * 4 + 2 * 8 * 4 + 8 * 4;   // per wave: rows, stats, merge weights (+ references)
 constexpr int pipe_tail_lds(int gq) { return kWaves * gq * kPartStride * 4; }
-constexpr int pipe_lds_bytes(int nw, int strip, int gq) {
+constexpr int pipe_lds_bytes(int nw, int strip, int gq, bool out = false) {
     const int loop = kPipeQueryLds + nw * strip, merge = nw * kPipeStateLds;
-    return (loop > merge ? loop : merge) + pipe_tail_lds(gq);
+    return (loop > merge ? loop : merge) + pipe_tail_lds(gq) + (out ? nw * 8 * kHeadDim * 4 : 0);   // + per-wave outlier terms
 }
 constexpr int pipe_tail_offset(int nw, int strip) {
     const int loop = kPipeQueryLds + nw * strip, merge = nw * kPipeStateLds;
     return loop > merge ? loop : merge;
 }
-constexpr int pipe_max_waves(int bits, int gq) { return 4 * pipe_waves(bits, gq); }
+constexpr int pipe_max_waves(int bits, int gq, bool out = false) { return 4 * pipe_waves(bits, gq, out); }
 
 // KT (per-token key groups, AXIS = 1): the key scales have the shape of the value scales, [token][NCG],
 // and travel the same way (one dword per lane per block, parked in the strip, read back as the
@@ -985,8 +467,15 @@ constexpr int pipe_max_waves(int bits, int gq) { return 4 * pipe_waves(bits, gq)
 // group's partial sum; each lane scales its own by the token's scale, adds zero x sum(q of the
 // group), and two DPP exchanges add the columns of the head up.  With eight query heads per KV head
 // a head has only its hi / lo columns, and four groups take two passes.
-template <int BITS, int GQ, int NCG, int AXIS>
-__global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_pipe(const DecodeArgs a) {
+// OUT (the cache carries outlier slots): an outlier has code 0, so the products see its group's
+// zero; what is missing, q[ch] * delta in the logit of its token and p * delta in channel ch of the
+// output, is added outside them.  The slot words of a block travel like its scales (two dwords per
+// lane and tensor, parked in the strip).  The logit term is added by the lanes that hold the
+// token's logit (the hi / lo lane pair splits the four slots; q is looked up in its plain copy in
+// LDS); the output term goes with LDS float atomics into a per-wave [8 rows][128] binary32 array
+// that is rescaled with its row whenever the row's reference maximum moves, and folded in at the merge.
+template <int BITS, int GQ, int NCG, int AXIS, bool OUT>
+__global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_attn_pipe(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int NT = (SLOTS == 2) ? 1 : 2;
     constexpr bool QUANT = BITS != 16;
@@ -995,7 +484,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     constexpr float kCodeUnit = QUANT ? 16777216.0f : 1.0f;
     constexpr int G = kHeadDim / NCG;
     constexpr int NGRP = (QUANT && !KT && G == 32) ? 2 : 1;   // key groups per 64-token chunk
-    using Geo = PipeGeom<BITS, NCG>;
+    using Geo = PipeGeom<BITS, NCG, OUT>;
+    constexpr int OFF_KO = Geo::OFF_KO, OFF_VO = Geo::OFF_VO;
     constexpr int VROW = Geo::VROW;
     constexpr int VSTRIP = 8 * NCG;                           // bytes of value scales of 4 consecutive tokens
     constexpr int OFF_KS = Geo::OFF_KS, OFF_KZ = Geo::OFF_KZ, OFF_VS = Geo::OFF_VS, OFF_VZ = Geo::OFF_VZ;
@@ -1011,6 +501,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     float* sO = reinterpret_cast<float*>(pipe_lds);                            // after the loop: [wave][8 rows][128]
     float* sS = reinterpret_cast<float*>(pipe_lds + nw * (8 * kHeadDim * 4));  //                 [wave][16 rows][m, l, oz[4]]
     float* sT = reinterpret_cast<float*>(pipe_lds + pipe_tail_offset(nw, STRIP));   // tail states [wave < 4][head][m, l, o[128]]
+    float* s_oc = reinterpret_cast<float*>(pipe_lds + pipe_tail_offset(nw, STRIP) + pipe_tail_lds(GQ));   // OUT: [wave][8 rows][128]
 
     const int bh = blockIdx.y;
 
@@ -1042,6 +533,13 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     // The loads of the pipeline are unconditional; when a wave has no further chunk they are pointed
     // at one 16-byte spot (lane offsets zeroed) instead of re-reading a whole chunk.
     uint32_t k_off = k_lane, v_off = v_lane, row_off = row_lane, vrow_off = vrow_lane;
+    // outlier slots: 16 bytes per token and tensor, a block's 512 bytes as two dwords per lane
+    const char* ko = OUT ? reinterpret_cast<const char*>(a.k_out) + (size_t)bh * a.n_cap * 16 : nullptr;
+    const char* vo = OUT ? reinterpret_cast<const char*>(a.v_out) + (size_t)bh * a.n_cap * 16 : nullptr;
+    uint32_t slot_off = (uint32_t)lane * 8;
+    const int row8 = (SLOTS == 2) ? slot * 4 + h : h;                  // the lane's row of the wave's outlier terms
+    float* oc = s_oc + (OUT ? wave * 8 * kHeadDim : 0);
+    (void)ko; (void)vo; (void)slot_off; (void)row8; (void)oc;
 
     // lane constants of the p*s operand: lo rows subtract the leading bits; a value lands in the
     // half-word of the lane's token slot (byte selectors for v_perm_b32: 0x0c gives a zero byte)
@@ -1082,6 +580,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
     KWords<BITS> ak0, ak1, bk0, bk1;
     VWords<BITS> av, bv;
     uint32_t a_ks = 0, a_kz[NGRP], a_vs = 0, a_vz = 0, b_ks = 0, b_kz = 0, b_vs = 0, b_vz = 0;
+    uint2 a_ko = make_uint2(0u, 0u), a_vo = a_ko, b_ko = a_ko, b_vo = a_ko;   // OUT: slot words of the blocks in flight
 #pragma unroll
     for (int i = 0; i < NGRP; ++i) a_kz[i] = 0;
 
@@ -1125,6 +624,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off);
             a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off);
         }
+        if constexpr (OUT) {
+            a_ko = *reinterpret_cast<const uint2*>(ko + (size_t)tb * 16 + slot_off);
+            a_vo = *reinterpret_cast<const uint2*>(vo + (size_t)tb * 16 + slot_off);
+        }
         load_v((BITS == 2) ? chunk : 2 * chunk, av);
     };
     auto load_B = [&](int chunk, bool two) {
@@ -1137,6 +640,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             } else if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_off);
             b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off);
             b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off);
+        }
+        if constexpr (OUT) {
+            b_ko = *reinterpret_cast<const uint2*>(ko + (size_t)tb * 16 + slot_off);
+            b_vo = *reinterpret_cast<const uint2*>(vo + (size_t)tb * 16 + slot_off);
         }
         if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv);
     };
@@ -1164,12 +671,16 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
 
     // one 32-token block: QK product, online softmax update, PV product
     auto compute = [&](const KWords<BITS>& k0, const KWords<BITS>& k1, uint32_t r_ks, uint32_t r_kz, bool new_group, float bias,
-                       const VWords<BITS>& vv, int vblk, uint32_t r_vs, uint32_t r_vz) {
+                       const VWords<BITS>& vv, int vblk, uint32_t r_vs, uint32_t r_vz, uint2 r_ko, uint2 r_vo) {
         uint32_t vsr[QUANT ? NT * 2 * NCG : 1], vzr[QUANT ? NT * 2 * NCG : 1];
         if constexpr (QUANT) {
             if constexpr (KT) { lds_put_v(OFF_KS, r_ks); lds_put_v(OFF_KZ, r_kz); }
             else if (new_group) lds_put(OFF_KS, r_ks);
             lds_put_v(OFF_VS, r_vs); lds_put_v(OFF_VZ, r_vz);
+            if constexpr (OUT) {
+                *reinterpret_cast<uint2*>(stage + OFF_KO + lane * 8) = r_ko;
+                *reinterpret_cast<uint2*>(stage + OFF_VO + lane * 8) = r_vo;
+            }
             if constexpr (KT) {
                 // (the masked query operand is re-read from LDS inside the pass loop below)
             } else if (new_group) {
@@ -1285,6 +796,22 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
                 lg[NT - 1][i] = __builtin_fmaf(s1, c_logit, bias_l2);
             }
         }
+        if constexpr (OUT) {
+            // key outliers of the lane's tokens: this lane takes slots 2 part, 2 part + 1, its pair the other two
+            const uint16_t* qrow = sq + h * kHeadDim;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int th = (SLOTS == 2) ? slot : t;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint2 w = *reinterpret_cast<const uint2*>(stage + OFF_KO + (16 * th + 4 * kb + i) * 16 + part * 8);
+                    float c = slot_delta(w.x) * __half2float(__ushort_as_half(qrow[w.x & 127u]));
+                    c = __builtin_fmaf(slot_delta(w.y), __half2float(__ushort_as_half(qrow[w.y & 127u])), c);
+                    c += pair_other(c);
+                    lg[t][i] = __builtin_fmaf(c, c_bias, lg[t][i]);
+                }
+            }
+        }
         float mx = lg[0][0];
 #pragma unroll
         for (int t = 0; t < NT; ++t)
@@ -1307,6 +834,19 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
 #pragma unroll
                 for (int i = 0; i < 4; ++i) O[t][i] *= ar[i];
             m_run = m_new;
+            if constexpr (OUT) {
+                // the eight lanes of a row (hi / lo pair x four kb) rescale 16 channels each of its outlier terms
+                if (live_row && alpha != 1.0f) {
+                    float* p16 = oc + row8 * kHeadDim + (part * 4 + kb) * 16;
+#pragma unroll
+                    for (int c = 0; c < 16; c += 4) {
+                        float4 v = *reinterpret_cast<float4*>(p16 + c);
+                        v.x *= alpha; v.y *= alpha; v.z *= alpha; v.w *= alpha;
+                        *reinterpret_cast<float4*>(p16 + c) = v;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // (LDS serves a wave in order; this only pins the compiler)
+            }
         }
         float p[NT][4];
 #pragma unroll
@@ -1317,6 +857,26 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
                 p[t][i] = __builtin_amdgcn_exp2f(lg[t][i] - (m_run + (float)e));
                 l_run = __builtin_fmaf(p[t][i], (float)(1 << e), l_run);
             }
+        if constexpr (OUT) {
+            // value outliers of the lane's tokens: weight x delta into channel ch of the lane's row
+            if (live_row) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int th = (SLOTS == 2) ? slot : t;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint2 w = *reinterpret_cast<const uint2*>(stage + OFF_VO + (16 * th + 4 * kb + i) * 16 + part * 8);
+                        const float pw = p[t][i] * (float)(1 << v_pos_log2<BITS>(vblk, i));
+                        // (an LDS atomic costs the CU a fixed time even with no lane active: skip those)
+                        if (__builtin_amdgcn_ballot_w64(w.x != 0u) != 0ull)
+                            if (w.x) atomicAdd(oc + row8 * kHeadDim + (w.x & 127u), pw * slot_delta(w.x));
+                        if (__builtin_amdgcn_ballot_w64(w.y != 0u) != 0ull)
+                            if (w.y) atomicAdd(oc + row8 * kHeadDim + (w.y & 127u), pw * slot_delta(w.y));
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        }
         Frag pa[NCG];
         if constexpr (!QUANT) {
 #pragma unroll
@@ -1431,6 +991,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             reinterpret_cast<uint32_t*>(sq)[item] = v;
         }
     }
+    if constexpr (OUT)
+        for (int item = threadIdx.x; item < nw * 8 * kHeadDim; item += blockDim.x) s_oc[item] = 0.f;
     __syncthreads();   // query rows staged, chunk counter set
 #pragma unroll
     for (int s = 0; s < 4; ++s)
@@ -1483,15 +1045,15 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
             bias0 = quad_rows_add(zc[0]);                     // rows >= NGRP are zero, so the sum is a broadcast
             if constexpr (NGRP == 2) bias1 = quad_rows_add(zc[1]);
         }
-        compute(ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, a_vs, a_vz);
+        compute(ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, a_vs, a_vz, a_ko, a_vo);
         if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
         // both blocks of the wave's next chunk are requested while this chunk's second block is computed
         const bool has_next = next < c_end;
         const int nx = has_next ? next : chunk;
         const bool two_nx = n_kept - nx * kChunk >= kChunk;
-        if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; }   // (wave-uniform; the loop ends after this pass)
+        if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; slot_off = 0; }   // (wave-uniform; the loop ends after this pass)
         load_A(nx);
-        if (two) compute(bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz);
+        if (two) compute(bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz, b_ko, b_vo);
         if (kEarlyB) load_B(nx, two_nx);
         chunk = next; two = two_nx;
     }
@@ -1540,7 +1102,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
                 for (int sl = 0; sl < SLOTS; ++sl) {
                     const float* st = sS + (w * 16 + sl * 8 + 2 * hh) * 6;
                     const float wgt = sW[(w * SLOTS + sl) * GQ + hh];
-                    const float o = sO[(w * 8 + sl * 4 + hh) * kHeadDim + d] * kCodeUnit + st[2 + cg];
+                    float o = sO[(w * 8 + sl * 4 + hh) * kHeadDim + d] * kCodeUnit + st[2 + cg];
+                    if constexpr (OUT) o += s_oc[(w * 8 + sl * 4 + hh) * kHeadDim + d];
                     acc = __builtin_fmaf(wgt, o, acc);
                     L = __builtin_fmaf(wgt, st[1], L);
                 }
@@ -1601,23 +1164,25 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ), 1) void decode_attn_
 template <int BITS, int GQ, int NCG>
 hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t stream) {
     const dim3 grid(a.n_partials, cfg.batch * cfg.n_kv_heads);
-    if (BITS != 16 && a.k_out != nullptr) {          // outlier slots: the plain split-K kernel serves both key axes
-        if constexpr (BITS != 16) {
-            if (cfg.key_axis == KVQP_KEY_PER_TOKEN)
-                hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 1, true>), grid, dim3(kThreads), 0, stream, a);
-            else
-                hipLaunchKernelGGL((decode_attn_splitk<BITS, GQ, NCG, 0, true>), grid, dim3(kThreads), 0, stream, a);
-        }
-    } else if (cfg.key_axis == KVQP_KEY_PER_TOKEN && BITS != 16) {
-        if constexpr (BITS != 16) {
-            constexpr int strip = PipeGeom<BITS, NCG>::STRIP;
-            const unsigned lds_bytes = pipe_lds_bytes(a.n_waves, strip, GQ) + 16;
-            hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG, 1>), grid, dim3(64 * a.n_waves), lds_bytes, stream, a);
-        }
+    const bool out = BITS != 16 && a.k_out != nullptr;
+    const bool token_keys = BITS != 16 && cfg.key_axis == KVQP_KEY_PER_TOKEN;
+    const unsigned lds_bytes = (out ? pipe_lds_bytes(a.n_waves, PipeGeom<BITS, NCG, true>::STRIP, GQ, true)
+                                    : pipe_lds_bytes(a.n_waves, PipeGeom<BITS, NCG, false>::STRIP, GQ, false)) + 16;
+    const dim3 block(64 * a.n_waves);
+    // (more than 64 KB of dynamic LDS has to be asked for: the variants with outlier terms can need it)
+    auto go = [&](auto kernel) {
+        if (lds_bytes > 65536u &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return;
+        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, a);
+    };
+    if constexpr (BITS != 16) {
+        if (out && token_keys) go(decode_attn_pipe<BITS, GQ, NCG, 1, true>);
+        else if (out) go(decode_attn_pipe<BITS, GQ, NCG, 0, true>);
+        else if (token_keys) go(decode_attn_pipe<BITS, GQ, NCG, 1, false>);
+        else go(decode_attn_pipe<BITS, GQ, NCG, 0, false>);
     } else {
-        constexpr int strip = PipeGeom<BITS, NCG>::STRIP;
-        const unsigned lds_bytes = pipe_lds_bytes(a.n_waves, strip, GQ) + 16;
-        hipLaunchKernelGGL((decode_attn_pipe<BITS, GQ, NCG, 0>), grid, dim3(64 * a.n_waves), lds_bytes, stream, a);
+        go(decode_attn_pipe<BITS, GQ, NCG, 0, false>);
     }
     return hipGetLastError();
 }
@@ -1642,16 +1207,12 @@ hipError_t launch_gq(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t strea
 
 }  // namespace
 
-// The pipelined kernel serves everything but caches with outlier slots, which run on the plain
-// split-K kernel.
-static bool uses_pipe(const kvqp_cfg& cfg) { return !outliers_on(cfg); }
-
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
     DecodePlan p;
     const int heads = cfg.batch * cfg.n_kv_heads;
     const int n_chunks = (n_kept + kChunk - 1) / kChunk;
     const int gq = cfg.n_q_heads / cfg.n_kv_heads;
-    if (uses_pipe(cfg)) {
+    {
         // Every workgroup takes a token range and a share of the tail rows.  By default the launch
         // is one resident round: as many workgroups as the chip holds at the kernel's occupancy.
         static const int n_cu = [] {
@@ -1661,7 +1222,7 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         }();
         // Waves a head may use: its share of what the chip holds at this kernel's occupancy, but no
         // fewer than two 64-token chunks per wave (below that the fixed costs win).
-        const int max_nw = pipe_max_waves(cfg.bits, gq);
+        const int max_nw = pipe_max_waves(cfg.bits, gq, outliers_on(cfg));
         int waves = (n_cu * max_nw) / heads;
         if (waves > n_chunks / 2) waves = n_chunks / 2;
         int splits, nw;
@@ -1683,18 +1244,6 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         p.chunks_per_split = (n_chunks + splits - 1) / splits;
         p.n_splits = p.chunks_per_split ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 1;
         p.n_partials = p.n_splits;
-    } else {
-        int splits = 0;
-        if (n_chunks > 0) {
-            splits = cfg.decode_splits > 0 ? cfg.decode_splits : (1024 + heads - 1) / heads;
-            const int max_splits = cfg.decode_splits > 0 ? n_chunks : (n_chunks + 2 * kWaves - 1) / (2 * kWaves);
-            if (splits > max_splits) splits = max_splits;
-            if (splits < 1) splits = 1;
-        }
-        p.chunks_per_split = splits ? (n_chunks + splits - 1) / splits : 0;
-        p.n_splits = splits ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 0;
-        p.n_partials = p.n_splits + (tail_len > 0 ? 1 : 0);   // one more workgroup per head for the tail rows
-        p.n_waves = kWaves;
     }
     p.ws_bytes = (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartStride * sizeof(float);
     return p;

@@ -39,7 +39,7 @@ CASES = [
     (8, 128, 1, 8, 160, 16, 1, 2),
     (4, 128, 1, 1, 96, 4, 1, 2),
     (2, 32, 1, 4, 1056, 32, 1, 2),
-    (4, 32, 1, 8, 288, 32, 1, 1),        # four groups and eight heads: the plain kernel
+    (4, 32, 1, 8, 288, 32, 1, 1),        # four groups and eight heads: two passes of the key product
     (4, 32, 0, 4, 0, 32, 1, 2),          # tail only
 ]
 
