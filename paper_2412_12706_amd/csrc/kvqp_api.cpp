@@ -179,8 +179,7 @@ static int quantize_selected_impl(const kvqp_cfg* cfg, const void* k, const void
     if ((head_count != nullptr) != (cache->head_n_kept != nullptr)) return KVQP_ERR_INVALID_ARG;
     if (head_count && (rc = check_head_counts(cfg, head_count, n_kept))) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
-    if (head_count && hipMemcpyAsync(cache->head_n_kept, head_count, (size_t)cfg->batch * cfg->n_kv_heads * sizeof(int32_t),
-                                     hipMemcpyHostToDevice, stream) != hipSuccess)
+    if (head_count && upload_counts(cache->head_n_kept, head_count, cfg->batch * cfg->n_kv_heads, stream) != hipSuccess)
         return KVQP_ERR_HIP;
     if (launch_quant_pack(*cfg, k, v, idx, n_kept, cache->head_n_kept, *cache, stream) != hipSuccess) return KVQP_ERR_HIP;
     cache->n_kept = n_kept;
@@ -224,9 +223,7 @@ static int compress_impl(const kvqp_cfg* cfg, const void* q_obs, const void* k, 
     if (((uintptr_t)workspace & 15) != 0) return KVQP_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
     int32_t* idx = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.off_idx);
-    if (head_budget &&
-        hipMemcpyAsync(cache->head_n_kept, head_budget, (size_t)heads * sizeof(int32_t), hipMemcpyHostToDevice, stream) != hipSuccess)
-        return KVQP_ERR_HIP;
+    if (head_budget && upload_counts(cache->head_n_kept, head_budget, heads, stream) != hipSuccess) return KVQP_ERR_HIP;
     if (n_kept > 0) {
         if (launch_select(*cfg, q_obs, k, idx, workspace, plan, cache->head_n_kept, score, stream) != hipSuccess) return KVQP_ERR_HIP;
         if (idx_out) {

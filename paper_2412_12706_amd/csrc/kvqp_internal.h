@@ -59,6 +59,9 @@ hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, 
                              int n_kept, const int32_t* head_n, const kvqp_cache& cache, hipStream_t stream);
 hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& cache, void* out,
                          void* ws, const DecodePlan& plan, hipStream_t stream);
+// n host integers into a device array, enqueued on the stream; src_host is read before the call returns.
+constexpr int kCountsPerLaunch = 768;   // (kernel arguments: 3 KB per launch)
+hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream_t stream);
 hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, hipStream_t stream);
 // head_n (device, or NULL): every head's own cut under plan.n_kept; score says whether any head drops a token
 hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx,

@@ -591,6 +591,26 @@ hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, 
     return launch_job(j, stream);
 }
 
+// Host counts -> device array, carried in kernel arguments (copied when the launch is enqueued, so
+// the caller's array may go away as soon as the call returns; no staging copy, no synchronisation).
+struct CountBatch { int32_t v[kCountsPerLaunch]; };
+__global__ void store_counts(int32_t* __restrict__ dst, CountBatch b, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = b.v[i];
+}
+hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream_t stream) {
+    for (int i0 = 0; i0 < n; i0 += kCountsPerLaunch) {
+        CountBatch b;
+        const int m = n - i0 < kCountsPerLaunch ? n - i0 : kCountsPerLaunch;
+        for (int i = 0; i < m; ++i) b.v[i] = src_host[i0 + i];
+        for (int i = m; i < kCountsPerLaunch; ++i) b.v[i] = 0;
+        hipLaunchKernelGGL(store_counts, dim3((m + 255) / 256), dim3(256), 0, stream, dst + i0, b, m);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 // The n_tokens oldest tail rows are quantized onto the end of the packed part, then the tail closes up.
 hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, hipStream_t stream) {
     QuantPackJob j{cache};
