@@ -126,7 +126,7 @@ typedef struct kvqp_cfg {
  * float(x) - float(z), z the stored zero of the element's group, bit 7 set,
  * bits 6..0 the channel; it dequantizes to float(z) + that difference (within
  * 2^-15 of |x - z|, finer than a binary16 step of x).  A row's slots are in
- * order of selection, unused slots are 0.
+ * ascending order of channel, unused slots are 0.
  *   k_out, v_out  uint32 [batch, Hkv, n_kept, KVQP_OUTLIER_SLOTS]
  *   (sizes from kvqp_outlier_sizes; NULL when filtering is off)
  */

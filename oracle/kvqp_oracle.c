@@ -318,9 +318,9 @@ int orc_quantize_group(const uint16_t *x, int n, int stride, int bits, uint16_t 
 /* holds the top 24 bits of the binary32 difference float(x) - float(z) */
 /* (z the stored zero-point of the element's group), a valid bit (bit   */
 /* 7) and the channel (bits 0-6); the element dequantizes to            */
-/* float(z) + difference.  A row's slots are in order of selection      */
-/* (largest magnitude first), unused slots are 0.  A group left with no */
-/* element stores scale 0, zero +0.                                     */
+/* float(z) + difference.  A row's slots are in ascending order of       */
+/* channel, unused slots are 0.  A group left with no element stores    */
+/* scale 0, zero +0.                                                    */
 /* Candidates beyond the ORC_OUT_SLOTS largest are quantized like any   */
 /* other element.                                                       */
 /* ------------------------------------------------------------------ */
@@ -572,17 +572,17 @@ static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kep
                 for (int t = 0; t < n_kept; ++t) {
                     uint32_t *ko = k_out + (head * (size_t)n_kept + t) * ORC_OUT_SLOTS;
                     uint32_t *vo = v_out + (head * (size_t)n_kept + t) * ORC_OUT_SLOTS;
+                    int nk = 0, nv = 0;
                     memset(ko, 0, sizeof(uint32_t) * ORC_OUT_SLOTS);
                     memset(vo, 0, sizeof(uint32_t) * ORC_OUT_SLOTS);
-                    for (int d = 0; d < D; ++d) {
+                    for (int d = 0; d < D; ++d) { /* ascending channel */
                         size_t mk = key_axis == 0 ? (head * (size_t)(n_kept / G) + t / G) * D + d
                                                   : (head * (size_t)n_kept + t) * (D / G) + d / G;
                         size_t mv = (head * (size_t)n_kept + t) * (D / G) + d / G;
-                        const int rk = kmask[(size_t)t * D + d], rv = vmask[(size_t)t * D + d];
-                        if (rk)
-                            ko[rk - 1] = orc_outlier_slot(kh[(size_t)id[t] * D + d], k_zero[mk], d);
-                        if (rv)
-                            vo[rv - 1] = orc_outlier_slot(vh[(size_t)id[t] * D + d], v_zero[mv], d);
+                        if (kmask[(size_t)t * D + d])
+                            ko[nk++] = orc_outlier_slot(kh[(size_t)id[t] * D + d], k_zero[mk], d);
+                        if (vmask[(size_t)t * D + d])
+                            vo[nv++] = orc_outlier_slot(vh[(size_t)id[t] * D + d], v_zero[mv], d);
                     }
                 }
             for (int i = 0; i < W; ++i) {

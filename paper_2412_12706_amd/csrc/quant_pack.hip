@@ -156,6 +156,16 @@ __device__ __forceinline__ uint32_t row16_max(uint32_t v) {
     v = max(v, dpp<kRowHalfMirror>(v)); v = max(v, dpp<kRowMirror>(v));
     return v;
 }
+// sum over the 16 lanes of a row, in every lane; and the sum over the lanes before this one
+__device__ __forceinline__ uint32_t row16_sum(uint32_t v) {
+    v += dpp<kQuadXor1>(v); v += dpp<kQuadXor2>(v); v += dpp<kRowHalfMirror>(v); v += dpp<kRowMirror>(v);
+    return v;
+}
+__device__ __forceinline__ uint32_t row16_before(uint32_t v) {
+    uint32_t s = v;
+    s += dpp<0x111>(s); s += dpp<0x112>(s); s += dpp<0x114>(s); s += dpp<0x118>(s);   // row_shr 1, 2, 4, 8 (zeros shifted in)
+    return s - v;
+}
 // 0xFFFF in the half-words whose bit (bit 0: low half, bit 1: high half) is set
 __device__ __forceinline__ uint32_t half_mask(uint32_t b) { return ((0u - (b & 1u)) & 0xFFFFu) | ((0u - ((b >> 1) & 1u)) << 16); }
 
@@ -227,28 +237,28 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         vw[j][0] = b.x; vw[j][1] = b.y; vw[j][2] = b.z; vw[j][3] = b.w;
     }
 
-    // Outlier marking (OUT): per token row, the elements with |x| above the threshold compete by
-    // magnitude (then lower channel) in up to four rounds over the row's 16 lanes; om gets a bit per
-    // own element that won, win the winners in order (0 = none) as |x| bits << 8 | (127 - channel)
-    // << 1 | sign, known to every lane of the row.
-    auto mark = [&](const uint32_t (&w)[R][4], uint32_t (&om)[R], uint32_t (&win)[R][4]) {
+    // Outlier marking (OUT): om gets a bit per own element that is an outlier of its token row.  A
+    // row's candidates are the elements with |x| above the threshold; when no row of the wave has more
+    // than four (the usual case) they all are outliers; otherwise the rows' elements compete by
+    // magnitude (then lower channel) in four rounds over the row's 16 lanes.
+    auto mark = [&](const uint32_t (&w)[R][4], uint32_t (&om)[R]) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            uint32_t key[8];
+            uint32_t key[8], cand = 0u;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint32_t hbits = (w[j][e >> 1] >> (16 * (e & 1))) & 0xffffu, mag = hbits & 0x7fffu;
-                key[e] = mag > tau_bits ? (mag << 8) | ((uint32_t)(127 - (8 * c8 + e)) << 1) | (hbits >> 15) : 0u;
+                const uint32_t mag = (w[j][e >> 1] >> (16 * (e & 1))) & 0x7fffu;
+                key[e] = mag > tau_bits ? (mag << 7) | (uint32_t)(127 - (8 * c8 + e)) : 0u;
+                cand |= mag > tau_bits ? (1u << e) : 0u;
             }
+            om[j] = cand;
+            const uint32_t total = row16_sum((uint32_t)__builtin_popcount(cand));
+            if (__builtin_amdgcn_ballot_w64(total > 4u) == 0ull) continue;   // (wave-uniform)
             om[j] = 0u;
-#pragma unroll
-            for (int sl = 0; sl < 4; ++sl) win[j][sl] = 0u;
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl) {
                 uint32_t m = max(max(max(key[0], key[1]), max(key[2], key[3])), max(max(key[4], key[5]), max(key[6], key[7])));
                 m = row16_max(m);
-                if (__builtin_amdgcn_ballot_w64(m != 0u) == 0ull) break;   // no row of this wave has a candidate left
-                win[j][sl] = m;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const bool mine = m != 0u && key[e] == m;
@@ -258,11 +268,32 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             }
         }
     };
-    // slot word of a winner given the float bits of its group's zero
-    auto slot_word = [](uint32_t win, float zf) -> uint32_t {
-        const uint32_t xh = (win >> 8) | ((win & 1u) << 15), ch = 127u - ((win >> 1) & 127u);
+    // slot word of element x (binary16 pattern) in channel ch given its group's zero
+    auto slot_word = [](uint32_t xh, uint32_t ch, float zf) -> uint32_t {
         const float diff = __fsub_rn(half_bits_to_float((uint16_t)xh), zf);
-        return win ? ((__float_as_uint(diff) & 0xFFFFFF00u) | 0x80u | ch) : 0u;
+        return (__float_as_uint(diff) & 0xFFFFFF00u) | 0x80u | ch;
+    };
+    // Slot words of the rows, in ascending channel order: an outlier's slot index is the number of
+    // outliers before it in the row (lanes before this one, then the lane's own earlier elements);
+    // lanes 0-3 of the row clear the unused slots.  zero_of(j, e): the zero of element e's group in row j.
+    auto store_slots = [&](uint32_t* out, const uint32_t (&w)[R][4], const uint32_t (&om)[R], auto zero_of) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if (!live[j]) continue;                                   // (uniform over the workgroup)
+            const uint32_t mine = (uint32_t)__builtin_popcount(om[j]);
+            const uint32_t total = row16_sum(mine);
+            uint32_t at = row16_before(mine);
+            uint32_t* row = out + ((size_t)head * n_cap + d0 + r + 16 * j) * 4;
+            if (c8 < 4 && (uint32_t)c8 >= total) row[c8] = 0u;
+            if (__builtin_amdgcn_ballot_w64(om[j] != 0u) == 0ull) continue;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if ((om[j] >> e) & 1u) {
+                    const uint32_t xh = (w[j][e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                    row[at] = slot_word(xh, (uint32_t)(8 * c8 + e), zero_of(j, e));
+                    ++at;
+                }
+        }
     };
 
     // Per-token groups (values always, keys on that axis): every row is complete inside GL lanes.
@@ -310,29 +341,12 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             }
         }
     };
-    // Slots of rows whose groups lie along the row: the zero of channel ch's group sits in lane ch / 8 of the row.
-    auto store_slots_per_token = [&](uint32_t* out, const uint32_t (&win)[R][4], const uint32_t (&zrow)[R]) {
-        const int row_lane0 = lane & ~15;
-#pragma unroll
-        for (int j = 0; j < R; ++j) {
-            uint32_t sw[4];
-#pragma unroll
-            for (int sl = 0; sl < 4; ++sl) {
-                const uint32_t ch = 127u - ((win[j][sl] >> 1) & 127u);
-                const uint32_t zb = (uint32_t)__builtin_amdgcn_ds_bpermute((row_lane0 + (int)(ch >> 3)) << 2, (int)zrow[j]);
-                sw[sl] = slot_word(win[j][sl], __uint_as_float(zb));
-            }
-            if (c8 == 0 && live[j])
-                *reinterpret_cast<uint4*>(out + ((size_t)head * n_cap + d0 + r + 16 * j) * 4) = make_uint4(sw[0], sw[1], sw[2], sw[3]);
-        }
-    };
-
     // ---------------- keys ----------------
     uint32_t* kc_head = k_codes + (size_t)head * ((size_t)n_cap * kHeadDim / E);
-    uint32_t om[R], win[R][4], zrow[R];   // outlier bits and winners of the tensor at hand (OUT)
+    uint32_t om[R], zrow[R];   // outlier bits of the tensor at hand (OUT); zero of the lane's own per-token group
 #pragma unroll
     for (int j = 0; j < R; ++j) om[j] = 0u;
-    if constexpr (OUT) mark(kw, om, win);
+    if constexpr (OUT) mark(kw, om);
     if constexpr (!QUANT) {
 #pragma unroll
         for (int j = 0; j < R; ++j)
@@ -406,22 +420,16 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
                 if constexpr (OUT) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) c[e] &= ((om[j] >> e) & 1u) - 1u;
-                    uint32_t sw[4];
-#pragma unroll
-                    for (int sl = 0; sl < 4; ++sl) {
-                        const uint32_t ch = 127u - ((win[j][sl] >> 1) & 127u);
-                        sw[sl] = slot_word(win[j][sl], s_par[ug * kHeadDim + ch].x);
-                    }
-                    if (c8 == 0 && live[j])
-                        *reinterpret_cast<uint4*>(k_out + ((size_t)head * n_cap + d0 + r + 16 * j) * 4) = make_uint4(sw[0], sw[1], sw[2], sw[3]);
                 }
                 if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, c);
             }
         }
+        if constexpr (OUT)   // the zero of (row j's key group, own channel 8 c8 + e) from the table the codes were made with
+            store_slots(k_out, kw, om, [&](int j, int e) { return s_par[(j / JPG) * kHeadDim + 8 * c8 + e].x; });
     } else {
         uint32_t codes[R][8];
         per_token(kw, k_scale, k_zero, codes, om, zrow);
-        if constexpr (OUT) store_slots_per_token(k_out, win, zrow);
+        if constexpr (OUT) store_slots(k_out, kw, om, [&](int j, int) { return __uint_as_float(zrow[j]); });
 #pragma unroll
         for (int j = 0; j < R; ++j)
             if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
@@ -439,9 +447,9 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             for (int dd = 0; dd < 8; ++dd) part[sb][dd] = 0u;
         if constexpr (QUANT) {
             uint32_t codes[R][8];
-            if constexpr (OUT) mark(vw, om, win);
+            if constexpr (OUT) mark(vw, om);
             per_token(vw, v_scale, v_zero, codes, om, zrow);
-            if constexpr (OUT) store_slots_per_token(v_out, win, zrow);
+            if constexpr (OUT) store_slots(v_out, vw, om, [&](int j, int) { return __uint_as_float(zrow[j]); });
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const int b32 = j >> 1, H = j & 1;
