@@ -166,7 +166,9 @@ int kvqp_cache_sizes_cap(const kvqp_cfg *cfg, int32_t n_cap, int32_t tail_cap, s
 int kvqp_outlier_sizes(const kvqp_cfg *cfg, int32_t n_cap, size_t sizes_out[2]);
 
 /* Workspace bytes needed by kvqp_compress and kvqp_decode_attn for this cfg
- * (either pointer may be NULL).  Host only. */
+ * (either pointer may be NULL).  decode_bytes depends on batch, heads, bits,
+ * decode_splits and outlier_threshold only: it serves a cache of any token
+ * count, also one that kvqp_append_tail has grown.  Host only. */
 int kvqp_workspace_bytes(const kvqp_cfg *cfg, size_t *compress_bytes, size_t *decode_bytes);
 
 /*
@@ -217,8 +219,9 @@ int kvqp_compress(const kvqp_cfg *cfg, const void *q_obs, const void *k, const v
  *   idx_out      int32 [batch, Hkv, n_kept] or NULL: the first head_budget[h]
  *                entries of head h are its survivors, the rest is unspecified.
  * kvqp_decode_attn reads such a cache through head_n_kept (tail_len must be
- * >= 1); kvqp_append_tail does not take one (UNSUPPORTED), and kvqp_compress
- * and kvqp_quantize_selected want head_n_kept == NULL (INVALID_ARG).
+ * >= 1) and kvqp_append_tail_ragged extends it; kvqp_append_tail does not take
+ * one (UNSUPPORTED), and kvqp_compress and kvqp_quantize_selected want
+ * head_n_kept == NULL (INVALID_ARG).
  */
 int kvqp_compress_ragged(const kvqp_cfg *cfg, const void *q_obs, const void *k, const void *v,
                          const int32_t *head_budget, kvqp_cache *cache, int32_t *idx_out,
@@ -282,6 +285,26 @@ int kvqp_decode_attn(const kvqp_cfg *cfg, const void *q, const kvqp_cache *cache
  * Errors: INVALID_ARG when the counts do not fit the rules above.
  */
 int kvqp_append_tail(const kvqp_cfg *cfg, kvqp_cache *cache, int32_t n_tokens, void *hip_stream);
+
+/*
+ * The same update for a cache with head-level counts (Section 3, Eq. (2) on a
+ * cache filled by kvqp_compress_ragged): every head takes the n_tokens oldest
+ * tail rows onto the end of ITS OWN packed part, so head h grows from
+ * head_count[h] to head_count[h] + n_tokens tokens; the bound n_kept grows by
+ * n_tokens and tail_len shrinks by it.
+ *   head_count  HOST int32 [batch * Hkv]: the heads' CURRENT counts (the array
+ *               given to kvqp_compress_ragged, plus earlier appends).  Every
+ *               entry a multiple of q (as for kvqp_append_tail) and <= n_kept.
+ *               Read before the call returns; cache->head_n_kept receives the
+ *               new counts (a copy enqueued on the stream).  The quantizer
+ *               takes a head's position from the device copy, cut to n_kept
+ *               and rounded down to a multiple of q, so an array that differs
+ *               from the device's misplaces tokens but never leaves the buffers.
+ *   n_tokens    as for kvqp_append_tail, with n_kept + n_tokens <= n_cap.
+ * Errors: INVALID_ARG as above, or when cache->head_n_kept is NULL.
+ */
+int kvqp_append_tail_ragged(const kvqp_cfg *cfg, kvqp_cache *cache, int32_t n_tokens,
+                            const int32_t *head_count, void *hip_stream);
 
 /* Static string for a return code. */
 const char *kvqp_strerror(int code);

@@ -1207,6 +1207,27 @@ hipError_t launch_gq(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t strea
 
 }  // namespace
 
+static int cu_count() {
+    static const int n_cu = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        return v;
+    }();
+    return n_cu;
+}
+
+// Workspace that covers the plan of every cache of this cfg's batch, heads and bits, whatever its
+// token count: no plan has more splits than the head's share of the chip in four-wave workgroups
+// (or the caller's decode_splits).
+size_t decode_ws_bound(const kvqp_cfg& cfg) {
+    const int heads = cfg.batch * cfg.n_kv_heads, gq = cfg.n_q_heads / cfg.n_kv_heads;
+    const int share = (cu_count() * pipe_max_waves(cfg.bits, gq, outliers_on(cfg))) / heads;
+    int splits = (share + kWaves - 1) / kWaves;
+    if (cfg.decode_splits > splits) splits = cfg.decode_splits;
+    if (splits < 1) splits = 1;
+    return (size_t)heads * splits * gq * kPartStride * sizeof(float);
+}
+
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
     DecodePlan p;
     const int heads = cfg.batch * cfg.n_kv_heads;
@@ -1215,11 +1236,7 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
     {
         // Every workgroup takes a token range and a share of the tail rows.  By default the launch
         // is one resident round: as many workgroups as the chip holds at the kernel's occupancy.
-        static const int n_cu = [] {
-            int dev = 0, v = 0;
-            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-            return v;
-        }();
+        const int n_cu = cu_count();
         // Waves a head may use: its share of what the chip holds at this kernel's occupancy, but no
         // fewer than two 64-token chunks per wave (below that the fixed costs win).
         const int max_nw = pipe_max_waves(cfg.bits, gq, outliers_on(cfg));

@@ -5,6 +5,8 @@
 
 #include "kvqp_internal.h"
 
+#include <vector>
+
 namespace kvqp {
 namespace {
 
@@ -101,7 +103,7 @@ using namespace kvqp;
 
 extern "C" {
 
-int kvqp_version(void) { return 300; }
+int kvqp_version(void) { return 400; }
 
 const char* kvqp_strerror(int code) {
     switch (code) {
@@ -153,8 +155,8 @@ int kvqp_workspace_bytes(const kvqp_cfg* cfg, size_t* compress_bytes, size_t* de
     const int n_kept = n_kept_of(cfg);
     if ((rc = check_n_kept(cfg, n_kept))) return rc;
     if (compress_bytes) *compress_bytes = plan_compress(*cfg).total;
-    // decode: sized for a non-empty tail so that appended tokens never outgrow it
-    if (decode_bytes) *decode_bytes = plan_decode(*cfg, n_kept, 1).ws_bytes;
+    // decode: covers every token count, so a cache that grows by appended tokens never outgrows it
+    if (decode_bytes) *decode_bytes = decode_ws_bound(*cfg);
     return KVQP_OK;
 }
 
@@ -248,11 +250,11 @@ int kvqp_compress_ragged(const kvqp_cfg* cfg, const void* q_obs, const void* k, 
     return compress_impl(cfg, q_obs, k, v, head_budget, cache, idx_out, workspace, workspace_bytes, hip_stream);
 }
 
-int kvqp_append_tail(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_tokens, void* hip_stream) {
+// Both forms of the decode-time update: head_count == NULL is the uniform one.
+static int append_impl(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_tokens, const int32_t* head_count, void* hip_stream) {
     int rc = check_common(cfg);
     if (rc) return rc;
     if (!cache || n_tokens < 1) return KVQP_ERR_INVALID_ARG;
-    if (cache->head_n_kept) return KVQP_ERR_UNSUPPORTED;   // head-level counts: the heads would need their own steps
     if (cache->n_kept < 0 || cache->tail_len < 0 || cache->tail_len > cache->tail_cap) return KVQP_ERR_INVALID_ARG;
     if (n_tokens > cache->tail_len) return KVQP_ERR_INVALID_ARG;
     // whole value superblocks and, for per-channel keys, whole key groups
@@ -262,10 +264,32 @@ int kvqp_append_tail(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_tokens, v
     const int cap = cache->n_cap > 0 ? cache->n_cap : cache->n_kept;
     if (cache->n_kept + n_tokens > cap) return KVQP_ERR_INVALID_ARG;
     if ((rc = check_cache_ptrs(cfg, cache, cache->n_kept + n_tokens, true))) return rc;
-    if (launch_append_tail(*cfg, *cache, n_tokens, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    const int heads = cfg->batch * cfg->n_kv_heads;
+    std::vector<int32_t> grown;
+    if (head_count) {
+        for (int h = 0; h < heads; ++h)
+            if (head_count[h] < 0 || head_count[h] > cache->n_kept || head_count[h] % quantum) return KVQP_ERR_INVALID_ARG;
+        grown.assign(head_count, head_count + heads);
+        for (int h = 0; h < heads; ++h) grown[h] += n_tokens;
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (launch_append_tail(*cfg, *cache, n_tokens, head_count ? quantum : 0, stream) != hipSuccess) return KVQP_ERR_HIP;
+    // (the new counts are stored after the quantizer, which takes its positions from the old ones)
+    if (head_count && upload_counts(cache->head_n_kept, grown.data(), heads, stream) != hipSuccess) return KVQP_ERR_HIP;
     cache->n_kept += n_tokens;
     cache->tail_len -= n_tokens;
     return KVQP_OK;
+}
+
+int kvqp_append_tail(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_tokens, void* hip_stream) {
+    if (cache && cache->head_n_kept) return KVQP_ERR_UNSUPPORTED;   // head-level counts: kvqp_append_tail_ragged
+    return append_impl(cfg, cache, n_tokens, nullptr, hip_stream);
+}
+
+int kvqp_append_tail_ragged(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_tokens, const int32_t* head_count,
+                            void* hip_stream) {
+    if (!head_count || !cache || !cache->head_n_kept) return KVQP_ERR_INVALID_ARG;
+    return append_impl(cfg, cache, n_tokens, head_count, hip_stream);
 }
 
 int kvqp_decode_attn(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache, void* out, void* workspace,

@@ -34,6 +34,8 @@ struct QuantPackJob {
     bool outliers;
     int heads, src_rows, window, n_tok, dst_base, n_cap, bits, group_size, key_axis;
     bool copy_tail;
+    const int32_t* head_base = nullptr;   // device: first destination token of each head in place of dst_base, or NULL
+    int base_quantum = 1;                 // what every head_base entry is a multiple of
 };
 
 typedef unsigned short us2v __attribute__((ext_vector_type(2)));
@@ -176,11 +178,15 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     uint16_t* __restrict__ k_zero, uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero,
     uint16_t* __restrict__ tail_k, uint16_t* __restrict__ tail_v, int L, int W, int n_kept, int key_axis,
     int tail_cap, int n_tok_blocks, int n_cap, int dst_base, const int32_t* __restrict__ head_n,
-    uint32_t* __restrict__ k_out, uint32_t* __restrict__ v_out, uint32_t tau_bits) {
+    uint32_t* __restrict__ k_out, uint32_t* __restrict__ v_out, uint32_t tau_bits,
+    const int32_t* __restrict__ head_base, int base_quantum) {
     // L: rows per head of the source tensors.  idx: source row of every token of this call
     // ([heads, n_kept]), or NULL for rows 0 .. n_kept-1.  The tokens land at positions dst_base ..
     // dst_base + n_kept - 1 of a cache whose buffers are laid out for n_cap tokens per head.
     // head_n: a head's own token count in place of n_kept (idx keeps its stride of n_kept), or NULL.
+    // head_base: a head's own first position in place of dst_base, or NULL; it is cut to dst_base and
+    // rounded down to a multiple of base_quantum, so whatever the array holds the stores stay inside
+    // the buffers and on group and superblock boundaries.
     // OUT: outlier filtering; k_out / v_out receive four slot words per token row.
     constexpr bool QUANT = BITS != 16;
     constexpr int TB = (QUANT && G == 128) ? 128 : 64;   // tokens per workgroup
@@ -218,7 +224,12 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c8 = threadIdx.x & 15, r = threadIdx.x >> 4, i4 = (threadIdx.x >> 4) & 3;
     const int t0 = blockIdx.x * TB;
-    const int d0 = dst_base + t0;            // first destination token: a multiple of the group and superblock sizes
+    int base = dst_base;
+    if (head_base) {
+        base = min(max(head_base[head], 0), dst_base);
+        base -= base % base_quantum;
+    }
+    const int d0 = base + t0;                // first destination token: a multiple of the group and superblock sizes
     const int n_head = head_n ? head_n[head] : n_kept;
     if (t0 >= n_head) return;                // (the whole workgroup: nothing of this head left)
     const int ntok = min(TB, n_head - t0);   // a multiple of 32 (and of G for per-channel keys)
@@ -509,7 +520,8 @@ hipError_t launch_bits_g(const QuantPackJob& j, hipStream_t stream) {
                        (const uint16_t*)j.v, j.idx, (uint32_t*)j.c.k_codes, (uint32_t*)j.c.v_codes, (uint16_t*)j.c.k_scale,
                        (uint16_t*)j.c.k_zero, (uint16_t*)j.c.v_scale, (uint16_t*)j.c.v_zero, (uint16_t*)j.c.tail_k,
                        (uint16_t*)j.c.tail_v, j.src_rows, j.window, j.n_tok, j.key_axis, j.c.tail_cap, nblk, j.n_cap,
-                       j.dst_base, j.head_n, (uint32_t*)j.c.k_out, (uint32_t*)j.c.v_out, j.tau_bits);
+                       j.dst_base, j.head_n, (uint32_t*)j.c.k_out, (uint32_t*)j.c.v_out, j.tau_bits, j.head_base,
+                       j.base_quantum);
     return hipGetLastError();
 }
 template <int BITS>
@@ -620,10 +632,12 @@ hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream
 }
 
 // The n_tokens oldest tail rows are quantized onto the end of the packed part, then the tail closes up.
-hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, hipStream_t stream) {
+// base_quantum > 0: every head at its own count (cache.head_n_kept), counts being multiples of it.
+hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, int base_quantum, hipStream_t stream) {
     QuantPackJob j{cache};
     set_outliers(j, cfg);
     j.k = cache.tail_k; j.v = cache.tail_v; j.idx = nullptr; j.head_n = nullptr;
+    if (base_quantum > 0) { j.head_base = cache.head_n_kept; j.base_quantum = base_quantum; }
     j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cache.tail_cap; j.window = 0;
     j.n_tok = n_tokens; j.dst_base = cache.n_kept; j.n_cap = cache.n_cap > 0 ? cache.n_cap : cache.n_kept;
     j.bits = cfg.bits; j.group_size = cfg.group_size; j.key_axis = cfg.key_axis; j.copy_tail = false;

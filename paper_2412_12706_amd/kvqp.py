@@ -17,7 +17,7 @@ KVQP_OK = 0
 KEY_PER_CHANNEL = 0
 KEY_PER_TOKEN = 1
 EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_outlier_sizes", "kvqp_workspace_bytes", "kvqp_compress",
-           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
+           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_append_tail_ragged", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
 
 
 class KvqpError(RuntimeError):
@@ -55,6 +55,7 @@ def lib():
         L.kvqp_cache_sizes_cap.argtypes = [C.POINTER(CfgStruct), C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         L.kvqp_outlier_sizes.argtypes = [C.POINTER(CfgStruct), C.c_int32, C.POINTER(C.c_size_t)]
         L.kvqp_append_tail.argtypes = [C.POINTER(CfgStruct), C.POINTER(CacheStruct), C.c_int32, C.c_void_p]
+        L.kvqp_append_tail_ragged.argtypes = [C.POINTER(CfgStruct), C.POINTER(CacheStruct), C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
         L.kvqp_workspace_bytes.argtypes = [C.POINTER(CfgStruct), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.kvqp_compress.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(CacheStruct),
                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -256,6 +257,21 @@ def append_tail(cfg: Cfg, cache: Cache, n_tokens: int, stream=None):
     rc = lib().kvqp_append_tail(C.byref(cfg.struct()), C.byref(cs), n_tokens, _stream_ptr(stream))
     if rc:
         raise KvqpError(rc, "kvqp_append_tail")
+    cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
+    return cache
+
+
+def append_tail_ragged(cfg: Cfg, cache: Cache, n_tokens: int, head_count, stream=None):
+    """kvqp_append_tail_ragged: every head takes the n_tokens oldest tail rows at its own count
+    (head_count: the heads' current counts, a host sequence)."""
+    n = cfg.batch * cfg.n_kv_heads
+    if len(head_count) != n:
+        raise ValueError(f"head_count needs {n} entries")
+    hc = (C.c_int32 * n)(*[int(x) for x in head_count])
+    cs = cache.struct()
+    rc = lib().kvqp_append_tail_ragged(C.byref(cfg.struct()), C.byref(cs), n_tokens, hc, _stream_ptr(stream))
+    if rc:
+        raise KvqpError(rc, "kvqp_append_tail_ragged")
     cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
     return cache
 

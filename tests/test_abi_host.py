@@ -58,11 +58,11 @@ def test_cache_sizes_match_bytes_per_token(lib, bits, G):
     assert s2[0] == 2 * 96 * 128 * 2 // 8 and s2[1] == 2 * 128 * 128 * 2 // 8
 
 
-def test_workspace_sizes_are_positive_and_grow_with_the_problem(lib):
+def test_workspace_sizes_are_positive_and_compress_grows_with_the_problem(lib):
     small = kvqp.Cfg(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024)
     big = kvqp.Cfg(batch=32, n_q_heads=32, n_kv_heads=8, seq_len=32768, window=32, budget=8192)
     (c0, d0), (c1, d1) = kvqp.workspace_bytes(small), kvqp.workspace_bytes(big)
-    assert 0 < c0 < c1 and 0 < d0 < d1
+    assert 0 < c0 < c1 and d0 > 0 and d1 > 0     # (decode: partials of the token-axis splits, few heads -> more splits)
 
 
 BAD = [
@@ -168,6 +168,20 @@ def test_head_level_count_argument_checks(lib):
     assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, fake, 1 << 30, None) == -1
     cs.n_kept, cs.tail_len, cs.n_cap = 256, 32, 320
     assert lib.kvqp_append_tail(C.byref(st), C.byref(cs), 64, None) == -2
+    # the head-level form checks the heads' current counts before anything is enqueued
+    app = lambda counts, n=64, cache=cs: lib.kvqp_append_tail_ragged(C.byref(st), C.byref(cache), n,
+                                                                      (C.c_int32 * 2)(*counts) if counts else None, None)
+    cs.tail_len = 64
+    assert app(None) == -1
+    assert app([256, 96]) == -1           # not whole key groups
+    assert app([256, 320]) == -1          # above the bound n_kept
+    assert app([-64, 64]) == -1
+    assert app([256, 64], 32) == -1       # n_tokens not whole groups
+    assert app([256, 64], 128) == -1      # more than the tail holds (and than the capacity)
+    no_counts = kvqp.CacheStruct.from_buffer_copy(cs)
+    no_counts.head_n_kept = None
+    assert app([256, 64], 64, no_counts) == -1
+    assert (cs.n_kept, cs.tail_len) == (256, 64)
     cs.tail_len = 0
     assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1   # a head may be empty
 
@@ -193,6 +207,22 @@ def test_outlier_filtering_argument_checks(lib):
     assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, fake, 1 << 30, None) == -1   # no slot buffers
     cs.n_kept, cs.tail_len = 256, 32
     assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1
+
+
+def test_decode_workspace_covers_every_token_count(lib):
+    """The decode workspace size does not depend on the token count, so a cache grown by appended
+    tokens never outgrows it."""
+    for heads, bits in ((8, 4), (8, 2), (256, 4), (2, 16)):
+        sizes = set()
+        for budget in (64, 1024, 8192, 32768):
+            cfg = kvqp.Cfg(batch=heads // 2, n_q_heads=8, n_kv_heads=2, seq_len=40000, window=32, budget=budget, bits=bits,
+                           group_size=32)
+            sizes.add(kvqp.workspace_bytes(cfg)[1])
+        assert len(sizes) == 1 and min(sizes) > 0, (heads, bits, sizes)
+    a = kvqp.workspace_bytes(kvqp.Cfg(batch=1, n_q_heads=8, n_kv_heads=2, seq_len=4096, window=32, budget=1024, bits=4))[1]
+    b = kvqp.workspace_bytes(kvqp.Cfg(batch=1, n_q_heads=8, n_kv_heads=2, seq_len=4096, window=32, budget=1024, bits=4,
+                                      decode_splits=500))[1]
+    assert b >= 2 * 500 * 4 * 130 * 4 and b > a      # the caller's split count is covered
 
 
 def test_binding_raises_with_the_library_message(lib):

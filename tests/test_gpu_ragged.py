@@ -207,3 +207,73 @@ def test_quantize_given_survivors_with_head_level_counts(orc, bits, G, key_axis)
                 assert np.array_equal(head_share(gc, nm, np.uint16, heads, h, ref.size), ref), nm
         ref = orc.decode_attn(q[b:b + 1, g * gq:(g + 1) * gq], oc, sm)
         assert np.abs(out[b, g * gq:(g + 1) * gq] - ref[0]).max() <= 2e-3
+
+
+@pytest.mark.parametrize("bits,G,key_axis,n_app,tau", [(4, 64, kvqp.KEY_PER_TOKEN, 32, 0.0), (2, 32, kvqp.KEY_PER_CHANNEL, 64, 0.0),
+                                                        (4, 128, kvqp.KEY_PER_CHANNEL, 128, 0.0), (8, 32, kvqp.KEY_PER_TOKEN, 96, 0.0),
+                                                        (16, 32, kvqp.KEY_PER_CHANNEL, 32, 0.0), (4, 32, kvqp.KEY_PER_CHANNEL, 64, 6.0)])
+def test_append_with_head_level_counts(orc, bits, G, key_axis, n_app, tau):
+    """Decode-time update (Eq. (2)) of a cache with head-level counts: every head takes the oldest
+    tail rows onto the end of its own packed part.  Per head, the result is the checker's
+    quantization of that head's survivors plus the moved rows in one go; twice in a row."""
+    print(f"case ragged append bits={bits} G={G} axis={key_axis} n={n_app} tau={tau}", flush=True)
+    B, Hq, Hkv, W, bound, P = 2, 8, 2, 8, 512, 900
+    q_app = 64 if bits == 2 else 32
+    if bits != 16 and key_axis == kvqp.KEY_PER_CHANNEL:
+        q_app = max(q_app, G)
+    counts = [c - c % q_app for c in (512, 128, 0, 384)]
+    grown = W + 2 * n_app + 5                          # tail rows after some decoding
+    _, k, v = synth.prompt_host(B, Hq, Hkv, P + grown, grown, 128, config=69)
+    if tau:
+        v[..., [3, 64]] *= 12                          # value outliers too
+    rng = np.random.default_rng(69 + bits)
+    idx = np.zeros((B, Hkv, bound), np.int32)
+    for h, n in enumerate(counts):
+        idx[h // Hkv, h % Hkv, :n] = np.sort(rng.choice(P, n, replace=False))
+    cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=P + grown, window=W, budget=bound, bits=bits,
+                   group_size=G, key_axis=key_axis, outlier_threshold=tau)
+    cap = grown + 3
+    gc = kvqp.alloc_cache(cfg, tail_cap=cap, n_cap=bound + 2 * n_app + (-(bound + 2 * n_app)) % 128, ragged=True)
+    for t in gc.buffers.values():
+        t.fill_(0x3C)
+    kvqp.quantize_selected_ragged(cfg, dev(k), dev(v), dev(idx), counts, gc)
+    heads, E, sm, gq = B * Hkv, 32 // bits, float(np.float32(cfg.sm_scale)), Hq // Hkv
+    for name, src in (("tail_k", k), ("tail_v", v)):   # the caller's appended rows
+        rows = torch.from_numpy(np.ascontiguousarray(src[:, :, P:P + grown]).view(np.uint16).copy()).cuda()
+        gc.buffers[name].view(torch.uint16).view(heads, cap, 128)[:, :grown] = rows.view(heads, grown, 128)
+    gc.tail_len = grown
+    ws = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg)[1])
+    kw = dict(tau=tau) if tau else {}
+    for rnd in (1, 2):
+        kvqp.append_tail_ragged(cfg, gc, n_app, counts)
+        counts = [c + n_app for c in counts]
+        moved = rnd * n_app
+        torch.cuda.synchronize()
+        assert gc.head_n_kept.cpu().tolist() == counts and gc.n_kept == bound + moved and gc.tail_len == grown - moved
+        q = synth.decode_query_host(B, Hq, 128, config=69, step=rnd)
+        out = kvqp.decode_attn(cfg, dev(q), gc, workspace=ws)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy().astype(np.float64)
+        for h, n in enumerate(counts):
+            b, g = h // Hkv, h % Hkv
+            own = np.concatenate([idx[b, g, :n - moved], np.arange(P, P + moved, dtype=np.int32)]).reshape(1, 1, n)
+            oc = orc.quantize_selected(k[b:b + 1, g:g + 1], v[b:b + 1, g:g + 1], own, W=grown - moved, bits=bits, G=G,
+                                       key_axis=key_axis, **kw)
+            assert np.array_equal(head_share(gc, "k_codes", np.uint32, heads, h, n * 128 // E), oc.k_codes.reshape(-1)), h
+            assert np.array_equal(head_share(gc, "v_codes", np.uint32, heads, h, oc.v_codes.size), oc.v_codes.reshape(-1)), h
+            names = ["k_scale", "k_zero", "v_scale", "v_zero"] if bits != 16 else []
+            dts = {nm: np.uint16 for nm in names}
+            if tau:
+                names += ["k_out", "v_out"]
+                dts.update(k_out=np.uint32, v_out=np.uint32)
+            for nm in names:
+                ref = getattr(oc, nm).reshape(-1)
+                assert np.array_equal(head_share(gc, nm, dts[nm], heads, h, ref.size), ref), (nm, h)
+            for nm in ("tail_k", "tail_v"):
+                ref = getattr(oc, nm).reshape(-1)[: (grown - moved) * 128]
+                assert np.array_equal(head_share(gc, nm, np.uint16, heads, h, ref.size), ref), (nm, h)
+            ref = orc.decode_attn(q[b:b + 1, g * gq:(g + 1) * gq], oc, sm)
+            err = np.abs(out[b, g * gq:(g + 1) * gq] - ref[0]) / np.maximum(1.0, np.abs(ref[0]))
+            assert err.max() <= 2e-3, (h, err.max())
+    with pytest.raises(kvqp.KvqpError):
+        kvqp.append_tail_ragged(cfg, gc, n_app, counts)          # the tail no longer holds that many rows
