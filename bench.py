@@ -72,8 +72,9 @@ def read_traffic_note(kernel_tag):
 
 def cpu_baseline(q_obs1, k1, v1, sm_scale):
     """The CPU checker, untuned, timed on the host cores on a bounded sample:
-    one layer of the (8192 tokens, 4 bit) setting -- compress once, then 4
-    decode steps."""
+    one layer of the (8192 tokens, 4 bit) setting -- compress once, then as
+    many decode steps as the GPU's timed loop runs per setting (about 10 s of
+    CPU work in all)."""
     import numpy as np
     from oracle import kvqp_oracle as orc
     from paper_2412_12706_amd import synth
@@ -81,7 +82,7 @@ def cpu_baseline(q_obs1, k1, v1, sm_scale):
     cache, idx, _ = orc.compress(q_obs1, k1, v1, window=W, pool=POOL, budget=8192, bits=4, G=G, sm_scale=sm_scale,
                                  want_pooled=False)
     t1 = time.perf_counter()
-    n_dec = 4
+    n_dec = DECODE_STEPS
     for s in range(n_dec):
         q = synth.decode_query_host(1, HQ, D, config=CONFIG_ID, layer=0, step=s)
         orc.decode_attn(q, cache, sm_scale)
