@@ -343,9 +343,35 @@ def main():
             "bytes_per_step": t_bytes,
         }
         del tc
-        return per_layer, append_us, layer_wise, outlier_leg, token_keys
 
-    per_layer, append_us, layer_wise, outlier_leg, token_keys = (None,) * 5 if args.sweep_only else extra_legs()
+        # ---- the sweep's launches with the memory-side cache flushed before each one (outside the timed
+        # steps): consecutive decode steps re-read the same cache, and the library leaves the first 240 MB
+        # of a large launch's working set resident in the 256 MB memory-side cache while the rest streams
+        # past it; this leg shows the launches with nothing resident (2 GiB are read before each; a reading
+        # flush, so that no write-back of dirty lines lands inside the timed interval) ----
+        f_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        f_dst = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        cold = []
+        for s in settings:
+            pairs = []
+            for t in range(17):
+                sink += f_src.sum()
+                sink += f_dst.sum()
+                a, bq = ev(), ev()
+                a.record()
+                kvqp.decode_attn(s["cfg"], queries[t], s["cache"], out, s["ws_d"])
+                bq.record()
+                pairs.append((a, bq))
+            torch.cuda.synchronize()
+            us = sorted(x.elapsed_time(y) * 1e3 for x, y in pairs[1:])[len(pairs) // 2 - 1]
+            b = decode_bytes(LAYERS, s["n_kept"], s["bits"], G, W)
+            cold.append({"tokens": s["n_kept"], "bits": s["bits"], "decode_us_per_step": round(us, 2),
+                         "decode_gbs": round(b / (us * 1e-6) / 1e9, 1), "pct_of_8TBs": round(100 * b / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 1)})
+        del f_src, f_dst
+        return per_layer, append_us, layer_wise, outlier_leg, token_keys, cold
+
+    per_layer, append_us, layer_wise, outlier_leg, token_keys, cold = (None,) * 6 if args.sweep_only else extra_legs()
 
     # ---- roofline of the dominant kernel: the decode launch that takes most of the step ----
     dom = max(range(len(settings)), key=lambda i: settings[i]["t_decode_ms"])
@@ -400,6 +426,10 @@ def main():
         "append_note": f"kvqp_append_tail of {G} tokens per cache, 32 layers as one batch, 4-bit setting",
         "layer_wise_counts": layer_wise, "outlier_filtering": outlier_leg, "per_token_keys": token_keys,
         "sweep": sweep, "per_layer_calls": per_layer,
+        "cold_memory_side_cache": cold,
+        "cold_note": "each launch timed alone (median of 16, HIP events around the one launch) right after 2 GiB of "
+                     "other data were read, so nothing of the cache is resident in the 256 MB memory-side cache; in "
+                     "the timed sweep consecutive steps re-read the same cache and up to 240 MB of it stay resident",
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -82,6 +82,16 @@ __device__ __forceinline__ float row_ror8(float v) {
     return __uint_as_float(__builtin_amdgcn_mov_dpp(__float_as_uint(v), 0x128 /*row_ror:8*/, 0xf, 0xf, true));
 }
 
+// A load of cache data, which a launch reads exactly once.
+typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u2v __attribute__((ext_vector_type(2)));
+template <typename T, bool NT>
+__device__ __forceinline__ T stream_load(const char* p) {
+    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+    else return *reinterpret_cast<const T*>(p);
+}
+template <bool B> struct BoolC { static constexpr bool value = B; };
+
 __device__ __forceinline__ h2v as_h2(uint32_t u) { union { uint32_t u; h2v h; } c; c.u = u; return c.h; }
 __device__ __forceinline__ uint32_t as_u32(h2v h) { union { uint32_t u; h2v h; } c; c.h = h; return c.u; }
 // two binary32 values cut (toward zero) to binary16, (lo, hi) half-words
@@ -199,6 +209,7 @@ struct DecodeArgs {
     int n_splits, chunks_per_split, n_partials;
     int n_waves;              // waves per workgroup of the pipelined kernel
     int group;                // G
+    int stream_from;          // chunks from this one on are loaded with the non-temporal hint
     float sm_scale;
 };
 
@@ -474,7 +485,7 @@ constexpr int pipe_max_waves(int bits, int gq, bool out = false) { return 4 * pi
 // token's logit (the hi / lo lane pair splits the four slots; q is looked up in its plain copy in
 // LDS); the output term goes with LDS float atomics into a per-wave [8 rows][128] binary32 array
 // that is rescaled with its row whenever the row's reference maximum moves, and folded in at the merge.
-template <int BITS, int GQ, int NCG, int AXIS, bool OUT>
+template <int BITS, int GQ, int NCG, int AXIS, bool OUT, bool MIX = true>
 __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_attn_pipe(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int NT = (SLOTS == 2) ? 1 : 2;
@@ -584,68 +595,81 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
 #pragma unroll
     for (int i = 0; i < NGRP; ++i) a_kz[i] = 0;
 
-    auto load_k = [&](int tok, KWords<BITS>& dst) {
+    auto load_k = [&](int tok, KWords<BITS>& dst, auto nt) {
+        constexpr bool NT = decltype(nt)::value;
         const char* p = kc + (size_t)tok * (16 * BITS) + k_off;
         if constexpr (BITS == 2) {
-            const uint2 v = *reinterpret_cast<const uint2*>(p);
-            dst.w[0] = v.x; dst.w[1] = v.y;
+            const u2v v = stream_load<u2v, NT>(p);
+            dst.w[0] = v[0]; dst.w[1] = v[1];
         } else {
 #pragma unroll
             for (int i = 0; i < BITS / 4; ++i) {
-                const uint4 v = reinterpret_cast<const uint4*>(p)[i];
-                dst.w[4 * i] = v.x; dst.w[4 * i + 1] = v.y; dst.w[4 * i + 2] = v.z; dst.w[4 * i + 3] = v.w;
+                const u4v v = stream_load<u4v, NT>(p + 16 * i);
+                dst.w[4 * i] = v[0]; dst.w[4 * i + 1] = v[1]; dst.w[4 * i + 2] = v[2]; dst.w[4 * i + 3] = v[3];
             }
         }
     };
-    auto load_v = [&](int sb, VWords<BITS>& dst) {
+    auto load_v = [&](int sb, VWords<BITS>& dst, auto nt) {
+        constexpr bool NT = decltype(nt)::value;
         const char* p = vc + (size_t)sb * (v_superblock_words(BITS) * 4) + v_off;
 #pragma unroll
         for (int q = 0; q < VGeom<BITS>::kWordsPerLoad / 4; ++q) {
-            const uint4 v = *reinterpret_cast<const uint4*>(p + q * 1024);
-            dst.w[4 * q] = v.x; dst.w[4 * q + 1] = v.y; dst.w[4 * q + 2] = v.z; dst.w[4 * q + 3] = v.w;
+            const u4v v = stream_load<u4v, NT>(p + q * 1024);
+            dst.w[4 * q] = v[0]; dst.w[4 * q + 1] = v[1]; dst.w[4 * q + 2] = v[2]; dst.w[4 * q + 3] = v[3];
         }
     };
-    auto dword_at = [](const char* base, uint32_t off) { return *reinterpret_cast<const uint32_t*>(base + off); };
+    auto dword_at = [](const char* base, uint32_t off, auto nt) { return stream_load<uint32_t, decltype(nt)::value>(base + off); };
     // Loads are unconditional (indices clamped to valid blocks) so that the loop body is
     // straight-line code and the hardware wait counters can be tracked exactly.
-    auto load_A = [&](int chunk) {
+    auto load_A_as = [&](int chunk, auto nt) {
         const int tb = chunk * kChunk;
-        load_k(tb + 0, ak0); load_k(tb + 16, ak1);
+        load_k(tb + 0, ak0, nt); load_k(tb + 16, ak1, nt);
         if constexpr (QUANT) {
             if constexpr (KT) {
-                a_ks = dword_at(ks, (uint32_t)tb * (2 * NCG) + vrow_off);
-                a_kz[0] = dword_at(kz, (uint32_t)tb * (2 * NCG) + vrow_off);
+                a_ks = dword_at(ks, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
+                a_kz[0] = dword_at(kz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
             } else {
                 const int u = tb / G;
-                a_ks = dword_at(ks, (uint32_t)u * 256 + row_off);
+                a_ks = dword_at(ks, (uint32_t)u * 256 + row_off, nt);
 #pragma unroll
-                for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_off);
+                for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_off, nt);
             }
-            a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off);
-            a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off);
+            a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
+            a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
         }
         if constexpr (OUT) {
             a_ko = *reinterpret_cast<const uint2*>(ko + (size_t)tb * 16 + slot_off);
             a_vo = *reinterpret_cast<const uint2*>(vo + (size_t)tb * 16 + slot_off);
         }
-        load_v((BITS == 2) ? chunk : 2 * chunk, av);
+        load_v((BITS == 2) ? chunk : 2 * chunk, av, nt);
     };
-    auto load_B = [&](int chunk, bool two) {
+    auto load_B_as = [&](int chunk, bool two, auto nt) {
         const int tb = chunk * kChunk + (two ? 32 : 0);
-        load_k(tb + 0, bk0); load_k(tb + 16, bk1);
+        load_k(tb + 0, bk0, nt); load_k(tb + 16, bk1, nt);
         if constexpr (QUANT) {
             if constexpr (KT) {
-                b_ks = dword_at(ks, (uint32_t)tb * (2 * NCG) + vrow_off);
-                b_kz = dword_at(kz, (uint32_t)tb * (2 * NCG) + vrow_off);
-            } else if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_off);
-            b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off);
-            b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off);
+                b_ks = dword_at(ks, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
+                b_kz = dword_at(kz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
+            } else if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_off, nt);
+            b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
+            b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
         }
         if constexpr (OUT) {
             b_ko = *reinterpret_cast<const uint2*>(ko + (size_t)tb * 16 + slot_off);
             b_vo = *reinterpret_cast<const uint2*>(vo + (size_t)tb * 16 + slot_off);
         }
-        if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv);
+        if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv, nt);
+    };
+    // Chunks from a.stream_from on are read with the non-temporal hint (wave-uniform choice; MIX =
+    // false: no chunk is).  The empty statements keep the two arms apart: merged, the loads would
+    // lose the hint.
+    auto load_A = [&](int chunk) {
+        if (MIX && chunk >= a.stream_from) { asm volatile("; streamed"); load_A_as(chunk, BoolC<true>{}); asm volatile("; streamed"); }
+        else load_A_as(chunk, BoolC<false>{});
+    };
+    auto load_B = [&](int chunk, bool two) {
+        if (MIX && chunk >= a.stream_from) { asm volatile("; streamed"); load_B_as(chunk, two, BoolC<true>{}); asm volatile("; streamed"); }
+        else load_B_as(chunk, two, BoolC<false>{});
     };
     auto lds_put = [&](int off, uint32_t v) { *reinterpret_cast<uint32_t*>(stage + off + row_lane) = v; };
     auto lds_put_v = [&](int off, uint32_t v) { if (lane < VROW / 4) *reinterpret_cast<uint32_t*>(stage + off + row_lane) = v; };
@@ -1161,6 +1185,22 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     merge_if_last<GQ>(a, bh);
 }
 
+// Which chunks of every head a launch streams past the memory-side cache.  A decode loop reads the
+// same cache again at every step; of a working set beyond the 256 MB memory-side cache only a
+// part can stay there, and loads that merely pass through it run slower than loads that go round
+// it.  So when one launch reads more than kCacheAllBelow bytes, the first kCacheKeepBytes of it
+// (the same leading share of every head) are read normally and stay resident from step to step,
+// and the rest carries the non-temporal hint.  Both constants were swept on the MI355X.
+constexpr int kNoStream = 0x7fffffff;
+constexpr double kCacheKeepBytes = 240e6, kCacheAllBelow = 288e6;
+static int stream_from_chunk(const kvqp_cfg& cfg, int n_kept) {
+    const double bpt = cfg.bits == 16 ? 4.0 * kHeadDim : 2.0 * (kHeadDim * cfg.bits / 8.0 + 4.0 * kHeadDim / cfg.group_size);
+    const double total = (double)cfg.batch * cfg.n_kv_heads * (double)n_kept * bpt;
+    if (total <= kCacheAllBelow) return kNoStream;
+    const int n_chunks = (n_kept + kChunk - 1) / kChunk;
+    return (int)(n_chunks * (kCacheKeepBytes / total));
+}
+
 template <int BITS, int GQ, int NCG>
 hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t stream) {
     const dim3 grid(a.n_partials, cfg.batch * cfg.n_kv_heads);
@@ -1182,7 +1222,9 @@ hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t str
         else if (token_keys) go(decode_attn_pipe<BITS, GQ, NCG, 1, false>);
         else go(decode_attn_pipe<BITS, GQ, NCG, 0, false>);
     } else {
-        go(decode_attn_pipe<BITS, GQ, NCG, 0, false>);
+        // (16-bit blocks are four times larger; the variant without the choice is a little faster when nothing is streamed)
+        if (a.stream_from == kNoStream) go(decode_attn_pipe<BITS, GQ, NCG, 0, false, false>);
+        else go(decode_attn_pipe<BITS, GQ, NCG, 0, false, true>);
     }
     return hipGetLastError();
 }
@@ -1286,6 +1328,7 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;
     a.n_waves = plan.n_waves;
     a.group = cfg.group_size; a.sm_scale = cfg.sm_scale;
+    a.stream_from = stream_from_chunk(cfg, c.n_kept);
     hipError_t e;
     switch (cfg.bits) {
         case 2: e = launch_gq<2>(cfg, a, stream); break;

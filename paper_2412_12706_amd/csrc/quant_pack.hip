@@ -242,10 +242,13 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         const int t = r + 16 * j;
         live[j] = 32 * (j >> 1) < ntok;   // ntok is a multiple of 32: the same for the whole workgroup
         const int pos = !live[j] ? 0 : idx ? idx[(size_t)head * n_kept + t0 + t] : t0 + t;
-        const uint4 a = live[j] ? *reinterpret_cast<const uint4*>(kh + (size_t)pos * kHeadDim + 8 * c8) : make_uint4(0, 0, 0, 0);
-        const uint4 b = live[j] ? *reinterpret_cast<const uint4*>(vh + (size_t)pos * kHeadDim + 8 * c8) : make_uint4(0, 0, 0, 0);
-        kw[j][0] = a.x; kw[j][1] = a.y; kw[j][2] = a.z; kw[j][3] = a.w;
-        vw[j][0] = b.x; vw[j][1] = b.y; vw[j][2] = b.z; vw[j][3] = b.w;
+        // (prompt rows are read once: non-temporal)
+        typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+        const u4v zero4 = {0u, 0u, 0u, 0u};
+        const u4v a = live[j] ? __builtin_nontemporal_load(reinterpret_cast<const u4v*>(kh + (size_t)pos * kHeadDim + 8 * c8)) : zero4;
+        const u4v b = live[j] ? __builtin_nontemporal_load(reinterpret_cast<const u4v*>(vh + (size_t)pos * kHeadDim + 8 * c8)) : zero4;
+        kw[j][0] = a[0]; kw[j][1] = a[1]; kw[j][2] = a[2]; kw[j][3] = a[3];
+        vw[j][0] = b[0]; vw[j][1] = b[1]; vw[j][2] = b[2]; vw[j][3] = b[3];
     }
 
     // Outlier marking (OUT): om gets a bit per own element that is an outlier of its token row.  A
