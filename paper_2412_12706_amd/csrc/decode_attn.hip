@@ -638,8 +638,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
         }
         if constexpr (OUT) {
-            a_ko = *reinterpret_cast<const uint2*>(ko + (size_t)tb * 16 + slot_off);
-            a_vo = *reinterpret_cast<const uint2*>(vo + (size_t)tb * 16 + slot_off);
+            { const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); a_ko = make_uint2(w[0], w[1]); }
+            { const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); a_vo = make_uint2(w[0], w[1]); }
         }
         load_v((BITS == 2) ? chunk : 2 * chunk, av, nt);
     };
@@ -655,8 +655,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
         }
         if constexpr (OUT) {
-            b_ko = *reinterpret_cast<const uint2*>(ko + (size_t)tb * 16 + slot_off);
-            b_vo = *reinterpret_cast<const uint2*>(vo + (size_t)tb * 16 + slot_off);
+            { const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); b_ko = make_uint2(w[0], w[1]); }
+            { const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); b_vo = make_uint2(w[0], w[1]); }
         }
         if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv, nt);
     };
@@ -1194,7 +1194,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
 constexpr int kNoStream = 0x7fffffff;
 constexpr double kCacheKeepBytes = 240e6, kCacheAllBelow = 288e6;
 static int stream_from_chunk(const kvqp_cfg& cfg, int n_kept) {
-    const double bpt = cfg.bits == 16 ? 4.0 * kHeadDim : 2.0 * (kHeadDim * cfg.bits / 8.0 + 4.0 * kHeadDim / cfg.group_size);
+    double bpt = cfg.bits == 16 ? 4.0 * kHeadDim : 2.0 * (kHeadDim * cfg.bits / 8.0 + 4.0 * kHeadDim / cfg.group_size);
+    if (outliers_on(cfg)) bpt += 2.0 * KVQP_OUTLIER_SLOTS * 4;   // slot words of both tensors
     const double total = (double)cfg.batch * cfg.n_kv_heads * (double)n_kept * bpt;
     if (total <= kCacheAllBelow) return kNoStream;
     const int n_chunks = (n_kept + kChunk - 1) / kChunk;
