@@ -354,20 +354,26 @@ def main():
         sink = torch.zeros(1, dtype=torch.float32, device=dev)
         cold = []
         for s in settings:
-            pairs = []
-            for t in range(17):
-                sink += f_src.sum()
-                sink += f_dst.sum()
-                a, bq = ev(), ev()
-                a.record()
-                kvqp.decode_attn(s["cfg"], queries[t], s["cache"], out, s["ws_d"])
-                bq.record()
-                pairs.append((a, bq))
-            torch.cuda.synchronize()
-            us = sorted(x.elapsed_time(y) * 1e3 for x, y in pairs[1:])[len(pairs) // 2 - 1]
+            rec = {"tokens": s["n_kept"], "bits": s["bits"]}
             b = decode_bytes(LAYERS, s["n_kept"], s["bits"], G, W)
-            cold.append({"tokens": s["n_kept"], "bits": s["bits"], "decode_us_per_step": round(us, 2),
-                         "decode_gbs": round(b / (us * 1e-6) / 1e9, 1), "pct_of_8TBs": round(100 * b / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 1)})
+            # (library's choice of loads, then the hint of a caller who knows the cache will not survive)
+            for key, hint in (("", kvqp.CACHE_AUTO), ("stream_hint_", kvqp.CACHE_STREAM)):
+                cfg_h = kvqp.Cfg(**{**s["cfg"].__dict__, "decode_cache_hint": hint})
+                pairs = []
+                for t in range(17):
+                    sink += f_src.sum()
+                    sink += f_dst.sum()
+                    a, bq = ev(), ev()
+                    a.record()
+                    kvqp.decode_attn(cfg_h, queries[t], s["cache"], out, s["ws_d"])
+                    bq.record()
+                    pairs.append((a, bq))
+                torch.cuda.synchronize()
+                us = sorted(x.elapsed_time(y) * 1e3 for x, y in pairs[1:])[len(pairs) // 2 - 1]
+                rec[key + "decode_us_per_step"] = round(us, 2)
+                rec[key + "decode_gbs"] = round(b / (us * 1e-6) / 1e9, 1)
+                rec[key + "pct_of_8TBs"] = round(100 * b / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 1)
+            cold.append(rec)
         del f_src, f_dst
         return per_layer, append_us, layer_wise, outlier_leg, token_keys, cold
 
@@ -429,7 +435,8 @@ def main():
         "cold_memory_side_cache": cold,
         "cold_note": "each launch timed alone (median of 16, HIP events around the one launch) right after 2 GiB of "
                      "other data were read, so nothing of the cache is resident in the 256 MB memory-side cache; in "
-                     "the timed sweep consecutive steps re-read the same cache and up to 240 MB of it stay resident",
+                     "the timed sweep consecutive steps re-read the same cache and up to 240 MB of it stay resident; "
+                     "stream_hint_*: the same with cfg.decode_cache_hint = KVQP_CACHE_STREAM (every load non-temporal)",
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

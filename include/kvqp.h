@@ -54,7 +54,7 @@ extern "C" {
  * and pool_kernel belong to the attention-score pruning rule below).
  * Supported in this build: head_dim == 128; n_q_heads / n_kv_heads in
  * {1,2,4,8}; bits in {2,4,8,16}; group_size in {32,64,128};
- * outlier_threshold 0, or > 0 with bits in {2,4,8};
+ * outlier_threshold 0, or > 0 with bits in {2,4,8}; decode_cache_hint one of KVQP_CACHE_*;
  * window * (n_q_heads/n_kv_heads) <= 256; pool_kernel odd, <= 63;
  * seq_len - window <= 131072.
  */
@@ -73,7 +73,31 @@ typedef struct kvqp_cfg {
     int32_t decode_splits;/* token-axis splits of decode attention; 0 = library chooses  */
     float sm_scale;       /* logit scale > 0, e.g. 1/sqrt(D) (Eq. (3) omits it)          */
     float outlier_threshold; /* tau; > 0 turns outlier filtering on (below), 0 = off     */
+    int32_t decode_cache_hint; /* KVQP_CACHE_*: how kvqp_decode_attn's loads treat the
+                             chip's memory-side cache (below); 0 = library chooses      */
 } kvqp_cfg;
+
+/*
+ * decode_cache_hint.  A decode loop reads the same cache again at every step.
+ * The chip has a 256 MB memory-side cache; what of a launch's working set can
+ * stay there is re-read quickly at the next step, while loads of data that
+ * cannot stay run faster when they go round it (non-temporal loads).
+ *   KVQP_CACHE_AUTO    a launch that reads more than 288 MB reads the leading
+ *                      share of every head that adds up to 240 MB normally and
+ *                      the rest non-temporally (all of it beyond 600 MB);
+ *                      smaller launches read everything normally.  Right for
+ *                      a loop of decode steps over one batch of caches with
+ *                      little else in between.
+ *   KVQP_CACHE_STREAM  every load non-temporal: for a caller that knows the
+ *                      cache will have been evicted before it is read again
+ *                      (weights and other layers pass through in between).
+ *   KVQP_CACHE_KEEP    every load normal.
+ * 16-bit caches are read normally whatever the hint (measured: non-temporal
+ * loads are slower there).  Results do not depend on the hint.
+ */
+#define KVQP_CACHE_AUTO 0
+#define KVQP_CACHE_STREAM 1
+#define KVQP_CACHE_KEEP 2
 
 /*
  * The compressed cache of one layer.  All eight buffers are device memory of

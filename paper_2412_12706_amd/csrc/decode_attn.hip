@@ -485,7 +485,7 @@ constexpr int pipe_max_waves(int bits, int gq, bool out = false) { return 4 * pi
 // token's logit (the hi / lo lane pair splits the four slots; q is looked up in its plain copy in
 // LDS); the output term goes with LDS float atomics into a per-wave [8 rows][128] binary32 array
 // that is rescaled with its row whenever the row's reference maximum moves, and folded in at the merge.
-template <int BITS, int GQ, int NCG, int AXIS, bool OUT, bool MIX = true>
+template <int BITS, int GQ, int NCG, int AXIS, bool OUT>
 __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_attn_pipe(const DecodeArgs a) {
     constexpr int SLOTS = (GQ <= 4) ? 2 : 1;
     constexpr int NT = (SLOTS == 2) ? 1 : 2;
@@ -660,9 +660,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         }
         if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv, nt);
     };
-    // Chunks from a.stream_from on are read with the non-temporal hint (wave-uniform choice; MIX =
-    // false: no chunk is).  The empty statements keep the two arms apart: merged, the loads would
-    // lose the hint.
+    // Chunks from a.stream_from on are read with the non-temporal hint (wave-uniform choice; a 16-bit
+    // cache never is).  The empty statements keep the two arms apart: merged, the loads would lose
+    // the hint.
+    constexpr bool MIX = QUANT;
     auto load_A = [&](int chunk) {
         if (MIX && chunk >= a.stream_from) { asm volatile("; streamed"); load_A_as(chunk, BoolC<true>{}); asm volatile("; streamed"); }
         else load_A_as(chunk, BoolC<false>{});
@@ -1190,14 +1191,20 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
 // part can stay there, and loads that merely pass through it run slower than loads that go round
 // it.  So when one launch reads more than kCacheAllBelow bytes, the first kCacheKeepBytes of it
 // (the same leading share of every head) are read normally and stay resident from step to step,
-// and the rest carries the non-temporal hint.  Both constants were swept on the MI355X.
+// and the rest carries the non-temporal hint; beyond kCacheNoneAbove keeping a part resident no
+// longer pays and everything is streamed.  The constants were swept on the MI355X.  16-bit caches
+// are always read normally: a lane's 64 bytes of a row take four load instructions, and lines
+// evicted between them cost more than the hint gains (measured at 0.27, 0.55 and 1.1 GB).
 constexpr int kNoStream = 0x7fffffff;
-constexpr double kCacheKeepBytes = 240e6, kCacheAllBelow = 288e6;
+constexpr double kCacheKeepBytes = 240e6, kCacheAllBelow = 288e6, kCacheNoneAbove = 600e6;
 static int stream_from_chunk(const kvqp_cfg& cfg, int n_kept) {
-    double bpt = cfg.bits == 16 ? 4.0 * kHeadDim : 2.0 * (kHeadDim * cfg.bits / 8.0 + 4.0 * kHeadDim / cfg.group_size);
+    if (cfg.bits == 16 || cfg.decode_cache_hint == KVQP_CACHE_KEEP) return kNoStream;
+    if (cfg.decode_cache_hint == KVQP_CACHE_STREAM) return 0;
+    double bpt = 2.0 * (kHeadDim * cfg.bits / 8.0 + 4.0 * kHeadDim / cfg.group_size);
     if (outliers_on(cfg)) bpt += 2.0 * KVQP_OUTLIER_SLOTS * 4;   // slot words of both tensors
     const double total = (double)cfg.batch * cfg.n_kv_heads * (double)n_kept * bpt;
     if (total <= kCacheAllBelow) return kNoStream;
+    if (total > kCacheNoneAbove) return 0;
     const int n_chunks = (n_kept + kChunk - 1) / kChunk;
     return (int)(n_chunks * (kCacheKeepBytes / total));
 }
@@ -1223,9 +1230,7 @@ hipError_t launch_axis(const kvqp_cfg& cfg, const DecodeArgs& a, hipStream_t str
         else if (token_keys) go(decode_attn_pipe<BITS, GQ, NCG, 1, false>);
         else go(decode_attn_pipe<BITS, GQ, NCG, 0, false>);
     } else {
-        // (16-bit blocks are four times larger; the variant without the choice is a little faster when nothing is streamed)
-        if (a.stream_from == kNoStream) go(decode_attn_pipe<BITS, GQ, NCG, 0, false, false>);
-        else go(decode_attn_pipe<BITS, GQ, NCG, 0, false, true>);
+        go(decode_attn_pipe<BITS, GQ, NCG, 0, false>);
     }
     return hipGetLastError();
 }

@@ -26,6 +26,7 @@ int check_common(const kvqp_cfg* c) {
     if (!(c->sm_scale > 0.0f) || c->sm_scale > 3.0e38f) return KVQP_ERR_INVALID_ARG;   /* positive and finite */
     if (!(c->outlier_threshold >= 0.0f) || c->outlier_threshold > 3.0e38f) return KVQP_ERR_INVALID_ARG;
     if (c->outlier_threshold > 0.0f && c->bits == 16) return KVQP_ERR_INVALID_ARG;   /* nothing is quantized at 16 bits */
+    if (c->decode_cache_hint < KVQP_CACHE_AUTO || c->decode_cache_hint > KVQP_CACHE_KEEP) return KVQP_ERR_INVALID_ARG;
     const int gq = c->n_q_heads / c->n_kv_heads;
     if (c->head_dim != kHeadDim) return KVQP_ERR_UNSUPPORTED;
     if (!(gq == 1 || gq == 2 || gq == 4 || gq == 8)) return KVQP_ERR_UNSUPPORTED;
@@ -103,7 +104,7 @@ using namespace kvqp;
 
 extern "C" {
 
-int kvqp_version(void) { return 400; }
+int kvqp_version(void) { return 500; }
 
 const char* kvqp_strerror(int code) {
     switch (code) {

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libkvqp.so")
 KVQP_OK = 0
 KEY_PER_CHANNEL = 0
 KEY_PER_TOKEN = 1
+CACHE_AUTO, CACHE_STREAM, CACHE_KEEP = 0, 1, 2     # kvqp_cfg.decode_cache_hint
 EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_outlier_sizes", "kvqp_workspace_bytes", "kvqp_compress",
            "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_append_tail_ragged", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
 
@@ -29,7 +30,8 @@ class KvqpError(RuntimeError):
 class CfgStruct(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "seq_len", "window",
                                          "pool_kernel", "budget", "bits", "group_size", "key_axis",
-                                         "decode_splits")] + [("sm_scale", C.c_float), ("outlier_threshold", C.c_float)]
+                                         "decode_splits")] + [("sm_scale", C.c_float), ("outlier_threshold", C.c_float),
+                                                            ("decode_cache_hint", C.c_int32)]
 
 
 class CacheStruct(C.Structure):
@@ -96,11 +98,12 @@ class Cfg:
     decode_splits: int = 0
     sm_scale: float = 128 ** -0.5
     outlier_threshold: float = 0.0
+    decode_cache_hint: int = 0      # CACHE_AUTO / CACHE_STREAM / CACHE_KEEP
 
     def struct(self) -> CfgStruct:
         return CfgStruct(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.seq_len, self.window,
                          self.pool_kernel, self.budget, self.bits, self.group_size, self.key_axis,
-                         self.decode_splits, self.sm_scale, self.outlier_threshold)
+                         self.decode_splits, self.sm_scale, self.outlier_threshold, self.decode_cache_hint)
 
     @property
     def n_kept(self) -> int:

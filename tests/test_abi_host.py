@@ -71,7 +71,7 @@ BAD = [
     (dict(pool_kernel=0), -1), (dict(window=0), -1), (dict(window=5000), -1), (dict(budget=-1), -1),
     (dict(budget=1000), -1),            # not a multiple of the group size
     (dict(key_axis=2), -1), (dict(batch=0), -1), (dict(window=128), -2), (dict(decode_splits=-1), -1),
-    (dict(sm_scale=float("nan")), -1),
+    (dict(sm_scale=float("nan")), -1), (dict(decode_cache_hint=3), -1), (dict(decode_cache_hint=-1), -1),
 ]
 
 

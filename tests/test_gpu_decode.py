@@ -185,3 +185,29 @@ def test_seeded_random_shapes(orc):
         print(f"    max-abs error {err:.3e}", flush=True)
         assert err <= TOL, f"case {case}: max-abs error {err:.3e}"
     print(f"  worst max-abs error {worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("bits,Gq,axis,splits", [(4, 4, 0, 0), (2, 8, 0, 3), (8, 2, 1, 0), (16, 4, 0, 2), (4, 1, 1, 5)])
+def test_cache_hint_of_the_loads_does_not_change_the_result(orc, bits, Gq, axis, splits):
+    """The three decode_cache_hint settings choose between ordinary and non-temporal loads of the
+    cache; each must give the checker's result.  (Without a hint the library streams only launches
+    far larger than these, so the streamed flavour of every load is exercised here.)"""
+    B, Hkv, n_kept, W, G = 2, 2, 1024 + 96 * (bits != 2), 17, 32
+    Hq, L = Hkv * Gq, n_kept + W + 40
+    _, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, config=700 + bits)
+    rng = np.random.default_rng(700 + bits)
+    idx = np.stack([np.sort(rng.choice(L - W, n_kept, replace=False)) for _ in range(B * Hkv)]).astype(np.int32).reshape(B, Hkv, n_kept)
+    oc = orc.quantize_selected(k, v, idx, W=W, bits=bits, G=G, key_axis=axis)
+    q = synth.decode_query_host(B, Hq, 128, config=700 + bits)
+    gc = upload_cache(oc)
+    ref = None
+    for hint in (kvqp.CACHE_AUTO, kvqp.CACHE_STREAM, kvqp.CACHE_KEEP):
+        cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, budget=n_kept, bits=bits, group_size=G,
+                       key_axis=axis, decode_splits=splits, decode_cache_hint=hint)
+        if ref is None:
+            ref = orc.decode_attn(q, oc, cfg.sm_scale)
+        out = kvqp.decode_attn(cfg, dev(q), gc)
+        torch.cuda.synchronize()
+        err = np.abs(out.cpu().numpy().astype(np.float64) - ref).max()
+        print(f"  bits={bits} hint={hint} max-abs error {err:.3e}", flush=True)
+        assert err <= TOL

@@ -2,7 +2,7 @@
 with head-level counts), optionally the decode-time append (Section 3, Eq. (2)),
 then decode attention -- every configuration switch drawn at random from the
 supported space (bits, group size, key axis, heads per KV head, window, pool
-width, budget, outlier filtering, capacity layout).
+width, budget, outlier filtering, capacity layout, cache hint of the loads).
 
 The definition is per head (each KV head is the uniform method run on that head
 alone), so the CPU checker is called per head on the head's slice: indices
@@ -43,7 +43,8 @@ def draw_case(rng):
     heads = B * Hkv
     counts = [unit * int(rng.integers(0, 1 + bound // unit)) for _ in range(heads)] if ragged else [bound] * heads
     n_app = q_app * int(rng.integers(1, 3)) if append else 0
-    return dict(bits=bits, G=G, axis=axis, Gq=Gq, Hkv=Hkv, B=B, W=W, pool=pool, tau=tau, ragged=ragged, P=P, bound=bound,
+    hint = int(rng.choice([kvqp.CACHE_AUTO, kvqp.CACHE_STREAM, kvqp.CACHE_KEEP]))
+    return dict(hint=hint, bits=bits, G=G, axis=axis, Gq=Gq, Hkv=Hkv, B=B, W=W, pool=pool, tau=tau, ragged=ragged, P=P, bound=bound,
                 counts=counts, n_app=n_app)
 
 
@@ -94,7 +95,7 @@ def test_random_walks_through_the_path(orc, block):
         if tau:
             v[..., [5, 77]] *= 10
         cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, pool_kernel=pool, budget=bound, bits=bits,
-                       group_size=G, key_axis=axis, outlier_threshold=tau)
+                       group_size=G, key_axis=axis, outlier_threshold=tau, decode_cache_hint=c["hint"])
         sm = float(np.float32(cfg.sm_scale))
         assert cfg.n_kept == bound
         n_cap = 0
