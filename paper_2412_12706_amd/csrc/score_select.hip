@@ -116,7 +116,8 @@ __global__ __launch_bounds__(kThreads, RPW == 32 ? 4 : 2) void score_pass(const 
 #define KVQP_ISSUE(chunk_)                                                                             \
     _Pragma("unroll") for (int i_ = 0; i_ < NPRE; ++i_) {                                              \
         const int key_ = min((chunk_) * CK + pre_row + 16 * i_, a.L - 1); /* rows past the end are masked */ \
-        pre[i_] = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(kh + (size_t)key_ * kHeadDim + pre_col * 8)); /* streamed: 2 GB per pass */ \
+        const u4v* src_ = reinterpret_cast<const u4v*>(kh + (size_t)key_ * kHeadDim + pre_col * 8);    \
+        pre[i_] = (PASS == PASS_VOTES) ? __builtin_nontemporal_load(src_) : *src_; /* last read of a key: streamed */ \
     }
 #define KVQP_COMMIT()                                                                                  \
     _Pragma("unroll") for (int i_ = 0; i_ < NPRE; ++i_)                                                \
