@@ -280,7 +280,8 @@ int kvqp_quantize_selected_ragged(const kvqp_cfg *cfg, const void *k, const void
  *   q   half [batch, Hq, D]
  *   out half [batch, Hq, D]   binary32 accumulation, rounded once at the end
  * cfg fields used: batch, heads, head_dim, bits, group_size, key_axis,
- * decode_splits, sm_scale.  n_kept + tail_len must be >= 1.  With head-level
+ * decode_splits, sm_scale, outlier_threshold, decode_cache_hint.
+ * n_kept + tail_len must be >= 1.  With head-level
  * counts (cache->head_n_kept non-NULL) head h attends its first
  * head_n_kept[h] tokens; the counts are read on the device, where a count
  * above n_kept is cut to n_kept and rounded down to a multiple of 32
