@@ -433,10 +433,14 @@ def main():
         "layer_wise_counts": layer_wise, "outlier_filtering": outlier_leg, "per_token_keys": token_keys,
         "sweep": sweep, "per_layer_calls": per_layer,
         "cold_memory_side_cache": cold,
+        "cold_value_gbs": None if cold is None else round(
+            sum(decode_bytes(LAYERS, c["tokens"], c["bits"], G, W) for c in cold)
+            / sum(min(c["decode_us_per_step"], c["stream_hint_decode_us_per_step"]) for c in cold) / 1e3, 1),
         "cold_note": "each launch timed alone (median of 16, HIP events around the one launch) right after 2 GiB of "
                      "other data were read, so nothing of the cache is resident in the 256 MB memory-side cache; in "
                      "the timed sweep consecutive steps re-read the same cache and up to 240 MB of it stay resident; "
-                     "stream_hint_*: the same with cfg.decode_cache_hint = KVQP_CACHE_STREAM (every load non-temporal)",
+                     "stream_hint_*: the same with cfg.decode_cache_hint = KVQP_CACHE_STREAM (every load non-temporal); "
+                     "cold_value_gbs: the sweep figure from the better of the two cold times of each setting",
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
