@@ -5,8 +5,6 @@
 
 #include "kvqp_internal.h"
 
-#include <vector>
-
 namespace kvqp {
 namespace {
 
@@ -266,17 +264,14 @@ static int append_impl(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_tokens,
     if (cache->n_kept + n_tokens > cap) return KVQP_ERR_INVALID_ARG;
     if ((rc = check_cache_ptrs(cfg, cache, cache->n_kept + n_tokens, true))) return rc;
     const int heads = cfg->batch * cfg->n_kv_heads;
-    std::vector<int32_t> grown;
     if (head_count) {
         for (int h = 0; h < heads; ++h)
             if (head_count[h] < 0 || head_count[h] > cache->n_kept || head_count[h] % quantum) return KVQP_ERR_INVALID_ARG;
-        grown.assign(head_count, head_count + heads);
-        for (int h = 0; h < heads; ++h) grown[h] += n_tokens;
     }
     hipStream_t stream = (hipStream_t)hip_stream;
     if (launch_append_tail(*cfg, *cache, n_tokens, head_count ? quantum : 0, stream) != hipSuccess) return KVQP_ERR_HIP;
     // (the new counts are stored after the quantizer, which takes its positions from the old ones)
-    if (head_count && upload_counts(cache->head_n_kept, grown.data(), heads, stream) != hipSuccess) return KVQP_ERR_HIP;
+    if (head_count && upload_counts(cache->head_n_kept, head_count, heads, stream, n_tokens) != hipSuccess) return KVQP_ERR_HIP;
     cache->n_kept += n_tokens;
     cache->tail_len -= n_tokens;
     return KVQP_OK;

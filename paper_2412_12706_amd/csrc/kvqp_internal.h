@@ -62,7 +62,7 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
                          void* ws, const DecodePlan& plan, hipStream_t stream);
 // n host integers into a device array, enqueued on the stream; src_host is read before the call returns.
 constexpr int kCountsPerLaunch = 768;   // (kernel arguments: 3 KB per launch)
-hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream_t stream);
+hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream_t stream, int add = 0);   // dst[i] = src_host[i] + add
 hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, int base_quantum, hipStream_t stream);
 // head_n (device, or NULL): every head's own cut under plan.n_kept; score says whether any head drops a token
 hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx,

@@ -621,11 +621,11 @@ __global__ void store_counts(int32_t* __restrict__ dst, CountBatch b, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = b.v[i];
 }
-hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream_t stream) {
+hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream_t stream, int add) {
     for (int i0 = 0; i0 < n; i0 += kCountsPerLaunch) {
         CountBatch b;
         const int m = n - i0 < kCountsPerLaunch ? n - i0 : kCountsPerLaunch;
-        for (int i = 0; i < m; ++i) b.v[i] = src_host[i0 + i];
+        for (int i = 0; i < m; ++i) b.v[i] = src_host[i0 + i] + add;
         for (int i = m; i < kCountsPerLaunch; ++i) b.v[i] = 0;
         hipLaunchKernelGGL(store_counts, dim3((m + 255) / 256), dim3(256), 0, stream, dst + i0, b, m);
         const hipError_t e = hipGetLastError();
