@@ -259,7 +259,7 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
     const size_t stride = (size_t)GQ * kPartStride;
     // Device-scope loads are slow (they go to the coherence point) and are kept in program order,
     // so many are put in flight per round trip: kMergeBatch partials of both of a thread's outputs.
-    constexpr int kMergeBatch = 12;
+    constexpr int kMergeBatch = 16;
     constexpr int ITEMS = (GQ * kHeadDim + kThreads - 1) / kThreads;
     float M[ITEMS], acc[ITEMS], L[ITEMS];
 #pragma unroll
@@ -271,9 +271,17 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
             const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
             const int h = item / kHeadDim, d = item % kHeadDim;
 #pragma unroll
-            for (int u = 0; u < kMergeBatch; ++u) {
-                const float* q = base + (size_t)h * kPartStride + (size_t)min(s0 + u, a.n_partials - 1) * stride;
-                m[it][u] = ld_dev(q); l[it][u] = ld_dev(q + 1); o[it][u] = ld_dev(q + 2 + d);
+            for (int u4 = 0; u4 < kMergeBatch; u4 += 4) {
+                if (s0 + u4 < a.n_partials) {          // (uniform: whole groups of four beyond the last partial are not fetched)
+#pragma unroll
+                    for (int u = u4; u < u4 + 4; ++u) {
+                        const float* q = base + (size_t)h * kPartStride + (size_t)min(s0 + u, a.n_partials - 1) * stride;
+                        m[it][u] = ld_dev(q); l[it][u] = ld_dev(q + 1); o[it][u] = ld_dev(q + 2 + d);
+                    }
+                } else {
+#pragma unroll
+                    for (int u = u4; u < u4 + 4; ++u) { m[it][u] = kNegBig; l[it][u] = 0.f; o[it][u] = 0.f; }
+                }
             }
         }
 #pragma unroll
