@@ -1294,10 +1294,10 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         // is one resident round: as many workgroups as the chip holds at the kernel's occupancy.
         const int n_cu = cu_count();
         // Waves a head may use: its share of what the chip holds at this kernel's occupancy, but no
-        // fewer than two 64-token chunks per wave (below that the fixed costs win).
+        // more than it has 64-token chunks.
         const int max_nw = pipe_max_waves(cfg.bits, gq, outliers_on(cfg));
         int waves = (n_cu * max_nw) / heads;
-        if (waves > n_chunks / 2) waves = n_chunks / 2;
+        if (waves > n_chunks) waves = n_chunks;
         int splits, nw;
         if (cfg.decode_splits > 0) {            // caller's choice: that many four-wave workgroups
             splits = cfg.decode_splits < n_chunks ? cfg.decode_splits : n_chunks;
@@ -1307,6 +1307,10 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
             nw = waves / kWaves * kWaves;
         } else {                                // several workgroups per head: small ones while CUs are left over
             nw = (int)((long long)waves * heads / n_cu) / kWaves * kWaves;
+            // (the last workgroup of a head fetches sixteen partials per round trip: larger workgroups
+            // rather than more of them while that keeps a head within one round)
+            const int nw16 = ((waves + 15) / 16 + kWaves - 1) / kWaves * kWaves;
+            if (nw < nw16) nw = nw16;
             if (nw > max_nw) nw = max_nw;
             if (nw < kWaves) nw = kWaves;
             splits = (waves + nw - 1) / nw;
