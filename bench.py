@@ -224,23 +224,27 @@ def main():
             us = a.elapsed_time(bq) * 1e3 / reps
             b = decode_bytes(LAYERS, s["n_kept"], s["bits"], G, W)
             # the same 32 launches recorded once in a HIP graph and replayed (no host work per launch)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                for l in range(LAYERS):
-                    kvqp.decode_attn(cfg1, queries[0][l:l + 1], caches[l], out[l:l + 1], ws1)
-            graph.replay()
-            torch.cuda.synchronize()
-            g0, g1 = ev(), ev()
-            g0.record()
-            for rep in range(reps):
+            us_g = None
+            try:
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for l in range(LAYERS):
+                        kvqp.decode_attn(cfg1, queries[0][l:l + 1], caches[l], out[l:l + 1], ws1)
                 graph.replay()
-            g1.record()
-            torch.cuda.synchronize()
-            us_g = g0.elapsed_time(g1) * 1e3 / reps
-            del graph
+                torch.cuda.synchronize()
+                g0, g1 = ev(), ev()
+                g0.record()
+                for rep in range(reps):
+                    graph.replay()
+                g1.record()
+                torch.cuda.synchronize()
+                us_g = g0.elapsed_time(g1) * 1e3 / reps
+                del graph
+            except RuntimeError as e:       # (a leg outside the timed steps must not take the benchmark down)
+                print(f"bench.py: graph replay of the per-layer calls skipped: {e}", file=sys.stderr)
             per_layer.append({"tokens": s["n_kept"], "bits": s["bits"], "decode_us_per_step": round(us, 1),
-                              "decode_gbs": round(b / (us * 1e-6) / 1e9, 1), "graph_us_per_step": round(us_g, 1),
-                              "graph_gbs": round(b / (us_g * 1e-6) / 1e9, 1)})
+                              "decode_gbs": round(b / (us * 1e-6) / 1e9, 1), "graph_us_per_step": None if us_g is None else round(us_g, 1),
+                              "graph_gbs": None if us_g is None else round(b / (us_g * 1e-6) / 1e9, 1)})
 
         # ---- decode-time cache update (outside the timed steps): 32 decoded tokens per layer move from the
         # full-precision tail into the 4-bit part of a cache laid out with room to grow ----
