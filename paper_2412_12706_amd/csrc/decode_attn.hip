@@ -91,6 +91,7 @@ __device__ __forceinline__ T stream_load(const char* p) {
     else return *reinterpret_cast<const T*>(p);
 }
 template <bool B> struct BoolC { static constexpr bool value = B; };
+template <int I> struct BoolI { static constexpr int value = I; };
 
 __device__ __forceinline__ h2v as_h2(uint32_t u) { union { uint32_t u; h2v h; } c; c.u = u; return c.h; }
 __device__ __forceinline__ uint32_t as_u32(h2v h) { union { uint32_t u; h2v h; } c; c.h = h; return c.u; }
@@ -629,7 +630,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     auto dword_at = [](const char* base, uint32_t off, auto nt) { return stream_load<uint32_t, decltype(nt)::value>(base + off); };
     // Loads are unconditional (indices clamped to valid blocks) so that the loop body is
     // straight-line code and the hardware wait counters can be tracked exactly.
-    auto load_A_as = [&](int chunk, auto nt) {
+    // A block's loads come in two parts: the key side (codes, key scales / zeros, key outlier slots)
+    // and the value side (codes, value scales / zeros, value outlier slots).
+    auto load_Ak_as = [&](int chunk, auto nt) {
         const int tb = chunk * kChunk;
         load_k(tb + 0, ak0, nt); load_k(tb + 16, ak1, nt);
         if constexpr (QUANT) {
@@ -642,16 +645,19 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
 #pragma unroll
                 for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_off, nt);
             }
+        }
+        if constexpr (OUT) { const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); a_ko = make_uint2(w[0], w[1]); }
+    };
+    auto load_Av_as = [&](int chunk, auto nt) {
+        const int tb = chunk * kChunk;
+        if constexpr (QUANT) {
             a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
             a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
         }
-        if constexpr (OUT) {
-            { const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); a_ko = make_uint2(w[0], w[1]); }
-            { const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); a_vo = make_uint2(w[0], w[1]); }
-        }
+        if constexpr (OUT) { const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); a_vo = make_uint2(w[0], w[1]); }
         load_v((BITS == 2) ? chunk : 2 * chunk, av, nt);
     };
-    auto load_B_as = [&](int chunk, bool two, auto nt) {
+    auto load_Bk_as = [&](int chunk, bool two, auto nt) {
         const int tb = chunk * kChunk + (two ? 32 : 0);
         load_k(tb + 0, bk0, nt); load_k(tb + 16, bk1, nt);
         if constexpr (QUANT) {
@@ -659,26 +665,46 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                 b_ks = dword_at(ks, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
                 b_kz = dword_at(kz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
             } else if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_off, nt);
+        }
+        if constexpr (OUT) { const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); b_ko = make_uint2(w[0], w[1]); }
+    };
+    auto load_Bv_as = [&](int chunk, bool two, auto nt) {
+        const int tb = chunk * kChunk + (two ? 32 : 0);
+        if constexpr (QUANT) {
             b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
             b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
         }
-        if constexpr (OUT) {
-            { const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); b_ko = make_uint2(w[0], w[1]); }
-            { const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); b_vo = make_uint2(w[0], w[1]); }
-        }
+        if constexpr (OUT) { const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); b_vo = make_uint2(w[0], w[1]); }
         if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv, nt);
     };
     // Chunks from a.stream_from on are read with the non-temporal hint (wave-uniform choice; a 16-bit
     // cache never is).  The empty statements keep the two arms apart: merged, the loads would lose
     // the hint.
     constexpr bool MIX = QUANT;
+    auto streamed = [&](int chunk) { return MIX && chunk >= a.stream_from; };
+    auto load_Ak = [&](int chunk) {
+        if (streamed(chunk)) { asm volatile("; streamed"); load_Ak_as(chunk, BoolC<true>{}); asm volatile("; streamed"); }
+        else load_Ak_as(chunk, BoolC<false>{});
+    };
+    auto load_Av = [&](int chunk) {
+        if (streamed(chunk)) { asm volatile("; streamed"); load_Av_as(chunk, BoolC<true>{}); asm volatile("; streamed"); }
+        else load_Av_as(chunk, BoolC<false>{});
+    };
+    auto load_Bk = [&](int chunk, bool two) {
+        if (streamed(chunk)) { asm volatile("; streamed"); load_Bk_as(chunk, two, BoolC<true>{}); asm volatile("; streamed"); }
+        else load_Bk_as(chunk, two, BoolC<false>{});
+    };
+    auto load_Bv = [&](int chunk, bool two) {
+        if (streamed(chunk)) { asm volatile("; streamed"); load_Bv_as(chunk, two, BoolC<true>{}); asm volatile("; streamed"); }
+        else load_Bv_as(chunk, two, BoolC<false>{});
+    };
     auto load_A = [&](int chunk) {
-        if (MIX && chunk >= a.stream_from) { asm volatile("; streamed"); load_A_as(chunk, BoolC<true>{}); asm volatile("; streamed"); }
-        else load_A_as(chunk, BoolC<false>{});
+        if (streamed(chunk)) { asm volatile("; streamed"); load_Ak_as(chunk, BoolC<true>{}); load_Av_as(chunk, BoolC<true>{}); asm volatile("; streamed"); }
+        else { load_Ak_as(chunk, BoolC<false>{}); load_Av_as(chunk, BoolC<false>{}); }
     };
     auto load_B = [&](int chunk, bool two) {
-        if (MIX && chunk >= a.stream_from) { asm volatile("; streamed"); load_B_as(chunk, two, BoolC<true>{}); asm volatile("; streamed"); }
-        else load_B_as(chunk, two, BoolC<false>{});
+        if (streamed(chunk)) { asm volatile("; streamed"); load_Bk_as(chunk, two, BoolC<true>{}); load_Bv_as(chunk, two, BoolC<true>{}); asm volatile("; streamed"); }
+        else { load_Bk_as(chunk, two, BoolC<false>{}); load_Bv_as(chunk, two, BoolC<false>{}); }
     };
     auto lds_put = [&](int off, uint32_t v) { *reinterpret_cast<uint32_t*>(stage + off + row_lane) = v; };
     auto lds_put_v = [&](int off, uint32_t v) { if (lane < VROW / 4) *reinterpret_cast<uint32_t*>(stage + off + row_lane) = v; };
@@ -702,18 +728,58 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         }
     };
 
-    // one 32-token block: QK product, online softmax update, PV product
-    auto compute = [&](const KWords<BITS>& k0, const KWords<BITS>& k1, uint32_t r_ks, uint32_t r_kz, bool new_group, float bias,
-                       const VWords<BITS>& vv, int vblk, uint32_t r_vs, uint32_t r_vz, uint2 r_ko, uint2 r_vo) {
+    // Move the softmax reference when a row maximum (already reduced over the row's lanes) asks for it.
+    auto advance_reference = [&](float mx) {
+        // The running maximum is only a scaling reference: it is moved (and O, l rescaled) when
+        // some row's maximum has grown by more than 2^kLazyLog2, so probabilities stay below that.
+        const float m_new = fmaxf(m_run, mx);
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run + kLazyLog2) != 0ull) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run *= alpha;
+#pragma unroll
+            for (int c = 0; c < NCG; ++c) oz[c] *= alpha;
+            float ar[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ar[i] = __shfl(alpha, 4 * kb + i);
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) O[t][i] *= ar[i];
+            m_run = m_new;
+            if constexpr (OUT) {
+                // the eight lanes of a row (hi / lo pair x four kb) rescale 16 channels each of its outlier terms
+                if (live_row && alpha != 1.0f) {
+                    float* p16 = oc + row8 * kHeadDim + (part * 4 + kb) * 16;
+#pragma unroll
+                    for (int c = 0; c < 16; c += 4) {
+                        float4 v = *reinterpret_cast<float4*>(p16 + c);
+                        v.x *= alpha; v.y *= alpha; v.z *= alpha; v.w *= alpha;
+                        *reinterpret_cast<float4*>(p16 + c) = v;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // (LDS serves a wave in order; this only pins the compiler)
+            }
+        }
+    };
+
+    // one 32-token block: QK product, online softmax update, PV product.  mode 0: all of it; mode 1:
+    // the logits only (into lgio); mode 2: the rest, from the logits in lgio, the reference having
+    // been moved by the caller for both blocks of the chunk at once.
+    auto compute = [&](auto mode, float (&lgio)[NT][4], const KWords<BITS>& k0, const KWords<BITS>& k1, uint32_t r_ks, uint32_t r_kz,
+                       bool new_group, float bias, const VWords<BITS>& vv, int vblk, uint32_t r_vs, uint32_t r_vz, uint2 r_ko,
+                       uint2 r_vo) {
+        constexpr int MODE = decltype(mode)::value;
         uint32_t vsr[QUANT ? NT * 2 * NCG : 1], vzr[QUANT ? NT * 2 * NCG : 1];
-        if constexpr (QUANT) {
+        if constexpr (QUANT && MODE != 2) {
             if constexpr (KT) { lds_put_v(OFF_KS, r_ks); lds_put_v(OFF_KZ, r_kz); }
             else if (new_group) lds_put(OFF_KS, r_ks);
+            if constexpr (OUT) *reinterpret_cast<uint2*>(stage + OFF_KO + lane * 8) = r_ko;
+        }
+        if constexpr (QUANT && MODE != 1) {
             lds_put_v(OFF_VS, r_vs); lds_put_v(OFF_VZ, r_vz);
-            if constexpr (OUT) {
-                *reinterpret_cast<uint2*>(stage + OFF_KO + lane * 8) = r_ko;
-                *reinterpret_cast<uint2*>(stage + OFF_VO + lane * 8) = r_vo;
-            }
+            if constexpr (OUT) *reinterpret_cast<uint2*>(stage + OFF_VO + lane * 8) = r_vo;
+        }
+        if constexpr (QUANT && MODE != 2) {
             if constexpr (KT) {
                 // (the masked query operand is re-read from LDS inside the pass loop below)
             } else if (new_group) {
@@ -736,6 +802,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                             bq[s].h[r] = __builtin_elementwise_fma(as_h2(qw[4 * s + r]), as_h2(sw[4 * s + r]), -bq[s].h[r]);
                 }
             }
+        }
+        if constexpr (QUANT && MODE != 1) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const int th = (SLOTS == 2) ? slot : t;
@@ -743,6 +811,13 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                 lds_get_strip(OFF_VZ + (16 * th + 4 * kb) * (2 * NCG), vzr + t * 2 * NCG);
             }
         }
+        float lg[NT][4];
+        if constexpr (MODE == 2) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) lg[t][i] = lgio[t][i];
+        } else {
         f4v acc0 = (f4v){0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
         if constexpr (!KT) {
 #pragma unroll
@@ -752,7 +827,6 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             }
         }
         const float bias_l2 = bias * c_bias;
-        float lg[NT][4];
         if constexpr (KT) {
             // The lane's column holds one channel group (per pass): the product with the masked query,
             // re-read from LDS rather than kept (16 registers), then scale by the token's scale of that
@@ -845,41 +919,21 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                 }
             }
         }
-        float mx = lg[0][0];
+        }   // (MODE != 2: the logits)
+        if constexpr (MODE == 1) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lg[t][i]);
-        mx = quad_rows_max(mx);
-        // The running maximum is only a scaling reference: it is moved (and O, l rescaled) when
-        // some row's maximum has grown by more than 2^kLazyLog2, so probabilities stay below that.
-        const float m_new = fmaxf(m_run, mx);
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run + kLazyLog2) != 0ull) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            l_run *= alpha;
+                for (int i = 0; i < 4; ++i) lgio[t][i] = lg[t][i];
+            return;
+        }
+        if constexpr (MODE == 0) {
+            float mx = lg[0][0];
 #pragma unroll
-            for (int c = 0; c < NCG; ++c) oz[c] *= alpha;
-            float ar[4];
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ar[i] = __shfl(alpha, 4 * kb + i);
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) O[t][i] *= ar[i];
-            m_run = m_new;
-            if constexpr (OUT) {
-                // the eight lanes of a row (hi / lo pair x four kb) rescale 16 channels each of its outlier terms
-                if (live_row && alpha != 1.0f) {
-                    float* p16 = oc + row8 * kHeadDim + (part * 4 + kb) * 16;
-#pragma unroll
-                    for (int c = 0; c < 16; c += 4) {
-                        float4 v = *reinterpret_cast<float4*>(p16 + c);
-                        v.x *= alpha; v.y *= alpha; v.z *= alpha; v.w *= alpha;
-                        *reinterpret_cast<float4*>(p16 + c) = v;
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // (LDS serves a wave in order; this only pins the compiler)
-            }
+                for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lg[t][i]);
+            advance_reference(quad_rows_max(mx));
         }
         float p[NT][4];
 #pragma unroll
@@ -985,6 +1039,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     // on their way before anything waits); the 16-bit variant, whose blocks are four times larger,
     // runs faster when it asks at the top of the chunk's own iteration.
     constexpr bool kEarlyB = QUANT;
+    constexpr bool kJoint = BITS == 2 && !KT && !OUT;   // (the variant bound by instruction issue: see the loop)
     if (chunk < c_end) { load_A(chunk); if (kEarlyB) load_B(chunk, two); }   // issued before anything else waits on memory
     // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
     // (head row, channel block kb).  The quantized variants park them in LDS (same for every wave)
@@ -1078,16 +1133,46 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             bias0 = quad_rows_add(zc[0]);                     // rows >= NGRP are zero, so the sum is a broadcast
             if constexpr (NGRP == 2) bias1 = quad_rows_add(zc[1]);
         }
-        compute(ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, a_vs, a_vz, a_ko, a_vo);
-        if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
-        // both blocks of the wave's next chunk are requested while this chunk's second block is computed
         const bool has_next = next < c_end;
         const int nx = has_next ? next : chunk;
         const bool two_nx = n_kept - nx * kChunk >= kChunk;
-        if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; slot_off = 0; }   // (wave-uniform; the loop ends after this pass)
-        load_A(nx);
-        if (two) compute(bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz, b_ko, b_vo);
-        if (kEarlyB) load_B(nx, two_nx);
+        float lgA[NT][4], lgB[NT][4];
+        const uint2 no_slots = make_uint2(0u, 0u);
+        if constexpr (kJoint) {
+            // Both blocks' logits first, one move of the reference for the whole chunk, then both
+            // blocks' softmax and PV products: one check per chunk instead of two, and each half of
+            // the next chunk's loads leaves as soon as its registers are free.
+            compute(BoolI<1>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, 0u, 0u, no_slots, no_slots);
+            if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; slot_off = 0; }   // (wave-uniform; the loop ends after this pass)
+            load_Ak(nx);
+            float mx = lgA[0][0];
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lgA[t][i]);
+            if (two) {
+                compute(BoolI<1>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, 1, 0u, 0u, no_slots, no_slots);
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lgB[t][i]);
+            }
+            load_Bk(nx, two_nx);
+            advance_reference(quad_rows_max(mx));
+            compute(BoolI<2>{}, lgA, ak0, ak1, 0u, 0u, true, 0.f, av, 0, a_vs, a_vz, no_slots, no_slots);
+            bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
+            load_Av(nx);
+            if (two) compute(BoolI<2>{}, lgB, bk0, bk1, 0u, 0u, false, 0.f, bv, 1, b_vs, b_vz, no_slots, no_slots);
+            load_Bv(nx, two_nx);
+        } else {
+            compute(BoolI<0>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, a_vs, a_vz, a_ko, a_vo);
+            if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
+            // both blocks of the wave's next chunk are requested while this chunk's second block is computed
+            if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; slot_off = 0; }   // (wave-uniform; the loop ends after this pass)
+            load_A(nx);
+            if (two) compute(BoolI<0>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz, b_ko, b_vo);
+            if (kEarlyB) load_B(nx, two_nx);
+        }
         chunk = next; two = two_nx;
     }
 
