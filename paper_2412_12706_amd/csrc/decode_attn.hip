@@ -1039,7 +1039,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     // on their way before anything waits); the 16-bit variant, whose blocks are four times larger,
     // runs faster when it asks at the top of the chunk's own iteration.
     constexpr bool kEarlyB = QUANT;
-    constexpr bool kJoint = BITS == 2 && !KT && !OUT;   // (the variant bound by instruction issue: see the loop)
+    constexpr bool kJoint = QUANT && !KT && !OUT;   // (per-channel keys without outlier slots: see the loop)
     if (chunk < c_end) { load_A(chunk); if (kEarlyB) load_B(chunk, two); }   // issued before anything else waits on memory
     // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
     // (head row, channel block kb).  The quantized variants park them in LDS (same for every wave)
@@ -1151,7 +1151,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
 #pragma unroll
                 for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lgA[t][i]);
             if (two) {
-                compute(BoolI<1>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, 1, 0u, 0u, no_slots, no_slots);
+                compute(BoolI<1>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, 0, 0u, 0u, no_slots, no_slots);
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -1160,9 +1160,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             load_Bk(nx, two_nx);
             advance_reference(quad_rows_max(mx));
             compute(BoolI<2>{}, lgA, ak0, ak1, 0u, 0u, true, 0.f, av, 0, a_vs, a_vz, no_slots, no_slots);
-            bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
+            if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
             load_Av(nx);
-            if (two) compute(BoolI<2>{}, lgB, bk0, bk1, 0u, 0u, false, 0.f, bv, 1, b_vs, b_vz, no_slots, no_slots);
+            if (two) compute(BoolI<2>{}, lgB, bk0, bk1, 0u, 0u, false, 0.f, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz, no_slots, no_slots);
             load_Bv(nx, two_nx);
         } else {
             compute(BoolI<0>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, a_vs, a_vz, a_ko, a_vo);
