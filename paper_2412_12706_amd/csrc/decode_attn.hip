@@ -568,6 +568,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     const uint32_t sel_even = slot ? 0x01000C0Cu : 0x0C0C0100u;   // low half-word of the pair
     const uint32_t sel_odd = slot ? 0x03020C0Cu : 0x0C0C0302u;    // high half-word of the pair
     (void)lo_mask; (void)slot_mask; (void)sel_even; (void)sel_odd;
+    const uint32_t zrow_mask = (n < NGRP) ? 0xFFFFFFFFu : 0u;   // rows of the zero-term product that hold a key group
+    (void)zrow_mask;
     const float c_logit = a.sm_scale * kLog2e * kCodeUnit;
     const float c_bias = a.sm_scale * kLog2e;
     // per-token keys: the channel group of the lane's column, whether the lane's 32 channels lie in
@@ -1127,7 +1129,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             for (int s = 0; s < 4; ++s) {
                 Frag zf, qf;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) { zf.u[r] = (n < NGRP) ? zw[4 * s + r] : 0u; qf.u[r] = qw[4 * s + r]; }
+                for (int r = 0; r < 4; ++r) { zf.u[r] = zw[4 * s + r] & zrow_mask; qf.u[r] = qw[4 * s + r]; }
                 zc = __builtin_amdgcn_mfma_f32_16x16x32_f16(zf.v, qf.v, zc, 0, 0, 0);
             }
             bias0 = quad_rows_add(zc[0]);                     // rows >= NGRP are zero, so the sum is a broadcast
