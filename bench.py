@@ -410,7 +410,9 @@ def main():
         "algorithmic_bytes_per_launch": dom_r["bytes_per_step"], "launch_us": dom_r["decode_us_per_step"],
         "roofline_time_us": max(dom_r["t_hbm_us"], dom_r["t_plain_alu_us"]),
         "note": "the products run on the matrix cores with the codes as operands, so the plain-ALU bound does not "
-                "apply; at 2 bits the measured limit is vector-instruction issue for operand preparation",
+                "apply; at 2 bits the measured limit is vector-instruction issue for operand preparation; in the timed loop "
+                "consecutive steps re-read the same cache and part of the bytes comes from the 256 MB memory-side cache "
+                "(the traffic counter sits before it): cold_memory_side_cache has the launches with nothing resident",
     }
 
     # ---- what a plain device copy reaches on this machine (1 GiB read + 1 GiB written per copy) ----
