@@ -820,108 +820,108 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
 #pragma unroll
                 for (int i = 0; i < 4; ++i) lg[t][i] = lgio[t][i];
         } else {
-        f4v acc0 = (f4v){0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
-        if constexpr (!KT) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq[s].v, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq[s].v, acc1, 0, 0, 0);
-            }
-        }
-        const float bias_l2 = bias * c_bias;
-        if constexpr (KT) {
-            // The lane's column holds one channel group (per pass): the product with the masked query,
-            // re-read from LDS rather than kept (16 registers), then scale by the token's scale of that
-            // group and add its zero term.  One tile's strips at a time (16 registers), and only the
-            // slot's own tile where the other one is not needed.
-            constexpr bool kBothTiles = SLOTS == 1 || NCG == 4;
-            float tt[2][4];
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) tt[t][i] = 0.f;
-#pragma unroll
-            for (int ps = 0; ps < KP; ++ps) {
-                acc0 = (f4v){0.f, 0.f, 0.f, 0.f}; acc1 = acc0;
+            f4v acc0 = (f4v){0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+            if constexpr (!KT) {
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    const uint4 v = sqpos[(ps * 4 + s) * 64 + lane];
-                    Frag bqs;
-                    bqs.u[0] = v.x; bqs.u[1] = v.y; bqs.u[2] = v.z; bqs.u[3] = v.w;
-                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bqs.v, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bqs.v, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bq[s].v, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bq[s].v, acc1, 0, 0, 0);
+                }
+            }
+            const float bias_l2 = bias * c_bias;
+            if constexpr (KT) {
+                // The lane's column holds one channel group (per pass): the product with the masked query,
+                // re-read from LDS rather than kept (16 registers), then scale by the token's scale of that
+                // group and add its zero term.  One tile's strips at a time (16 registers), and only the
+                // slot's own tile where the other one is not needed.
+                constexpr bool kBothTiles = SLOTS == 1 || NCG == 4;
+                float tt[2][4];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) tt[t][i] = 0.f;
+#pragma unroll
+                for (int ps = 0; ps < KP; ++ps) {
+                    acc0 = (f4v){0.f, 0.f, 0.f, 0.f}; acc1 = acc0;
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        const uint4 v = sqpos[(ps * 4 + s) * 64 + lane];
+                        Frag bqs;
+                        bqs.u[0] = v.x; bqs.u[1] = v.y; bqs.u[2] = v.z; bqs.u[3] = v.w;
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k0, s).v, bqs.v, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(k_frag<BITS>(k1, s).v, bqs.v, acc1, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        if (!kBothTiles && t != 0) continue;
+                        const int tile = kBothTiles ? t : slot;
+                        uint32_t ksr[2 * NCG], kzr[2 * NCG];
+                        lds_get_strip(OFF_KS + (16 * tile + 4 * kb) * (2 * NCG), ksr);
+                        lds_get_strip(OFF_KZ + (16 * tile + 4 * kb) * (2 * NCG), kzr);
+                        auto at = [&](const uint32_t* w, int i) -> float {   // half (token i, the column's group) of the strip
+                            if constexpr (NCG == 4) {
+                                return (float)as_h2(__builtin_amdgcn_perm(w[2 * i + 1], w[2 * i], kt_sel[ps]))[0];
+                            } else if constexpr (NCG == 2) {
+                                return (float)as_h2(__builtin_amdgcn_perm(w[i], w[i], kt_sel[ps]))[0];
+                            } else {
+                                return (float)as_h2(w[i >> 1])[i & 1];
+                            }
+                        };
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float acc = kBothTiles ? (t ? acc1[i] : acc0[i]) : (slot ? acc1[i] : acc0[i]);
+                            tt[t][i] += __builtin_fmaf(acc, at(ksr, i), at(kzr, i) * kt_qs[ps]);
+                        }
+                    }
                 }
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    if (!kBothTiles && t != 0) continue;
-                    const int tile = kBothTiles ? t : slot;
-                    uint32_t ksr[2 * NCG], kzr[2 * NCG];
-                    lds_get_strip(OFF_KS + (16 * tile + 4 * kb) * (2 * NCG), ksr);
-                    lds_get_strip(OFF_KZ + (16 * tile + 4 * kb) * (2 * NCG), kzr);
-                    auto at = [&](const uint32_t* w, int i) -> float {   // half (token i, the column's group) of the strip
-                        if constexpr (NCG == 4) {
-                            return (float)as_h2(__builtin_amdgcn_perm(w[2 * i + 1], w[2 * i], kt_sel[ps]))[0];
-                        } else if constexpr (NCG == 2) {
-                            return (float)as_h2(__builtin_amdgcn_perm(w[i], w[i], kt_sel[ps]))[0];
-                        } else {
-                            return (float)as_h2(w[i >> 1])[i & 1];
-                        }
-                    };
+                for (int i = 0; i < 4; ++i) {
+                    if constexpr (SLOTS == 2 && NCG == 4) {          // four columns per head: both tiles are summed, then the slot's is kept
+                        float t0 = tt[0][i], t1 = tt[1][i];
+                        t0 += pair_other(t0); t1 += pair_other(t1);
+                        t0 += row_ror8(t0); t1 += row_ror8(t1);
+                        lg[0][i] = (slot ? t1 : t0) * c_logit;
+                    } else if constexpr (SLOTS == 2) {
+                        float s = tt[0][i];
+                        s += pair_other(s);
+                        lg[0][i] = s * c_logit;
+                    } else {
+                        float t0 = tt[0][i], t1 = tt[1][i];
+                        t0 += pair_other(t0); t1 += pair_other(t1);
+                        lg[0][i] = t0 * c_logit; lg[NT - 1][i] = t1 * c_logit;
+                    }
+                }
+            } else
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (SLOTS == 2) {
+                    float s = slot ? acc1[i] : acc0[i];
+                    s += pair_other(s);
+                    lg[0][i] = __builtin_fmaf(s, c_logit, bias_l2);
+                } else {
+                    float s0 = acc0[i], s1 = acc1[i];
+                    s0 += pair_other(s0); s1 += pair_other(s1);
+                    lg[0][i] = __builtin_fmaf(s0, c_logit, bias_l2);
+                    lg[NT - 1][i] = __builtin_fmaf(s1, c_logit, bias_l2);
+                }
+            }
+            if constexpr (OUT) {
+                // key outliers of the lane's tokens: this lane takes slots 2 part, 2 part + 1, its pair the other two
+                const uint16_t* qrow = sq + h * kHeadDim;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int th = (SLOTS == 2) ? slot : t;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float acc = kBothTiles ? (t ? acc1[i] : acc0[i]) : (slot ? acc1[i] : acc0[i]);
-                        tt[t][i] += __builtin_fmaf(acc, at(ksr, i), at(kzr, i) * kt_qs[ps]);
+                        const uint2 w = *reinterpret_cast<const uint2*>(stage + OFF_KO + (16 * th + 4 * kb + i) * 16 + part * 8);
+                        float c = slot_delta(w.x) * __half2float(__ushort_as_half(qrow[w.x & 127u]));
+                        c = __builtin_fmaf(slot_delta(w.y), __half2float(__ushort_as_half(qrow[w.y & 127u])), c);
+                        c += pair_other(c);
+                        lg[t][i] = __builtin_fmaf(c, c_bias, lg[t][i]);
                     }
                 }
             }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if constexpr (SLOTS == 2 && NCG == 4) {          // four columns per head: both tiles are summed, then the slot's is kept
-                    float t0 = tt[0][i], t1 = tt[1][i];
-                    t0 += pair_other(t0); t1 += pair_other(t1);
-                    t0 += row_ror8(t0); t1 += row_ror8(t1);
-                    lg[0][i] = (slot ? t1 : t0) * c_logit;
-                } else if constexpr (SLOTS == 2) {
-                    float s = tt[0][i];
-                    s += pair_other(s);
-                    lg[0][i] = s * c_logit;
-                } else {
-                    float t0 = tt[0][i], t1 = tt[1][i];
-                    t0 += pair_other(t0); t1 += pair_other(t1);
-                    lg[0][i] = t0 * c_logit; lg[NT - 1][i] = t1 * c_logit;
-                }
-            }
-        } else
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if constexpr (SLOTS == 2) {
-                float s = slot ? acc1[i] : acc0[i];
-                s += pair_other(s);
-                lg[0][i] = __builtin_fmaf(s, c_logit, bias_l2);
-            } else {
-                float s0 = acc0[i], s1 = acc1[i];
-                s0 += pair_other(s0); s1 += pair_other(s1);
-                lg[0][i] = __builtin_fmaf(s0, c_logit, bias_l2);
-                lg[NT - 1][i] = __builtin_fmaf(s1, c_logit, bias_l2);
-            }
         }
-        if constexpr (OUT) {
-            // key outliers of the lane's tokens: this lane takes slots 2 part, 2 part + 1, its pair the other two
-            const uint16_t* qrow = sq + h * kHeadDim;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int th = (SLOTS == 2) ? slot : t;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint2 w = *reinterpret_cast<const uint2*>(stage + OFF_KO + (16 * th + 4 * kb + i) * 16 + part * 8);
-                    float c = slot_delta(w.x) * __half2float(__ushort_as_half(qrow[w.x & 127u]));
-                    c = __builtin_fmaf(slot_delta(w.y), __half2float(__ushort_as_half(qrow[w.y & 127u])), c);
-                    c += pair_other(c);
-                    lg[t][i] = __builtin_fmaf(c, c_bias, lg[t][i]);
-                }
-            }
-        }
-        }   // (MODE != 2: the logits)
         if constexpr (MODE == 1) {
 #pragma unroll
             for (int t = 0; t < NT; ++t)
