@@ -91,7 +91,10 @@ typedef struct kvqp_cfg {
  *   KVQP_CACHE_STREAM  every load non-temporal: for a caller that knows the
  *                      cache will have been evicted before it is read again
  *                      (weights and other layers pass through in between).
- *   KVQP_CACHE_KEEP    every load normal.
+ *   KVQP_CACHE_KEEP    every load normal.  A caller that issues one call per
+ *                      layer can apply the automatic rule to its whole step:
+ *                      KEEP for the layers whose caches add up to 240 MB,
+ *                      STREAM for the rest.
  * 16-bit caches are read normally whatever the hint (measured: non-temporal
  * loads are slower there).  Results do not depend on the hint.
  */
