@@ -1041,7 +1041,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     // on their way before anything waits); the 16-bit variant, whose blocks are four times larger,
     // runs faster when it asks at the top of the chunk's own iteration.
     constexpr bool kEarlyB = QUANT;
-    constexpr bool kJoint = QUANT && !KT && !OUT;   // (per-channel keys without outlier slots: see the loop)
+    constexpr bool kJoint = QUANT && !OUT && !(KT && BITS == 2);   // (where it measured faster: see the loop)
     if (chunk < c_end) { load_A(chunk); if (kEarlyB) load_B(chunk, two); }   // issued before anything else waits on memory
     // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
     // (head row, channel block kb).  The quantized variants park them in LDS (same for every wave)
