@@ -33,6 +33,19 @@ def test_every_declared_symbol_is_exported(lib):
         assert getattr(lib, n) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own, with no C++ or HIP types."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "t.c"
+    src.write_text('#include "kvqp.h"\nint main(void) { kvqp_cfg c; kvqp_cache k; (void)c; (void)k; return KVQP_OK; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_version_and_strerror(lib):
     assert kvqp.version() >= 100
     assert kvqp.strerror(0) == "ok"
