@@ -13,7 +13,7 @@ import pytest
 import torch
 
 from paper_2412_12706_amd import kvqp, synth
-from tests.gpu_util import dev, download
+from tests.gpu_util import attn_excess, attn_maxabs, dev, download
 from tests.test_gpu_compress import check_indices
 
 pytestmark = pytest.mark.gpu
@@ -273,7 +273,8 @@ def test_append_with_head_level_counts(orc, bits, G, key_axis, n_app, tau):
                 ref = getattr(oc, nm).reshape(-1)[: (grown - moved) * 128]
                 assert np.array_equal(head_share(gc, nm, np.uint16, heads, h, ref.size), ref), (nm, h)
             ref = orc.decode_attn(q[b:b + 1, g * gq:(g + 1) * gq], oc, sm)
-            err = np.abs(out[b, g * gq:(g + 1) * gq] - ref[0]) / np.maximum(1.0, np.abs(ref[0]))
-            assert err.max() <= 2e-3, (h, err.max())
+            # plain max-abs 2e-3 (with outlier slots: the checker rounded to binary16 where |ref| >= 4)
+            excess = attn_excess(out[b, g * gq:(g + 1) * gq], ref[0]) if tau else attn_maxabs(out[b, g * gq:(g + 1) * gq], ref[0]) - 2e-3
+            assert excess <= 0.0, (h, excess)
     with pytest.raises(kvqp.KvqpError):
         kvqp.append_tail_ragged(cfg, gc, n_app, counts)          # the tail no longer holds that many rows

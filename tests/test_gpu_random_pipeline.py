@@ -14,7 +14,7 @@ import pytest
 import torch
 
 from paper_2412_12706_amd import kvqp, synth
-from tests.gpu_util import dev
+from tests.gpu_util import ATTN_TOL, attn_excess, attn_maxabs, dev
 from tests.test_gpu_compress import check_indices
 from tests.test_gpu_ragged import head_share
 
@@ -72,7 +72,9 @@ def decode_and_compare(orc, cfg, gc, refs, q, ws, Hkv, gq, sm):
     for h, oc in enumerate(refs):
         b, g = h // Hkv, h % Hkv
         ref = orc.decode_attn(q[b:b + 1, g * gq:(g + 1) * gq], oc, sm)[0]
-        worst = max(worst, (np.abs(out[b, g * gq:(g + 1) * gq] - ref) / np.maximum(1.0, np.abs(ref))).max())
+        got = out[b, g * gq:(g + 1) * gq]
+        # plain max-abs; only the walks with planted value outliers (tau > 0) use the large-output allowance
+        worst = max(worst, attn_excess(got, ref) + ATTN_TOL if cfg.outlier_threshold > 0 else attn_maxabs(got, ref))
     return worst
 
 

@@ -135,6 +135,21 @@ def test_value_layout_matches_worked_examples(orc):
         assert got == 1, (bits, t, d, word, shift)
 
 
+def test_key_layout_matches_worked_examples(orc):
+    # hand-derived from the format statement (adjacent channels share a field index, low / high half-word)
+    rows = [tuple(map(int, l.split())) for l in open(os.path.join(GOLD, "k_layout_examples.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 24 and {r[0] for r in rows} == {2, 4, 8, 16}
+    for bits, t, d, word, shift in rows:
+        n_tok = 64
+        buf = np.zeros(orc.k_words(n_tok, 128, bits), np.uint32)
+        buf[word] = np.uint32((1 << shift) & 0xFFFFFFFF)
+        assert orc.k_code_at(buf, 128, bits, t, d) == 1, (bits, t, d, word, shift)
+        # and nobody else reads that bit
+        hits = sum(orc.k_code_at(buf, 128, bits, tt, dd) != 0 for tt in sorted({0, t}) for dd in range(128))
+        assert hits == 1, (bits, t, d)
+
+
 @pytest.mark.parametrize("bits", [2, 4, 8, 16])
 @pytest.mark.parametrize("D", [64, 128])
 def test_layouts_are_bijections(orc, bits, D):
