@@ -138,7 +138,7 @@ def main():
         wc, wd = kvqp.workspace_bytes(cfg)
         settings.append({
             "cfg": cfg, "cache": kvqp.alloc_cache(cfg, device=dev), "ws_c": kvqp.alloc_workspace(wc, dev),
-            "ws_d": kvqp.alloc_workspace(wd, dev), "n_kept": n_kept, "bits": bits,
+            "ws_d": kvqp.alloc_decode_workspace(cfg, dev), "n_kept": n_kept, "bits": bits,
             "t_compress_ms": 0.0, "t_decode_ms": 0.0,
         })
 
@@ -210,7 +210,7 @@ def main():
                     per = t.numel() // LAYERS
                     bufs[name] = t[l * per:(l + 1) * per]
                 caches.append(kvqp.Cache(bufs, s["cache"].n_kept, s["cache"].tail_len, s["cache"].tail_cap))
-            ws1 = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg1)[1], dev)
+            ws1 = kvqp.alloc_decode_workspace(cfg1, dev)
             reps = 8
             for rep in range(reps + 1):
                 if rep == 1:
@@ -288,7 +288,7 @@ def main():
         counts = [int(round(mean * (1.5 - l / (LAYERS - 1)) / 64)) * 64 for l in range(LAYERS)]
         cfg_r = kvqp.Cfg(**{**s4["cfg"].__dict__, "budget": max(counts)})
         rag = kvqp.alloc_cache(cfg_r, device=dev, ragged=True)
-        ws_rc, ws_rd = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_r))
+        ws_rc, ws_rd = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg_r)[0], dev), kvqp.alloc_decode_workspace(cfg_r, dev)
         head_counts = [counts[h // HKV] for h in range(LAYERS * HKV)]
         reps = 3
         for rep in range(reps + 1):
@@ -320,7 +320,7 @@ def main():
         # |x| > 6 kept beside the codes, four slot words per token row and tensor ----
         cfg_o = kvqp.Cfg(**{**s4["cfg"].__dict__, "outlier_threshold": 6.0})
         oc_cache = kvqp.alloc_cache(cfg_o, device=dev)
-        ws_oc, ws_od = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_o))
+        ws_oc, ws_od = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg_o)[0], dev), kvqp.alloc_decode_workspace(cfg_o, dev)
         reps = 3
         for rep in range(reps + 1):
             if rep == 1:
@@ -354,7 +354,7 @@ def main():
         # ---- per-token key groups (the FlexGen axis of the paper's ablation and of its head-level methods) ----
         cfg_t = kvqp.Cfg(**{**s4["cfg"].__dict__, "key_axis": kvqp.KEY_PER_TOKEN})
         tc = kvqp.alloc_cache(cfg_t, device=dev)
-        ws_tc, ws_td = (kvqp.alloc_workspace(n, dev) for n in kvqp.workspace_bytes(cfg_t))
+        ws_tc, ws_td = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg_t)[0], dev), kvqp.alloc_decode_workspace(cfg_t, dev)
         for rep in range(reps + 1):
             if rep == 1:
                 torch.cuda.synchronize()

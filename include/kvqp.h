@@ -213,7 +213,10 @@ int kvqp_workspace_bytes(const kvqp_cfg *cfg, size_t *compress_bytes, size_t *de
  *   survivors are stored in ascending position.
  *   Scores are evaluated in binary32 on the matrix cores; candidates whose
  *   pooled score lies within a relative 2e-5 of the cut are re-scored in
- *   binary64 before the cut is made.
+ *   binary64 before the cut is made.  The re-scoring holds up to 512 such
+ *   candidates and the 2048 distinct positions under their pooling windows
+ *   per head; a head with more (e.g. all keys identical) is cut by the
+ *   binary32 scores and the position rule, and says so in unrefined_out.
  * The survivors are then quantized as described at kvqp_cache.
  *
  *   q_obs  half [batch, Hq, W, D]   queries of the last W prompt positions
@@ -221,12 +224,15 @@ int kvqp_workspace_bytes(const kvqp_cfg *cfg, size_t *compress_bytes, size_t *de
  *   cache  buffers filled; n_kept and tail_len (= W) set; tail_cap must be set
  *          by the caller and be >= W
  *   idx_out int32 [batch, Hkv, n_kept] ascending survivors, or NULL
+ *   unrefined_out int32 [batch, Hkv] or NULL: per head 0 when every candidate
+ *          near the cut was re-scored in binary64 (or none needed it), else
+ *          the number of candidates near the cut that binary32 decided
  * Errors: INVALID_ARG on NULL/shape problems (incl. n_kept % G != 0 for
  * per-channel keys), UNSUPPORTED outside the supported set, WORKSPACE, HIP.
  */
 int kvqp_compress(const kvqp_cfg *cfg, const void *q_obs, const void *k, const void *v,
-                  kvqp_cache *cache, int32_t *idx_out, void *workspace, size_t workspace_bytes,
-                  void *hip_stream);
+                  kvqp_cache *cache, int32_t *idx_out, int32_t *unrefined_out, void *workspace,
+                  size_t workspace_bytes, void *hip_stream);
 
 /*
  * Compression with a token count of its own for every KV head (Section 5, Q1, and
@@ -245,6 +251,7 @@ int kvqp_compress(const kvqp_cfg *cfg, const void *q_obs, const void *k, const v
  *                n_kept is set to the bound, tail_len to W.
  *   idx_out      int32 [batch, Hkv, n_kept] or NULL: the first head_budget[h]
  *                entries of head h are its survivors, the rest is unspecified.
+ *   unrefined_out as for kvqp_compress.
  * kvqp_decode_attn reads such a cache through head_n_kept (tail_len must be
  * >= 1) and kvqp_append_tail_ragged extends it; kvqp_append_tail does not take
  * one (UNSUPPORTED), and kvqp_compress and kvqp_quantize_selected want
@@ -252,7 +259,8 @@ int kvqp_compress(const kvqp_cfg *cfg, const void *q_obs, const void *k, const v
  */
 int kvqp_compress_ragged(const kvqp_cfg *cfg, const void *q_obs, const void *k, const void *v,
                          const int32_t *head_budget, kvqp_cache *cache, int32_t *idx_out,
-                         void *workspace, size_t workspace_bytes, void *hip_stream);
+                         int32_t *unrefined_out, void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
 
 /*
  * The quantization half alone (Section 3 "KV Quantization" applied to given
@@ -289,12 +297,28 @@ int kvqp_quantize_selected_ragged(const kvqp_cfg *cfg, const void *k, const void
  * head_n_kept[h] tokens; the counts are read on the device, where a count
  * above n_kept is cut to n_kept and rounded down to a multiple of 32
  * (group_size for per-channel keys).
- * Calls of kvqp_decode_attn must not overlap in time on one device: the merge of the
- * token-axis splits uses device-wide arrival counters owned by the library (calls
- * issued on one stream never overlap).
+ * Workspace: kvqp_workspace_bytes' decode_bytes, 16-byte aligned, prepared ONCE with
+ * kvqp_decode_workspace_init before its first use.  It holds the partial results of
+ * the token-axis splits and, at its head, one arrival counter per (batch, KV head)
+ * that is zero between calls (the workgroup that merges a head puts it back).  Calls
+ * that use different workspaces are independent and may overlap in time (several
+ * streams, several graphs in flight); calls that share one workspace must not
+ * overlap (calls issued on one stream never do).
  */
 int kvqp_decode_attn(const kvqp_cfg *cfg, const void *q, const kvqp_cache *cache, void *out,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Prepares a decode workspace (the split merge of kvqp_decode_attn, Eq. (3) evaluated
+ * in token ranges): zeroes its arrival counters with a small kernel enqueued on the
+ * stream.  Needed once after allocation -- fresh device memory holds arbitrary bytes
+ * -- and again only if a kvqp_decode_attn launch on this workspace did not run to
+ * completion (device reset, aborted process).  cfg fields used: batch, n_kv_heads
+ * (the counters of a larger batch * n_kv_heads cover a smaller one).
+ * Errors: WORKSPACE when workspace is NULL or smaller than the counters.
+ */
+int kvqp_decode_workspace_init(const kvqp_cfg *cfg, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
 
 /*
  * Decode-time cache update (Section 3, Eq. (2): the new token's key and value

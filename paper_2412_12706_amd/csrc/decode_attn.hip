@@ -199,6 +199,7 @@ struct DecodeArgs {
     const uint16_t* tail_k;
     const uint16_t* tail_v;
     float* part;              // [B*Hkv, n_partials, GQ, D+2]
+    unsigned int* arrivals;   // [B*Hkv] arrival counters at the head of the workspace, zero between launches
     uint16_t* out;            // [B, Hq, D]
     int n_kept, tail_len, tail_cap;
     int n_cap;                // tokens the packed buffers are laid out for (head strides); >= n_kept
@@ -233,24 +234,30 @@ __device__ __forceinline__ int head_chunks_per_split(const DecodeArgs& a, int n_
 __device__ __forceinline__ void st_dev(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// Arrival counters, one per (batch, kv head).  Every workgroup of a head bumps its counter after
-// its partial is written; the last one to arrive merges the head's partials and puts the counter
-// back to zero, so the array is all zeros again when the launch has drained (it starts that way:
-// static storage).  Launches that overlap in time on one device would share these counters.
-__device__ unsigned int g_arrivals[65536];
-
+// Arrival counters, one per (batch, kv head), at the head of the call's workspace.  Every workgroup
+// of a head bumps its counter after its partial is written; the last one to arrive merges the
+// head's partials and puts the counter back to zero, so the counters are all zero again when the
+// launch has drained (kvqp_decode_workspace_init zeroes them once, before the first use).  Calls
+// with different workspaces share nothing and may overlap in time.
 // Merge the splits of one KV head's query heads and round once to binary16 (last workgroup only).
 template <int GQ>
 __device__ void merge_if_last(const DecodeArgs& a, int bh) {
     __shared__ int s_last;
-    // this workgroup's partial stores (device scope, write-through) must have completed
+    // Ordering of the partials before the counter, without an agent-scope release fence (which
+    // writes back the whole L2).  What this relies on, all of it stated for gfx942 / gfx950 in the
+    // AMDGPU memory model: (1) a relaxed atomic store at agent scope is a write-through store: it is
+    // performed at the device's coherence point, not left dirty in the XCD's L2; (2) vmcnt counts
+    // stores, and s_waitcnt vmcnt(0) returns only when every earlier store of the wave has been
+    // acknowledged from there; (3) the barrier after it orders every wave's wait before thread 0's
+    // read-modify-write, which is performed at the same coherence point.  A workgroup that sees the
+    // bumped counter therefore finds the partials with agent-scope loads (which do not hit in its L2).
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-        const unsigned prev = __hip_atomic_fetch_add(&g_arrivals[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned prev = __hip_atomic_fetch_add(&a.arrivals[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int last = prev == (unsigned)(a.n_partials - 1);
-        if (last) __hip_atomic_store(&g_arrivals[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (last) __hip_atomic_store(&a.arrivals[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = last;
     }
     __syncthreads();
@@ -1362,13 +1369,17 @@ static int cu_count() {
 // Workspace that covers the plan of every cache of this cfg's batch, heads and bits, whatever its
 // token count: no plan has more splits than the head's share of the chip in four-wave workgroups
 // (or the caller's decode_splits).
+size_t decode_ws_header_bytes(const kvqp_cfg& cfg) {
+    return ((size_t)cfg.batch * cfg.n_kv_heads * sizeof(unsigned int) + 255) / 256 * 256;
+}
+
 size_t decode_ws_bound(const kvqp_cfg& cfg) {
     const int heads = cfg.batch * cfg.n_kv_heads, gq = cfg.n_q_heads / cfg.n_kv_heads;
     const int share = (cu_count() * pipe_max_waves(cfg.bits, gq, outliers_on(cfg))) / heads;
     int splits = (share + kWaves - 1) / kWaves;
     if (cfg.decode_splits > splits) splits = cfg.decode_splits;
     if (splits < 1) splits = 1;
-    return (size_t)heads * splits * gq * kPartStride * sizeof(float);
+    return decode_ws_header_bytes(cfg) + (size_t)heads * splits * gq * kPartStride * sizeof(float);
 }
 
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
@@ -1409,8 +1420,19 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         p.n_splits = p.chunks_per_split ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 1;
         p.n_partials = p.n_splits;
     }
-    p.ws_bytes = (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartStride * sizeof(float);
+    p.ws_bytes = decode_ws_header_bytes(cfg) + (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartStride * sizeof(float);
     return p;
+}
+
+// Zeroes the arrival counters of a workspace (a fill kernel, not a memset node: callers may capture it).
+__global__ void zero_words(unsigned int* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+hipError_t launch_ws_init(const kvqp_cfg& cfg, void* ws, hipStream_t stream) {
+    const int n = (int)(decode_ws_header_bytes(cfg) / sizeof(unsigned int));
+    hipLaunchKernelGGL(zero_words, dim3((n + 255) / 256), dim3(256), 0, stream, (unsigned int*)ws, n);
+    return hipGetLastError();
 }
 
 hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c, void* out, void* ws,
@@ -1421,7 +1443,8 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.k_scale = (const uint16_t*)c.k_scale; a.k_zero = (const uint16_t*)c.k_zero;
     a.v_scale = (const uint16_t*)c.v_scale; a.v_zero = (const uint16_t*)c.v_zero;
     a.tail_k = (const uint16_t*)c.tail_k; a.tail_v = (const uint16_t*)c.tail_v;
-    a.part = (float*)ws;
+    a.arrivals = (unsigned int*)ws;
+    a.part = (float*)(static_cast<char*>(ws) + decode_ws_header_bytes(cfg));
     a.out = (uint16_t*)out;
     a.n_kept = c.n_kept; a.tail_len = c.tail_len; a.tail_cap = c.tail_cap;
     a.n_cap = c.n_cap > 0 ? c.n_cap : c.n_kept;

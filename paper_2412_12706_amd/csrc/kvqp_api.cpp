@@ -29,7 +29,7 @@ int check_common(const kvqp_cfg* c) {
     if (c->head_dim != kHeadDim) return KVQP_ERR_UNSUPPORTED;
     if (!(gq == 1 || gq == 2 || gq == 4 || gq == 8)) return KVQP_ERR_UNSUPPORTED;
     if (c->bits != 16 && !is_pow2_group(c->group_size)) return KVQP_ERR_UNSUPPORTED;
-    if ((long long)c->batch * c->n_kv_heads > 65535) return KVQP_ERR_UNSUPPORTED;
+    if ((long long)c->batch * c->n_kv_heads > 65535) return KVQP_ERR_UNSUPPORTED;   // (batch, kv head) is the y index of every launch
     return KVQP_OK;
 }
 
@@ -201,7 +201,8 @@ int kvqp_quantize_selected_ragged(const kvqp_cfg* cfg, const void* k, const void
 
 // Both forms of compression: head_budget == NULL is the uniform one.
 static int compress_impl(const kvqp_cfg* cfg, const void* q_obs, const void* k, const void* v, const int32_t* head_budget,
-                         kvqp_cache* cache, int32_t* idx_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                         kvqp_cache* cache, int32_t* idx_out, int32_t* unrefined_out, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
     int rc = check_common(cfg);
     if (rc) return rc;
     if ((rc = check_prompt(cfg))) return rc;
@@ -225,8 +226,9 @@ static int compress_impl(const kvqp_cfg* cfg, const void* q_obs, const void* k, 
     hipStream_t stream = (hipStream_t)hip_stream;
     int32_t* idx = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.off_idx);
     if (head_budget && upload_counts(cache->head_n_kept, head_budget, heads, stream) != hipSuccess) return KVQP_ERR_HIP;
+    if (n_kept == 0 && unrefined_out && upload_counts(unrefined_out, nullptr, heads, stream) != hipSuccess) return KVQP_ERR_HIP;   // nothing is cut
     if (n_kept > 0) {
-        if (launch_select(*cfg, q_obs, k, idx, workspace, plan, cache->head_n_kept, score, stream) != hipSuccess) return KVQP_ERR_HIP;
+        if (launch_select(*cfg, q_obs, k, idx, unrefined_out, workspace, plan, cache->head_n_kept, score, stream) != hipSuccess) return KVQP_ERR_HIP;
         if (idx_out) {
             const size_t bytes = (size_t)heads * n_kept * sizeof(int32_t);
             if (hipMemcpyAsync(idx_out, idx, bytes, hipMemcpyDeviceToDevice, stream) != hipSuccess) return KVQP_ERR_HIP;
@@ -239,14 +241,15 @@ static int compress_impl(const kvqp_cfg* cfg, const void* q_obs, const void* k, 
 }
 
 int kvqp_compress(const kvqp_cfg* cfg, const void* q_obs, const void* k, const void* v, kvqp_cache* cache,
-                  int32_t* idx_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    return compress_impl(cfg, q_obs, k, v, nullptr, cache, idx_out, workspace, workspace_bytes, hip_stream);
+                  int32_t* idx_out, int32_t* unrefined_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return compress_impl(cfg, q_obs, k, v, nullptr, cache, idx_out, unrefined_out, workspace, workspace_bytes, hip_stream);
 }
 
 int kvqp_compress_ragged(const kvqp_cfg* cfg, const void* q_obs, const void* k, const void* v, const int32_t* head_budget,
-                         kvqp_cache* cache, int32_t* idx_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                         kvqp_cache* cache, int32_t* idx_out, int32_t* unrefined_out, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
     if (!head_budget) return KVQP_ERR_INVALID_ARG;
-    return compress_impl(cfg, q_obs, k, v, head_budget, cache, idx_out, workspace, workspace_bytes, hip_stream);
+    return compress_impl(cfg, q_obs, k, v, head_budget, cache, idx_out, unrefined_out, workspace, workspace_bytes, hip_stream);
 }
 
 // Both forms of the decode-time update: head_count == NULL is the uniform one.
@@ -288,8 +291,8 @@ int kvqp_append_tail_ragged(const kvqp_cfg* cfg, kvqp_cache* cache, int32_t n_to
     return append_impl(cfg, cache, n_tokens, head_count, hip_stream);
 }
 
-int kvqp_decode_attn(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache, void* out, void* workspace,
-                     size_t workspace_bytes, void* hip_stream) {
+// Checks shared by both decode entry points; the plan comes back through *plan.
+static int check_decode(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache, const void* out, DecodePlan* plan) {
     int rc = check_common(cfg);
     if (rc) return rc;
     if (!q || !out || !cache) return KVQP_ERR_INVALID_ARG;
@@ -298,10 +301,27 @@ int kvqp_decode_attn(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache
     if (cache->head_n_kept && cache->tail_len < 1) return KVQP_ERR_INVALID_ARG;   // a head may hold no packed token at all
     if ((rc = check_n_kept(cfg, cache->n_kept))) return rc;
     if ((rc = check_cache_ptrs(cfg, cache, cache->n_kept, cache->tail_len > 0))) return rc;
-    const DecodePlan plan = plan_decode(*cfg, cache->n_kept, cache->tail_len);
+    *plan = plan_decode(*cfg, cache->n_kept, cache->tail_len);
+    return KVQP_OK;
+}
+
+int kvqp_decode_attn(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache, void* out, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+    DecodePlan plan;
+    const int rc = check_decode(cfg, q, cache, out, &plan);
+    if (rc) return rc;
     if (!workspace || workspace_bytes < plan.ws_bytes) return KVQP_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 15) != 0) return KVQP_ERR_INVALID_ARG;
     if (launch_decode(*cfg, q, *cache, out, workspace, plan, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    return KVQP_OK;
+}
+
+int kvqp_decode_workspace_init(const kvqp_cfg* cfg, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const int rc = check_common(cfg);
+    if (rc) return rc;
+    if (!workspace || workspace_bytes < decode_ws_header_bytes(*cfg)) return KVQP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15) != 0) return KVQP_ERR_INVALID_ARG;
+    if (launch_ws_init(*cfg, workspace, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
     return KVQP_OK;
 }
 

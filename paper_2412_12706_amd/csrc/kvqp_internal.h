@@ -44,6 +44,8 @@ struct DecodePlan {
 };
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len);
 size_t decode_ws_bound(const kvqp_cfg& cfg);   // >= plan_decode(cfg, n, t).ws_bytes for every n and t
+size_t decode_ws_header_bytes(const kvqp_cfg& cfg);   // arrival counters at the head of a decode workspace
+hipError_t launch_ws_init(const kvqp_cfg& cfg, void* ws, hipStream_t stream);   // zeroes them
 
 // Compress workspace layout (bytes offsets), pure function of cfg.
 struct CompressPlan {
@@ -62,10 +64,11 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
                          void* ws, const DecodePlan& plan, hipStream_t stream);
 // n host integers into a device array, enqueued on the stream; src_host is read before the call returns.
 constexpr int kCountsPerLaunch = 768;   // (kernel arguments: 3 KB per launch)
-hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream_t stream, int add = 0);   // dst[i] = src_host[i] + add
+hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream_t stream, int add = 0);   // dst[i] = src_host[i] + add (src_host == NULL: zeros)
 hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int n_tokens, int base_quantum, hipStream_t stream);
 // head_n (device, or NULL): every head's own cut under plan.n_kept; score says whether any head drops a token
-hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx,
+// unrefined (device [heads], or NULL): per head, how many candidates near the cut binary32 had to decide
+hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx, int32_t* unrefined,
                          void* ws, const CompressPlan& plan, const int32_t* head_n, bool score, hipStream_t stream);
 
 }  // namespace kvqp

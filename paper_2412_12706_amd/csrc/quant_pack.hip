@@ -625,7 +625,7 @@ hipError_t upload_counts(int32_t* dst, const int32_t* src_host, int n, hipStream
     for (int i0 = 0; i0 < n; i0 += kCountsPerLaunch) {
         CountBatch b;
         const int m = n - i0 < kCountsPerLaunch ? n - i0 : kCountsPerLaunch;
-        for (int i = 0; i < m; ++i) b.v[i] = src_host[i0 + i] + add;
+        for (int i = 0; i < m; ++i) b.v[i] = (src_host ? src_host[i0 + i] : 0) + add;
         for (int i = m; i < kCountsPerLaunch; ++i) b.v[i] = 0;
         hipLaunchKernelGGL(store_counts, dim3((m + 255) / 256), dim3(256), 0, stream, dst + i0, b, m);
         const hipError_t e = hipGetLastError();

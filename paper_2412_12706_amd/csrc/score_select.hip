@@ -281,8 +281,8 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxRows = 128;         // rows of 1024 candidates: prefixes up to 131072 tokens
 constexpr int kRegRows = 32;          // rows whose pooled scores stay in registers (prefixes up to 32768)
-constexpr int kMaxBand = 256;         // candidates re-scored per head; beyond that binary32 decides
-constexpr int kVoteSlots = 2048;       // binary64 partial votes held in LDS during the re-scoring
+constexpr int kMaxBand = 512;         // candidates re-scored per head; beyond that binary32 decides (and the caller is told)
+constexpr int kVoteSlots = 2048;       // binary64 votes (distinct positions) held in LDS during the re-scoring
 constexpr int kStageRows = 4;          // rows of votes staged in LDS per pooling step
 constexpr int kMaxPoolRadius = 31;     // pool_kernel <= 63
 constexpr float kBandRel = 2.0e-5f;   // >> the binary32 error of a vote (a few 1e-7 relative)
@@ -291,6 +291,7 @@ struct SelectArgs {
     const float* vote;      // [heads, P]
     float* pooled;          // [heads, P]
     int32_t* idx;           // [heads, n_kept]
+    int32_t* unrefined;     // [heads] or NULL: candidates near the cut that binary32 decided (0: all re-scored)
     const int32_t* head_n;  // a head's own cut (<= n_kept), or NULL for n_kept everywhere
     const uint16_t* q_obs;
     const uint16_t* k;
@@ -417,6 +418,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
     const int n_rows = (P + kSelThreads - 1) / kSelThreads;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
+    if (a.unrefined && threadIdx.x == 0) a.unrefined[head] = 0;   // (overwritten below by the same thread if binary32 decides)
     if (k <= 0) return;   // (a head-level count may be zero)
     if (k >= P) {  // budget covers the prefix: identity, the scores are not looked at
         for (int j = threadIdx.x; j < k; j += kSelThreads) idx[j] = j;
@@ -565,28 +567,21 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
         }
         __syncthreads();
         n_pos = band_off[tot_band];
-        refine = n_pos <= kSelThreads && n_pos * n_parts <= kVoteSlots;
+        refine = n_pos <= kVoteSlots;
     }
     if (refine) {
-        // ---- binary64 re-scoring: one wave per (position, 32 window rows) ----
-        for (int item = wave; item < n_pos * n_parts; item += kSelWaves) {
-            const int pos = item / n_parts, part = item % n_parts;
+        // ---- binary64 re-scoring: one wave per position, 32 window rows at a time, the parts
+        // summed in ascending order ----
+        for (int pos = wave; pos < n_pos; pos += kSelWaves) {
             int lo_c = 0, hi_c = tot_band - 1;           // owner: last member with band_off <= pos
             while (lo_c < hi_c) {
                 const int mid = (lo_c + hi_c + 1) >> 1;
                 if (band_off[mid] <= pos) lo_c = mid; else hi_c = mid - 1;
             }
             const int j = band_start[lo_c] + (pos - band_off[lo_c]);
-            const double v = vote_f64_part(a, head, j, 32 * part);
-            if (lane == 0) pos_vote[item] = v;
-        }
-        __syncthreads();
-        {   // parts summed in a fixed order, then stored over the parts
             double sum = 0.0;
-            if ((int)threadIdx.x < n_pos)
-                for (int q = 0; q < n_parts; ++q) sum += pos_vote[threadIdx.x * n_parts + q];
-            __syncthreads();
-            if ((int)threadIdx.x < n_pos) pos_vote[threadIdx.x] = sum;
+            for (int part = 0; part < n_parts; ++part) sum += vote_f64_part(a, head, j, 32 * part);
+            if (lane == 0) pos_vote[pos] = sum;
         }
         __syncthreads();
         // ---- pooled binary64 score of each member ----
@@ -631,6 +626,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
         )
     } else {
         // binary32 decides: everything above the cut, then the first need_at_cut equal to it
+        if (a.unrefined && threadIdx.x == 0) a.unrefined[head] = tot_band;
         KVQP_FOR_ROWS(
             const unsigned long long bs = __builtin_amdgcn_ballot_w64(v > cut);
             const unsigned long long bb = __builtin_amdgcn_ballot_w64(v == cut);
@@ -703,7 +699,7 @@ CompressPlan plan_compress(const kvqp_cfg& cfg) {
     return p;
 }
 
-hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx, void* ws,
+hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, int32_t* idx, int32_t* unrefined, void* ws,
                          const CompressPlan& plan, const int32_t* head_n, bool score, hipStream_t stream) {
     char* base = static_cast<char*>(ws);
     const int heads = cfg.batch * cfg.n_kv_heads;
@@ -738,7 +734,7 @@ hipError_t launch_select(const kvqp_cfg& cfg, const void* q_obs, const void* k, 
         if (e != hipSuccess) return e;
     }
     SelectArgs s;
-    s.vote = a.vote; s.pooled = reinterpret_cast<float*>(base + plan.off_pooled); s.idx = idx; s.head_n = head_n;
+    s.vote = a.vote; s.pooled = reinterpret_cast<float*>(base + plan.off_pooled); s.idx = idx; s.unrefined = unrefined; s.head_n = head_n;
     s.q_obs = a.q_obs; s.k = a.k; s.stats = stats; s.zsum = zsum;
     s.P = plan.P; s.L = cfg.seq_len; s.W = cfg.window; s.n_kept = plan.n_kept; s.pool = cfg.pool_kernel;
     s.gq = a.gq; s.n_q_heads = cfg.n_q_heads; s.n_kv_heads = cfg.n_kv_heads; s.rows = a.rows; s.rows_pad = a.rows_pad;

@@ -18,7 +18,7 @@ KEY_PER_CHANNEL = 0
 KEY_PER_TOKEN = 1
 CACHE_AUTO, CACHE_STREAM, CACHE_KEEP = 0, 1, 2     # kvqp_cfg.decode_cache_hint
 EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_outlier_sizes", "kvqp_workspace_bytes", "kvqp_compress",
-           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_append_tail_ragged", "kvqp_decode_attn", "kvqp_strerror", "kvqp_version"]
+           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_append_tail_ragged", "kvqp_decode_attn", "kvqp_decode_workspace_init", "kvqp_strerror", "kvqp_version"]
 
 
 class KvqpError(RuntimeError):
@@ -60,16 +60,17 @@ def lib():
         L.kvqp_append_tail_ragged.argtypes = [C.POINTER(CfgStruct), C.POINTER(CacheStruct), C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
         L.kvqp_workspace_bytes.argtypes = [C.POINTER(CfgStruct), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.kvqp_compress.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(CacheStruct),
-                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvqp_compress_ragged.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.POINTER(C.c_int32), C.POINTER(CacheStruct), C.c_void_p, C.c_void_p,
-                                           C.c_size_t, C.c_void_p]
+                                           C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvqp_quantize_selected.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                              C.POINTER(CacheStruct), C.c_void_p]
         L.kvqp_quantize_selected_ragged.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                                     C.POINTER(C.c_int32), C.POINTER(CacheStruct), C.c_void_p]
         L.kvqp_decode_attn.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.POINTER(CacheStruct), C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
+        L.kvqp_decode_workspace_init.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
 
@@ -196,20 +197,35 @@ def alloc_workspace(nbytes: int, device="cuda"):
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
 
 
-def compress(cfg: Cfg, q_obs, k, v, cache: Cache, idx_out=None, workspace=None, stream=None):
-    """kvqp_compress: q_obs [B,Hq,W,D], k/v [B,Hkv,L,D] half tensors on the device."""
+def decode_workspace_init(cfg: Cfg, workspace, stream=None):
+    """kvqp_decode_workspace_init: zero the arrival counters at the head of a decode workspace."""
+    rc = lib().kvqp_decode_workspace_init(C.byref(cfg.struct()), _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    if rc:
+        raise KvqpError(rc, "kvqp_decode_workspace_init")
+    return workspace
+
+
+def alloc_decode_workspace(cfg: Cfg, device="cuda", stream=None):
+    """A decode workspace of kvqp_workspace_bytes' size, prepared for its first use."""
+    return decode_workspace_init(cfg, alloc_workspace(workspace_bytes(cfg)[1], device), stream)
+
+
+def compress(cfg: Cfg, q_obs, k, v, cache: Cache, idx_out=None, workspace=None, stream=None, unrefined_out=None):
+    """kvqp_compress: q_obs [B,Hq,W,D], k/v [B,Hkv,L,D] half tensors on the device;
+    unrefined_out: int32 device tensor [B*Hkv] or None."""
     if workspace is None:
         workspace = alloc_workspace(workspace_bytes(cfg)[0], k.device)
     cs = cache.struct()
     rc = lib().kvqp_compress(C.byref(cfg.struct()), _ptr(q_obs), _ptr(k), _ptr(v), C.byref(cs), _ptr(idx_out),
-                             _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+                             _ptr(unrefined_out), _ptr(workspace), workspace.numel(), _stream_ptr(stream))
     if rc:
         raise KvqpError(rc, "kvqp_compress")
     cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
     return cache
 
 
-def compress_ragged(cfg: Cfg, q_obs, k, v, head_budget, cache: Cache, idx_out=None, workspace=None, stream=None):
+def compress_ragged(cfg: Cfg, q_obs, k, v, head_budget, cache: Cache, idx_out=None, workspace=None, stream=None,
+                    unrefined_out=None):
     """kvqp_compress_ragged: head_budget is a host sequence of batch * Hkv token counts."""
     if workspace is None:
         workspace = alloc_workspace(workspace_bytes(cfg)[0], k.device)
@@ -219,7 +235,8 @@ def compress_ragged(cfg: Cfg, q_obs, k, v, head_budget, cache: Cache, idx_out=No
     hb = (C.c_int32 * n)(*[int(x) for x in head_budget])
     cs = cache.struct()
     rc = lib().kvqp_compress_ragged(C.byref(cfg.struct()), _ptr(q_obs), _ptr(k), _ptr(v), hb, C.byref(cs),
-                                    _ptr(idx_out), _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+                                    _ptr(idx_out), _ptr(unrefined_out), _ptr(workspace), workspace.numel(),
+                                    _stream_ptr(stream))
     if rc:
         raise KvqpError(rc, "kvqp_compress_ragged")
     cache.n_kept, cache.tail_len = cs.n_kept, cs.tail_len
@@ -285,10 +302,11 @@ def decode_attn(cfg: Cfg, q, cache: Cache, out=None, workspace=None, stream=None
     if out is None:
         out = torch.empty_like(q)
     if workspace is None:
-        workspace = alloc_workspace(workspace_bytes(cfg)[1], q.device)
+        workspace = alloc_decode_workspace(cfg, q.device, stream)
     cs = cache.struct()
     rc = lib().kvqp_decode_attn(C.byref(cfg.struct()), _ptr(q), C.byref(cs), _ptr(out), _ptr(workspace),
                                 workspace.numel(), _stream_ptr(stream))
     if rc:
         raise KvqpError(rc, "kvqp_decode_attn")
     return out
+

@@ -102,18 +102,18 @@ def test_entry_points_reject_null_pointers_without_touching_the_device(lib):
     cfg = kvqp.Cfg(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024)
     cs = kvqp.CacheStruct()
     st = cfg.struct()
-    assert lib.kvqp_compress(C.byref(st), None, None, None, C.byref(cs), None, None, 0, None) == -1
-    assert lib.kvqp_compress(None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.kvqp_compress(C.byref(st), None, None, None, C.byref(cs), None, None, None, 0, None) == -1
+    assert lib.kvqp_compress(None, None, None, None, None, None, None, None, 0, None) == -1
     assert lib.kvqp_quantize_selected(C.byref(st), None, None, None, 1024, C.byref(cs), None) == -1
     assert lib.kvqp_decode_attn(C.byref(st), None, C.byref(cs), None, None, 0, None) == -1
     # plausible non-null data pointers but cache buffers missing
     fake = C.c_void_p(0x1000)
     cs.tail_cap = 32
-    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, None, 0, None) == -1
+    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, None, None, 0, None) == -1
     # complete pointers, workspace missing -> workspace error, still nothing launched
     for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
         setattr(cs, name, 0x1000)
-    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, None, 0, None) == -3
+    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, None, None, 0, None) == -3
     cs.n_kept, cs.tail_len = 1024, 32
     assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, None, 0, None) == -3
     assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 16, None) == -3
@@ -163,22 +163,22 @@ def test_head_level_count_argument_checks(lib):
     cs.tail_cap = 32
     fake = C.c_void_p(0x1000)
     call = lambda counts, cache=cs: lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(*counts),
-                                                             C.byref(cache), None, fake, 1 << 30, None)
+                                                             C.byref(cache), None, None, fake, 1 << 30, None)
     assert call([256, 96]) == -1          # per-channel keys: whole groups of 64
     assert call([256, 320]) == -1         # above the bound
     assert call([-64, 64]) == -1
-    assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, None, C.byref(cs), None, fake, 1 << 30, None) == -1
+    assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, None, C.byref(cs), None, None, fake, 1 << 30, None) == -1
     no_counts = kvqp.CacheStruct.from_buffer_copy(cs)
     no_counts.head_n_kept = None
     assert call([256, 64], no_counts) == -1
-    assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(256, 64), C.byref(cs), None, fake,
+    assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(256, 64), C.byref(cs), None, None, fake,
                                     16, None) == -3      # counts fine, workspace too small: still nothing launched
     assert lib.kvqp_quantize_selected_ragged(C.byref(st), fake, fake, fake, 256, (C.c_int32 * 2)(256, 96), C.byref(cs),
                                              None) == -1
     assert lib.kvqp_quantize_selected_ragged(C.byref(st), fake, fake, fake, 256, None, C.byref(cs), None) == -1
     assert lib.kvqp_quantize_selected(C.byref(st), fake, fake, fake, 256, C.byref(cs), None) == -1
     # uniform calls refuse a cache that carries head-level counts
-    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, fake, 1 << 30, None) == -1
+    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, None, fake, 1 << 30, None) == -1
     cs.n_kept, cs.tail_len, cs.n_cap = 256, 32, 320
     assert lib.kvqp_append_tail(C.byref(st), C.byref(cs), 64, None) == -2
     # the head-level form checks the heads' current counts before anything is enqueued
@@ -217,7 +217,7 @@ def test_outlier_filtering_argument_checks(lib):
         setattr(cs, name, 0x1000)
     cs.tail_cap = 32
     fake = C.c_void_p(0x1000)
-    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, fake, 1 << 30, None) == -1   # no slot buffers
+    assert lib.kvqp_compress(C.byref(st), fake, fake, fake, C.byref(cs), None, None, fake, 1 << 30, None) == -1   # no slot buffers
     cs.n_kept, cs.tail_len = 256, 32
     assert lib.kvqp_decode_attn(C.byref(st), fake, C.byref(cs), fake, fake, 1 << 30, None) == -1
 
@@ -251,3 +251,16 @@ def test_product_package_does_not_import_the_checker():
             if f.endswith((".py", ".hip", ".cpp", ".h")):
                 text = open(os.path.join(root, f)).read()
                 assert "oracle" not in text.lower(), f"{f} mentions the checker"
+
+
+def test_decode_workspace_init_validates_on_the_host(lib):
+    """The workspace preparation rejects bad calls before anything is enqueued (no GPU needed): it
+    wants a workspace that holds the arrival counters."""
+    cfg = kvqp.Cfg(batch=4, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024, bits=4)
+    st = cfg.struct()
+    fake = C.c_void_p(0x1000)
+    assert lib.kvqp_decode_workspace_init(None, fake, 1 << 20, None) == -1
+    assert lib.kvqp_decode_workspace_init(C.byref(st), None, 1 << 20, None) == -3
+    assert lib.kvqp_decode_workspace_init(C.byref(st), fake, 64, None) == -3            # 32 counters need 128 bytes
+    assert lib.kvqp_decode_workspace_init(C.byref(st), C.c_void_p(0x1004), 1 << 20, None) == -1
+    assert kvqp.workspace_bytes(cfg)[1] >= 256 + 32 * 4 * 130 * 4                           # counters, then partials

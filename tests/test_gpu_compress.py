@@ -78,9 +78,12 @@ def test_all_keys_equal_falls_back_to_position_order(orc):
     cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, budget=128, bits=4, group_size=32)
     gc = kvqp.alloc_cache(cfg)
     idx_dev = torch.empty((B, Hkv, 128), dtype=torch.int32, device="cuda")
-    kvqp.compress(cfg, dev(q_obs), dev(k), dev(v), gc, idx_out=idx_dev)
+    unrefined = torch.full((B * Hkv,), -1, dtype=torch.int32, device="cuda")
+    kvqp.compress(cfg, dev(q_obs), dev(k), dev(v), gc, idx_out=idx_dev, unrefined_out=unrefined)
     torch.cuda.synchronize()
     assert np.array_equal(idx_dev.cpu().numpy(), np.broadcast_to(np.arange(128, dtype=np.int32), (B, Hkv, 128)))
+    # all 768 prefix scores lie at the cut: more than the binary64 re-scoring holds, and the call says so
+    assert unrefined.cpu().tolist() == [L - W] * (B * Hkv)
 
 
 def test_compress_then_decode_end_to_end(orc):
@@ -100,3 +103,30 @@ def test_compress_then_decode_end_to_end(orc):
         out = kvqp.decode_attn(cfg, dev(q), gc)
         torch.cuda.synchronize()
         assert np.abs(out.cpu().numpy().astype(np.float64) - ref).max() <= 2e-3
+
+
+def test_ordinary_prompts_report_no_fallback_and_repeat_bit_for_bit(orc):
+    """What is reproducible run to run: survivor indices and every packed byte (no floating-point
+    atomics on that path, fixed summation orders).  Compress the same prompt three times into
+    pre-filled buffers and compare all bytes; no head may report a binary32 decision at the cut."""
+    B, Hq, Hkv, L, W = 2, 8, 2, 3000, 32
+    q_obs, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, config=43)
+    for bits, axis, tau in ((4, 0, 0.0), (2, 1, 0.0), (8, 0, 6.0)):
+        print(f"case repeat bits={bits} axis={axis} tau={tau}", flush=True)
+        cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, budget=1024, bits=bits, group_size=32,
+                       key_axis=axis, outlier_threshold=tau)
+        runs = []
+        for rep in range(3):
+            gc = kvqp.alloc_cache(cfg)
+            for t in gc.buffers.values():
+                t.fill_(0x11 * (rep + 1))
+            idx_dev = torch.full((B, Hkv, 1024), -7, dtype=torch.int32, device="cuda")
+            unrefined = torch.full((B * Hkv,), -1, dtype=torch.int32, device="cuda")
+            kvqp.compress(cfg, dev(q_obs), dev(k), dev(v), gc, idx_out=idx_dev, unrefined_out=unrefined)
+            torch.cuda.synchronize()
+            assert unrefined.cpu().tolist() == [0] * (B * Hkv)
+            runs.append((idx_dev.cpu(), {n: t.cpu() for n, t in gc.buffers.items()}))
+        for idx_r, bufs in runs[1:]:
+            assert torch.equal(idx_r, runs[0][0])
+            for n, t in bufs.items():
+                assert torch.equal(t, runs[0][1][n]), n

@@ -38,11 +38,14 @@ def test_full_size_compress_and_decode(orc, workload, n_kept, bits):
                    bits=bits, group_size=G, sm_scale=sm)
     cache = kvqp.alloc_cache(cfg, device="cuda:0")
     idx_dev = torch.empty((LAYERS, HKV, n_kept), dtype=torch.int32, device="cuda:0")
-    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev)
+    unrefined = torch.full((LAYERS * HKV,), -1, dtype=torch.int32, device="cuda:0")
+    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev, unrefined_out=unrefined)
     q = synth.decode_query_device(LAYERS, HQ, D, config=2, step=0, device="cuda:0")
     out = kvqp.decode_attn(cfg, q, cache)
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
+    # every one of the 256 heads re-scored its candidates near the cut in binary64: none fell back to binary32
+    assert int(unrefined.abs().sum().item()) == 0, unrefined.nonzero().flatten().tolist()
     idx_all = idx_dev.cpu().numpy()
     assert np.all(np.diff(idx_all, axis=-1) > 0) and idx_all.min() >= 0 and idx_all.max() < L - W
 
@@ -107,11 +110,13 @@ def test_longest_context_shape(orc):
                    bits=bits, group_size=Gc, sm_scale=sm)
     cache = kvqp.alloc_cache(cfg, device="cuda:0")
     idx_dev = torch.empty((1, HKV, n_kept), dtype=torch.int32, device="cuda:0")
-    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev)
+    unrefined = torch.full((HKV,), -1, dtype=torch.int32, device="cuda:0")
+    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev, unrefined_out=unrefined)
     q = synth.decode_query_device(1, HQ, D, config=4, step=0, device="cuda:0")
     out = kvqp.decode_attn(cfg, q, cache)
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
+    assert int(unrefined.abs().sum().item()) == 0, unrefined.tolist()      # no head fell back to binary32 at the cut
     idx_all = idx_dev.cpu().numpy()
     assert np.all(np.diff(idx_all, axis=-1) > 0) and idx_all.min() >= 0 and idx_all.max() < Lc - Wc
     heads = [1, 6]
@@ -154,11 +159,13 @@ def check_one_layer(orc, *, B, Hq, Hkv, Lc, Wc, n_kept, bits, Gc, axis, config, 
                    bits=bits, group_size=Gc, key_axis=axis, sm_scale=sm)
     cache = kvqp.alloc_cache(cfg, device="cuda:0")
     idx_dev = torch.empty((B, Hkv, n_kept), dtype=torch.int32, device="cuda:0")
-    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev)
+    unrefined = torch.full((B * Hkv,), -1, dtype=torch.int32, device="cuda:0")
+    kvqp.compress(cfg, q_obs, k, v, cache, idx_out=idx_dev, unrefined_out=unrefined)
     q = synth.decode_query_device(B, Hq, D, config=config, step=0, device="cuda:0")
     out = kvqp.decode_attn(cfg, q, cache)
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
+    assert int(unrefined.abs().sum().item()) == 0, unrefined.nonzero().flatten().tolist()   # no head fell back to binary32 at the cut
     idx_all = idx_dev.cpu().numpy()
     assert np.all(np.diff(idx_all, axis=-1) > 0) and idx_all.min() >= 0 and idx_all.max() < Lc - Wc
     for b, g in samples:

@@ -27,7 +27,7 @@ def test_decode_replays_from_a_captured_graph(orc, bits, Gq, Hkv, n_kept, splits
     gc = upload_cache(oc)
     cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, budget=n_kept, bits=bits, group_size=G,
                    decode_splits=splits, decode_cache_hint=hint)
-    ws = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg)[1])
+    ws = kvqp.alloc_decode_workspace(cfg)
     q_in = torch.zeros(B, Hq, 128, dtype=torch.float16, device="cuda")
     out = torch.empty_like(q_in)
     kvqp.decode_attn(cfg, q_in, gc, out, ws)                  # one eager call first (the library's one-time set-up)

@@ -242,7 +242,7 @@ def test_append_with_head_level_counts(orc, bits, G, key_axis, n_app, tau):
         rows = torch.from_numpy(np.ascontiguousarray(src[:, :, P:P + grown]).view(np.uint16).copy()).cuda()
         gc.buffers[name].view(torch.uint16).view(heads, cap, 128)[:, :grown] = rows.view(heads, grown, 128)
     gc.tail_len = grown
-    ws = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg)[1])
+    ws = kvqp.alloc_decode_workspace(cfg)
     kw = dict(tau=tau) if tau else {}
     for rnd in (1, 2):
         kvqp.append_tail_ragged(cfg, gc, n_app, counts)

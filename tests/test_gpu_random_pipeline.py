@@ -130,7 +130,7 @@ def test_random_walks_through_the_path(orc, block):
             compare_head(orc, gc, oc, h, heads, n, bits, tau, W)
             refs.append(oc)
             kept.append(got.reshape(-1))
-        ws = kvqp.alloc_workspace(kvqp.workspace_bytes(cfg)[1])
+        ws = kvqp.alloc_decode_workspace(cfg)
         q = synth.decode_query_host(B, Hq, D, config=500 + 10 * block + case, step=0)
         worst = decode_and_compare(orc, cfg, gc, refs, q, ws, Hkv, Gq, sm)
         print(f"    after compress: worst attention error {worst:.2e}", flush=True)
