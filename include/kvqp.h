@@ -321,6 +321,27 @@ int kvqp_decode_workspace_init(const kvqp_cfg *cfg, void *workspace, size_t work
                                void *hip_stream);
 
 /*
+ * kvqp_decode_attn for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same result, no workspace: the partial
+ * results and arrival counters of the token-axis splits live in an array of
+ * KVQP_STATIC_SCRATCH_BYTES that the library owns (static device storage, one
+ * copy per GPU the library runs on, held until the process ends).  The call
+ * allocates and frees nothing and never synchronises.
+ *   - A launch whose splits need more than KVQP_STATIC_SCRATCH_BYTES (see
+ *     kvqp_workspace_bytes' decode_bytes) returns KVQP_ERR_WORKSPACE and
+ *     launches nothing: use kvqp_decode_attn.
+ *   - Every such call on one GPU shares that GPU's array: calls that overlap
+ *     in time on one GPU (two streams, two graphs in flight) race.  Calls on
+ *     one stream never overlap.
+ *   - The first call on a GPU looks the array's address up and zeroes its
+ *     counters with a small kernel on the given stream.
+ */
+#define KVQP_STATIC_SCRATCH_BYTES (4u << 20)
+int kvqp_decode_attn_static(const kvqp_cfg *cfg, const void *q, const kvqp_cache *cache, void *out,
+                            void *hip_stream);
+
+/*
  * Decode-time cache update (Section 3, Eq. (2): the new token's key and value
  * are concatenated to the cache; the paper's quantizer, KIVI, keeps the most
  * recent tokens in full precision and quantizes them group by group).  The

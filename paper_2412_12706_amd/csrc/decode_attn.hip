@@ -27,7 +27,18 @@
 // and writes the output itself; otherwise a head is split over several
 // workgroups whose partial (m, l, O) go to the workspace, and the last one to
 // arrive merges them (no second kernel).
+#include <mutex>
+
 #include "kvqp_internal.h"
+
+// ---- library-owned decode workspace, for callers that cannot allocate device memory ----
+// One array per device that runs the library, held until the process ends.  In host code the
+// array's name is only a handle: its device address is asked for once per device
+// (hipGetSymbolAddress, with that device current) and that pointer is what kernels and fills get.
+// Each device's copy starts all zero (static storage) and every completed launch leaves the
+// arrival counters at its head zero again; they are nevertheless zeroed by a fill kernel when a
+// device's address is first taken.  Calls that use it share it: they must not overlap on one device.
+static __device__ __align__(256) unsigned char scratch[KVQP_STATIC_SCRATCH_BYTES];
 
 namespace kvqp {
 namespace {
@@ -1433,6 +1444,37 @@ hipError_t launch_ws_init(const kvqp_cfg& cfg, void* ws, hipStream_t stream) {
     const int n = (int)(decode_ws_header_bytes(cfg) / sizeof(unsigned int));
     hipLaunchKernelGGL(zero_words, dim3((n + 255) / 256), dim3(256), 0, stream, (unsigned int*)ws, n);
     return hipGetLastError();
+}
+
+// ---- the library-owned decode workspace (the array `scratch` at the top of this file) ----
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];     // per device: the address of its copy of `scratch`, or NULL
+}
+
+hipError_t static_scratch(const kvqp_cfg& cfg, void** ptr, hipStream_t stream) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        // counters for the largest head count the launches accept (a fill kernel: the call may be under capture)
+        constexpr int n = 65536;
+        static_assert((size_t)n * sizeof(unsigned int) <= kStaticScratchBytes, "counters fit the array");
+        hipLaunchKernelGGL(zero_words, dim3(n / 256), dim3(256), 0, stream, (unsigned int*)p, n);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = p;
+    }
+    (void)cfg;
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c, void* out, void* ws,

@@ -316,6 +316,17 @@ int kvqp_decode_attn(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache
     return KVQP_OK;
 }
 
+int kvqp_decode_attn_static(const kvqp_cfg* cfg, const void* q, const kvqp_cache* cache, void* out, void* hip_stream) {
+    DecodePlan plan;
+    const int rc = check_decode(cfg, q, cache, out, &plan);
+    if (rc) return rc;
+    if (plan.ws_bytes > kStaticScratchBytes) return KVQP_ERR_WORKSPACE;   // beyond the library's array: use kvqp_decode_attn
+    void* ws = nullptr;
+    if (static_scratch(*cfg, &ws, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    if (launch_decode(*cfg, q, *cache, out, ws, plan, (hipStream_t)hip_stream) != hipSuccess) return KVQP_ERR_HIP;
+    return KVQP_OK;
+}
+
 int kvqp_decode_workspace_init(const kvqp_cfg* cfg, void* workspace, size_t workspace_bytes, void* hip_stream) {
     const int rc = check_common(cfg);
     if (rc) return rc;

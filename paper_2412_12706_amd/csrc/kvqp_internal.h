@@ -46,6 +46,10 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len);
 size_t decode_ws_bound(const kvqp_cfg& cfg);   // >= plan_decode(cfg, n, t).ws_bytes for every n and t
 size_t decode_ws_header_bytes(const kvqp_cfg& cfg);   // arrival counters at the head of a decode workspace
 hipError_t launch_ws_init(const kvqp_cfg& cfg, void* ws, hipStream_t stream);   // zeroes them
+// The library's own decode workspace (a static device array): its address on the current device,
+// prepared on first use.  KVQP_STATIC_SCRATCH_BYTES in kvqp.h is its size.
+constexpr size_t kStaticScratchBytes = KVQP_STATIC_SCRATCH_BYTES;
+hipError_t static_scratch(const kvqp_cfg& cfg, void** ptr, hipStream_t stream);
 
 // Compress workspace layout (bytes offsets), pure function of cfg.
 struct CompressPlan {

@@ -18,7 +18,7 @@ KEY_PER_CHANNEL = 0
 KEY_PER_TOKEN = 1
 CACHE_AUTO, CACHE_STREAM, CACHE_KEEP = 0, 1, 2     # kvqp_cfg.decode_cache_hint
 EXPORTS = ["kvqp_cache_sizes", "kvqp_cache_sizes_cap", "kvqp_outlier_sizes", "kvqp_workspace_bytes", "kvqp_compress",
-           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_append_tail_ragged", "kvqp_decode_attn", "kvqp_decode_workspace_init", "kvqp_strerror", "kvqp_version"]
+           "kvqp_compress_ragged", "kvqp_quantize_selected", "kvqp_quantize_selected_ragged", "kvqp_append_tail", "kvqp_append_tail_ragged", "kvqp_decode_attn", "kvqp_decode_attn_static", "kvqp_decode_workspace_init", "kvqp_strerror", "kvqp_version"]
 
 
 class KvqpError(RuntimeError):
@@ -70,6 +70,7 @@ def lib():
                                                     C.POINTER(C.c_int32), C.POINTER(CacheStruct), C.c_void_p]
         L.kvqp_decode_attn.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.POINTER(CacheStruct), C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
+        L.kvqp_decode_attn_static.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.POINTER(CacheStruct), C.c_void_p, C.c_void_p]
         L.kvqp_decode_workspace_init.argtypes = [C.POINTER(CfgStruct), C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
@@ -310,3 +311,11 @@ def decode_attn(cfg: Cfg, q, cache: Cache, out=None, workspace=None, stream=None
         raise KvqpError(rc, "kvqp_decode_attn")
     return out
 
+
+def decode_attn_static(cfg: Cfg, q, cache: Cache, out, stream=None):
+    """kvqp_decode_attn_static: the decode step on the library's own scratch array; out is the caller's."""
+    cs = cache.struct()
+    rc = lib().kvqp_decode_attn_static(C.byref(cfg.struct()), _ptr(q), C.byref(cs), _ptr(out), _stream_ptr(stream))
+    if rc:
+        raise KvqpError(rc, "kvqp_decode_attn_static")
+    return out

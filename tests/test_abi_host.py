@@ -253,9 +253,10 @@ def test_product_package_does_not_import_the_checker():
                 assert "oracle" not in text.lower(), f"{f} mentions the checker"
 
 
-def test_decode_workspace_init_validates_on_the_host(lib):
-    """The workspace preparation rejects bad calls before anything is enqueued (no GPU needed): it
-    wants a workspace that holds the arrival counters."""
+def test_decode_workspace_init_and_static_entry_validate_on_the_host(lib):
+    """The two decode-side additions reject bad calls before anything is enqueued (no GPU needed):
+    the workspace preparation wants a workspace that holds the arrival counters, and the entry
+    point on the library's own scratch array refuses launches whose partials do not fit it."""
     cfg = kvqp.Cfg(batch=4, n_q_heads=32, n_kv_heads=8, seq_len=4096, window=32, budget=1024, bits=4)
     st = cfg.struct()
     fake = C.c_void_p(0x1000)
@@ -264,3 +265,12 @@ def test_decode_workspace_init_validates_on_the_host(lib):
     assert lib.kvqp_decode_workspace_init(C.byref(st), fake, 64, None) == -3            # 32 counters need 128 bytes
     assert lib.kvqp_decode_workspace_init(C.byref(st), C.c_void_p(0x1004), 1 << 20, None) == -1
     assert kvqp.workspace_bytes(cfg)[1] >= 256 + 32 * 4 * 130 * 4                           # counters, then partials
+    cs = kvqp.CacheStruct()
+    for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
+        setattr(cs, name, 0x1000)
+    cs.n_kept, cs.tail_len, cs.tail_cap = 1024, 32, 32
+    assert lib.kvqp_decode_attn_static(C.byref(st), None, C.byref(cs), fake, None) == -1
+    assert lib.kvqp_decode_attn_static(C.byref(st), fake, None, fake, None) == -1
+    big = kvqp.Cfg(batch=8192, n_q_heads=56, n_kv_heads=7, seq_len=4096, window=32, budget=1024, bits=4)
+    assert kvqp.workspace_bytes(big)[1] > (4 << 20)
+    assert lib.kvqp_decode_attn_static(C.byref(big.struct()), fake, C.byref(cs), fake, None) == -3
