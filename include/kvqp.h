@@ -74,29 +74,23 @@ typedef struct kvqp_cfg {
     float sm_scale;       /* logit scale > 0, e.g. 1/sqrt(D) (Eq. (3) omits it)          */
     float outlier_threshold; /* tau; > 0 turns outlier filtering on (below), 0 = off     */
     int32_t decode_cache_hint; /* KVQP_CACHE_*: how kvqp_decode_attn's loads treat the
-                             chip's memory-side cache (below); 0 = library chooses      */
+                             chip's memory-side cache (below); 0 = streamed            */
 } kvqp_cfg;
 
 /*
- * decode_cache_hint.  A decode loop reads the same cache again at every step.
- * The chip has a 256 MB memory-side cache; what of a launch's working set can
- * stay there is re-read quickly at the next step, while loads of data that
- * cannot stay run faster when they go round it (non-temporal loads).
- *   KVQP_CACHE_AUTO    a launch that reads more than 288 MB reads the leading
- *                      share of every head that adds up to 240 MB normally and
- *                      the rest non-temporally (all of it beyond 600 MB);
- *                      smaller launches read everything normally.  Right for
- *                      a loop of decode steps over one batch of caches with
- *                      little else in between.
- *   KVQP_CACHE_STREAM  every load non-temporal: for a caller that knows the
- *                      cache will have been evicted before it is read again
- *                      (weights and other layers pass through in between).
- *   KVQP_CACHE_KEEP    every load normal.  A caller that issues one call per
- *                      layer can apply the automatic rule to its whole step:
- *                      KEEP for the layers whose caches add up to 240 MB,
- *                      STREAM for the rest.
- * 16-bit caches are read normally whatever the hint (measured: non-temporal
- * loads are slower there).  Results do not depend on the hint.
+ * decode_cache_hint: how kvqp_decode_attn's loads treat the chip's 256 MB
+ * memory-side cache.  A decode step reads every layer's cache exactly once, and
+ * between two steps the model's weights and activations pass through the chip,
+ * so a cache is normally gone from there before it is read again; loads of such
+ * data run faster when they go round that cache (non-temporal loads).
+ *   KVQP_CACHE_AUTO    = KVQP_CACHE_STREAM: the case above.
+ *   KVQP_CACHE_STREAM  every load non-temporal.
+ *   KVQP_CACHE_KEEP    every load normal: for a caller that knows the cache
+ *                      will still be resident when it is read again (the caches
+ *                      of all layers of a step add up to well under 256 MB and
+ *                      little else runs in between), or one that issues a call
+ *                      per layer and wants the first layers' caches to stay.
+ * Results do not depend on the hint.
  */
 #define KVQP_CACHE_AUTO 0
 #define KVQP_CACHE_STREAM 1

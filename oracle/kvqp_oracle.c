@@ -840,3 +840,15 @@ int orc_threads(void)
     return 1;
 #endif
 }
+
+/* Number of OpenMP threads the loops over (batch, KV head) may use from now on
+ * (plumbing for the benchmark's single-thread timing; no arithmetic). */
+void orc_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1)
+        omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

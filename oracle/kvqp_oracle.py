@@ -76,6 +76,11 @@ def threads() -> int:
     return int(lib().orc_threads())
 
 
+def set_threads(n: int) -> None:
+    """OpenMP threads used from now on (the benchmark times the oracle on one thread and on all)."""
+    lib().orc_set_threads(int(n))
+
+
 def half_to_double(bits16):
     a = _u16(bits16)
     out = np.empty(a.shape, np.float64)

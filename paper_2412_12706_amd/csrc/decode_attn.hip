@@ -562,7 +562,11 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     const char* kz = QUANT ? reinterpret_cast<const char*>(a.k_zero) + (size_t)bh * k_meta_head : nullptr;
     const char* vs = QUANT ? reinterpret_cast<const char*>(a.v_scale) + (size_t)bh * a.n_cap * NCG * 2 : nullptr;
     const char* vz = QUANT ? reinterpret_cast<const char*>(a.v_zero) + (size_t)bh * a.n_cap * NCG * 2 : nullptr;
-    const uint32_t k_lane = (uint32_t)n * (16 * BITS) + (uint32_t)kb * (4 * BITS);   // within a 16-token key tile
+    // within a 16-token key tile.  Quantized rows: the lane's 32 channels are one contiguous piece.
+    // 16-bit rows: contraction step s takes the 64-byte stretch s of the row, 16 bytes per lane, so
+    // that one load instruction covers whole half-lines of 16 rows (the channel order inside the
+    // contraction is free as long as the query operand follows it).
+    const uint32_t k_lane = (uint32_t)n * (16 * BITS) + (uint32_t)kb * (QUANT ? 4 * BITS : 16);
     const uint32_t v_lane = (uint32_t)lane * 16;
     const uint32_t row_lane = (uint32_t)lane * 4;                                     // dword of a 256-byte scale row
     const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
@@ -633,7 +637,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         } else {
 #pragma unroll
             for (int i = 0; i < BITS / 4; ++i) {
-                const u4v v = stream_load<u4v, NT>(p + 16 * i);
+                const u4v v = stream_load<u4v, NT>(p + (QUANT ? 16 : 64) * i);
                 dst.w[4 * i] = v[0]; dst.w[4 * i + 1] = v[1]; dst.w[4 * i + 2] = v[2]; dst.w[4 * i + 3] = v[3];
             }
         }
@@ -700,7 +704,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     // Chunks from a.stream_from on are read with the non-temporal hint (wave-uniform choice; a 16-bit
     // cache never is).  The empty statements keep the two arms apart: merged, the loads would lose
     // the hint.
-    constexpr bool MIX = QUANT;
+    constexpr bool MIX = true;
     auto streamed = [&](int chunk) { return MIX && chunk >= a.stream_from; };
     auto load_Ak = [&](int chunk) {
         if (streamed(chunk)) { asm volatile("; streamed"); load_Ak_as(chunk, BoolC<true>{}); asm volatile("; streamed"); }
@@ -1067,10 +1071,11 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     h2v qpos[QUANT ? 1 : 16];
     if (!QUANT || wave == 0) {
         h2v qn[16];
-        const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + 32 * kb;
+        // (16-bit rows: step i of the contraction covers channels 32 i + 8 kb .. + 8, see k_lane)
+        const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + g * GQ + (live_row ? h : 0)) * kHeadDim + (QUANT ? 32 : 8) * kb;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint4 v = reinterpret_cast<const uint4*>(qp)[i];
+            const uint4 v = *reinterpret_cast<const uint4*>(qp + (QUANT ? 8 : 32) * i);
             qn[4 * i] = as_h2(live_row ? v.x : 0u); qn[4 * i + 1] = as_h2(live_row ? v.y : 0u);
             qn[4 * i + 2] = as_h2(live_row ? v.z : 0u); qn[4 * i + 3] = as_h2(live_row ? v.w : 0u);
         }
@@ -1299,27 +1304,17 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     merge_if_last<GQ>(a, bh);
 }
 
-// Which chunks of every head a launch streams past the memory-side cache.  A decode loop reads the
-// same cache again at every step; of a working set beyond the 256 MB memory-side cache only a
-// part can stay there, and loads that merely pass through it run slower than loads that go round
-// it.  So when one launch reads more than kCacheAllBelow bytes, the first kCacheKeepBytes of it
-// (the same leading share of every head) are read normally and stay resident from step to step,
-// and the rest carries the non-temporal hint; beyond kCacheNoneAbove keeping a part resident no
-// longer pays and everything is streamed.  The constants were swept on the MI355X.  16-bit caches
-// are always read normally: a lane's 64 bytes of a row take four load instructions, and lines
-// evicted between them cost more than the hint gains (measured at 0.27, 0.55 and 1.1 GB).
+// Which chunks of every head a launch reads with the non-temporal hint (streamed round the 256 MB
+// memory-side cache) -- chunks from the returned index on.  A decode step reads every layer's cache
+// exactly once and a model's weights pass through the chip between two steps, so nothing of a cache
+// survives there until it is read again; loads that merely pass through that cache run slower than
+// loads that go round it (measured with launches that rotate over several caches: 4 bits 65.2 ->
+// 60.4 us, 8 bits 57.3 -> 53.8 us, 16 bits 55.6 -> 52.9 us per 256-head launch).  So the library
+// streams everything unless the caller says the cache will still be resident (KVQP_CACHE_KEEP).
 constexpr int kNoStream = 0x7fffffff;
-constexpr double kCacheKeepBytes = 240e6, kCacheAllBelow = 288e6, kCacheNoneAbove = 600e6;
 static int stream_from_chunk(const kvqp_cfg& cfg, int n_kept) {
-    if (cfg.bits == 16 || cfg.decode_cache_hint == KVQP_CACHE_KEEP) return kNoStream;
-    if (cfg.decode_cache_hint == KVQP_CACHE_STREAM) return 0;
-    double bpt = 2.0 * (kHeadDim * cfg.bits / 8.0 + 4.0 * kHeadDim / cfg.group_size);
-    if (outliers_on(cfg)) bpt += 2.0 * KVQP_OUTLIER_SLOTS * 4;   // slot words of both tensors
-    const double total = (double)cfg.batch * cfg.n_kv_heads * (double)n_kept * bpt;
-    if (total <= kCacheAllBelow) return kNoStream;
-    if (total > kCacheNoneAbove) return 0;
-    const int n_chunks = (n_kept + kChunk - 1) / kChunk;
-    return (int)(n_chunks * (kCacheKeepBytes / total));
+    (void)n_kept;
+    return cfg.decode_cache_hint == KVQP_CACHE_KEEP ? kNoStream : 0;
 }
 
 template <int BITS, int GQ, int NCG>
