@@ -309,46 +309,45 @@ int orc_quantize_group(const uint16_t *x, int n, int stride, int bits, uint16_t 
 /* Outlier filtering (Section 6.3, item (1); Appendix B "KV             */
 /* quantization": numbers whose absolute value exceeds a threshold, 6   */
 /* in the paper, about 1 % of them, are excluded from quantization).    */
-/* Reading used here, bounded per token so that storage is fixed: in    */
-/* every kept token's key row and value row, the elements with          */
-/* |x| > tau are candidates; the ORC_OUT_SLOTS candidates of largest    */
-/* magnitude (equal magnitudes: lower channel first) are the row's      */
-/* outliers.  An outlier takes no part in its group's min / max, gets   */
-/* code 0, and is kept at full precision beside the codes: a slot word  */
-/* holds the top 24 bits of the binary32 difference float(x) - float(z) */
-/* (z the stored zero-point of the element's group), a valid bit (bit   */
-/* 7) and the channel (bits 0-6); the element dequantizes to            */
-/* float(z) + difference.  A row's slots are in ascending order of       */
-/* channel, unused slots are 0.  A group left with no element stores    */
-/* scale 0, zero +0.                                                    */
-/* Candidates beyond the ORC_OUT_SLOTS largest are quantized like any   */
-/* other element.                                                       */
+/* Every element of a kept token's key row or value row with |x| > tau  */
+/* is an outlier -- there is no limit per row.  An outlier takes no     */
+/* part in its group's min / max, gets code 0, and is kept at full      */
+/* precision beside the codes as a 32-bit word: the top 24 bits of the  */
+/* binary32 difference float(x) - float(z) (z the stored zero-point of  */
+/* the element's group), a valid bit (bit 7) and the channel (bits      */
+/* 0-6); the element dequantizes to float(z) + difference.  A group     */
+/* left with no element stores scale 0, zero +0.                        */
+/* Where the words go is storage format (the paper gives none): a       */
+/* row's first ORC_OUT_SLOTS outliers in ascending channel order sit    */
+/* in the row's slots (unused slots are 0); a row's further outliers    */
+/* go, in ascending (token, channel) order, to the head's overflow      */
+/* list as entries (word, token), with a prefix count per block of 32   */
+/* tokens in front of it:                                               */
+/*   int32  start[n_tok/32 + 1], padded to a multiple of 4 ints:        */
+/*          start[b] = overflow entries of tokens before 32 b           */
+/*   uint32 entry[ovf_cap][2] = (word, token index in the head)         */
+/* Entries beyond ovf_cap are not stored (start[] still counts them, so  */
+/* the shortfall is visible); such an element dequantizes to z.         */
 /* ------------------------------------------------------------------ */
 #define ORC_OUT_SLOTS 4
 
-/* is_out[d] = 1 + rank of selection for the row's outliers, 0 elsewhere.  Returns how many there are. */
+/* is_out[d] = 1 + (number of outliers of the row in lower channels) for the row's outliers,
+ * 0 elsewhere (D <= 128, so the count fits a byte).  Returns how many there are. */
 int orc_mark_outliers(const uint16_t *row, int D, double tau, uint8_t *is_out)
 {
     int n = 0;
-    memset(is_out, 0, (size_t)D);
-    for (int s = 0; s < ORC_OUT_SLOTS; ++s) {
-        int best = -1;
-        double best_mag = 0.0;
-        for (int d = 0; d < D; ++d) {
-            if (is_out[d])
-                continue;
-            double mag = fabs(orc_half_to_double(row[d]));
-            if (mag > tau && (best < 0 || mag > best_mag)) { /* strict: the lower channel keeps a tie */
-                best = d;
-                best_mag = mag;
-            }
-        }
-        if (best < 0)
-            break;
-        is_out[best] = (uint8_t)(s + 1);
-        ++n;
+    for (int d = 0; d < D; ++d) {
+        double mag = fabs(orc_half_to_double(row[d]));
+        is_out[d] = mag > tau ? (uint8_t)(++n) : 0;
     }
     return n;
+}
+
+/* Words of one head's overflow buffer laid out for n_tok tokens and cap entries (format above). */
+size_t orc_ovf_words(int n_tok, int cap)
+{
+    size_t start = ((size_t)(n_tok / 32 + 1) + 3) / 4 * 4;
+    return start + 2 * (size_t)cap;
 }
 
 /* Slot word of an outlier x in channel d whose group stores zero-point zb. */
@@ -479,19 +478,21 @@ static void v_code_put(uint32_t *codes, int D, int bits, int t, int d, uint32_t 
 /*   v_scale/v_zero: [B,Hkv,n_kept,D/G]                                 */
 /*   tail_k/tail_v : [B,Hkv,tail_cap,D], first W rows written           */
 /* ------------------------------------------------------------------ */
-/* tau < 0: no outlier filtering (k_out, v_out unused).  Otherwise k_out, v_out
- * [B,Hkv,n_kept,ORC_OUT_SLOTS] receive the slot words (bits 2, 4, 8 only). */
+/* tau < 0: no outlier filtering (k_out, v_out, k_ovf, v_ovf unused).  Otherwise k_out, v_out
+ * [B,Hkv,n_kept,ORC_OUT_SLOTS] receive the slot words and k_ovf, v_ovf
+ * [B,Hkv,orc_ovf_words(n_kept, ovf_cap)] the overflow buffers (bits 2, 4, 8 only; n_kept % 32 == 0). */
 static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kept, int bits, int G,
                                   int key_axis, int tail_cap, const uint16_t *k, const uint16_t *v,
                                   const int32_t *idx, uint32_t *k_codes, uint32_t *v_codes,
                                   uint16_t *k_scale, uint16_t *k_zero, uint16_t *v_scale,
                                   uint16_t *v_zero, uint16_t *tail_k, uint16_t *tail_v, double tau,
-                                  uint32_t *k_out, uint32_t *v_out)
+                                  uint32_t *k_out, uint32_t *v_out, int ovf_cap, uint32_t *k_ovf,
+                                  uint32_t *v_ovf)
 {
     if (!(bits == 2 || bits == 4 || bits == 8 || bits == 16) || D % 64 || W > tail_cap || W > L)
         return -1;
     const int filt = tau >= 0.0;
-    if (filt && (bits == 16 || !k_out || !v_out || D > 128))
+    if (filt && (bits == 16 || !k_out || !v_out || !k_ovf || !v_ovf || ovf_cap < 0 || D > 128 || n_kept % 32))
         return -1;
     if (bits != 16 && (G < 1 || D % G || (key_axis == 0 && n_kept % G)))
         return -1;
@@ -568,23 +569,56 @@ static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kep
                             v_code_put(vc, D, bits, t, c * G + e, codes[e]);
                     }
             }
-            if (filt)
+            if (filt) {
+                const size_t ow = orc_ovf_words(n_kept, ovf_cap);
+                const size_t n_start = ow - 2 * (size_t)ovf_cap;
+                uint32_t *kov = k_ovf + head * ow, *vov = v_ovf + head * ow;
+                memset(kov, 0, ow * 4);
+                memset(vov, 0, ow * 4);
+                int32_t nko = 0, nvo = 0; /* overflow entries so far */
                 for (int t = 0; t < n_kept; ++t) {
                     uint32_t *ko = k_out + (head * (size_t)n_kept + t) * ORC_OUT_SLOTS;
                     uint32_t *vo = v_out + (head * (size_t)n_kept + t) * ORC_OUT_SLOTS;
-                    int nk = 0, nv = 0;
                     memset(ko, 0, sizeof(uint32_t) * ORC_OUT_SLOTS);
                     memset(vo, 0, sizeof(uint32_t) * ORC_OUT_SLOTS);
+                    if (t % 32 == 0) {
+                        kov[t / 32] = (uint32_t)nko;
+                        vov[t / 32] = (uint32_t)nvo;
+                    }
                     for (int d = 0; d < D; ++d) { /* ascending channel */
                         size_t mk = key_axis == 0 ? (head * (size_t)(n_kept / G) + t / G) * D + d
                                                   : (head * (size_t)n_kept + t) * (D / G) + d / G;
                         size_t mv = (head * (size_t)n_kept + t) * (D / G) + d / G;
-                        if (kmask[(size_t)t * D + d])
-                            ko[nk++] = orc_outlier_slot(kh[(size_t)id[t] * D + d], k_zero[mk], d);
-                        if (vmask[(size_t)t * D + d])
-                            vo[nv++] = orc_outlier_slot(vh[(size_t)id[t] * D + d], v_zero[mv], d);
+                        const int rk = kmask[(size_t)t * D + d], rv = vmask[(size_t)t * D + d];
+                        if (rk) {
+                            uint32_t w = orc_outlier_slot(kh[(size_t)id[t] * D + d], k_zero[mk], d);
+                            if (rk <= ORC_OUT_SLOTS)
+                                ko[rk - 1] = w;
+                            else {
+                                if (nko < ovf_cap) {
+                                    kov[n_start + 2 * (size_t)nko] = w;
+                                    kov[n_start + 2 * (size_t)nko + 1] = (uint32_t)t;
+                                }
+                                ++nko;
+                            }
+                        }
+                        if (rv) {
+                            uint32_t w = orc_outlier_slot(vh[(size_t)id[t] * D + d], v_zero[mv], d);
+                            if (rv <= ORC_OUT_SLOTS)
+                                vo[rv - 1] = w;
+                            else {
+                                if (nvo < ovf_cap) {
+                                    vov[n_start + 2 * (size_t)nvo] = w;
+                                    vov[n_start + 2 * (size_t)nvo + 1] = (uint32_t)t;
+                                }
+                                ++nvo;
+                            }
+                        }
                     }
                 }
+                kov[n_kept / 32] = (uint32_t)nko;
+                vov[n_kept / 32] = (uint32_t)nvo;
+            }
             for (int i = 0; i < W; ++i) {
                 memcpy(tail_k + (head * tail_cap + i) * (size_t)D, kh + (size_t)(P + i) * D,
                        sizeof(uint16_t) * (size_t)D);
@@ -606,7 +640,7 @@ int orc_quantize_selected(int B, int Hkv, int D, int L, int W, int n_kept, int b
 {
     return quantize_selected_impl(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap, k, v, idx,
                                   k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k,
-                                  tail_v, -1.0, NULL, NULL);
+                                  tail_v, -1.0, NULL, NULL, 0, NULL, NULL);
 }
 
 /* The same with outlier filtering at threshold tau >= 0. */
@@ -616,13 +650,13 @@ int orc_quantize_selected_outliers(int B, int Hkv, int D, int L, int W, int n_ke
                                    uint32_t *k_codes, uint32_t *v_codes, uint16_t *k_scale,
                                    uint16_t *k_zero, uint16_t *v_scale, uint16_t *v_zero,
                                    uint16_t *tail_k, uint16_t *tail_v, uint32_t *k_out,
-                                   uint32_t *v_out)
+                                   uint32_t *v_out, int ovf_cap, uint32_t *k_ovf, uint32_t *v_ovf)
 {
     if (tau < 0.0)
         return -1;
     return quantize_selected_impl(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap, k, v, idx,
                                   k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k,
-                                  tail_v, tau, k_out, v_out);
+                                  tail_v, tau, k_out, v_out, ovf_cap, k_ovf, v_ovf);
 }
 
 /*
@@ -672,12 +706,14 @@ int orc_compress(int B, int Hq, int Hkv, int D, int L, int W, int pool, int budg
 /* ------------------------------------------------------------------ */
 
 /* Dequantize one head into dense rows: Kd, Vd [n_kept + tail_len, D]. */
-/* ko, vo: the head's outlier slots [n_kept, ORC_OUT_SLOTS], or NULL. */
+/* ko, vo: the head's outlier slots [n_kept, ORC_OUT_SLOTS], or NULL; kov, vov: its overflow
+ * buffers for n_kept tokens and ovf_cap entries (with ko, vo). */
 static void dequantize_head(int D, int n_kept, int bits, int G, int key_axis, int tail_len,
                             const uint32_t *kc, const uint32_t *vc, const uint16_t *ks,
                             const uint16_t *kz, const uint16_t *vs, const uint16_t *vz,
                             const uint16_t *tk, const uint16_t *tv, const uint32_t *ko,
-                            const uint32_t *vo, double *Kd, double *Vd)
+                            const uint32_t *vo, int ovf_cap, const uint32_t *kov,
+                            const uint32_t *vov, double *Kd, double *Vd)
 {
     for (int t = 0; t < n_kept; ++t)
         for (int d = 0; d < D; ++d) {
@@ -707,6 +743,21 @@ static void dequantize_head(int D, int n_kept, int bits, int G, int key_axis, in
                 Vd[(size_t)t * D + d] = orc_outlier_value(c, vz[(size_t)t * (D / G) + d / G]);
             }
         }
+    if (ko && vo && kov && vov) { /* the rows' further outliers */
+        const size_t n_start = orc_ovf_words(n_kept, ovf_cap) - 2 * (size_t)ovf_cap;
+        const uint32_t nk = kov[n_kept / 32], nv = vov[n_kept / 32];
+        for (uint32_t e = 0; e < nk && e < (uint32_t)ovf_cap; ++e) {
+            uint32_t a = kov[n_start + 2 * (size_t)e];
+            int t = (int)kov[n_start + 2 * (size_t)e + 1], d = (int)(a & 0x7Fu);
+            size_t mk = key_axis == 0 ? (size_t)(t / G) * D + d : (size_t)t * (D / G) + d / G;
+            Kd[(size_t)t * D + d] = orc_outlier_value(a, kz[mk]);
+        }
+        for (uint32_t e = 0; e < nv && e < (uint32_t)ovf_cap; ++e) {
+            uint32_t c = vov[n_start + 2 * (size_t)e];
+            int t = (int)vov[n_start + 2 * (size_t)e + 1], d = (int)(c & 0x7Fu);
+            Vd[(size_t)t * D + d] = orc_outlier_value(c, vz[(size_t)t * (D / G) + d / G]);
+        }
+    }
     for (int t = 0; t < tail_len; ++t)
         for (int d = 0; d < D; ++d) {
             Kd[(size_t)(n_kept + t) * D + d] = orc_half_to_double(tk[(size_t)t * D + d]);
@@ -721,10 +772,11 @@ static int decode_attn_impl(int B, int Hq, int Hkv, int D, int n_kept, int bits,
                             const uint16_t *k_scale, const uint16_t *k_zero,
                             const uint16_t *v_scale, const uint16_t *v_zero, const uint16_t *tail_k,
                             const uint16_t *tail_v, const uint32_t *k_out, const uint32_t *v_out,
-                            double *out)
+                            int ovf_cap, const uint32_t *k_ovf, const uint32_t *v_ovf, double *out)
 {
     if (Hq % Hkv || tail_len > tail_cap || n_kept + tail_len < 1)
         return -1;
+    const size_t ow = k_out ? orc_ovf_words(n_kept, ovf_cap) : 0;
     const int Gq = Hq / Hkv, T = n_kept + tail_len;
     const size_t kw = orc_k_words(n_kept, D, bits), vw = orc_v_words(n_kept, D, bits);
     const size_t kmeta = bits == 16 ? 0
@@ -752,7 +804,8 @@ static int decode_attn_impl(int B, int Hq, int Hkv, int D, int n_kept, int bits,
                             tail_k + head * (size_t)tail_cap * D,
                             tail_v + head * (size_t)tail_cap * D,
                             k_out ? k_out + head * (size_t)n_kept * ORC_OUT_SLOTS : NULL,
-                            v_out ? v_out + head * (size_t)n_kept * ORC_OUT_SLOTS : NULL, Kd, Vd);
+                            v_out ? v_out + head * (size_t)n_kept * ORC_OUT_SLOTS : NULL, ovf_cap,
+                            k_out ? k_ovf + head * ow : NULL, k_out ? v_ovf + head * ow : NULL, Kd, Vd);
             for (int h = g * Gq; h < (g + 1) * Gq; ++h) {
                 const uint16_t *qr = q + ((size_t)b * Hq + h) * (size_t)D;
                 double mx = -INFINITY;
@@ -792,23 +845,25 @@ int orc_decode_attn(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G, 
 {
     return decode_attn_impl(B, Hq, Hkv, D, n_kept, bits, G, key_axis, sm_scale, tail_len, tail_cap,
                             q, k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k, tail_v,
-                            NULL, NULL, out);
+                            NULL, NULL, 0, NULL, NULL, out);
 }
 
-/* The same over a cache with outlier slots k_out, v_out [B,Hkv,n_kept,ORC_OUT_SLOTS]. */
+/* The same over a cache with outlier slots k_out, v_out [B,Hkv,n_kept,ORC_OUT_SLOTS] and overflow
+ * buffers k_ovf, v_ovf [B,Hkv,orc_ovf_words(n_kept, ovf_cap)]. */
 int orc_decode_attn_outliers(int B, int Hq, int Hkv, int D, int n_kept, int bits, int G,
                              int key_axis, double sm_scale, int tail_len, int tail_cap,
                              const uint16_t *q, const uint32_t *k_codes, const uint32_t *v_codes,
                              const uint16_t *k_scale, const uint16_t *k_zero,
                              const uint16_t *v_scale, const uint16_t *v_zero,
                              const uint16_t *tail_k, const uint16_t *tail_v, const uint32_t *k_out,
-                             const uint32_t *v_out, double *out)
+                             const uint32_t *v_out, int ovf_cap, const uint32_t *k_ovf,
+                             const uint32_t *v_ovf, double *out)
 {
-    if (!k_out || !v_out)
+    if (!k_out || !v_out || !k_ovf || !v_ovf || ovf_cap < 0 || n_kept % 32)
         return -1;
     return decode_attn_impl(B, Hq, Hkv, D, n_kept, bits, G, key_axis, sm_scale, tail_len, tail_cap,
                             q, k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k, tail_v,
-                            k_out, v_out, out);
+                            k_out, v_out, ovf_cap, k_ovf, v_ovf, out);
 }
 
 /* Dense dequantized K', V' of one head, for tests of the error bound
@@ -818,17 +873,18 @@ int orc_dequantize_head(int D, int n_kept, int bits, int G, int key_axis, const 
                         const uint16_t *vs, const uint16_t *vz, double *Kd, double *Vd)
 {
     dequantize_head(D, n_kept, bits, G, key_axis, 0, kc, vc, ks, kz, vs, vz, NULL, NULL, NULL, NULL,
-                    Kd, Vd);
+                    0, NULL, NULL, Kd, Vd);
     return 0;
 }
 
 int orc_dequantize_head_outliers(int D, int n_kept, int bits, int G, int key_axis,
                                  const uint32_t *kc, const uint32_t *vc, const uint16_t *ks,
                                  const uint16_t *kz, const uint16_t *vs, const uint16_t *vz,
-                                 const uint32_t *ko, const uint32_t *vo, double *Kd, double *Vd)
+                                 const uint32_t *ko, const uint32_t *vo, int ovf_cap,
+                                 const uint32_t *kov, const uint32_t *vov, double *Kd, double *Vd)
 {
-    dequantize_head(D, n_kept, bits, G, key_axis, 0, kc, vc, ks, kz, vs, vz, NULL, NULL, ko, vo, Kd,
-                    Vd);
+    dequantize_head(D, n_kept, bits, G, key_axis, 0, kc, vc, ks, kz, vs, vz, NULL, NULL, ko, vo,
+                    ovf_cap, kov, vov, Kd, Vd);
     return 0;
 }
 

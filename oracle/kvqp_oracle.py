@@ -52,6 +52,8 @@ def lib():
         L.orc_v_code_get.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
         L.orc_threads.restype = C.c_int
         L.orc_mark_outliers.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_void_p]
+        L.orc_ovf_words.restype = C.c_size_t
+        L.orc_ovf_words.argtypes = [C.c_int, C.c_int]
         L.orc_outlier_slot.restype = C.c_uint32
         L.orc_outlier_slot.argtypes = [C.c_uint16, C.c_uint16, C.c_int]
         L.orc_outlier_value.restype = C.c_double
@@ -141,8 +143,23 @@ def quantize_group(x, bits):
 OUT_SLOTS = 4
 
 
+def ovf_words(n_tok, cap):
+    """32-bit words of one head's overflow buffer laid out for n_tok tokens and cap entries."""
+    return int(lib().orc_ovf_words(int(n_tok), int(cap)))
+
+
+def ovf_entries(buf, n_tok, cap):
+    """One head's overflow buffer -> (start int32 [n_tok/32 + 1], entries uint32 [min(total, cap), 2])."""
+    buf = np.ascontiguousarray(buf).view(np.uint32).reshape(-1)
+    n_start = ovf_words(n_tok, cap) - 2 * cap
+    start = buf[: n_tok // 32 + 1].astype(np.int64)
+    n = min(int(start[-1]), cap)
+    return start, buf[n_start:n_start + 2 * n].reshape(n, 2)
+
+
 def mark_outliers(row, tau):
-    """row: 1-D float16 token row -> uint8 mask of its outliers at threshold tau."""
+    """row: 1-D float16 token row -> uint8 array: 1 + (outliers of the row in lower channels) at its
+    outliers (|x| > tau), 0 elsewhere."""
     row = _u16(row)
     mask = np.zeros(row.size, np.uint8)
     lib().orc_mark_outliers(_p(row), row.size, C.c_double(tau), _p(mask))
@@ -197,6 +214,9 @@ class Cache:
     tail_v: np.ndarray
     k_out: np.ndarray = None  # uint32 [B,Hkv,n_kept,OUT_SLOTS] outlier slots, or None (no filtering)
     v_out: np.ndarray = None
+    ovf_cap: int = 0          # entries per head of the overflow lists
+    k_ovf: np.ndarray = None  # uint32 [B,Hkv,ovf_words(n_kept, ovf_cap)] overflow buffers (with k_out)
+    v_ovf: np.ndarray = None
 
     def k_code(self, b, g, t, d):
         return k_code_at(self.k_codes[b, g], self.D, self.bits, t, d)
@@ -220,8 +240,9 @@ def _alloc_cache(B, Hkv, D, n_kept, bits, G, key_axis, W, tail_cap):
                  np.zeros((B, Hkv, tail_cap, D), np.uint16), np.zeros((B, Hkv, tail_cap, D), np.uint16))
 
 
-def quantize_selected(k, v, idx, W, bits, G, key_axis=0, tail_cap=None, tau=None):
-    """Quantize the survivors listed in idx [B,Hkv,n_kept] (ascending); tau: outlier threshold or None."""
+def quantize_selected(k, v, idx, W, bits, G, key_axis=0, tail_cap=None, tau=None, ovf_cap=None):
+    """Quantize the survivors listed in idx [B,Hkv,n_kept] (ascending); tau: outlier threshold or None;
+    ovf_cap: entries per head of the overflow lists (default: room for every element)."""
     k, v = _u16(k), _u16(v)
     B, Hkv, L, D = k.shape
     idx = np.ascontiguousarray(idx, np.int32)
@@ -235,24 +256,28 @@ def quantize_selected(k, v, idx, W, bits, G, key_axis=0, tail_cap=None, tau=None
     else:
         c.k_out = np.zeros((B, Hkv, n_kept, OUT_SLOTS), np.uint32)
         c.v_out = np.zeros((B, Hkv, n_kept, OUT_SLOTS), np.uint32)
+        c.ovf_cap = n_kept * (D - OUT_SLOTS) if ovf_cap is None else int(ovf_cap)
+        c.k_ovf = np.zeros((B, Hkv, ovf_words(n_kept, c.ovf_cap)), np.uint32)
+        c.v_ovf = np.zeros((B, Hkv, ovf_words(n_kept, c.ovf_cap)), np.uint32)
         rc = lib().orc_quantize_selected_outliers(B, Hkv, D, L, W, n_kept, bits, G, key_axis, tail_cap,
                                                   C.c_double(tau), _p(k), _p(v), _p(idx), _p(c.k_codes),
                                                   _p(c.v_codes), _p(c.k_scale), _p(c.k_zero), _p(c.v_scale),
-                                                  _p(c.v_zero), _p(c.tail_k), _p(c.tail_v), _p(c.k_out), _p(c.v_out))
+                                                  _p(c.v_zero), _p(c.tail_k), _p(c.tail_v), _p(c.k_out), _p(c.v_out),
+                                                  c.ovf_cap, _p(c.k_ovf), _p(c.v_ovf))
     if rc:
         raise ValueError(f"orc_quantize_selected rc={rc}")
     return c
 
 
 def compress(q_obs, k, v, *, window, pool, budget, bits, G, sm_scale, key_axis=0, tail_cap=None,
-             want_pooled=True, tau=None):
+             want_pooled=True, tau=None, ovf_cap=None):
     """Whole prefill-time compression.  Returns (cache, idx, pooled).  With an outlier threshold
     the survivors are the same (selection looks at the unquantized keys) and only their
     quantization differs."""
     if tau is not None:
         _, idx, pooled = compress(q_obs, k, v, window=window, pool=pool, budget=budget, bits=bits, G=G,
                                   sm_scale=sm_scale, key_axis=key_axis, tail_cap=tail_cap, want_pooled=want_pooled)
-        return quantize_selected(k, v, idx, window, bits, G, key_axis, tail_cap, tau), idx, pooled
+        return quantize_selected(k, v, idx, window, bits, G, key_axis, tail_cap, tau, ovf_cap), idx, pooled
     q_obs, k, v = _u16(q_obs), _u16(k), _u16(v)
     B, Hq, W, D = q_obs.shape
     assert W == window
@@ -287,7 +312,7 @@ def decode_attn(q, cache: Cache, sm_scale, n_q_heads=None):
                                             C.c_double(sm_scale), c.tail_len, c.tail_cap, _p(q), _p(c.k_codes),
                                             _p(c.v_codes), _p(c.k_scale), _p(c.k_zero), _p(c.v_scale),
                                             _p(c.v_zero), _p(c.tail_k), _p(c.tail_v), _p(c.k_out), _p(c.v_out),
-                                            _p(out))
+                                            c.ovf_cap, _p(c.k_ovf), _p(c.v_ovf), _p(out))
     if rc:
         raise ValueError(f"orc_decode_attn rc={rc}")
     return out
@@ -307,5 +332,7 @@ def dequantize_head(cache: Cache, b, g):
                                            _p(c.v_codes[b, g]), _p(c.k_scale[b, g]), _p(c.k_zero[b, g]),
                                            _p(c.v_scale[b, g]), _p(c.v_zero[b, g]),
                                            _p(np.ascontiguousarray(c.k_out[b, g])),
-                                           _p(np.ascontiguousarray(c.v_out[b, g])), _p(Kd), _p(Vd))
+                                           _p(np.ascontiguousarray(c.v_out[b, g])), c.ovf_cap,
+                                           _p(np.ascontiguousarray(c.k_ovf[b, g])),
+                                           _p(np.ascontiguousarray(c.v_ovf[b, g])), _p(Kd), _p(Vd))
     return Kd, Vd

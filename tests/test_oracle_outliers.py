@@ -1,9 +1,10 @@
 """Pins for the CPU checker's outlier filtering (paper, Section 6.3 item (1) and
 Appendix B "KV quantization": numbers with |x| > 6, about 1 %, are excluded from
-quantization).  The bounded-per-token reading (at most four outliers per token row
-per tensor, largest magnitudes first, stored in ascending channel order) and the slot format are this build's; the
-pins below fix them with hand-worked values, closed forms and properties that do
-not go through the checker's own arithmetic."""
+quantization -- every such number, with no limit per row).  Where the excluded
+numbers are kept (four slots per token row, an overflow list per head for rows with
+more) and the word format are this build's; the pins below fix them with hand-worked
+values, closed forms and properties that do not go through the checker's own
+arithmetic."""
 import numpy as np
 import pytest
 
@@ -51,6 +52,46 @@ def test_hand_worked_row_2_bits(orc):
     assert np.array_equal(Kd, rows.astype(np.float64)) and np.array_equal(Vd, rows.astype(np.float64))
 
 
+def test_hand_worked_row_with_more_outliers_than_slots(orc):
+    """Six outliers in a row: the four in the lowest channels fill the slots, the other two go to
+    the head's overflow list as (word, token) in (token, channel) order, with the prefix count of
+    every block of 32 tokens in front.  Token 40 alone has them; 64 tokens, so the prefix array is
+    (0, 0, 2) padded to four ints.  All six come back exactly; the rest is lossless."""
+    base = (np.arange(128) % 4).astype(np.float16)
+    rows = np.tile(base, (64, 1))
+    big = {3: 100.0, 10: -50.0, 64: 7.0, 65: -6.5, 100: 24.0, 127: 9.0}      # channel -> value, all |x| > 6
+    for d, x in big.items():
+        rows[40, d] = x
+    k, v = one_head(rows, rows)
+    idx = np.arange(64, dtype=np.int32)[None, None]
+    c = orc.quantize_selected(k, v, idx, W=1, bits=2, G=128, key_axis=1, tau=6.0, ovf_cap=5)
+    word = lambda x, d: (f32_bits(x) & 0xFFFFFF00) | 0x80 | d            # the group's zero-point is 0
+    want_slots = np.array([word(100.0, 3), word(-50.0, 10), word(7.0, 64), word(-6.5, 65)], np.uint32)
+    assert f32_bits(7.0) == 0x40E00000 and f32_bits(-6.5) == 0xC0D00000 and f32_bits(24.0) == 0x41C00000 and f32_bits(9.0) == 0x41100000
+    for out, ovf in ((c.k_out, c.k_ovf), (c.v_out, c.v_ovf)):
+        assert np.array_equal(out[0, 0, 40], want_slots)
+        assert not out[0, 0, :40].any() and not out[0, 0, 41:].any()
+        buf = ovf[0, 0]
+        assert buf.size == 4 + 2 * 5                                      # three prefix counts padded to four, five entries of two words
+        assert buf[:4].tolist() == [0, 0, 2, 0]
+        assert buf[4:8].tolist() == [0x41C00000 | 0x80 | 100, 40, 0x41100000 | 0x80 | 127, 40]
+        assert not buf[8:].any()
+    for t in range(64):
+        for d in range(128):
+            expect = 0 if (t == 40 and d in big) else int(base[d])
+            assert c.v_code(0, 0, t, d) == expect and c.k_code(0, 0, t, d) == expect
+    Kd, Vd = orc.dequantize_head(c, 0, 0)
+    assert np.array_equal(Kd, rows.astype(np.float64)) and np.array_equal(Vd, rows.astype(np.float64))
+    # an overflow list that is too short loses the entries beyond it (those elements read as their
+    # group's zero-point) and shows the shortfall in the prefix counts
+    short = orc.quantize_selected(k, v, idx, W=1, bits=2, G=128, key_axis=1, tau=6.0, ovf_cap=1)
+    assert short.k_ovf[0, 0][:3].tolist() == [0, 0, 2] and short.k_ovf[0, 0][4:6].tolist() == [0x41C00000 | 0x80 | 100, 40]
+    Ks, _ = orc.dequantize_head(short, 0, 0)
+    lost = rows.astype(np.float64).copy()
+    lost[40, 127] = 0.0
+    assert np.array_equal(Ks, lost)
+
+
 def test_threshold_out_of_reach_changes_nothing(orc):
     B, Hq, Hkv, L, W = 1, 4, 2, 300, 8
     _, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, outlier=10.0, config=70)
@@ -60,12 +101,12 @@ def test_threshold_out_of_reach_changes_nothing(orc):
         b = orc.quantize_selected(k, v, idx, W=W, bits=4, G=32, key_axis=axis, tau=7.0e4)   # above the binary16 range
         for n in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero"):
             assert np.array_equal(getattr(a, n), getattr(b, n)), n
-        assert not b.k_out.any() and not b.v_out.any()
+        assert not b.k_out.any() and not b.v_out.any() and not b.k_ovf.any() and not b.v_ovf.any()
 
 
 def test_which_elements_are_outliers(orc):
-    """Brute force: candidates |x| > tau ordered by (magnitude descending, channel ascending), the
-    first four.  Includes rows with none, with more than four and with equal magnitudes."""
+    """Brute force: every element with |x| > tau, numbered in ascending channel order.  Includes rows
+    with none, with more than four and with magnitudes exactly at the threshold."""
     rng = np.random.default_rng(71)
     for trial in range(300):
         row = rng.standard_normal(128).astype(np.float16)
@@ -76,9 +117,8 @@ def test_which_elements_are_outliers(orc):
         mask = orc.mark_outliers(row, 6.0)
         a = np.abs(row.astype(np.float64))
         cand = [d for d in range(128) if a[d] > 6.0]
-        cand.sort(key=lambda d: (-a[d], d))
         want = np.zeros(128, np.uint8)
-        want[cand[:4]] = np.arange(1, len(cand[:4]) + 1)          # 1 + rank of selection
+        want[cand] = np.arange(1, len(cand) + 1)                  # 1 + outliers in lower channels
         assert np.array_equal(mask, want)
 
 
@@ -107,22 +147,33 @@ def test_group_ranges_exclude_outliers_and_errors_stay_bounded(orc, bits, G, axi
     B, Hq, Hkv, L, W, n = 1, 4, 1, 400, 8, 256
     _, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, outlier=20.0, config=73)
     v[..., [3, 64]] = (v[..., [3, 64]].astype(np.float32) * 12).astype(np.float16)   # values get outlier channels too
+    k[..., [50, 51, 90]] = (k[..., [50, 51, 90]].astype(np.float32) * 15).astype(np.float16)   # key rows with up to seven
     idx = np.sort(np.random.default_rng(73).choice(L - W, n, replace=False)).astype(np.int32)[None, None]
     c = orc.quantize_selected(k, v, idx, W=W, bits=bits, G=G, key_axis=axis, tau=6.0)
     Kd, Vd = orc.dequantize_head(c, 0, 0)
     levels = 2**bits - 1
-    for name, src, deq, scale, zero, out, ax in (("k", k, Kd, c.k_scale, c.k_zero, c.k_out, axis),
-                                                 ("v", v, Vd, c.v_scale, c.v_zero, c.v_out, 1)):
+    for name, src, deq, scale, zero, out, ovf, ax in (("k", k, Kd, c.k_scale, c.k_zero, c.k_out, c.k_ovf, axis),
+                                                      ("v", v, Vd, c.v_scale, c.v_zero, c.v_out, c.v_ovf, 1)):
         rows = src[0, 0][idx[0, 0]]                                  # [n, 128] float16
         x = rows.astype(np.float64)
-        rank = np.stack([orc.mark_outliers(r, 6.0) for r in rows])
-        mask = rank.astype(bool)
+        mask = np.abs(x) > 6.0                                       # the paper's rule, nothing else
         assert mask.sum() > 0.003 * mask.size                        # the case does contain outliers
-        # slots list exactly the marked channels in ascending order, zeros after
+        if name == "k":
+            assert (mask.sum(axis=1) > 4).sum() > n // 4             # and key rows that overflow their slots
+        # slots list the first four marked channels in ascending order, zeros after; the overflow
+        # list holds the rest in (token, channel) order and its prefix counts match
+        start, entries = orc.ovf_entries(ovf[0, 0], n, c.ovf_cap)
+        want_entries, want_start = [], [0]
         for t in range(n):
+            marked = np.flatnonzero(mask[t]).tolist()
             chans = [int(s & 0x7F) for s in out[0, 0, t] if s & 0x80]
-            assert chans == np.flatnonzero(mask[t]).tolist()
+            assert chans == marked[:4]
             assert all(s == 0 for s in out[0, 0, t][len(chans):])
+            want_entries += [(d, t) for d in marked[4:]]
+            if t % 32 == 31:
+                want_start.append(len(want_entries))
+        assert start.tolist() == want_start
+        assert [(int(w & 0x7F), int(t)) for w, t in entries] == want_entries and all(w & 0x80 for w, _ in entries)
         if ax == 0:    # groups of G tokens per channel
             xs = x.reshape(n // G, G, 128).transpose(0, 2, 1)        # [group, channel, member]
             ms = mask.reshape(n // G, G, 128).transpose(0, 2, 1)
