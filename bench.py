@@ -351,8 +351,9 @@ def main():
 
         # ---- outlier filtering at the paper's threshold: the 4-bit setting with |x| > 6 kept beside the
         # codes, four slot words per token row and tensor ----
-        cfg_o = kvqp.Cfg(**{**s4["cfg"].__dict__, "outlier_threshold": 6.0})
-        slot_bytes = LAYERS * HKV * s4["n_kept"] * 2 * 16
+        cfg_o = kvqp.Cfg(**{**s4["cfg"].__dict__, "outlier_threshold": 6.0, "outlier_overflow_cap": 4096})
+        slot_bytes = LAYERS * HKV * s4["n_kept"] * 2 * (16 + 4 / 32)      # slot words and the overflow lists' prefix counts
+        slot_bytes = int(slot_bytes)
         oc, outlier_leg = leg(cfg_o, lambda: [kvqp.alloc_cache(cfg_o, device=dev) for _ in range(3)],
                               lambda c, ws: kvqp.compress(cfg_o, q_obs, k, v, c, workspace=ws),
                               decode_bytes(LAYERS, s4["n_kept"], 4, G, W) + slot_bytes)

@@ -75,6 +75,8 @@ typedef struct kvqp_cfg {
     float outlier_threshold; /* tau; > 0 turns outlier filtering on (below), 0 = off     */
     int32_t decode_cache_hint; /* KVQP_CACHE_*: how kvqp_decode_attn's loads treat the
                              chip's memory-side cache (below); 0 = streamed            */
+    int32_t outlier_overflow_cap; /* outlier filtering: entries of the overflow list of one
+                             (batch, KV head) and tensor (below); >= 0                  */
 } kvqp_cfg;
 
 /*
@@ -136,20 +138,31 @@ typedef struct kvqp_cfg {
  *
  * Outlier filtering (Section 6.3, item (1); Appendix B: numbers whose absolute
  * value exceeds 6, about 1 %, are excluded from quantization).  With
- * cfg->outlier_threshold = tau > 0 (bits 2, 4, 8): in every kept token's key
- * row and value row the elements with |x| > tau are candidates and the
- * KVQP_OUTLIER_SLOTS candidates of largest magnitude (equal magnitudes: lower
- * channel first) are the row's outliers -- a bound per token, so that storage
- * is fixed; further candidates are quantized like any other element.  An
- * outlier takes no part in its group's min / max and gets code 0; a group left
- * with no element stores scale 0, zero +0.  The outlier is kept beside the
- * codes in a slot word: bits 31..8 the top 24 bits of the binary32 difference
- * float(x) - float(z), z the stored zero of the element's group, bit 7 set,
- * bits 6..0 the channel; it dequantizes to float(z) + that difference (within
- * 2^-15 of |x - z|, finer than a binary16 step of x).  A row's slots are in
- * ascending order of channel, unused slots are 0.
+ * cfg->outlier_threshold = tau > 0 (bits 2, 4, 8) every element of a kept
+ * token's key row or value row with |x| > tau is an outlier, however many a
+ * row has.  An outlier takes no part in its group's min / max and gets code 0;
+ * a group left with no element stores scale 0, zero +0.  The outlier is kept
+ * beside the codes as a 32-bit word: bits 31..8 the top 24 bits of the
+ * binary32 difference float(x) - float(z), z the stored zero of the element's
+ * group, bit 7 set, bits 6..0 the channel; it dequantizes to float(z) + that
+ * difference (within 2^-15 of |x - z|, finer than a binary16 step of x).
+ * Where the words are kept:
  *   k_out, v_out  uint32 [batch, Hkv, n_kept, KVQP_OUTLIER_SLOTS]
- *   (sizes from kvqp_outlier_sizes; NULL when filtering is off)
+ *     a row's first KVQP_OUTLIER_SLOTS outliers in ascending order of channel,
+ *     unused slots 0;
+ *   k_ovf, v_ovf  uint32 [batch, Hkv, S + 2 * cfg->outlier_overflow_cap],
+ *     S = n_kept/32 + 1 rounded up to a multiple of 4: per (batch, KV head)
+ *     first the int32 prefix counts start[0 .. n_kept/32] -- start[b] = number
+ *     of list entries of the head's tokens before 32 b -- then the list: the
+ *     outliers beyond their rows' slots as entries (word, token index in the
+ *     head), in ascending (token, channel) order.  start[n_kept/32] is the
+ *     number of entries the head needs; entries beyond outlier_overflow_cap
+ *     are not stored and those elements read as their group's zero, so a
+ *     caller that sizes the list below n_kept * (D - KVQP_OUTLIER_SLOTS)
+ *     compares that count (device memory) with its capacity.  Words of the
+ *     list beyond the stored entries, and of the prefix array beyond
+ *     start[n_kept/32], are unspecified.
+ *   (sizes from kvqp_outlier_sizes; all four NULL when filtering is off)
  */
 #define KVQP_OUTLIER_SLOTS 4
 typedef struct kvqp_cache {
@@ -171,6 +184,7 @@ typedef struct kvqp_cache {
                          head_n_kept[h] <= n_kept tokens at the start of its share of every
                          buffer, and n_kept is only the bound the counts stay under.       */
     void *k_out, *v_out;  /* outlier slots when cfg->outlier_threshold > 0, else unused (NULL) */
+    void *k_ovf, *v_ovf;  /* overflow lists of the rows with more outliers than slots (the same) */
 } kvqp_cache;
 
 /* Bytes of the eight cache buffers (order of the struct) for n_kept =
@@ -181,10 +195,10 @@ int kvqp_cache_sizes(const kvqp_cfg *cfg, int32_t tail_cap, size_t sizes_out[8])
  * group_size, >= 0); cfg->seq_len, window and budget are not read.  Host only. */
 int kvqp_cache_sizes_cap(const kvqp_cfg *cfg, int32_t n_cap, int32_t tail_cap, size_t sizes_out[8]);
 
-/* Bytes of k_out and v_out for buffers laid out for n_cap tokens per head
- * (n_cap = 0: for n_kept = min(budget, L - W)); both 0 when cfg->outlier_threshold
- * is 0.  Host only. */
-int kvqp_outlier_sizes(const kvqp_cfg *cfg, int32_t n_cap, size_t sizes_out[2]);
+/* Bytes of k_out, v_out, k_ovf and v_ovf for buffers laid out for n_cap tokens per
+ * head (n_cap = 0: for n_kept = min(budget, L - W)) and cfg->outlier_overflow_cap
+ * list entries; all 0 when cfg->outlier_threshold is 0.  Host only. */
+int kvqp_outlier_sizes(const kvqp_cfg *cfg, int32_t n_cap, size_t sizes_out[4]);
 
 /* Workspace bytes needed by kvqp_compress and kvqp_decode_attn for this cfg
  * (either pointer may be NULL).  decode_bytes depends on batch, heads, bits,

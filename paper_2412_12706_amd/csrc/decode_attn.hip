@@ -217,6 +217,9 @@ struct DecodeArgs {
     const int32_t* head_n_kept;   // per (batch, kv head) token counts under the bound n_kept, or NULL
     const uint32_t* k_out;        // outlier slots [B*Hkv, n_cap, 4] (filtering on), else NULL
     const uint32_t* v_out;
+    const uint32_t* k_ovf;        // overflow buffers [B*Hkv, ovf_words(n_cap, ovf_cap)] (filtering on), else NULL
+    const uint32_t* v_ovf;
+    int ovf_cap;                  // entries of a head's overflow list
     int quantum;              // a head's count is a multiple of this power of two (32, or G for per-channel keys)
     int n_q_heads, n_kv_heads;
     int n_splits, chunks_per_split, n_partials;
@@ -579,6 +582,14 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     const char* ko = OUT ? reinterpret_cast<const char*>(a.k_out) + (size_t)bh * a.n_cap * 16 : nullptr;
     const char* vo = OUT ? reinterpret_cast<const char*>(a.v_out) + (size_t)bh * a.n_cap * 16 : nullptr;
     uint32_t slot_off = (uint32_t)lane * 8;
+    // a row's outliers beyond its four slots: the head's overflow lists, prefix counts per 32 tokens in front
+    const uint32_t* kov = OUT ? a.k_ovf + (size_t)bh * ovf_words(a.n_cap, a.ovf_cap) : nullptr;
+    const uint32_t* vov = OUT ? a.v_ovf + (size_t)bh * ovf_words(a.n_cap, a.ovf_cap) : nullptr;
+    const uint32_t* kov_e = OUT ? kov + ovf_start_words(a.n_cap) : nullptr;
+    const uint32_t* vov_e = OUT ? vov + ovf_start_words(a.n_cap) : nullptr;
+    uint32_t a_kov = 0, a_vov = 0, b_kov = 0, b_vov = 0;   // lanes 0, 1: the block's range in the list (requested with its codes)
+    const uint32_t ovf_lane = (uint32_t)min(lane, 1) * 4;   // lane 0: entry of the block, other lanes: the entry after it (always inside the array)
+    (void)kov_e; (void)vov_e; (void)ovf_lane;
     const int row8 = (SLOTS == 2) ? slot * 4 + h : h;                  // the lane's row of the wave's outlier terms
     float* oc = s_oc + (OUT ? wave * 8 * kHeadDim : 0);
     (void)ko; (void)vo; (void)slot_off; (void)row8; (void)oc;
@@ -670,7 +681,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                 for (int i = 0; i < NGRP; ++i) a_kz[i] = dword_at(kz, (uint32_t)min(u + i, n_kgroups - 1) * 256 + row_off, nt);
             }
         }
-        if constexpr (OUT) { const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); a_ko = make_uint2(w[0], w[1]); }
+        if constexpr (OUT) {
+            const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); a_ko = make_uint2(w[0], w[1]);
+            a_kov = kov[tb / 32 + ovf_lane / 4];
+        }
     };
     auto load_Av_as = [&](int chunk, auto nt) {
         const int tb = chunk * kChunk;
@@ -678,7 +692,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             a_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
             a_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
         }
-        if constexpr (OUT) { const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); a_vo = make_uint2(w[0], w[1]); }
+        if constexpr (OUT) {
+            const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); a_vo = make_uint2(w[0], w[1]);
+            a_vov = vov[tb / 32 + ovf_lane / 4];
+        }
         load_v((BITS == 2) ? chunk : 2 * chunk, av, nt);
     };
     auto load_Bk_as = [&](int chunk, bool two, auto nt) {
@@ -690,7 +707,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                 b_kz = dword_at(kz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
             } else if constexpr (NGRP == 2) b_ks = dword_at(ks, (uint32_t)(tb / G) * 256 + row_off, nt);
         }
-        if constexpr (OUT) { const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); b_ko = make_uint2(w[0], w[1]); }
+        if constexpr (OUT) {
+            const u2v w = stream_load<u2v, decltype(nt)::value>(ko + (size_t)tb * 16 + slot_off); b_ko = make_uint2(w[0], w[1]);
+            b_kov = kov[tb / 32 + ovf_lane / 4];
+        }
     };
     auto load_Bv_as = [&](int chunk, bool two, auto nt) {
         const int tb = chunk * kChunk + (two ? 32 : 0);
@@ -698,7 +718,10 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             b_vs = dword_at(vs, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
             b_vz = dword_at(vz, (uint32_t)tb * (2 * NCG) + vrow_off, nt);
         }
-        if constexpr (OUT) { const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); b_vo = make_uint2(w[0], w[1]); }
+        if constexpr (OUT) {
+            const u2v w = stream_load<u2v, decltype(nt)::value>(vo + (size_t)tb * 16 + slot_off); b_vo = make_uint2(w[0], w[1]);
+            b_vov = vov[tb / 32 + ovf_lane / 4];
+        }
         if constexpr (BITS != 2) load_v(2 * chunk + (two ? 1 : 0), bv, nt);
     };
     // Chunks from a.stream_from on are read with the non-temporal hint (wave-uniform choice; a 16-bit
@@ -791,7 +814,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     // been moved by the caller for both blocks of the chunk at once.
     auto compute = [&](auto mode, float (&lgio)[NT][4], const KWords<BITS>& k0, const KWords<BITS>& k1, uint32_t r_ks, uint32_t r_kz,
                        bool new_group, float bias, const VWords<BITS>& vv, int vblk, uint32_t r_vs, uint32_t r_vz, uint2 r_ko,
-                       uint2 r_vo) {
+                       uint2 r_vo, uint32_t r_kov, uint32_t r_vov, int tok0) {
         constexpr int MODE = decltype(mode)::value;
         uint32_t vsr[QUANT ? NT * 2 * NCG : 1], vzr[QUANT ? NT * 2 * NCG : 1];
         if constexpr (QUANT && MODE != 2) {
@@ -942,6 +965,22 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                         lg[t][i] = __builtin_fmaf(c, c_bias, lg[t][i]);
                     }
                 }
+                // key outliers beyond the rows' slots (rare): the block's stretch of the head's overflow list;
+                // both lanes of a hi / lo pair hold the token's logit and both add the whole term
+                const uint32_t e0 = (uint32_t)__builtin_amdgcn_readlane((int)r_kov, 0);
+                const uint32_t e1 = min((uint32_t)__builtin_amdgcn_readlane((int)r_kov, 1), (uint32_t)a.ovf_cap);
+                for (uint32_t e = e0; e < e1; ++e) {
+                    const uint32_t w = kov_e[2 * (size_t)e];
+                    const int tl = (int)kov_e[2 * (size_t)e + 1] - tok0;          // token within the block
+                    if (tl < 0 || tl >= 32) continue;                             // (never, for a list the library wrote)
+                    const float term = slot_delta(w) * __half2float(__ushort_as_half(qrow[w & 127u])) * c_bias;
+                    const bool mine = ((tl >> 2) & 3) == kb && ((SLOTS == 2) ? (tl >> 4) == slot : true);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (mine && (tl & 3) == i && ((SLOTS == 2) || (tl >> 4) == t)) lg[t][i] += term;
+                }
             }
         }
         if constexpr (MODE == 1) {
@@ -984,6 +1023,24 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                         if (__builtin_amdgcn_ballot_w64(w.y != 0u) != 0ull)
                             if (w.y) atomicAdd(oc + row8 * kHeadDim + (w.y & 127u), pw * slot_delta(w.y));
                     }
+                }
+            }
+            // value outliers beyond the rows' slots (rare): one lane per (row, token) -- the hi lane of the pair
+            {
+                const uint32_t e0 = (uint32_t)__builtin_amdgcn_readlane((int)r_vov, 0);
+                const uint32_t e1 = min((uint32_t)__builtin_amdgcn_readlane((int)r_vov, 1), (uint32_t)a.ovf_cap);
+                for (uint32_t e = e0; e < e1; ++e) {
+                    const uint32_t w = vov_e[2 * (size_t)e];
+                    const int tl = (int)vov_e[2 * (size_t)e + 1] - tok0;
+                    if (tl < 0 || tl >= 32) continue;
+                    const bool mine = live_row && part == 0 && ((tl >> 2) & 3) == kb && ((SLOTS == 2) ? (tl >> 4) == slot : true);
+                    float pw = 0.f;
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if ((tl & 3) == i && ((SLOTS == 2) || (tl >> 4) == t)) pw = p[t][i] * (float)(1 << v_pos_log2<BITS>(vblk, i));
+                    if (mine) atomicAdd(oc + row8 * kHeadDim + (w & 127u), pw * slot_delta(w));
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1167,7 +1224,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             // Both blocks' logits first, one move of the reference for the whole chunk, then both
             // blocks' softmax and PV products: one check per chunk instead of two, and each half of
             // the next chunk's loads leaves as soon as its registers are free.
-            compute(BoolI<1>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, 0u, 0u, no_slots, no_slots);
+            compute(BoolI<1>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, 0u, 0u, no_slots, no_slots, 0u, 0u, 0);
             if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; slot_off = 0; }   // (wave-uniform; the loop ends after this pass)
             load_Ak(nx);
             float mx = lgA[0][0];
@@ -1176,7 +1233,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
 #pragma unroll
                 for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lgA[t][i]);
             if (two) {
-                compute(BoolI<1>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, 0, 0u, 0u, no_slots, no_slots);
+                compute(BoolI<1>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, 0, 0u, 0u, no_slots, no_slots, 0u, 0u, 0);
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -1184,18 +1241,19 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             }
             load_Bk(nx, two_nx);
             advance_reference(quad_rows_max(mx));
-            compute(BoolI<2>{}, lgA, ak0, ak1, 0u, 0u, true, 0.f, av, 0, a_vs, a_vz, no_slots, no_slots);
+            compute(BoolI<2>{}, lgA, ak0, ak1, 0u, 0u, true, 0.f, av, 0, a_vs, a_vz, no_slots, no_slots, 0u, 0u, 0);
             if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
             load_Av(nx);
-            if (two) compute(BoolI<2>{}, lgB, bk0, bk1, 0u, 0u, false, 0.f, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz, no_slots, no_slots);
+            if (two) compute(BoolI<2>{}, lgB, bk0, bk1, 0u, 0u, false, 0.f, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz, no_slots, no_slots, 0u, 0u, 0);
             load_Bv(nx, two_nx);
         } else {
-            compute(BoolI<0>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, a_vs, a_vz, a_ko, a_vo);
+            compute(BoolI<0>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, a_vs, a_vz, a_ko, a_vo, a_kov, a_vov, chunk * kChunk);
             if constexpr (BITS == 2) bv = av;   // one 2-bit value word spans both blocks; keep it past the next prefetch
             // both blocks of the wave's next chunk are requested while this chunk's second block is computed
             if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; slot_off = 0; }   // (wave-uniform; the loop ends after this pass)
             load_A(nx);
-            if (two) compute(BoolI<0>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz, b_ko, b_vo);
+            if (two) compute(BoolI<0>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, (BITS == 2) ? 1 : 0, b_vs, b_vz, b_ko, b_vo, b_kov, b_vov,
+                             chunk * kChunk + 32);
             if (kEarlyB) load_B(nx, two_nx);
         }
         chunk = next; two = two_nx;
@@ -1488,6 +1546,9 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.head_n_kept = c.head_n_kept;
     a.k_out = outliers_on(cfg) ? (const uint32_t*)c.k_out : nullptr;
     a.v_out = outliers_on(cfg) ? (const uint32_t*)c.v_out : nullptr;
+    a.k_ovf = outliers_on(cfg) ? (const uint32_t*)c.k_ovf : nullptr;
+    a.v_ovf = outliers_on(cfg) ? (const uint32_t*)c.v_ovf : nullptr;
+    a.ovf_cap = cfg.outlier_overflow_cap;
     a.quantum = (cfg.bits != 16 && cfg.key_axis == KVQP_KEY_PER_CHANNEL) ? cfg.group_size : 32;
     a.n_q_heads = cfg.n_q_heads; a.n_kv_heads = cfg.n_kv_heads;
     a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;

@@ -25,6 +25,7 @@ int check_common(const kvqp_cfg* c) {
     if (!(c->outlier_threshold >= 0.0f) || c->outlier_threshold > 3.0e38f) return KVQP_ERR_INVALID_ARG;
     if (c->outlier_threshold > 0.0f && c->bits == 16) return KVQP_ERR_INVALID_ARG;   /* nothing is quantized at 16 bits */
     if (c->decode_cache_hint < KVQP_CACHE_AUTO || c->decode_cache_hint > KVQP_CACHE_KEEP) return KVQP_ERR_INVALID_ARG;
+    if (c->outlier_overflow_cap < 0 || c->outlier_overflow_cap > (1 << 28)) return KVQP_ERR_INVALID_ARG;
     const int gq = c->n_q_heads / c->n_kv_heads;
     if (c->head_dim != kHeadDim) return KVQP_ERR_UNSUPPORTED;
     if (!(gq == 1 || gq == 2 || gq == 4 || gq == 8)) return KVQP_ERR_UNSUPPORTED;
@@ -89,7 +90,7 @@ int check_cache_ptrs(const kvqp_cfg* c, const kvqp_cache* cache, int n_kept, boo
         if (!cache->k_codes || !cache->v_codes) return KVQP_ERR_INVALID_ARG;
         if (c->bits != 16 && (!cache->k_scale || !cache->k_zero || !cache->v_scale || !cache->v_zero))
             return KVQP_ERR_INVALID_ARG;
-        if (outliers_on(*c) && (!cache->k_out || !cache->v_out)) return KVQP_ERR_INVALID_ARG;
+        if (outliers_on(*c) && (!cache->k_out || !cache->v_out || !cache->k_ovf || !cache->v_ovf)) return KVQP_ERR_INVALID_ARG;
     }
     if (need_tail && (!cache->tail_k || !cache->tail_v)) return KVQP_ERR_INVALID_ARG;
     return KVQP_OK;
@@ -133,7 +134,7 @@ int kvqp_cache_sizes_cap(const kvqp_cfg* cfg, int32_t n_cap, int32_t tail_cap, s
     return fill_sizes(cfg, n_cap, tail_cap, sizes_out);
 }
 
-int kvqp_outlier_sizes(const kvqp_cfg* cfg, int32_t n_cap, size_t sizes_out[2]) {
+int kvqp_outlier_sizes(const kvqp_cfg* cfg, int32_t n_cap, size_t sizes_out[4]) {
     int rc = check_common(cfg);
     if (rc) return rc;
     if (!sizes_out || n_cap < 0) return KVQP_ERR_INVALID_ARG;
@@ -142,8 +143,11 @@ int kvqp_outlier_sizes(const kvqp_cfg* cfg, int32_t n_cap, size_t sizes_out[2]) 
         if ((rc = check_prompt(cfg))) return rc;
         n = n_kept_of(cfg);
     }
-    const size_t bytes = outliers_on(*cfg) ? (size_t)cfg->batch * cfg->n_kv_heads * (size_t)n * KVQP_OUTLIER_SLOTS * sizeof(uint32_t) : 0;
+    const size_t heads = (size_t)cfg->batch * cfg->n_kv_heads;
+    const size_t bytes = outliers_on(*cfg) ? heads * (size_t)n * KVQP_OUTLIER_SLOTS * sizeof(uint32_t) : 0;
+    const size_t list = outliers_on(*cfg) ? heads * ovf_words(n, cfg->outlier_overflow_cap) * sizeof(uint32_t) : 0;
     sizes_out[0] = bytes; sizes_out[1] = bytes;
+    sizes_out[2] = list; sizes_out[3] = list;
     return KVQP_OK;
 }
 

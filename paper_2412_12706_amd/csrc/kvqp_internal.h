@@ -26,6 +26,11 @@ inline size_t v_code_words(int n_kept, int bits) {
     return (size_t)((n_kept + sb - 1) / sb) * v_superblock_words(bits);
 }
 
+// Overflow buffer of one head and tensor (format statement in kvqp.h, "Outlier filtering"): the
+// prefix counts per 32 tokens, padded to a multiple of four words, then `cap` entries of two words.
+__host__ __device__ constexpr size_t ovf_start_words(int n_tok) { return ((size_t)(n_tok / 32 + 1) + 3) / 4 * 4; }
+__host__ __device__ constexpr size_t ovf_words(int n_tok, int cap) { return ovf_start_words(n_tok) + 2 * (size_t)cap; }
+
 // Element counts of scale/zero arrays per (batch, kv-head).
 inline size_t k_meta_elems(int n_kept, int bits, int G, int key_axis) {
     if (bits == 16) return 0;

@@ -1,8 +1,11 @@
 // Gather the surviving tokens, quantize them group by group and write the
 // packed cache (paper Section 3, "KV Quantization": z = min, m = max,
 // s = (m - z)/(2^B - 1), Q(G) = round((G - z)/s); grouping axes of Section 2 /
-// Section 6.3).  Memory-bound by design: every survivor row is read once
-// (2 x 256 B) and k*bpt bytes are written; there is no reuse to exploit.
+// Section 6.3).  Every survivor row is read once (2 x 256 B, scattered) and
+// k*bpt bytes are written; there is no reuse to exploit.  What bounds it on
+// the MI355X is the vector ALU as much as memory: the 2-bit variant runs with
+// the vector units ~98 % busy (order keys, the quantizer's individually
+// rounded binary32 steps, field packing) at ~5 TB/s of gathers and stores.
 //
 // One workgroup owns TB consecutive kept tokens of one (batch, kv head): whole
 // key groups (G | TB) and whole value superblocks (SB | TB).  Thread
@@ -36,6 +39,7 @@ struct QuantPackJob {
     bool copy_tail;
     const int32_t* head_base = nullptr;   // device: first destination token of each head in place of dst_base, or NULL
     int base_quantum = 1;                 // what every head_base entry is a multiple of
+    int ovf_cap = 0;                      // outlier filtering: entries of a head's overflow list
 };
 
 typedef unsigned short us2v __attribute__((ext_vector_type(2)));
@@ -179,7 +183,8 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     uint16_t* __restrict__ tail_k, uint16_t* __restrict__ tail_v, int L, int W, int n_kept, int key_axis,
     int tail_cap, int n_tok_blocks, int n_cap, int dst_base, const int32_t* __restrict__ head_n,
     uint32_t* __restrict__ k_out, uint32_t* __restrict__ v_out, uint32_t tau_bits,
-    const int32_t* __restrict__ head_base, int base_quantum) {
+    const int32_t* __restrict__ head_base, int base_quantum, uint32_t* __restrict__ k_ovf,
+    uint32_t* __restrict__ v_ovf, int ovf_cap) {
     // L: rows per head of the source tensors.  idx: source row of every token of this call
     // ([heads, n_kept]), or NULL for rows 0 .. n_kept-1.  The tokens land at positions dst_base ..
     // dst_base + n_kept - 1 of a cache whose buffers are laid out for n_cap tokens per head.
@@ -187,7 +192,9 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     // head_base: a head's own first position in place of dst_base, or NULL; it is cut to dst_base and
     // rounded down to a multiple of base_quantum, so whatever the array holds the stores stay inside
     // the buffers and on group and superblock boundaries.
-    // OUT: outlier filtering; k_out / v_out receive four slot words per token row.
+    // OUT: outlier filtering; k_out / v_out receive four slot words per token row, and the number of
+    // a block's further outliers is left at entry (block + 1) of the head's overflow prefix array
+    // (k_ovf / v_ovf), which ovf_scan then turns into prefix counts and ovf_fill completes.
     constexpr bool QUANT = BITS != 16;
     constexpr int TB = (QUANT && G == 128) ? 128 : 64;   // tokens per workgroup
     constexpr int R = TB / 16;                            // rows per thread
@@ -204,6 +211,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     __shared__ __align__(16) uint16_t s_min[QUANT ? 4 * NG * kHeadDim : 8];   // per wave: channel minima / maxima (order keys)
     __shared__ __align__(16) uint16_t s_max[QUANT ? 4 * NG * kHeadDim : 8];
     __shared__ __align__(16) float2 s_par[QUANT ? NG * kHeadDim : 1];     // (z, 1/s) per (key group, channel)
+    __shared__ int s_cnt[2][OUT ? TB / 32 : 1];                           // OUT: outliers beyond the slots per 32-token block (keys, values)
 
     const int head = blockIdx.y;
     const uint16_t* kh = k + (size_t)head * L * kHeadDim;
@@ -233,6 +241,10 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     const int n_head = head_n ? head_n[head] : n_kept;
     if (t0 >= n_head) return;                // (the whole workgroup: nothing of this head left)
     const int ntok = min(TB, n_head - t0);   // a multiple of 32 (and of G for per-channel keys)
+    if constexpr (OUT) {
+        if (threadIdx.x < 2 * (TB / 32)) (&s_cnt[0][0])[threadIdx.x] = 0;
+        __syncthreads();
+    }
 
     // ---- gather: all of the thread's rows of both tensors are requested before anything is used ----
     uint32_t kw[R][4], vw[R][4];
@@ -251,35 +263,18 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         vw[j][0] = b[0]; vw[j][1] = b[1]; vw[j][2] = b[2]; vw[j][3] = b[3];
     }
 
-    // Outlier marking (OUT): om gets a bit per own element that is an outlier of its token row.  A
-    // row's candidates are the elements with |x| above the threshold; when no row of the wave has more
-    // than four (the usual case) they all are outliers; otherwise the rows' elements compete by
-    // magnitude (then lower channel) in four rounds over the row's 16 lanes.
+    // Outlier marking (OUT): om gets a bit per own element whose magnitude is above the threshold --
+    // every such element of the row is an outlier (Section 6.3 item (1): no limit per row).
     auto mark = [&](const uint32_t (&w)[R][4], uint32_t (&om)[R]) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            uint32_t key[8], cand = 0u;
+            uint32_t cand = 0u;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint32_t mag = (w[j][e >> 1] >> (16 * (e & 1))) & 0x7fffu;
-                key[e] = mag > tau_bits ? (mag << 7) | (uint32_t)(127 - (8 * c8 + e)) : 0u;
                 cand |= mag > tau_bits ? (1u << e) : 0u;
             }
             om[j] = cand;
-            const uint32_t total = row16_sum((uint32_t)__builtin_popcount(cand));
-            if (__builtin_amdgcn_ballot_w64(total > 4u) == 0ull) continue;   // (wave-uniform)
-            om[j] = 0u;
-#pragma unroll
-            for (int sl = 0; sl < 4; ++sl) {
-                uint32_t m = max(max(max(key[0], key[1]), max(key[2], key[3])), max(max(key[4], key[5]), max(key[6], key[7])));
-                m = row16_max(m);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const bool mine = m != 0u && key[e] == m;
-                    om[j] |= mine ? (1u << e) : 0u;
-                    key[e] = mine ? 0u : key[e];
-                }
-            }
         }
     };
     // slot word of element x (binary16 pattern) in channel ch given its group's zero
@@ -287,10 +282,12 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         const float diff = __fsub_rn(half_bits_to_float((uint16_t)xh), zf);
         return (__float_as_uint(diff) & 0xFFFFFF00u) | 0x80u | ch;
     };
-    // Slot words of the rows, in ascending channel order: an outlier's slot index is the number of
-    // outliers before it in the row (lanes before this one, then the lane's own earlier elements);
-    // lanes 0-3 of the row clear the unused slots.  zero_of(j, e): the zero of element e's group in row j.
-    auto store_slots = [&](uint32_t* out, const uint32_t (&w)[R][4], const uint32_t (&om)[R], auto zero_of) {
+    // Slot words of the rows: an outlier's index is the number of outliers before it in the row
+    // (lanes before this one, then the lane's own earlier elements); the first four go to the row's
+    // slots in that (ascending channel) order, lanes 0-3 of the row clear the unused slots.  Outliers
+    // beyond the fourth belong to the head's overflow list, which a later kernel fills; here they are
+    // only counted per block of 32 tokens (cnt, in LDS).  zero_of(j, e): the zero of element e's group in row j.
+    auto store_slots = [&](uint32_t* out, int* cnt, const uint32_t (&w)[R][4], const uint32_t (&om)[R], auto zero_of) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             if (!live[j]) continue;                                   // (uniform over the workgroup)
@@ -300,11 +297,12 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             uint32_t* row = out + ((size_t)head * n_cap + d0 + r + 16 * j) * 4;
             if (c8 < 4 && (uint32_t)c8 >= total) row[c8] = 0u;
             if (__builtin_amdgcn_ballot_w64(om[j] != 0u) == 0ull) continue;
+            if (c8 == 0 && total > 4u) atomicAdd(&cnt[j >> 1], (int)(total - 4u));
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 if ((om[j] >> e) & 1u) {
                     const uint32_t xh = (w[j][e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                    row[at] = slot_word(xh, (uint32_t)(8 * c8 + e), zero_of(j, e));
+                    if (at < 4u) row[at] = slot_word(xh, (uint32_t)(8 * c8 + e), zero_of(j, e));
                     ++at;
                 }
         }
@@ -439,11 +437,11 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             }
         }
         if constexpr (OUT)   // the zero of (row j's key group, own channel 8 c8 + e) from the table the codes were made with
-            store_slots(k_out, kw, om, [&](int j, int e) { return s_par[(j / JPG) * kHeadDim + 8 * c8 + e].x; });
+            store_slots(k_out, s_cnt[0], kw, om, [&](int j, int e) { return s_par[(j / JPG) * kHeadDim + 8 * c8 + e].x; });
     } else {
         uint32_t codes[R][8];
         per_token(kw, k_scale, k_zero, codes, om, zrow);
-        if constexpr (OUT) store_slots(k_out, kw, om, [&](int j, int) { return __uint_as_float(zrow[j]); });
+        if constexpr (OUT) store_slots(k_out, s_cnt[0], kw, om, [&](int j, int) { return __uint_as_float(zrow[j]); });
 #pragma unroll
         for (int j = 0; j < R; ++j)
             if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
@@ -463,7 +461,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             uint32_t codes[R][8];
             if constexpr (OUT) mark(vw, om);
             per_token(vw, v_scale, v_zero, codes, om, zrow);
-            if constexpr (OUT) store_slots(v_out, vw, om, [&](int j, int) { return __uint_as_float(zrow[j]); });
+            if constexpr (OUT) store_slots(v_out, s_cnt[1], vw, om, [&](int j, int) { return __uint_as_float(zrow[j]); });
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const int b32 = j >> 1, H = j & 1;
@@ -509,6 +507,104 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         for (int item = threadIdx.x; item < n_sb * SBW / 4; item += kThreads)
             reinterpret_cast<uint4*>(vc)[item] = reinterpret_cast<const uint4*>(s_words)[item];
     }
+    if constexpr (OUT) {   // (the barrier before the value store orders every row's count before this)
+        const int tensor = threadIdx.x / (TB / 32), blk = threadIdx.x % (TB / 32);
+        if (threadIdx.x < 2 * (TB / 32) && 32 * blk < ntok) {
+            uint32_t* ovf = (tensor ? v_ovf : k_ovf) + (size_t)head * ovf_words(n_cap, ovf_cap);
+            ovf[d0 / 32 + blk + 1] = (uint32_t)s_cnt[tensor][blk];
+        }
+    }
+}
+
+// Raw block counts -> prefix counts, in place: entry b + 1 of a head's prefix array holds the
+// number of overflow outliers of block b (left there by the quantizer) for blocks first .. first +
+// n - 1, and entry `first` the prefix so far (set to 0 here when first == 0).  One wave per (head,
+// tensor); 64 blocks per round.
+__global__ __launch_bounds__(64) void ovf_scan(uint32_t* __restrict__ k_ovf, uint32_t* __restrict__ v_ovf, int n_cap, int ovf_cap,
+                                               int dst_base, int n_tok, const int32_t* __restrict__ head_n,
+                                               const int32_t* __restrict__ head_base, int base_quantum) {
+    const int head = blockIdx.x, lane = threadIdx.x;
+    uint32_t* start = (blockIdx.y ? v_ovf : k_ovf) + (size_t)head * ovf_words(n_cap, ovf_cap);
+    int base = dst_base;
+    if (head_base) {
+        base = min(max(head_base[head], 0), dst_base);
+        base -= base % base_quantum;
+    }
+    const int n_head = head_n ? min(max(head_n[head], 0), n_tok) : n_tok;
+    const int first = base / 32, n = n_head / 32;
+    if (first == 0 && lane == 0) start[0] = 0u;
+    __syncthreads();
+    uint32_t carry = start[first];
+    for (int b0 = 0; b0 < n; b0 += 64) {
+        const int b = b0 + lane;
+        uint32_t v = b < n ? start[first + b + 1] : 0u;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t o = __shfl_up(v, off);
+            if (lane >= off) v += o;
+        }
+        if (b < n) start[first + b + 1] = carry + v;
+        carry += __shfl(v, 63);
+    }
+}
+
+// The overflow entries of one block of 32 tokens (one wave): the block's rows are read again, the
+// outliers beyond a row's fourth found in channel order, and written as (word, token) at the block's
+// place in the head's list -- position = prefix count of the block + entries of the block's earlier
+// rows -- unless they lie beyond the list's capacity.  Most blocks have none and leave at once.
+template <int G>
+__global__ __launch_bounds__(64) void ovf_fill(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                               const int32_t* __restrict__ idx, const uint16_t* __restrict__ k_zero,
+                                               const uint16_t* __restrict__ v_zero, uint32_t* __restrict__ k_ovf,
+                                               uint32_t* __restrict__ v_ovf, int L, int n_kept, int key_axis, int n_cap,
+                                               int dst_base, const int32_t* __restrict__ head_n, uint32_t tau_bits,
+                                               const int32_t* __restrict__ head_base, int base_quantum, int ovf_cap) {
+    const int head = blockIdx.y, lane = threadIdx.x, tensor = blockIdx.z;
+    int base = dst_base;
+    if (head_base) {
+        base = min(max(head_base[head], 0), dst_base);
+        base -= base % base_quantum;
+    }
+    const int n_head = head_n ? min(max(head_n[head], 0), n_kept) : n_kept;
+    const int t0 = 32 * blockIdx.x;
+    if (t0 >= n_head) return;
+    uint32_t* ovf = (tensor ? v_ovf : k_ovf) + (size_t)head * ovf_words(n_cap, ovf_cap);
+    const int blk = (base + t0) / 32;
+    uint32_t at = ovf[blk];
+    if (ovf[blk + 1] == at) return;                  // (wave-uniform) nothing beyond the slots in this block
+    uint32_t* entries = ovf + ovf_start_words(n_cap);
+    const uint16_t* src = (tensor ? v : k) + (size_t)head * L * kHeadDim;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int t = t0; t < t0 + 32; ++t) {
+        const int pos = idx ? idx[(size_t)head * n_kept + t] : t;
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(src + (size_t)pos * kHeadDim + 2 * lane);   // channels 2 lane, 2 lane + 1
+        const bool c0 = (w & 0x7fffu) > tau_bits, c1 = ((w >> 16) & 0x7fffu) > tau_bits;
+        const unsigned long long b0 = __builtin_amdgcn_ballot_w64(c0), b1 = __builtin_amdgcn_ballot_w64(c1);
+        const uint32_t total = (uint32_t)(__popcll(b0) + __popcll(b1));
+        if (total <= 4u) continue;                   // (wave-uniform)
+        const uint32_t r0 = (uint32_t)(__popcll(b0 & lt_mask) + __popcll(b1 & lt_mask)), r1 = r0 + (c0 ? 1u : 0u);
+        const int tok = base + t;                    // the token's position in the head
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const bool is = e ? c1 : c0;
+            const uint32_t rank = e ? r1 : r0;
+            if (is && rank >= 4u) {
+                const int d = 2 * lane + e;
+                const size_t m = (tensor == 0 && key_axis == KVQP_KEY_PER_CHANNEL)
+                                     ? ((size_t)head * (n_cap / G) + tok / G) * kHeadDim + d
+                                     : ((size_t)head * n_cap + tok) * (kHeadDim / G) + d / G;
+                const float zf = half_bits_to_float((tensor ? v_zero : k_zero)[m]);
+                const uint32_t xh = e ? (w >> 16) : (w & 0xffffu);
+                const float diff = __fsub_rn(half_bits_to_float((uint16_t)xh), zf);
+                const uint32_t e_at = at + rank - 4u;
+                if (e_at < (uint32_t)ovf_cap) {
+                    entries[2 * (size_t)e_at] = (__float_as_uint(diff) & 0xFFFFFF00u) | 0x80u | (uint32_t)d;
+                    entries[2 * (size_t)e_at + 1] = (uint32_t)tok;
+                }
+            }
+        }
+        at += total - 4u;
+    }
 }
 #undef KVQP_SWAP16
 #undef KVQP_SWAP32
@@ -524,8 +620,19 @@ hipError_t launch_bits_g(const QuantPackJob& j, hipStream_t stream) {
                        (uint16_t*)j.c.k_zero, (uint16_t*)j.c.v_scale, (uint16_t*)j.c.v_zero, (uint16_t*)j.c.tail_k,
                        (uint16_t*)j.c.tail_v, j.src_rows, j.window, j.n_tok, j.key_axis, j.c.tail_cap, nblk, j.n_cap,
                        j.dst_base, j.head_n, (uint32_t*)j.c.k_out, (uint32_t*)j.c.v_out, j.tau_bits, j.head_base,
-                       j.base_quantum);
-    return hipGetLastError();
+                       j.base_quantum, (uint32_t*)j.c.k_ovf, (uint32_t*)j.c.v_ovf, j.ovf_cap);
+    hipError_t e = hipGetLastError();
+    if constexpr (OUT) {
+        if (e != hipSuccess || j.n_tok == 0) return e;
+        hipLaunchKernelGGL(ovf_scan, dim3(j.heads, 2), dim3(64), 0, stream, (uint32_t*)j.c.k_ovf, (uint32_t*)j.c.v_ovf, j.n_cap,
+                           j.ovf_cap, j.dst_base, j.n_tok, j.head_n, j.head_base, j.base_quantum);
+        hipLaunchKernelGGL((ovf_fill<G>), dim3(j.n_tok / 32, j.heads, 2), dim3(64), 0, stream, (const uint16_t*)j.k,
+                           (const uint16_t*)j.v, j.idx, (const uint16_t*)j.c.k_zero, (const uint16_t*)j.c.v_zero,
+                           (uint32_t*)j.c.k_ovf, (uint32_t*)j.c.v_ovf, j.src_rows, j.n_tok, j.key_axis, j.n_cap, j.dst_base,
+                           j.head_n, j.tau_bits, j.head_base, j.base_quantum, j.ovf_cap);
+        e = hipGetLastError();
+    }
+    return e;
 }
 template <int BITS>
 hipError_t launch_bits(const QuantPackJob& j, hipStream_t stream) {
@@ -600,6 +707,7 @@ static uint32_t threshold_bits(float tau) {
 }
 static void set_outliers(QuantPackJob& j, const kvqp_cfg& cfg) {
     j.outliers = outliers_on(cfg);
+    j.ovf_cap = cfg.outlier_overflow_cap;
     j.tau_bits = j.outliers ? threshold_bits(cfg.outlier_threshold) : 0x7fffu;
 }
 

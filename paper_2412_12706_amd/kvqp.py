@@ -31,14 +31,16 @@ class CfgStruct(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "seq_len", "window",
                                          "pool_kernel", "budget", "bits", "group_size", "key_axis",
                                          "decode_splits")] + [("sm_scale", C.c_float), ("outlier_threshold", C.c_float),
-                                                            ("decode_cache_hint", C.c_int32)]
+                                                            ("decode_cache_hint", C.c_int32),
+                                                            ("outlier_overflow_cap", C.c_int32)]
 
 
 class CacheStruct(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero",
                                           "tail_k", "tail_v")] + [(n, C.c_int32) for n in
                                                                   ("n_kept", "tail_len", "tail_cap", "n_cap")] + [
-        ("head_n_kept", C.c_void_p), ("k_out", C.c_void_p), ("v_out", C.c_void_p)]
+        ("head_n_kept", C.c_void_p), ("k_out", C.c_void_p), ("v_out", C.c_void_p), ("k_ovf", C.c_void_p),
+        ("v_ovf", C.c_void_p)]
 
 
 _lib = None
@@ -101,11 +103,13 @@ class Cfg:
     sm_scale: float = 128 ** -0.5
     outlier_threshold: float = 0.0
     decode_cache_hint: int = 0      # CACHE_AUTO / CACHE_STREAM / CACHE_KEEP
+    outlier_overflow_cap: int = 0   # entries of one head's overflow list (outlier filtering)
 
     def struct(self) -> CfgStruct:
         return CfgStruct(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.seq_len, self.window,
                          self.pool_kernel, self.budget, self.bits, self.group_size, self.key_axis,
-                         self.decode_splits, self.sm_scale, self.outlier_threshold, self.decode_cache_hint)
+                         self.decode_splits, self.sm_scale, self.outlier_threshold, self.decode_cache_hint,
+                         self.outlier_overflow_cap)
 
     @property
     def n_kept(self) -> int:
@@ -129,7 +133,7 @@ def cache_sizes_cap(cfg: Cfg, n_cap: int, tail_cap: int):
 
 
 def outlier_sizes(cfg: Cfg, n_cap: int = 0):
-    out = (C.c_size_t * 2)()
+    out = (C.c_size_t * 4)()
     rc = lib().kvqp_outlier_sizes(C.byref(cfg.struct()), n_cap, out)
     if rc:
         raise KvqpError(rc, "kvqp_outlier_sizes")
@@ -161,7 +165,7 @@ class Cache:
     def struct(self) -> CacheStruct:
         ptrs = [self.buffers[n].data_ptr() if self.buffers[n].numel() else None for n in _NAMES]
         outs = [self.buffers[n].data_ptr() if n in self.buffers and self.buffers[n].numel() else None
-                for n in ("k_out", "v_out")]
+                for n in ("k_out", "v_out", "k_ovf", "v_ovf")]
         return CacheStruct(*ptrs, self.n_kept, self.tail_len, self.tail_cap, self.n_cap,
                            None if self.head_n_kept is None else self.head_n_kept.data_ptr(), *outs)
 
@@ -177,7 +181,7 @@ def alloc_cache(cfg: Cfg, tail_cap: int | None = None, device="cuda", n_cap: int
     sizes = cache_sizes_cap(cfg, n_cap, tail_cap) if n_cap else cache_sizes(cfg, tail_cap)
     bufs = {n: torch.empty(max(s, 0), dtype=torch.uint8, device=device) for n, s in zip(_NAMES, sizes)}
     if cfg.outlier_threshold > 0:
-        for n, s in zip(("k_out", "v_out"), outlier_sizes(cfg, n_cap)):
+        for n, s in zip(("k_out", "v_out", "k_ovf", "v_ovf"), outlier_sizes(cfg, n_cap)):
             bufs[n] = torch.empty(s, dtype=torch.uint8, device=device)
     counts = torch.zeros(cfg.batch * cfg.n_kv_heads, dtype=torch.int32, device=device) if ragged else None
     return Cache(bufs, 0, 0, tail_cap, n_cap, counts)

@@ -18,10 +18,31 @@ def upload_cache(oc, device="cuda"):
     for n in NAMES:
         arr = np.ascontiguousarray(getattr(oc, n))
         bufs[n] = torch.from_numpy(arr.view(np.uint8).reshape(-1).copy()).to(device)
-    if getattr(oc, "k_out", None) is not None:        # outlier slots
-        for n in ("k_out", "v_out"):
+    if getattr(oc, "k_out", None) is not None:        # outlier slots and overflow lists (compact layout: the same bytes)
+        for n in ("k_out", "v_out", "k_ovf", "v_ovf"):
             bufs[n] = torch.from_numpy(np.ascontiguousarray(getattr(oc, n)).view(np.uint8).reshape(-1).copy()).to(device)
     return kvqp.Cache(bufs, oc.n_kept, oc.tail_len, oc.tail_cap)
+
+
+def ovf_split(words, n_layout, cap):
+    """One head's overflow buffer (uint32 words, laid out for n_layout tokens and cap entries, the
+    format statement of kvqp.h) -> (prefix counts [n_layout/32 + 1], entry words [cap, 2])."""
+    n_start = (n_layout // 32 + 1 + 3) // 4 * 4
+    words = np.asarray(words).reshape(-1)
+    assert words.size == n_start + 2 * cap, (words.size, n_start, cap)
+    return words[: n_layout // 32 + 1], words[n_start:].reshape(cap, 2)
+
+
+def assert_overflow_equal(got_words, n_layout, ref_words, n_tok, cap, what=""):
+    """The library's overflow buffer of one head (laid out for n_layout >= n_tok tokens) against the
+    checker's (laid out for n_tok): the prefix counts of the n_tok tokens and the stored entries;
+    what lies beyond them is unspecified."""
+    gs, ge = ovf_split(got_words, n_layout, cap)
+    rs, re_ = ovf_split(ref_words, n_tok, cap)
+    assert np.array_equal(gs[: n_tok // 32 + 1], rs), (what, gs[: n_tok // 32 + 1][-4:], rs[-4:])
+    n = min(int(rs[-1]), cap)
+    assert np.array_equal(ge[:n], re_[:n]), (what, n)
+    return int(rs[-1])
 
 
 def download(cache, name, dtype):
@@ -32,6 +53,13 @@ def assert_cache_equal(gc, oc):
     """Every buffer of the device cache equals the checker's, bit for bit."""
     assert gc.n_kept == oc.n_kept and gc.tail_len == oc.tail_len
     names = NAMES + (("k_out", "v_out") if getattr(oc, "k_out", None) is not None else ())
+    if getattr(oc, "k_out", None) is not None:
+        heads = oc.B * oc.Hkv
+        for n in ("k_ovf", "v_ovf"):
+            got = download(gc, n, np.uint32).reshape(heads, -1)
+            ref = np.ascontiguousarray(getattr(oc, n)).reshape(heads, -1)
+            for h in range(heads):
+                assert_overflow_equal(got[h], gc.n_cap or gc.n_kept, ref[h], oc.n_kept, oc.ovf_cap, f"{n} head {h}")
     for n in names:
         ref = np.ascontiguousarray(getattr(oc, n))
         got = download(gc, n, ref.dtype)

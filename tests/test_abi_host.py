@@ -203,9 +203,11 @@ def test_outlier_filtering_argument_checks(lib):
     """Slot buffer sizes and the host-side rejects of the outlier-filtering mode."""
     base = dict(batch=2, n_q_heads=8, n_kv_heads=2, seq_len=800, window=32, budget=256, bits=4, group_size=32)
     on = kvqp.Cfg(**base, outlier_threshold=6.0)
-    assert kvqp.outlier_sizes(on) == [2 * 2 * 256 * 4 * 4] * 2              # heads x tokens x 4 slots x 4 bytes
-    assert kvqp.outlier_sizes(on, 320) == [2 * 2 * 320 * 4 * 4] * 2
-    assert kvqp.outlier_sizes(kvqp.Cfg(**base)) == [0, 0]
+    assert kvqp.outlier_sizes(on)[:2] == [2 * 2 * 256 * 4 * 4] * 2          # heads x tokens x 4 slots x 4 bytes
+    assert kvqp.outlier_sizes(on, 320)[:2] == [2 * 2 * 320 * 4 * 4] * 2
+    assert kvqp.outlier_sizes(on)[2:] == [2 * 2 * 12 * 4] * 2               # no list entries asked for: the prefix counts (9, padded to 12) alone
+    assert kvqp.outlier_sizes(kvqp.Cfg(**{**on.__dict__, 'outlier_overflow_cap': 100}), 320)[2:] == [2 * 2 * (12 + 200) * 4] * 2
+    assert kvqp.outlier_sizes(kvqp.Cfg(**base)) == [0, 0, 0, 0]
     for bad in (-1.0, float("nan"), float("inf")):
         with pytest.raises(kvqp.KvqpError):
             kvqp.outlier_sizes(kvqp.Cfg(**base, outlier_threshold=bad))

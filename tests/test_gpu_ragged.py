@@ -13,7 +13,7 @@ import pytest
 import torch
 
 from paper_2412_12706_amd import kvqp, synth
-from tests.gpu_util import attn_excess, attn_maxabs, dev, download
+from tests.gpu_util import assert_overflow_equal, attn_excess, attn_maxabs, dev, download
 from tests.test_gpu_compress import check_indices
 
 pytestmark = pytest.mark.gpu
@@ -231,7 +231,7 @@ def test_append_with_head_level_counts(orc, bits, G, key_axis, n_app, tau):
     for h, n in enumerate(counts):
         idx[h // Hkv, h % Hkv, :n] = np.sort(rng.choice(P, n, replace=False))
     cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=P + grown, window=W, budget=bound, bits=bits,
-                   group_size=G, key_axis=key_axis, outlier_threshold=tau)
+                   group_size=G, key_axis=key_axis, outlier_threshold=tau, outlier_overflow_cap=500 if tau else 0)
     cap = grown + 3
     gc = kvqp.alloc_cache(cfg, tail_cap=cap, n_cap=bound + 2 * n_app + (-(bound + 2 * n_app)) % 128, ragged=True)
     for t in gc.buffers.values():
@@ -243,7 +243,7 @@ def test_append_with_head_level_counts(orc, bits, G, key_axis, n_app, tau):
         gc.buffers[name].view(torch.uint16).view(heads, cap, 128)[:, :grown] = rows.view(heads, grown, 128)
     gc.tail_len = grown
     ws = kvqp.alloc_decode_workspace(cfg)
-    kw = dict(tau=tau) if tau else {}
+    kw = dict(tau=tau, ovf_cap=500) if tau else {}
     for rnd in (1, 2):
         kvqp.append_tail_ragged(cfg, gc, n_app, counts)
         counts = [c + n_app for c in counts]
@@ -269,6 +269,9 @@ def test_append_with_head_level_counts(orc, bits, G, key_axis, n_app, tau):
             for nm in names:
                 ref = getattr(oc, nm).reshape(-1)
                 assert np.array_equal(head_share(gc, nm, dts[nm], heads, h, ref.size), ref), (nm, h)
+            if tau:
+                for nm in ("k_ovf", "v_ovf"):
+                    assert_overflow_equal(download(gc, nm, np.uint32).reshape(heads, -1)[h], gc.n_cap, getattr(oc, nm).reshape(-1), n, 500, (nm, h))
             for nm in ("tail_k", "tail_v"):
                 ref = getattr(oc, nm).reshape(-1)[: (grown - moved) * 128]
                 assert np.array_equal(head_share(gc, nm, np.uint16, heads, h, ref.size), ref), (nm, h)

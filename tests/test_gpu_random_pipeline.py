@@ -14,7 +14,7 @@ import pytest
 import torch
 
 from paper_2412_12706_amd import kvqp, synth
-from tests.gpu_util import ATTN_TOL, attn_excess, attn_maxabs, dev
+from tests.gpu_util import ATTN_TOL, assert_overflow_equal, attn_excess, attn_maxabs, dev, download
 from tests.test_gpu_compress import check_indices
 from tests.test_gpu_ragged import head_share
 
@@ -48,7 +48,10 @@ def draw_case(rng):
                 counts=counts, n_app=n_app)
 
 
-def compare_head(orc, gc, oc, h, heads, n, bits, tau, tail_rows):
+OVF_CAP = 600     # overflow list entries per head in the walks with outlier filtering
+
+
+def compare_head(orc, gc, oc, h, heads, n, bits, tau, tail_rows, n_layout):
     E = 32 // bits
     assert np.array_equal(head_share(gc, "k_codes", np.uint32, heads, h, n * D // E), oc.k_codes.reshape(-1)), ("k_codes", h)
     assert np.array_equal(head_share(gc, "v_codes", np.uint32, heads, h, oc.v_codes.size), oc.v_codes.reshape(-1)), ("v_codes", h)
@@ -58,6 +61,10 @@ def compare_head(orc, gc, oc, h, heads, n, bits, tau, tail_rows):
     for nm, dt in names.items():
         ref = getattr(oc, nm).reshape(-1)
         assert np.array_equal(head_share(gc, nm, dt, heads, h, ref.size), ref), (nm, h)
+    if tau:    # the rows' outliers beyond their four slots: prefix counts and list entries
+        for nm in ("k_ovf", "v_ovf"):
+            got = download(gc, nm, np.uint32)
+            assert_overflow_equal(got.reshape(heads, -1)[h], n_layout, getattr(oc, nm).reshape(-1), n, OVF_CAP, (nm, h))
     for nm in ("tail_k", "tail_v"):
         ref = getattr(oc, nm).reshape(-1)[: tail_rows * D]
         assert np.array_equal(head_share(gc, nm, np.uint16, heads, h, ref.size), ref), (nm, h)
@@ -97,7 +104,8 @@ def test_random_walks_through_the_path(orc, block):
         if tau:
             v[..., [5, 77]] *= 10
         cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, pool_kernel=pool, budget=bound, bits=bits,
-                       group_size=G, key_axis=axis, outlier_threshold=tau, decode_cache_hint=c["hint"])
+                       group_size=G, key_axis=axis, outlier_threshold=tau, decode_cache_hint=c["hint"],
+                       outlier_overflow_cap=OVF_CAP if tau else 0)
         sm = float(np.float32(cfg.sm_scale))
         assert cfg.n_kept == bound
         n_cap = 0
@@ -116,7 +124,7 @@ def test_random_walks_through_the_path(orc, block):
         torch.cuda.synchronize()
         assert gc.n_kept == bound and gc.tail_len == W
         idx_gpu = idx_dev.cpu().numpy()
-        kw = dict(tau=tau) if tau else {}
+        kw = dict(tau=tau, ovf_cap=OVF_CAP) if tau else {}
         refs, kept = [], []
         for h in range(heads):
             b, g, n = h // Hkv, h % Hkv, counts[h]
@@ -127,7 +135,7 @@ def test_random_walks_through_the_path(orc, block):
                                                   bits=bits, G=G, sm_scale=sm, key_axis=axis, **kw)
                 check_indices(got, idx_orc, pooled)
             oc = orc.quantize_selected(ks, vs, got, W=W, bits=bits, G=G, key_axis=axis, **kw)
-            compare_head(orc, gc, oc, h, heads, n, bits, tau, W)
+            compare_head(orc, gc, oc, h, heads, n, bits, tau, W, n_cap or bound)
             refs.append(oc)
             kept.append(got.reshape(-1))
         ws = kvqp.alloc_decode_workspace(cfg)
@@ -157,7 +165,7 @@ def test_random_walks_through_the_path(orc, block):
             vs = np.concatenate([v[b:b + 1, g:g + 1], new_v[b:b + 1, g:g + 1]], axis=2)
             own = np.concatenate([kept[h], np.arange(P, P + n_app, dtype=np.int32)]).reshape(1, 1, n)
             oc = orc.quantize_selected(ks, vs, own, W=W + extra - n_app, bits=bits, G=G, key_axis=axis, **kw)
-            compare_head(orc, gc, oc, h, heads, n, bits, tau, W + extra - n_app)
+            compare_head(orc, gc, oc, h, heads, n, bits, tau, W + extra - n_app, n_cap or bound)
             refs.append(oc)
         q = synth.decode_query_host(B, Hq, D, config=500 + 10 * block + case, step=1)
         worst = decode_and_compare(orc, cfg, gc, refs, q, ws, Hkv, Gq, sm)
