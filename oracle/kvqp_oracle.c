@@ -323,7 +323,7 @@ int orc_quantize_group(const uint16_t *x, int n, int stride, int bits, uint16_t 
 /* go, in ascending (token, channel) order, to the head's overflow      */
 /* list as entries (word, token), with a prefix count per block of 32   */
 /* tokens in front of it:                                               */
-/*   int32  start[n_tok/32 + 1], padded to a multiple of 4 ints:        */
+/*   int32  start[ceil(n_tok/32) + 1], padded to a multiple of 4 ints:  */
 /*          start[b] = overflow entries of tokens before 32 b           */
 /*   uint32 entry[ovf_cap][2] = (word, token index in the head)         */
 /* Entries beyond ovf_cap are not stored (start[] still counts them, so  */
@@ -343,10 +343,12 @@ int orc_mark_outliers(const uint16_t *row, int D, double tau, uint8_t *is_out)
     return n;
 }
 
+int orc_rows(int n_tok); /* the token count rounded up to whole blocks of 32 (defined with the layouts) */
+
 /* Words of one head's overflow buffer laid out for n_tok tokens and cap entries (format above). */
 size_t orc_ovf_words(int n_tok, int cap)
 {
-    size_t start = ((size_t)(n_tok / 32 + 1) + 3) / 4 * 4;
+    size_t start = ((size_t)(orc_rows(n_tok) / 32 + 1) + 3) / 4 * 4;
     return start + 2 * (size_t)cap;
 }
 
@@ -393,7 +395,14 @@ double orc_outlier_value(uint32_t slot, uint16_t zb)
 
 static int fields_per_word(int bits) { return 32 / bits; }
 
-size_t orc_k_words(int n_tok, int D, int bits) { return (size_t)n_tok * D * bits / 32; }
+/* Token counts need not fill whole blocks or groups (Section 3: any s < n).  The per-token arrays
+ * of a head (key code rows, per-token scales and zeros, outlier slots) are laid out for the count
+ * rounded up to whole blocks of 32 tokens, the rows past the count holding zeros; per-channel key
+ * groups number ceil(n / G), the last one having fewer than G members when G does not divide n. */
+int orc_rows(int n_tok) { return (n_tok + 31) / 32 * 32; }
+int orc_key_groups(int n_tok, int G) { return (n_tok + G - 1) / G; }
+
+size_t orc_k_words(int n_tok, int D, int bits) { return (size_t)orc_rows(n_tok) * D * bits / 32; }
 
 static void k_locate(int D, int bits, int t, int d, size_t *word, int *shift)
 {
@@ -474,13 +483,16 @@ static void v_code_put(uint32_t *codes, int D, int bits, int t, int d, uint32_t 
 /* axis); key_axis 1 groups G consecutive channels of one token         */
 /* (per-token, the FlexGen axis).  Values are always per-token.  The    */
 /* last W prompt rows are copied unquantized into the tail.             */
-/*   k_scale/k_zero: [B,Hkv,n_kept/G,D] (axis 0) or [B,Hkv,n_kept,D/G]  */
-/*   v_scale/v_zero: [B,Hkv,n_kept,D/G]                                 */
+/*   k_scale/k_zero: [B,Hkv,ceil(n_kept/G),D] (axis 0) or              */
+/*                   [B,Hkv,rows,D/G], rows = orc_rows(n_kept)          */
+/*   v_scale/v_zero: [B,Hkv,rows,D/G]                                   */
+/* When G does not divide n_kept the last per-channel key group has the */
+/* remaining n_kept mod G tokens: the same quantizer on fewer members.  */
 /*   tail_k/tail_v : [B,Hkv,tail_cap,D], first W rows written           */
 /* ------------------------------------------------------------------ */
 /* tau < 0: no outlier filtering (k_out, v_out, k_ovf, v_ovf unused).  Otherwise k_out, v_out
- * [B,Hkv,n_kept,ORC_OUT_SLOTS] receive the slot words and k_ovf, v_ovf
- * [B,Hkv,orc_ovf_words(n_kept, ovf_cap)] the overflow buffers (bits 2, 4, 8 only; n_kept % 32 == 0). */
+ * [B,Hkv,rows,ORC_OUT_SLOTS] receive the slot words and k_ovf, v_ovf
+ * [B,Hkv,orc_ovf_words(n_kept, ovf_cap)] the overflow buffers (bits 2, 4, 8 only). */
 static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kept, int bits, int G,
                                   int key_axis, int tail_cap, const uint16_t *k, const uint16_t *v,
                                   const int32_t *idx, uint32_t *k_codes, uint32_t *v_codes,
@@ -492,10 +504,11 @@ static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kep
     if (!(bits == 2 || bits == 4 || bits == 8 || bits == 16) || D % 64 || W > tail_cap || W > L)
         return -1;
     const int filt = tau >= 0.0;
-    if (filt && (bits == 16 || !k_out || !v_out || !k_ovf || !v_ovf || ovf_cap < 0 || D > 128 || n_kept % 32))
+    if (filt && (bits == 16 || !k_out || !v_out || !k_ovf || !v_ovf || ovf_cap < 0 || D > 128))
         return -1;
-    if (bits != 16 && (G < 1 || D % G || (key_axis == 0 && n_kept % G)))
+    if (bits != 16 && (G < 1 || D % G))
         return -1;
+    const int rows = orc_rows(n_kept), n_groups = bits == 16 ? 0 : orc_key_groups(n_kept, G);
     const int P = L - W;
     const size_t kw = orc_k_words(n_kept, D, bits), vw = orc_v_words(n_kept, D, bits);
     uint8_t *codes = (uint8_t *)malloc((size_t)(G > D ? G : D) + 1);
@@ -536,22 +549,24 @@ static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kep
             } else {
                 if (key_axis == 0) {
                     uint16_t *gath = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)G);
-                    for (int u = 0; u < n_kept / G; ++u)
+                    for (int u = 0; u < n_groups; ++u) {
+                        const int members = n_kept - u * G < G ? n_kept - u * G : G; /* the last group may be short */
                         for (int d = 0; d < D; ++d) {
-                            for (int e = 0; e < G; ++e)
+                            for (int e = 0; e < members; ++e)
                                 gath[e] = kh[(size_t)id[u * G + e] * D + d];
-                            size_t m = (head * (size_t)(n_kept / G) + u) * D + d;
-                            quantize_group_excl(gath, G, 1, bits,
+                            size_t m = (head * (size_t)n_groups + u) * D + d;
+                            quantize_group_excl(gath, members, 1, bits,
                                                 filt ? kmask + (size_t)u * G * D + d : NULL, D,
                                                 &k_scale[m], &k_zero[m], codes);
-                            for (int e = 0; e < G; ++e)
+                            for (int e = 0; e < members; ++e)
                                 k_code_put(kc, D, bits, u * G + e, d, codes[e]);
                         }
+                    }
                     free(gath);
                 } else {
                     for (int t = 0; t < n_kept; ++t)
                         for (int c = 0; c < D / G; ++c) {
-                            size_t m = (head * (size_t)n_kept + t) * (D / G) + c;
+                            size_t m = (head * (size_t)rows + t) * (D / G) + c;
                             quantize_group_excl(kh + (size_t)id[t] * D + c * G, G, 1, bits,
                                                 filt ? kmask + (size_t)t * D + c * G : NULL, 1,
                                                 &k_scale[m], &k_zero[m], codes);
@@ -561,7 +576,7 @@ static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kep
                 }
                 for (int t = 0; t < n_kept; ++t)
                     for (int c = 0; c < D / G; ++c) {
-                        size_t m = (head * (size_t)n_kept + t) * (D / G) + c;
+                        size_t m = (head * (size_t)rows + t) * (D / G) + c;
                         quantize_group_excl(vh + (size_t)id[t] * D + c * G, G, 1, bits,
                                             filt ? vmask + (size_t)t * D + c * G : NULL, 1,
                                             &v_scale[m], &v_zero[m], codes);
@@ -577,8 +592,8 @@ static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kep
                 memset(vov, 0, ow * 4);
                 int32_t nko = 0, nvo = 0; /* overflow entries so far */
                 for (int t = 0; t < n_kept; ++t) {
-                    uint32_t *ko = k_out + (head * (size_t)n_kept + t) * ORC_OUT_SLOTS;
-                    uint32_t *vo = v_out + (head * (size_t)n_kept + t) * ORC_OUT_SLOTS;
+                    uint32_t *ko = k_out + (head * (size_t)rows + t) * ORC_OUT_SLOTS;
+                    uint32_t *vo = v_out + (head * (size_t)rows + t) * ORC_OUT_SLOTS;
                     memset(ko, 0, sizeof(uint32_t) * ORC_OUT_SLOTS);
                     memset(vo, 0, sizeof(uint32_t) * ORC_OUT_SLOTS);
                     if (t % 32 == 0) {
@@ -586,9 +601,9 @@ static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kep
                         vov[t / 32] = (uint32_t)nvo;
                     }
                     for (int d = 0; d < D; ++d) { /* ascending channel */
-                        size_t mk = key_axis == 0 ? (head * (size_t)(n_kept / G) + t / G) * D + d
-                                                  : (head * (size_t)n_kept + t) * (D / G) + d / G;
-                        size_t mv = (head * (size_t)n_kept + t) * (D / G) + d / G;
+                        size_t mk = key_axis == 0 ? (head * (size_t)n_groups + t / G) * D + d
+                                                  : (head * (size_t)rows + t) * (D / G) + d / G;
+                        size_t mv = (head * (size_t)rows + t) * (D / G) + d / G;
                         const int rk = kmask[(size_t)t * D + d], rv = vmask[(size_t)t * D + d];
                         if (rk) {
                             uint32_t w = orc_outlier_slot(kh[(size_t)id[t] * D + d], k_zero[mk], d);
@@ -616,8 +631,8 @@ static int quantize_selected_impl(int B, int Hkv, int D, int L, int W, int n_kep
                         }
                     }
                 }
-                kov[n_kept / 32] = (uint32_t)nko;
-                vov[n_kept / 32] = (uint32_t)nvo;
+                kov[rows / 32] = (uint32_t)nko;
+                vov[rows / 32] = (uint32_t)nvo;
             }
             for (int i = 0; i < W; ++i) {
                 memcpy(tail_k + (head * tail_cap + i) * (size_t)D, kh + (size_t)(P + i) * D,
@@ -745,7 +760,7 @@ static void dequantize_head(int D, int n_kept, int bits, int G, int key_axis, in
         }
     if (ko && vo && kov && vov) { /* the rows' further outliers */
         const size_t n_start = orc_ovf_words(n_kept, ovf_cap) - 2 * (size_t)ovf_cap;
-        const uint32_t nk = kov[n_kept / 32], nv = vov[n_kept / 32];
+        const uint32_t nk = kov[orc_rows(n_kept) / 32], nv = vov[orc_rows(n_kept) / 32];
         for (uint32_t e = 0; e < nk && e < (uint32_t)ovf_cap; ++e) {
             uint32_t a = kov[n_start + 2 * (size_t)e];
             int t = (int)kov[n_start + 2 * (size_t)e + 1], d = (int)(a & 0x7Fu);
@@ -779,10 +794,11 @@ static int decode_attn_impl(int B, int Hq, int Hkv, int D, int n_kept, int bits,
     const size_t ow = k_out ? orc_ovf_words(n_kept, ovf_cap) : 0;
     const int Gq = Hq / Hkv, T = n_kept + tail_len;
     const size_t kw = orc_k_words(n_kept, D, bits), vw = orc_v_words(n_kept, D, bits);
+    const size_t rows = (size_t)orc_rows(n_kept);
     const size_t kmeta = bits == 16 ? 0
-                         : key_axis == 0 ? (size_t)(n_kept / G) * D
-                                         : (size_t)n_kept * (D / G);
-    const size_t vmeta = bits == 16 ? 0 : (size_t)n_kept * (D / G);
+                         : key_axis == 0 ? (size_t)orc_key_groups(n_kept, G) * D
+                                         : rows * (D / G);
+    const size_t vmeta = bits == 16 ? 0 : rows * (D / G);
     int status = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic)
     for (int b = 0; b < B; ++b)
@@ -803,8 +819,8 @@ static int decode_attn_impl(int B, int Hq, int Hkv, int D, int n_kept, int bits,
                             v_scale + head * vmeta, v_zero + head * vmeta,
                             tail_k + head * (size_t)tail_cap * D,
                             tail_v + head * (size_t)tail_cap * D,
-                            k_out ? k_out + head * (size_t)n_kept * ORC_OUT_SLOTS : NULL,
-                            v_out ? v_out + head * (size_t)n_kept * ORC_OUT_SLOTS : NULL, ovf_cap,
+                            k_out ? k_out + head * rows * ORC_OUT_SLOTS : NULL,
+                            v_out ? v_out + head * rows * ORC_OUT_SLOTS : NULL, ovf_cap,
                             k_out ? k_ovf + head * ow : NULL, k_out ? v_ovf + head * ow : NULL, Kd, Vd);
             for (int h = g * Gq; h < (g + 1) * Gq; ++h) {
                 const uint16_t *qr = q + ((size_t)b * Hq + h) * (size_t)D;
@@ -859,7 +875,7 @@ int orc_decode_attn_outliers(int B, int Hq, int Hkv, int D, int n_kept, int bits
                              const uint32_t *v_out, int ovf_cap, const uint32_t *k_ovf,
                              const uint32_t *v_ovf, double *out)
 {
-    if (!k_out || !v_out || !k_ovf || !v_ovf || ovf_cap < 0 || n_kept % 32)
+    if (!k_out || !v_out || !k_ovf || !v_ovf || ovf_cap < 0)
         return -1;
     return decode_attn_impl(B, Hq, Hkv, D, n_kept, bits, G, key_axis, sm_scale, tail_len, tail_cap,
                             q, k_codes, v_codes, k_scale, k_zero, v_scale, v_zero, tail_k, tail_v,

@@ -51,6 +51,10 @@ def lib():
         L.orc_k_code_get.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
         L.orc_v_code_get.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
         L.orc_threads.restype = C.c_int
+        L.orc_rows.restype = C.c_int
+        L.orc_rows.argtypes = [C.c_int]
+        L.orc_key_groups.restype = C.c_int
+        L.orc_key_groups.argtypes = [C.c_int, C.c_int]
         L.orc_mark_outliers.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_void_p]
         L.orc_ovf_words.restype = C.c_size_t
         L.orc_ovf_words.argtypes = [C.c_int, C.c_int]
@@ -152,7 +156,7 @@ def ovf_entries(buf, n_tok, cap):
     """One head's overflow buffer -> (start int32 [n_tok/32 + 1], entries uint32 [min(total, cap), 2])."""
     buf = np.ascontiguousarray(buf).view(np.uint32).reshape(-1)
     n_start = ovf_words(n_tok, cap) - 2 * cap
-    start = buf[: n_tok // 32 + 1].astype(np.int64)
+    start = buf[: rows(n_tok) // 32 + 1].astype(np.int64)
     n = min(int(start[-1]), cap)
     return start, buf[n_start:n_start + 2 * n].reshape(n, 2)
 
@@ -184,6 +188,16 @@ def v_code_at(words, D, bits, t, d):
     return int(lib().orc_v_code_get(_p(words), D, bits, t, d))
 
 
+def rows(n_tok):
+    """Rows the per-token arrays of a head are laid out for (whole blocks of 32; the rest zeros)."""
+    return int(lib().orc_rows(int(n_tok)))
+
+
+def key_groups(n_tok, G):
+    """Per-channel key groups of n_tok tokens (the last one short when G does not divide n_tok)."""
+    return int(lib().orc_key_groups(int(n_tok), int(G)))
+
+
 def k_words(n_tok, D, bits):
     return int(lib().orc_k_words(n_tok, D, bits))
 
@@ -206,7 +220,7 @@ class Cache:
     tail_cap: int
     k_codes: np.ndarray  # uint32 [B,Hkv,k_words]
     v_codes: np.ndarray  # uint32 [B,Hkv,v_words]
-    k_scale: np.ndarray  # uint16
+    k_scale: np.ndarray  # uint16 [B,Hkv,key_groups,D] per channel, [B,Hkv,rows,D/G] per token
     k_zero: np.ndarray
     v_scale: np.ndarray
     v_zero: np.ndarray
@@ -231,8 +245,8 @@ def _alloc_cache(B, Hkv, D, n_kept, bits, G, key_axis, W, tail_cap):
         ks = (B, Hkv, 0)
         vs = (B, Hkv, 0)
     else:
-        ks = (B, Hkv, n_kept // G, D) if key_axis == 0 else (B, Hkv, n_kept, D // G)
-        vs = (B, Hkv, n_kept, D // G)
+        ks = (B, Hkv, key_groups(n_kept, G), D) if key_axis == 0 else (B, Hkv, rows(n_kept), D // G)
+        vs = (B, Hkv, rows(n_kept), D // G)
     return Cache(B, Hkv, D, n_kept, bits, G, key_axis, W, tail_cap,
                  np.zeros((B, Hkv, kw), np.uint32), np.zeros((B, Hkv, vw), np.uint32),
                  np.zeros(ks, np.uint16), np.zeros(ks, np.uint16),
@@ -254,8 +268,8 @@ def quantize_selected(k, v, idx, W, bits, G, key_axis=0, tail_cap=None, tau=None
                                          _p(idx), _p(c.k_codes), _p(c.v_codes), _p(c.k_scale), _p(c.k_zero),
                                          _p(c.v_scale), _p(c.v_zero), _p(c.tail_k), _p(c.tail_v))
     else:
-        c.k_out = np.zeros((B, Hkv, n_kept, OUT_SLOTS), np.uint32)
-        c.v_out = np.zeros((B, Hkv, n_kept, OUT_SLOTS), np.uint32)
+        c.k_out = np.zeros((B, Hkv, rows(n_kept), OUT_SLOTS), np.uint32)
+        c.v_out = np.zeros((B, Hkv, rows(n_kept), OUT_SLOTS), np.uint32)
         c.ovf_cap = n_kept * (D - OUT_SLOTS) if ovf_cap is None else int(ovf_cap)
         c.k_ovf = np.zeros((B, Hkv, ovf_words(n_kept, c.ovf_cap)), np.uint32)
         c.v_ovf = np.zeros((B, Hkv, ovf_words(n_kept, c.ovf_cap)), np.uint32)

@@ -126,3 +126,28 @@ def test_error_against_16bit_grows_as_bits_shrink(orc):
         if bits != 16:
             errs.append(acc)
     assert errs[0] < errs[1] < errs[2]
+
+
+def test_decode_over_a_count_that_is_no_multiple_of_the_block_or_group(orc):
+    """1000 kept tokens (Section 3: any s < n) at 4 bits, per-channel key groups of 32 (the last one
+    holds 8 tokens): decode equals plain float64 attention on the dequantized rows plus the tail."""
+    B, Hq, Hkv, L, W, n = 1, 4, 2, 1300, 8, 1000
+    q_obs, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, config=93)
+    c, idx, _ = orc.compress(q_obs, k, v, window=W, pool=7, budget=n, bits=4, G=32, sm_scale=0.0883883)
+    assert idx.shape == (B, Hkv, n) and c.k_scale.shape == (B, Hkv, 32, 128) and c.v_scale.shape == (B, Hkv, 1024, 4)
+    q = synth.decode_query_host(B, Hq, 128, config=93, step=0)
+    out = orc.decode_attn(q, c, 0.0883883)
+    for g in range(Hkv):
+        Kd, Vd = orc.dequantize_head(c, 0, g)
+        assert Kd.shape == (n, 128)
+        Kall = np.concatenate([Kd, k[0, g, L - W:].astype(np.float64)])
+        Vall = np.concatenate([Vd, v[0, g, L - W:].astype(np.float64)])
+        for hh in range(2 * g, 2 * g + 2):
+            s = 0.0883883 * (Kall @ q[0, hh].astype(np.float64))
+            p = np.exp(s - s.max())
+            assert np.abs(out[0, hh] - (p / p.sum()) @ Vall).max() <= 1e-12
+        # half-step error bound on every element, the short group included
+        x = k[0, g][idx[0, g]].astype(np.float64)
+        sc = c.k_scale[0, g].view(np.float16).astype(np.float64)                        # [32 groups, 128]
+        step = np.repeat(sc, 32, axis=0)[:n]
+        assert np.all(np.abs(Kd - x) <= step / 2 * (1 + 2.0**-9) + 15 * step * 2.0**-11 + 1e-12)

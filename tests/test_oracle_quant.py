@@ -247,3 +247,39 @@ def test_fewer_bits_lose_more(orc):
         Kd, Vd = orc.dequantize_head(c, 0, 0)
         e.append(np.abs(Vd - v[0, 0, :256].astype(np.float64)).mean() + np.abs(Kd - k[0, 0, :256].astype(np.float64)).mean())
     assert e[0] < e[1] < e[2]
+
+
+def test_token_count_that_fills_neither_a_block_nor_a_key_group(orc):
+    """Section 3 only asks for s < n kept tokens.  40 tokens with per-channel key groups of 32: group 0
+    has 32 members, group 1 the remaining 8 -- the same quantizer on fewer members, so closed forms
+    hold inside it: a ramp of the four 2-bit levels is lossless with scale = step, a constant channel
+    has scale 0, and the scale is the numpy float32 route of that group's own range.  Rows past the
+    count (the arrays are laid out for whole blocks of 32) stay zero."""
+    rng = np.random.default_rng(11)
+    n, G, D = 40, 32, 128
+    rows = rng.standard_normal((n, D)).astype(np.float16)
+    rows[32:, 5] = np.array([0.5, 1.0, 1.5, 2.0, 0.5, 2.0, 1.0, 1.5], np.float16)     # ramp 0.5 .. 2.0 in steps of 0.5
+    rows[32:, 6] = np.float16(-3.25)                                                    # constant in the short group only
+    k = np.concatenate([rows, np.zeros((1, D), np.float16)])[None, None]
+    idx = np.arange(n, dtype=np.int32)[None, None]
+    c = orc.quantize_selected(k, k.copy(), idx, W=1, bits=2, G=G, key_axis=0)
+    assert c.k_scale.shape == (1, 1, 2, D) and c.v_scale.shape == (1, 1, 64, D // G) and c.k_codes.shape[-1] == 64 * D * 2 // 32
+    h = lambda bits16: float(np.array([bits16], np.uint16).view(np.float16)[0])
+    assert h(c.k_scale[0, 0, 1, 5]) == 0.5 and h(c.k_zero[0, 0, 1, 5]) == 0.5
+    assert [c.k_code(0, 0, 32 + e, 5) for e in range(8)] == [0, 1, 2, 3, 0, 3, 1, 2]
+    assert c.k_scale[0, 0, 1, 6] == 0 and h(c.k_zero[0, 0, 1, 6]) == -3.25 and all(c.k_code(0, 0, 32 + e, 6) == 0 for e in range(8))
+    for d in range(D):
+        for u, (a, b) in enumerate(((0, 32), (32, 40))):
+            x = rows[a:b, d]
+            r = np.float32(x.max()) - np.float32(x.min())
+            assert c.k_scale[0, 0, u, d] == int((r / np.float32(3)).astype(np.float16).view(np.uint16)), (u, d)
+            assert h(c.k_zero[0, 0, u, d]) == float(x.min())
+    # nothing leaks into the rows past the count
+    assert not c.v_scale[0, 0, n:].any() and not c.v_zero[0, 0, n:].any()
+    assert all(c.k_code(0, 0, t, d) == 0 and c.v_code(0, 0, t, d) == 0 for t in range(n, 64) for d in (0, 5, 127))
+    Kd, Vd = orc.dequantize_head(c, 0, 0)
+    assert Kd.shape == (n, D) and np.array_equal(Kd[32:, 5], rows[32:, 5].astype(np.float64))
+    # the first group does not depend on what follows it: the same 32 tokens alone give the same codes
+    c32 = orc.quantize_selected(k, k.copy(), idx[..., :32], W=1, bits=2, G=G, key_axis=0)
+    assert np.array_equal(c32.k_scale[0, 0, 0], c.k_scale[0, 0, 0])
+    assert all(c32.k_code(0, 0, t, d) == c.k_code(0, 0, t, d) for t in range(32) for d in range(0, D, 7))
