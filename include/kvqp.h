@@ -68,7 +68,7 @@ typedef struct kvqp_cfg {
     int32_t pool_kernel;  /* odd; 1 = no pooling                                         */
     int32_t budget;       /* prefix tokens kept in low precision; n_kept = min(budget, L-W) */
     int32_t bits;         /* B: 2, 4, 8, or 16 (16 = keep half, no scale/zero)           */
-    int32_t group_size;   /* G; must divide D, and n_kept when keys are per channel      */
+    int32_t group_size;   /* G; must divide D                                            */
     int32_t key_axis;     /* KVQP_KEY_PER_CHANNEL or KVQP_KEY_PER_TOKEN                  */
     int32_t decode_splits;/* token-axis splits of decode attention; 0 = library chooses  */
     float sm_scale;       /* logit scale > 0, e.g. 1/sqrt(D) (Eq. (3) omits it)          */
@@ -102,7 +102,12 @@ typedef struct kvqp_cfg {
  * The compressed cache of one layer.  All eight buffers are device memory of
  * the sizes kvqp_cache_sizes reports, in this order.
  *
- * Key codes      k_codes  uint32 [batch, Hkv, n_kept * D * bits / 32]
+ * Token counts need not fill whole blocks or groups (Section 3 asks only for
+ * s < n): below, R = n_kept rounded up to a multiple of 32 is the number of rows
+ * the per-token arrays of one (batch, KV head) are laid out for, and rows past
+ * n_kept hold zeros (code 0, scale 0, zero +0, no outliers).
+ *
+ * Key codes      k_codes  uint32 [batch, Hkv, R * D * bits / 32]
  *   Row-major [token][channel].  A 32-bit word holds E = 32/bits fields.
  *   Field p of the low half-word (bits [bits*p, bits*p + bits)) and field p of
  *   the high half-word (16 bits higher) hold two adjacent channels: channel d
@@ -120,8 +125,10 @@ typedef struct kvqp_cfg {
  *     sb * (64*(D/16)*wpt) + ((y/4)*64 + kb*16 + n)*4 + y%4 .
  *   Tokens >= n_kept inside the last superblock hold zeros.
  * Key scale/zero k_scale, k_zero  half
- *   per channel: [batch, Hkv, n_kept/G, D];  per token: [batch, Hkv, n_kept, D/G]
- * Value scale/zero v_scale, v_zero  half [batch, Hkv, n_kept, D/G]
+ *   per channel: [batch, Hkv, ceil(n_kept/G), D] -- when G does not divide n_kept
+ *   the last group holds the remaining n_kept mod G tokens (the same quantizer on
+ *   fewer members);  per token: [batch, Hkv, R, D/G]
+ * Value scale/zero v_scale, v_zero  half [batch, Hkv, R, D/G]
  *   (absent, size 0, at bits == 16)
  * Tail           tail_k, tail_v  half [batch, Hkv, tail_cap, D], row-major; the
  *   first tail_len rows are attended at full precision after the kept tokens.
@@ -147,21 +154,21 @@ typedef struct kvqp_cfg {
  * group, bit 7 set, bits 6..0 the channel; it dequantizes to float(z) + that
  * difference (within 2^-15 of |x - z|, finer than a binary16 step of x).
  * Where the words are kept:
- *   k_out, v_out  uint32 [batch, Hkv, n_kept, KVQP_OUTLIER_SLOTS]
+ *   k_out, v_out  uint32 [batch, Hkv, R, KVQP_OUTLIER_SLOTS]
  *     a row's first KVQP_OUTLIER_SLOTS outliers in ascending order of channel,
  *     unused slots 0;
  *   k_ovf, v_ovf  uint32 [batch, Hkv, S + 2 * cfg->outlier_overflow_cap],
- *     S = n_kept/32 + 1 rounded up to a multiple of 4: per (batch, KV head)
- *     first the int32 prefix counts start[0 .. n_kept/32] -- start[b] = number
+ *     S = R/32 + 1 rounded up to a multiple of 4: per (batch, KV head)
+ *     first the int32 prefix counts start[0 .. R/32] -- start[b] = number
  *     of list entries of the head's tokens before 32 b -- then the list: the
  *     outliers beyond their rows' slots as entries (word, token index in the
- *     head), in ascending (token, channel) order.  start[n_kept/32] is the
+ *     head), in ascending (token, channel) order.  start[R/32] is the
  *     number of entries the head needs; entries beyond outlier_overflow_cap
  *     are not stored and those elements read as their group's zero, so a
  *     caller that sizes the list below n_kept * (D - KVQP_OUTLIER_SLOTS)
  *     compares that count (device memory) with its capacity.  Words of the
  *     list beyond the stored entries, and of the prefix array beyond
- *     start[n_kept/32], are unspecified.
+ *     start[R/32], are unspecified.
  *   (sizes from kvqp_outlier_sizes; all four NULL when filtering is off)
  */
 #define KVQP_OUTLIER_SLOTS 4
@@ -174,7 +181,7 @@ typedef struct kvqp_cache {
     int32_t tail_len; /* valid tail rows                                                */
     int32_t tail_cap; /* allocated tail rows, >= window                                 */
     int32_t n_cap;    /* tokens the six packed buffers are laid out for: every "n_kept"
-                         in the buffer shapes above is n_cap (the stride of the
+                         and "R" in the buffer shapes above is n_cap (the stride of the
                          [batch, Hkv] axes); 0 means n_kept, the compact layout of
                          kvqp_cache_sizes.  A larger n_cap (a multiple of 64 and of G,
                          sizes from kvqp_cache_sizes_cap) leaves room for
@@ -235,8 +242,8 @@ int kvqp_workspace_bytes(const kvqp_cfg *cfg, size_t *compress_bytes, size_t *de
  *   unrefined_out int32 [batch, Hkv] or NULL: per head 0 when every candidate
  *          near the cut was re-scored in binary64 (or none needed it), else
  *          the number of candidates near the cut that binary32 decided
- * Errors: INVALID_ARG on NULL/shape problems (incl. n_kept % G != 0 for
- * per-channel keys), UNSUPPORTED outside the supported set, WORKSPACE, HIP.
+ * Errors: INVALID_ARG on NULL/shape problems, UNSUPPORTED outside the
+ * supported set, WORKSPACE, HIP.
  */
 int kvqp_compress(const kvqp_cfg *cfg, const void *q_obs, const void *k, const void *v,
                   kvqp_cache *cache, int32_t *idx_out, int32_t *unrefined_out, void *workspace,
@@ -250,8 +257,7 @@ int kvqp_compress(const kvqp_cfg *cfg, const void *q_obs, const void *k, const v
  * window of 8).  The allocation rule itself is the caller's: this call takes
  * its result.  Scoring, the cut and the quantizer are those of kvqp_compress,
  * applied to head h with head_budget[h] in place of n_kept.
- *   head_budget  HOST int32 [batch * Hkv]; every entry a multiple of 32 (of
- *                group_size for per-channel keys), >= 0 and
+ *   head_budget  HOST int32 [batch * Hkv]; every entry >= 0 and
  *                <= min(cfg->budget, L - W).  Read before the call returns.
  *   cache        as for kvqp_compress with n_kept = min(cfg->budget, L - W) in
  *                every shape (or n_cap); head_n_kept must point to device memory
@@ -303,8 +309,7 @@ int kvqp_quantize_selected_ragged(const kvqp_cfg *cfg, const void *k, const void
  * n_kept + tail_len must be >= 1.  With head-level
  * counts (cache->head_n_kept non-NULL) head h attends its first
  * head_n_kept[h] tokens; the counts are read on the device, where a count
- * above n_kept is cut to n_kept and rounded down to a multiple of 32
- * (group_size for per-channel keys).
+ * above n_kept is cut to n_kept.
  * Workspace: kvqp_workspace_bytes' decode_bytes, 16-byte aligned, prepared ONCE with
  * kvqp_decode_workspace_init before its first use.  It holds the partial results of
  * the token-axis splits and, at its head, one arrival counter per (batch, KV head)

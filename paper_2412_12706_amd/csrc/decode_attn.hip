@@ -220,7 +220,6 @@ struct DecodeArgs {
     const uint32_t* k_ovf;        // overflow buffers [B*Hkv, ovf_words(n_cap, ovf_cap)] (filtering on), else NULL
     const uint32_t* v_ovf;
     int ovf_cap;                  // entries of a head's overflow list
-    int quantum;              // a head's count is a multiple of this power of two (32, or G for per-channel keys)
     int n_q_heads, n_kv_heads;
     int n_splits, chunks_per_split, n_partials;
     int n_waves;              // waves per workgroup of the pipelined kernel
@@ -229,13 +228,13 @@ struct DecodeArgs {
     float sm_scale;
 };
 
-// Tokens of one head: the launch's count, or the head's own, cut to the bound and to whole groups
-// so that no value found in memory can lead a load past the buffers.  Uniform over the workgroup.
+// Tokens of one head: the launch's count, or the head's own, cut to the bound so that no value found
+// in memory can lead a load past the buffers (they are laid out for the bound in whole blocks).
+// Uniform over the workgroup.
 __device__ __forceinline__ int head_tokens(const DecodeArgs& a, int bh) {
     if (!a.head_n_kept) return a.n_kept;
-    int n = a.head_n_kept[bh];
-    n = n < 0 ? 0 : (n > a.n_kept ? a.n_kept : n);
-    return n & ~(a.quantum - 1);
+    const int n = a.head_n_kept[bh];
+    return n < 0 ? 0 : (n > a.n_kept ? a.n_kept : n);
 }
 // 64-token chunks a split workgroup takes: the plan's share, or an even share of the head's own chunks
 __device__ __forceinline__ int head_chunks_per_split(const DecodeArgs& a, int n_chunks) {
@@ -560,7 +559,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     const char* kc = reinterpret_cast<const char*>(a.k_codes) + (size_t)bh * ((size_t)a.n_cap * kHeadDim * BITS / 8);
     const char* vc = reinterpret_cast<const char*>(a.v_codes) +
                      (size_t)bh * v_superblock_words(BITS) * 4 * ((a.n_cap + v_superblock(BITS) - 1) / v_superblock(BITS));
-    const size_t k_meta_head = KT ? (size_t)a.n_cap * NCG * 2 : (size_t)(a.n_cap / G) * kHeadDim * 2;   // bytes per head
+    const size_t k_meta_head = KT ? (size_t)a.n_cap * NCG * 2 : (size_t)((a.n_cap + G - 1) / G) * kHeadDim * 2;   // bytes per head
     const char* ks = QUANT ? reinterpret_cast<const char*>(a.k_scale) + (size_t)bh * k_meta_head : nullptr;
     const char* kz = QUANT ? reinterpret_cast<const char*>(a.k_zero) + (size_t)bh * k_meta_head : nullptr;
     const char* vs = QUANT ? reinterpret_cast<const char*>(a.v_scale) + (size_t)bh * a.n_cap * NCG * 2 : nullptr;
@@ -574,7 +573,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     const uint32_t row_lane = (uint32_t)lane * 4;                                     // dword of a 256-byte scale row
     const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
     const int n_kept = head_tokens(a, bh);
-    const int n_kgroups = QUANT ? max(n_kept / G, 1) : 0;
+    const int n_kgroups = QUANT ? max((n_kept + G - 1) / G, 1) : 0;   // (the last group may hold fewer than G tokens)
     // The loads of the pipeline are unconditional; when a wave has no further chunk they are pointed
     // at one 16-byte spot (lane offsets zeroed) instead of re-reading a whole chunk.
     uint32_t k_off = k_lane, v_off = v_lane, row_off = row_lane, vrow_off = vrow_lane;
@@ -983,6 +982,18 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                 }
             }
         }
+        if constexpr (MODE != 2) {
+            // the head's last block may be partly filled: tokens past the count take no part
+            if (tok0 + 32 > n_kept) {   // (wave-uniform, and false for all but one block of a head)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int th = (SLOTS == 2) ? slot : t;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (tok0 + 16 * th + 4 * kb + i >= n_kept) lg[t][i] = -INFINITY;   // weight exactly 0 (references stay finite)
+                }
+            }
+        }
         if constexpr (MODE == 1) {
 #pragma unroll
             for (int t = 0; t < NT; ++t)
@@ -1114,7 +1125,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         return __builtin_amdgcn_readfirstlane(v);
     };
     int chunk = c_begin + wave;
-    bool two = chunk < c_end && n_kept - chunk * kChunk >= kChunk;   // n_kept is a multiple of 32
+    bool two = chunk < c_end && n_kept - chunk * kChunk > 32;        // the chunk reaches into its second 32-token block
     // The second block of a chunk is requested right after the previous chunk's second block has
     // been consumed (quantized variants: more bytes in flight, and the first chunk's blocks are both
     // on their way before anything waits); the 16-bit variant, whose blocks are four times larger,
@@ -1217,14 +1228,14 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         }
         const bool has_next = next < c_end;
         const int nx = has_next ? next : chunk;
-        const bool two_nx = n_kept - nx * kChunk >= kChunk;
+        const bool two_nx = n_kept - nx * kChunk > 32;
         float lgA[NT][4], lgB[NT][4];
         const uint2 no_slots = make_uint2(0u, 0u);
         if constexpr (kJoint) {
             // Both blocks' logits first, one move of the reference for the whole chunk, then both
             // blocks' softmax and PV products: one check per chunk instead of two, and each half of
             // the next chunk's loads leaves as soon as its registers are free.
-            compute(BoolI<1>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, 0u, 0u, no_slots, no_slots, 0u, 0u, 0);
+            compute(BoolI<1>{}, lgA, ak0, ak1, a_ks, a_kz[0], true, bias0, av, 0, 0u, 0u, no_slots, no_slots, 0u, 0u, chunk * kChunk);
             if (!has_next) { k_off = 0; v_off = 0; row_off = 0; vrow_off = 0; slot_off = 0; }   // (wave-uniform; the loop ends after this pass)
             load_Ak(nx);
             float mx = lgA[0][0];
@@ -1233,7 +1244,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
 #pragma unroll
                 for (int i = 0; i < 4; ++i) mx = fmaxf(mx, lgA[t][i]);
             if (two) {
-                compute(BoolI<1>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, 0, 0u, 0u, no_slots, no_slots, 0u, 0u, 0);
+                compute(BoolI<1>{}, lgB, bk0, bk1, b_ks, b_kz, NGRP == 2, (NGRP == 2) ? bias1 : bias0, bv, 0, 0u, 0u, no_slots, no_slots, 0u, 0u, chunk * kChunk + 32);
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -1542,14 +1553,13 @@ hipError_t launch_decode(const kvqp_cfg& cfg, const void* q, const kvqp_cache& c
     a.part = (float*)(static_cast<char*>(ws) + decode_ws_header_bytes(cfg));
     a.out = (uint16_t*)out;
     a.n_kept = c.n_kept; a.tail_len = c.tail_len; a.tail_cap = c.tail_cap;
-    a.n_cap = c.n_cap > 0 ? c.n_cap : c.n_kept;
+    a.n_cap = layout_tokens(c, c.n_kept);
     a.head_n_kept = c.head_n_kept;
     a.k_out = outliers_on(cfg) ? (const uint32_t*)c.k_out : nullptr;
     a.v_out = outliers_on(cfg) ? (const uint32_t*)c.v_out : nullptr;
     a.k_ovf = outliers_on(cfg) ? (const uint32_t*)c.k_ovf : nullptr;
     a.v_ovf = outliers_on(cfg) ? (const uint32_t*)c.v_ovf : nullptr;
     a.ovf_cap = cfg.outlier_overflow_cap;
-    a.quantum = (cfg.bits != 16 && cfg.key_axis == KVQP_KEY_PER_CHANNEL) ? cfg.group_size : 32;
     a.n_q_heads = cfg.n_q_heads; a.n_kv_heads = cfg.n_kv_heads;
     a.n_splits = plan.n_splits; a.chunks_per_split = plan.chunks_per_split; a.n_partials = plan.n_partials;
     a.n_waves = plan.n_waves;

@@ -50,11 +50,10 @@ int n_kept_of(const kvqp_cfg* c) {
     return c->budget < P ? c->budget : P;
 }
 
+// Any count is fine: a partly filled last block and a short last key group are part of the format.
 int check_n_kept(const kvqp_cfg* c, int n_kept) {
-    if (n_kept < 0) return KVQP_ERR_INVALID_ARG;
-    if (n_kept % 32) return KVQP_ERR_INVALID_ARG;  // value blocks hold 32 tokens
-    if (c->bits != 16 && c->key_axis == KVQP_KEY_PER_CHANNEL && n_kept % c->group_size) return KVQP_ERR_INVALID_ARG;
-    return KVQP_OK;
+    (void)c;
+    return n_kept < 0 ? KVQP_ERR_INVALID_ARG : KVQP_OK;
 }
 
 // A non-zero capacity must hold the tokens and keep every head's buffers aligned.
@@ -76,11 +75,6 @@ int fill_sizes(const kvqp_cfg* cfg, int n_tok, int32_t tail_cap, size_t sizes_ou
     sizes_out[4] = vm; sizes_out[5] = vm;
     sizes_out[6] = tail; sizes_out[7] = tail;
     return KVQP_OK;
-}
-
-// Smallest step of a head-level token count: whole value blocks and, for per-channel keys, whole key groups.
-int head_quantum(const kvqp_cfg* c) {
-    return (c->bits != 16 && c->key_axis == KVQP_KEY_PER_CHANNEL && c->group_size > 32) ? c->group_size : 32;
 }
 
 int check_cache_ptrs(const kvqp_cfg* c, const kvqp_cache* cache, int n_kept, bool need_tail) {
@@ -144,7 +138,7 @@ int kvqp_outlier_sizes(const kvqp_cfg* cfg, int32_t n_cap, size_t sizes_out[4]) 
         n = n_kept_of(cfg);
     }
     const size_t heads = (size_t)cfg->batch * cfg->n_kv_heads;
-    const size_t bytes = outliers_on(*cfg) ? heads * (size_t)n * KVQP_OUTLIER_SLOTS * sizeof(uint32_t) : 0;
+    const size_t bytes = outliers_on(*cfg) ? heads * (size_t)rows32(n) * KVQP_OUTLIER_SLOTS * sizeof(uint32_t) : 0;
     const size_t list = outliers_on(*cfg) ? heads * ovf_words(n, cfg->outlier_overflow_cap) * sizeof(uint32_t) : 0;
     sizes_out[0] = bytes; sizes_out[1] = bytes;
     sizes_out[2] = list; sizes_out[3] = list;
@@ -165,9 +159,9 @@ int kvqp_workspace_bytes(const kvqp_cfg* cfg, size_t* compress_bytes, size_t* de
 
 // Host check of head-level counts against their bound.
 static int check_head_counts(const kvqp_cfg* cfg, const int32_t* counts, int bound) {
-    const int heads = cfg->batch * cfg->n_kv_heads, quantum = head_quantum(cfg);
+    const int heads = cfg->batch * cfg->n_kv_heads;
     for (int h = 0; h < heads; ++h)
-        if (counts[h] < 0 || counts[h] > bound || counts[h] % quantum) return KVQP_ERR_INVALID_ARG;
+        if (counts[h] < 0 || counts[h] > bound) return KVQP_ERR_INVALID_ARG;
     return KVQP_OK;
 }
 

@@ -20,7 +20,13 @@ __host__ __device__ constexpr int v_superblock_words(int bits) { return 64 * (kH
 // Outlier filtering is on (format statement in kvqp.h, "Outlier filtering").
 inline bool outliers_on(const kvqp_cfg& c) { return c.outlier_threshold > 0.0f; }
 
-inline size_t k_code_words(int n_kept, int bits) { return (size_t)n_kept * kHeadDim * bits / 32; }
+// Token counts need not fill whole blocks: the per-token arrays of a head (key code rows, per-token
+// scales and zeros, outlier slots) are laid out for the count rounded up to 32, zeros past the count.
+__host__ __device__ constexpr int rows32(int n) { return (n + 31) / 32 * 32; }
+// Tokens a cache's buffers are laid out for: its capacity, or its own count in whole blocks.
+inline int layout_tokens(const kvqp_cache& c, int n_kept) { return c.n_cap > 0 ? c.n_cap : rows32(n_kept); }
+
+inline size_t k_code_words(int n_kept, int bits) { return (size_t)rows32(n_kept) * kHeadDim * bits / 32; }
 inline size_t v_code_words(int n_kept, int bits) {
     const int sb = v_superblock(bits);
     return (size_t)((n_kept + sb - 1) / sb) * v_superblock_words(bits);
@@ -28,15 +34,16 @@ inline size_t v_code_words(int n_kept, int bits) {
 
 // Overflow buffer of one head and tensor (format statement in kvqp.h, "Outlier filtering"): the
 // prefix counts per 32 tokens, padded to a multiple of four words, then `cap` entries of two words.
-__host__ __device__ constexpr size_t ovf_start_words(int n_tok) { return ((size_t)(n_tok / 32 + 1) + 3) / 4 * 4; }
+__host__ __device__ constexpr size_t ovf_start_words(int n_tok) { return ((size_t)((n_tok + 31) / 32 + 1) + 3) / 4 * 4; }
 __host__ __device__ constexpr size_t ovf_words(int n_tok, int cap) { return ovf_start_words(n_tok) + 2 * (size_t)cap; }
 
 // Element counts of scale/zero arrays per (batch, kv-head).
 inline size_t k_meta_elems(int n_kept, int bits, int G, int key_axis) {
     if (bits == 16) return 0;
-    return key_axis == KVQP_KEY_PER_CHANNEL ? (size_t)(n_kept / G) * kHeadDim : (size_t)n_kept * (kHeadDim / G);
+    // (per channel: the last group may hold fewer than G tokens)
+    return key_axis == KVQP_KEY_PER_CHANNEL ? (size_t)((n_kept + G - 1) / G) * kHeadDim : (size_t)rows32(n_kept) * (kHeadDim / G);
 }
-inline size_t v_meta_elems(int n_kept, int bits, int G) { return bits == 16 ? 0 : (size_t)n_kept * (kHeadDim / G); }
+inline size_t v_meta_elems(int n_kept, int bits, int G) { return bits == 16 ? 0 : (size_t)rows32(n_kept) * (kHeadDim / G); }
 
 // Decode split-K geometry, a pure function of the problem so that the
 // workspace query and the launch agree.

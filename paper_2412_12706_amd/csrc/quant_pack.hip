@@ -240,7 +240,8 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     const int d0 = base + t0;                // first destination token: a multiple of the group and superblock sizes
     const int n_head = head_n ? head_n[head] : n_kept;
     if (t0 >= n_head) return;                // (the whole workgroup: nothing of this head left)
-    const int ntok = min(TB, n_head - t0);   // a multiple of 32 (and of G for per-channel keys)
+    const int ntok = min(TB, n_head - t0);   // any count: the head's last block and last key group may be partly filled
+    const int ntok_pad = rows32(ntok);       // rows of the last block past the count are written as zeros
     if constexpr (OUT) {
         if (threadIdx.x < 2 * (TB / 32)) (&s_cnt[0][0])[threadIdx.x] = 0;
         __syncthreads();
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const int t = r + 16 * j;
-        live[j] = 32 * (j >> 1) < ntok;   // ntok is a multiple of 32: the same for the whole workgroup
+        live[j] = t < ntok;               // (the same for the 16 lanes of a token row)
         const int pos = !live[j] ? 0 : idx ? idx[(size_t)head * n_kept + t0 + t] : t0 + t;
         // (prompt rows are read once: non-temporal)
         typedef uint32_t u4v __attribute__((ext_vector_type(4)));
@@ -290,7 +291,10 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     auto store_slots = [&](uint32_t* out, int* cnt, const uint32_t (&w)[R][4], const uint32_t (&om)[R], auto zero_of) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            if (!live[j]) continue;                                   // (uniform over the workgroup)
+            if (!live[j]) {                                           // (uniform over the row's 16 lanes)
+                if (r + 16 * j < ntok_pad && c8 < 4) out[((size_t)head * n_cap + d0 + r + 16 * j) * 4 + c8] = 0u;   // padding row: no outliers
+                continue;
+            }
             const uint32_t mine = (uint32_t)__builtin_popcount(om[j]);
             const uint32_t total = row16_sum(mine);
             uint32_t at = row16_before(mine);
@@ -335,9 +339,9 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             const uint32_t b = q4 == 0 ? mx[4 * jj] : q4 == 1 ? mx[4 * jj + 1] : q4 == 2 ? mx[4 * jj + 2] : mx[4 * jj + 3];
             const GroupParams gp = group_params<BITS>(a, b);
             const int t = r + 16 * (4 * jj + q4);
-            if (t < ntok && (c8 & (GL - 1)) < 4) {
+            if (t < ntok_pad && (c8 & (GL - 1)) < 4) {               // (padding rows of the last block: scale 0, zero +0)
                 const size_t m = ((size_t)head * n_cap + d0 + t) * CPT + c8 / GL;
-                scale[m] = gp.scale_h; zero[m] = gp.zero_h;
+                scale[m] = t < ntok ? gp.scale_h : (uint16_t)0; zero[m] = t < ntok ? gp.zero_h : (uint16_t)0;
             }
             const uint32_t zb = __float_as_uint(gp.zf), ib = __float_as_uint(gp.inv);
             const uint32_t zq[4] = {dpp<0x00>(zb), dpp<0x55>(zb), dpp<0xAA>(zb), dpp<0xFF>(zb)};
@@ -362,7 +366,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
     if constexpr (!QUANT) {
 #pragma unroll
         for (int j = 0; j < R; ++j)
-            if (live[j])
+            if (r + 16 * j < ntok_pad)     // (rows past the count were loaded as zeros)
                 *reinterpret_cast<uint4*>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / 2) + 4 * c8) = make_uint4(kw[j][0], kw[j][1], kw[j][2], kw[j][3]);
     } else if (key_axis == KVQP_KEY_PER_CHANNEL) {
         // minima / maxima per channel over the G tokens of a group: own rows, the four row lanes of
@@ -411,7 +415,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             const GroupParams gp = group_params<BITS>(a, b);
             s_par[item] = make_float2(gp.zf, gp.inv);
             if (ug * G < ntok) {
-                const size_t m = ((size_t)head * (n_cap / G) + (d0 / G + ug)) * kHeadDim + d;
+                const size_t m = ((size_t)head * ((n_cap + G - 1) / G) + (d0 / G + ug)) * kHeadDim + d;
                 k_scale[m] = gp.scale_h; k_zero[m] = gp.zero_h;
             }
         }
@@ -433,7 +437,11 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
 #pragma unroll
                     for (int e = 0; e < 8; ++e) c[e] &= ((om[j] >> e) & 1u) - 1u;
                 }
-                if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, c);
+                if (!live[j]) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) c[e] = 0u;           // padding rows of the last block hold code 0
+                }
+                if (r + 16 * j < ntok_pad) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, c);
             }
         }
         if constexpr (OUT)   // the zero of (row j's key group, own channel 8 c8 + e) from the table the codes were made with
@@ -443,8 +451,13 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         per_token(kw, k_scale, k_zero, codes, om, zrow);
         if constexpr (OUT) store_slots(k_out, s_cnt[0], kw, om, [&](int j, int) { return __uint_as_float(zrow[j]); });
 #pragma unroll
-        for (int j = 0; j < R; ++j)
-            if (live[j]) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
+        for (int j = 0; j < R; ++j) {
+            if (!live[j]) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) codes[j][e] = 0u;
+            }
+            if (r + 16 * j < ntok_pad) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
+        }
     }
 
     // ---------------- values ----------------
@@ -531,7 +544,7 @@ __global__ __launch_bounds__(64) void ovf_scan(uint32_t* __restrict__ k_ovf, uin
         base -= base % base_quantum;
     }
     const int n_head = head_n ? min(max(head_n[head], 0), n_tok) : n_tok;
-    const int first = base / 32, n = n_head / 32;
+    const int first = base / 32, n = (n_head + 31) / 32;
     if (first == 0 && lane == 0) start[0] = 0u;
     __syncthreads();
     uint32_t carry = start[first];
@@ -575,7 +588,7 @@ __global__ __launch_bounds__(64) void ovf_fill(const uint16_t* __restrict__ k, c
     uint32_t* entries = ovf + ovf_start_words(n_cap);
     const uint16_t* src = (tensor ? v : k) + (size_t)head * L * kHeadDim;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int t = t0; t < t0 + 32; ++t) {
+    for (int t = t0; t < min(t0 + 32, n_head); ++t) {
         const int pos = idx ? idx[(size_t)head * n_kept + t] : t;
         const uint32_t w = *reinterpret_cast<const uint32_t*>(src + (size_t)pos * kHeadDim + 2 * lane);   // channels 2 lane, 2 lane + 1
         const bool c0 = (w & 0x7fffu) > tau_bits, c1 = ((w >> 16) & 0x7fffu) > tau_bits;
@@ -591,7 +604,7 @@ __global__ __launch_bounds__(64) void ovf_fill(const uint16_t* __restrict__ k, c
             if (is && rank >= 4u) {
                 const int d = 2 * lane + e;
                 const size_t m = (tensor == 0 && key_axis == KVQP_KEY_PER_CHANNEL)
-                                     ? ((size_t)head * (n_cap / G) + tok / G) * kHeadDim + d
+                                     ? ((size_t)head * ((n_cap + G - 1) / G) + tok / G) * kHeadDim + d
                                      : ((size_t)head * n_cap + tok) * (kHeadDim / G) + d / G;
                 const float zf = half_bits_to_float((tensor ? v_zero : k_zero)[m]);
                 const uint32_t xh = e ? (w >> 16) : (w & 0xffffu);
@@ -626,7 +639,7 @@ hipError_t launch_bits_g(const QuantPackJob& j, hipStream_t stream) {
         if (e != hipSuccess || j.n_tok == 0) return e;
         hipLaunchKernelGGL(ovf_scan, dim3(j.heads, 2), dim3(64), 0, stream, (uint32_t*)j.c.k_ovf, (uint32_t*)j.c.v_ovf, j.n_cap,
                            j.ovf_cap, j.dst_base, j.n_tok, j.head_n, j.head_base, j.base_quantum);
-        hipLaunchKernelGGL((ovf_fill<G>), dim3(j.n_tok / 32, j.heads, 2), dim3(64), 0, stream, (const uint16_t*)j.k,
+        hipLaunchKernelGGL((ovf_fill<G>), dim3((j.n_tok + 31) / 32, j.heads, 2), dim3(64), 0, stream, (const uint16_t*)j.k,
                            (const uint16_t*)j.v, j.idx, (const uint16_t*)j.c.k_zero, (const uint16_t*)j.c.v_zero,
                            (uint32_t*)j.c.k_ovf, (uint32_t*)j.c.v_ovf, j.src_rows, j.n_tok, j.key_axis, j.n_cap, j.dst_base,
                            j.head_n, j.tau_bits, j.head_base, j.base_quantum, j.ovf_cap);
@@ -717,7 +730,7 @@ hipError_t launch_quant_pack(const kvqp_cfg& cfg, const void* k, const void* v, 
     set_outliers(j, cfg);
     j.k = k; j.v = v; j.idx = idx; j.head_n = head_n;
     j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cfg.seq_len; j.window = cfg.window;
-    j.n_tok = n_kept; j.dst_base = 0; j.n_cap = cache.n_cap > 0 ? cache.n_cap : n_kept;
+    j.n_tok = n_kept; j.dst_base = 0; j.n_cap = layout_tokens(cache, n_kept);
     j.bits = cfg.bits; j.group_size = cfg.group_size; j.key_axis = cfg.key_axis; j.copy_tail = true;
     return launch_job(j, stream);
 }
@@ -750,7 +763,7 @@ hipError_t launch_append_tail(const kvqp_cfg& cfg, const kvqp_cache& cache, int 
     j.k = cache.tail_k; j.v = cache.tail_v; j.idx = nullptr; j.head_n = nullptr;
     if (base_quantum > 0) { j.head_base = cache.head_n_kept; j.base_quantum = base_quantum; }
     j.heads = cfg.batch * cfg.n_kv_heads; j.src_rows = cache.tail_cap; j.window = 0;
-    j.n_tok = n_tokens; j.dst_base = cache.n_kept; j.n_cap = cache.n_cap > 0 ? cache.n_cap : cache.n_kept;
+    j.n_tok = n_tokens; j.dst_base = cache.n_kept; j.n_cap = layout_tokens(cache, cache.n_kept);
     j.bits = cfg.bits; j.group_size = cfg.group_size; j.key_axis = cfg.key_axis; j.copy_tail = false;
     hipError_t e = launch_job(j, stream);
     if (e != hipSuccess) return e;

@@ -27,10 +27,11 @@ def upload_cache(oc, device="cuda"):
 def ovf_split(words, n_layout, cap):
     """One head's overflow buffer (uint32 words, laid out for n_layout tokens and cap entries, the
     format statement of kvqp.h) -> (prefix counts [n_layout/32 + 1], entry words [cap, 2])."""
-    n_start = (n_layout // 32 + 1 + 3) // 4 * 4
+    blocks = (n_layout + 31) // 32
+    n_start = (blocks + 1 + 3) // 4 * 4
     words = np.asarray(words).reshape(-1)
     assert words.size == n_start + 2 * cap, (words.size, n_start, cap)
-    return words[: n_layout // 32 + 1], words[n_start:].reshape(cap, 2)
+    return words[: blocks + 1], words[n_start:].reshape(cap, 2)
 
 
 def assert_overflow_equal(got_words, n_layout, ref_words, n_tok, cap, what=""):
@@ -39,7 +40,8 @@ def assert_overflow_equal(got_words, n_layout, ref_words, n_tok, cap, what=""):
     what lies beyond them is unspecified."""
     gs, ge = ovf_split(got_words, n_layout, cap)
     rs, re_ = ovf_split(ref_words, n_tok, cap)
-    assert np.array_equal(gs[: n_tok // 32 + 1], rs), (what, gs[: n_tok // 32 + 1][-4:], rs[-4:])
+    nb = (n_tok + 31) // 32 + 1
+    assert np.array_equal(gs[:nb], rs), (what, gs[:nb][-4:], rs[-4:])
     n = min(int(rs[-1]), cap)
     assert np.array_equal(ge[:n], re_[:n]), (what, n)
     return int(rs[-1])

@@ -82,7 +82,7 @@ BAD = [
     (dict(bits=3), -1), (dict(bits=0), -1), (dict(group_size=48), -1), (dict(group_size=16), -2),
     (dict(head_dim=64), -2), (dict(n_q_heads=30), -1), (dict(n_q_heads=8 * 16), -2), (dict(pool_kernel=4), -1),
     (dict(pool_kernel=0), -1), (dict(window=0), -1), (dict(window=5000), -1), (dict(budget=-1), -1),
-    (dict(budget=1000), -1),            # not a multiple of the group size
+    (dict(outlier_overflow_cap=-1), -1),
     (dict(key_axis=2), -1), (dict(batch=0), -1), (dict(window=128), -2), (dict(decode_splits=-1), -1),
     (dict(sm_scale=float("nan")), -1), (dict(decode_cache_hint=3), -1), (dict(decode_cache_hint=-1), -1),
 ]
@@ -164,8 +164,9 @@ def test_head_level_count_argument_checks(lib):
     fake = C.c_void_p(0x1000)
     call = lambda counts, cache=cs: lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(*counts),
                                                              C.byref(cache), None, None, fake, 1 << 30, None)
-    assert call([256, 96]) == -1          # per-channel keys: whole groups of 64
-    assert call([256, 320]) == -1         # above the bound
+    assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(256, 97), C.byref(cs), None, None, fake,
+                                    16, None) == -3      # any count under the bound is fine: the call gets as far as the workspace check
+    assert call([256, 320]) == -1         # above the bound is not
     assert call([-64, 64]) == -1
     assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, None, C.byref(cs), None, None, fake, 1 << 30, None) == -1
     no_counts = kvqp.CacheStruct.from_buffer_copy(cs)
@@ -173,8 +174,8 @@ def test_head_level_count_argument_checks(lib):
     assert call([256, 64], no_counts) == -1
     assert lib.kvqp_compress_ragged(C.byref(st), fake, fake, fake, (C.c_int32 * 2)(256, 64), C.byref(cs), None, None, fake,
                                     16, None) == -3      # counts fine, workspace too small: still nothing launched
-    assert lib.kvqp_quantize_selected_ragged(C.byref(st), fake, fake, fake, 256, (C.c_int32 * 2)(256, 96), C.byref(cs),
-                                             None) == -1
+    assert lib.kvqp_quantize_selected_ragged(C.byref(st), fake, fake, fake, 256, (C.c_int32 * 2)(256, 257), C.byref(cs),
+                                             None) == -1      # above the bound
     assert lib.kvqp_quantize_selected_ragged(C.byref(st), fake, fake, fake, 256, None, C.byref(cs), None) == -1
     assert lib.kvqp_quantize_selected(C.byref(st), fake, fake, fake, 256, C.byref(cs), None) == -1
     # uniform calls refuse a cache that carries head-level counts
@@ -186,7 +187,7 @@ def test_head_level_count_argument_checks(lib):
                                                                       (C.c_int32 * 2)(*counts) if counts else None, None)
     cs.tail_len = 64
     assert app(None) == -1
-    assert app([256, 96]) == -1           # not whole key groups
+    assert app([256, 96]) == -1           # appending wants whole key groups under the new rows
     assert app([256, 320]) == -1          # above the bound n_kept
     assert app([-64, 64]) == -1
     assert app([256, 64], 32) == -1       # n_tokens not whole groups

@@ -155,8 +155,7 @@ def test_calls_that_do_not_take_head_level_counts(orc):
     gc = kvqp.alloc_cache(cfg, ragged=True)
     with pytest.raises(kvqp.KvqpError):
         kvqp.compress(cfg, dev(q_obs), dev(k), dev(v), gc)            # uniform call, ragged cache
-    with pytest.raises(kvqp.KvqpError):
-        kvqp.compress_ragged(cfg, dev(q_obs), dev(k), dev(v), [256, 100], gc)   # not whole groups
+    kvqp.compress_ragged(cfg, dev(q_obs), dev(k), dev(v), [256, 100], gc)       # any count under the bound is fine
     with pytest.raises(kvqp.KvqpError):
         kvqp.compress_ragged(cfg, dev(q_obs), dev(k), dev(v), [256, 288], gc)   # above the bound
     with pytest.raises(kvqp.KvqpError):
