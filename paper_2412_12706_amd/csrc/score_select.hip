@@ -570,20 +570,45 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
         refine = n_pos <= kVoteSlots;
     }
     if (refine) {
-        // ---- binary64 re-scoring: one wave per position, 32 window rows at a time, the parts
-        // summed in ascending order ----
-        for (int pos = wave; pos < n_pos; pos += kSelWaves) {
-            int lo_c = 0, hi_c = tot_band - 1;           // owner: last member with band_off <= pos
-            while (lo_c < hi_c) {
-                const int mid = (lo_c + hi_c + 1) >> 1;
-                if (band_off[mid] <= pos) lo_c = mid; else hi_c = mid - 1;
+        // ---- binary64 re-scoring.  Usual case: one wave per (position, 32 window rows), the parts of a
+        // position then summed in ascending order; when that would not fit the vote slots, one wave per
+        // position, its parts one after the other (the same sums in the same order) ----
+        if (n_pos * n_parts <= kVoteSlots) {
+            for (int item = wave; item < n_pos * n_parts; item += kSelWaves) {
+                const int pos = item / n_parts, part = item % n_parts;
+                int lo_c = 0, hi_c = tot_band - 1;           // owner: last member with band_off <= pos
+                while (lo_c < hi_c) {
+                    const int mid = (lo_c + hi_c + 1) >> 1;
+                    if (band_off[mid] <= pos) lo_c = mid; else hi_c = mid - 1;
+                }
+                const int j = band_start[lo_c] + (pos - band_off[lo_c]);
+                const double v = vote_f64_part(a, head, j, 32 * part);
+                if (lane == 0) pos_vote[item] = v;
             }
-            const int j = band_start[lo_c] + (pos - band_off[lo_c]);
-            double sum = 0.0;
-            for (int part = 0; part < n_parts; ++part) sum += vote_f64_part(a, head, j, 32 * part);
-            if (lane == 0) pos_vote[pos] = sum;
+            __syncthreads();
+            for (int p0 = 0; p0 < n_pos; p0 += kSelThreads) {   // parts summed in a fixed order, then stored over the parts
+                const int pos = p0 + (int)threadIdx.x;
+                double sum = 0.0;
+                if (pos < n_pos)
+                    for (int q = 0; q < n_parts; ++q) sum += pos_vote[pos * n_parts + q];
+                __syncthreads();
+                if (pos < n_pos) pos_vote[pos] = sum;           // (slot pos <= pos * n_parts: never a slot a later round still reads)
+                __syncthreads();
+            }
+        } else {
+            for (int pos = wave; pos < n_pos; pos += kSelWaves) {
+                int lo_c = 0, hi_c = tot_band - 1;
+                while (lo_c < hi_c) {
+                    const int mid = (lo_c + hi_c + 1) >> 1;
+                    if (band_off[mid] <= pos) lo_c = mid; else hi_c = mid - 1;
+                }
+                const int j = band_start[lo_c] + (pos - band_off[lo_c]);
+                double sum = 0.0;
+                for (int part = 0; part < n_parts; ++part) sum += vote_f64_part(a, head, j, 32 * part);
+                if (lane == 0) pos_vote[pos] = sum;
+            }
+            __syncthreads();
         }
-        __syncthreads();
         // ---- pooled binary64 score of each member ----
         for (int c = threadIdx.x; c < tot_band; c += kSelThreads) {
             const int jc = band_idx[c];
