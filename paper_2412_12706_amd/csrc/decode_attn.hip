@@ -600,7 +600,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     const uint32_t sel_even = slot ? 0x01000C0Cu : 0x0C0C0100u;   // low half-word of the pair
     const uint32_t sel_odd = slot ? 0x03020C0Cu : 0x0C0C0302u;    // high half-word of the pair
     (void)lo_mask; (void)slot_mask; (void)sel_even; (void)sel_odd;
-    const uint32_t zrow_mask = (n < NGRP) ? 0xFFFFFFFFu : 0u;   // rows of the zero-term product that hold a key group
+    uint32_t zrow_mask = (n < NGRP) ? 0xFFFFFFFFu : 0u;   // rows of the zero-term product that hold a key group
+    asm volatile("" : "+v"(zrow_mask));                    // (kept opaque: as a known select the sixteen ANDs become half-rate selects)
     (void)zrow_mask;
     const float c_logit = a.sm_scale * kLog2e * kCodeUnit;
     const float c_bias = a.sm_scale * kLog2e;

@@ -126,14 +126,15 @@ __device__ __forceinline__ void encode8(const uint32_t (&w)[4], float zf, float 
 
 // Key words of one row from the thread's eight codes (row-major layout of kvqp.h: channel d sits in
 // word d / E at half-word r % 2, field r / 2, r = d % E) and their store.  krow points at the row.
+// keep: all ones, or 0 for a padding row (its words are stored as zeros).
 template <int BITS>
-__device__ __forceinline__ void store_key_words(uint32_t* krow, int c8, const uint32_t (&c)[8]) {
+__device__ __forceinline__ void store_key_words(uint32_t* krow, int c8, const uint32_t (&c)[8], uint32_t keep = 0xFFFFFFFFu) {
     constexpr int E = 32 / BITS;
     if constexpr (E == 8) {
         uint32_t w = 0;
 #pragma unroll
         for (int dd = 0; dd < 8; ++dd) w |= c[dd] << (16 * (dd & 1) + BITS * (dd >> 1));
-        krow[c8] = w;
+        krow[c8] = w & keep;
     } else if constexpr (E == 4) {
         uint32_t w0 = 0, w1 = 0;
 #pragma unroll
@@ -141,7 +142,7 @@ __device__ __forceinline__ void store_key_words(uint32_t* krow, int c8, const ui
             w0 |= c[dd] << (16 * (dd & 1) + BITS * (dd >> 1));
             w1 |= c[4 + dd] << (16 * (dd & 1) + BITS * (dd >> 1));
         }
-        *reinterpret_cast<uint2*>(krow + 2 * c8) = make_uint2(w0, w1);
+        *reinterpret_cast<uint2*>(krow + 2 * c8) = make_uint2(w0 & keep, w1 & keep);
     } else {   // E == 16: the word spans this lane's channels and its neighbour's
         uint32_t w = 0;
 #pragma unroll
@@ -152,7 +153,7 @@ __device__ __forceinline__ void store_key_words(uint32_t* krow, int c8, const ui
         // odd lanes hold channels 8..15 of the word: fields 4..7 of each half-word
         if (c8 & 1) w <<= 4 * BITS;
         w |= dpp<kQuadXor1>(w);
-        if (!(c8 & 1)) krow[c8 >> 1] = w;
+        if (!(c8 & 1)) krow[c8 >> 1] = w & keep;
     }
 }
 
@@ -339,9 +340,9 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
             const uint32_t b = q4 == 0 ? mx[4 * jj] : q4 == 1 ? mx[4 * jj + 1] : q4 == 2 ? mx[4 * jj + 2] : mx[4 * jj + 3];
             const GroupParams gp = group_params<BITS>(a, b);
             const int t = r + 16 * (4 * jj + q4);
-            if (t < ntok_pad && (c8 & (GL - 1)) < 4) {               // (padding rows of the last block: scale 0, zero +0)
+            if (t < ntok_pad && (c8 & (GL - 1)) < 4) {               // (a padding row of the last block was loaded as zeros: scale 0, zero +0)
                 const size_t m = ((size_t)head * n_cap + d0 + t) * CPT + c8 / GL;
-                scale[m] = t < ntok ? gp.scale_h : (uint16_t)0; zero[m] = t < ntok ? gp.zero_h : (uint16_t)0;
+                scale[m] = gp.scale_h; zero[m] = gp.zero_h;
             }
             const uint32_t zb = __float_as_uint(gp.zf), ib = __float_as_uint(gp.inv);
             const uint32_t zq[4] = {dpp<0x00>(zb), dpp<0x55>(zb), dpp<0xAA>(zb), dpp<0xFF>(zb)};
@@ -437,11 +438,8 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
 #pragma unroll
                     for (int e = 0; e < 8; ++e) c[e] &= ((om[j] >> e) & 1u) - 1u;
                 }
-                if (!live[j]) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) c[e] = 0u;           // padding rows of the last block hold code 0
-                }
-                if (r + 16 * j < ntok_pad) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, c);
+                // (padding rows of the last block hold code 0)
+                if (r + 16 * j < ntok_pad) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, c, live[j] ? 0xFFFFFFFFu : 0u);
             }
         }
         if constexpr (OUT)   // the zero of (row j's key group, own channel 8 c8 + e) from the table the codes were made with
@@ -451,13 +449,8 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         per_token(kw, k_scale, k_zero, codes, om, zrow);
         if constexpr (OUT) store_slots(k_out, s_cnt[0], kw, om, [&](int j, int) { return __uint_as_float(zrow[j]); });
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            if (!live[j]) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) codes[j][e] = 0u;
-            }
+        for (int j = 0; j < R; ++j)      // (a padding row was loaded as zeros: scale 0, all codes 0)
             if (r + 16 * j < ntok_pad) store_key_words<BITS>(kc_head + (size_t)(d0 + r + 16 * j) * (kHeadDim / E), c8, codes[j]);
-        }
     }
 
     // ---------------- values ----------------
@@ -481,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
                 const int sb = (32 * b32) / SB, blk = b32 % (SB / 32);
                 const int p = (4 * blk + i4) % (E / 2);
 #pragma unroll
-                for (int dd = 0; dd < 8; ++dd) part[sb][dd] |= live[j] ? codes[j][dd] << (16 * H + BITS * p) : 0u;
+                for (int dd = 0; dd < 8; ++dd) part[sb][dd] |= codes[j][dd] << (16 * H + BITS * p);   // (a padding row's codes are all 0)
             }
         } else {
 #pragma unroll

@@ -395,7 +395,7 @@ __device__ double vote_f64_part(const SelectArgs& a, int head, int key, int row_
 // per-(row, wave) counts (one ballot each), one table scan, and a popcount below the lane.  The
 // pooled scores of prefixes up to 32768 tokens never leave the registers.
 __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
-    __shared__ __align__(16) int hist[kSelWaves][256];   // later reused for the binary64 votes (2048 doubles)
+    __shared__ __align__(16) int hist[kSelWaves][256];   // later reused for the binary64 partial votes (2048 doubles)
     __shared__ int tab_a[kMaxRows * kSelWaves];   // per (row, wave): survivors that need no second look
     __shared__ int tab_b[kMaxRows * kSelWaves];   // per (row, wave): band members (or ties at the cut)
     __shared__ int swave[kSelWaves];
@@ -407,7 +407,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
     __shared__ int band_off[kMaxBand + 1];        // offset of its owned votes in the vote list
     __shared__ double band_score[kMaxBand];
     __shared__ int band_take[kMaxBand + 1];       // after the scan: taken band members before position c
-    __shared__ float stage[kStageRows * kSelThreads + 2 * kMaxPoolRadius];   // votes of a few rows plus halo
+    __shared__ __align__(16) float stage[kStageRows * kSelThreads + 2 * kMaxPoolRadius];   // votes of a few rows plus halo; later the binary64 votes
 
     const int head = blockIdx.x;
     const int P = a.P, k = a.head_n ? a.head_n[head] : a.n_kept;
@@ -538,7 +538,8 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
     const int tot_band = scan_table(tab_b, n_rows * kSelWaves, swave);
     const int n_parts = (a.rows + 31) / 32;       // a wave re-scores 32 window rows of one position
     bool refine = tot_band <= kMaxBand;
-    double* pos_vote = reinterpret_cast<double*>(&hist[0][0]);
+    double* part_vote = reinterpret_cast<double*>(&hist[0][0]);   // kVoteSlots partial votes of a batch of positions
+    double* pos_vote = reinterpret_cast<double*>(&stage[0]);        // kVoteSlots votes, one per distinct position
     int n_pos = 0;
 
     if (refine) {
@@ -570,12 +571,14 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
         refine = n_pos <= kVoteSlots;
     }
     if (refine) {
-        // ---- binary64 re-scoring.  Usual case: one wave per (position, 32 window rows), the parts of a
-        // position then summed in ascending order; when that would not fit the vote slots, one wave per
-        // position, its parts one after the other (the same sums in the same order) ----
-        if (n_pos * n_parts <= kVoteSlots) {
-            for (int item = wave; item < n_pos * n_parts; item += kSelWaves) {
-                const int pos = item / n_parts, part = item % n_parts;
+        // ---- binary64 re-scoring: one wave per (position, 32 window rows); the parts of a position land
+        // in the histogram's LDS and are summed in ascending order into the position's vote, which is kept
+        // in the pooling stage's LDS (both are free by now).  Positions go in batches that fit the parts. ----
+        const int batch = kVoteSlots / n_parts;           // positions per batch (n_parts <= 8)
+        for (int p0 = 0; p0 < n_pos; p0 += batch) {
+            const int np = min(batch, n_pos - p0);
+            for (int item = wave; item < np * n_parts; item += kSelWaves) {
+                const int pos = p0 + item / n_parts, part = item % n_parts;
                 int lo_c = 0, hi_c = tot_band - 1;           // owner: last member with band_off <= pos
                 while (lo_c < hi_c) {
                     const int mid = (lo_c + hi_c + 1) >> 1;
@@ -583,29 +586,13 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
                 }
                 const int j = band_start[lo_c] + (pos - band_off[lo_c]);
                 const double v = vote_f64_part(a, head, j, 32 * part);
-                if (lane == 0) pos_vote[item] = v;
+                if (lane == 0) part_vote[item] = v;
             }
             __syncthreads();
-            for (int p0 = 0; p0 < n_pos; p0 += kSelThreads) {   // parts summed in a fixed order, then stored over the parts
-                const int pos = p0 + (int)threadIdx.x;
+            for (int i = threadIdx.x; i < np; i += kSelThreads) {
                 double sum = 0.0;
-                if (pos < n_pos)
-                    for (int q = 0; q < n_parts; ++q) sum += pos_vote[pos * n_parts + q];
-                __syncthreads();
-                if (pos < n_pos) pos_vote[pos] = sum;           // (slot pos <= pos * n_parts: never a slot a later round still reads)
-                __syncthreads();
-            }
-        } else {
-            for (int pos = wave; pos < n_pos; pos += kSelWaves) {
-                int lo_c = 0, hi_c = tot_band - 1;
-                while (lo_c < hi_c) {
-                    const int mid = (lo_c + hi_c + 1) >> 1;
-                    if (band_off[mid] <= pos) lo_c = mid; else hi_c = mid - 1;
-                }
-                const int j = band_start[lo_c] + (pos - band_off[lo_c]);
-                double sum = 0.0;
-                for (int part = 0; part < n_parts; ++part) sum += vote_f64_part(a, head, j, 32 * part);
-                if (lane == 0) pos_vote[pos] = sum;
+                for (int q = 0; q < n_parts; ++q) sum += part_vote[i * n_parts + q];
+                pos_vote[p0 + i] = sum;
             }
             __syncthreads();
         }
