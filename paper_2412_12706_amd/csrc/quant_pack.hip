@@ -248,21 +248,39 @@ __global__ __launch_bounds__(kThreads) void gather_quant_pack(
         __syncthreads();
     }
 
-    // ---- gather: all of the thread's rows of both tensors are requested before anything is used ----
+    // ---- gather: all of the thread's rows of both tensors are requested before anything is used.
+    // The row numbers come first, all of them, and then every row load leaves without waiting for
+    // another (two round trips to memory instead of one per row); a row past the count reads the
+    // block's last row instead, so no load depends on a branch, and is cleared afterwards. ----
     uint32_t kw[R][4], vw[R][4];
     bool live[R];
+    int pos[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const int t = r + 16 * j;
-        live[j] = t < ntok;               // (the same for the 16 lanes of a token row)
-        const int pos = !live[j] ? 0 : idx ? idx[(size_t)head * n_kept + t0 + t] : t0 + t;
+        live[j] = r + 16 * j < ntok;      // (the same for the 16 lanes of a token row)
+        pos[j] = t0 + min(r + 16 * j, ntok - 1);
+    }
+    if (idx) {                            // (uniform)
+        const int32_t* rows = idx + (size_t)head * n_kept;
+#pragma unroll
+        for (int j = 0; j < R; ++j) pos[j] = rows[pos[j]];
+    }
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
         // (prompt rows are read once: non-temporal)
         typedef uint32_t u4v __attribute__((ext_vector_type(4)));
-        const u4v zero4 = {0u, 0u, 0u, 0u};
-        const u4v a = live[j] ? __builtin_nontemporal_load(reinterpret_cast<const u4v*>(kh + (size_t)pos * kHeadDim + 8 * c8)) : zero4;
-        const u4v b = live[j] ? __builtin_nontemporal_load(reinterpret_cast<const u4v*>(vh + (size_t)pos * kHeadDim + 8 * c8)) : zero4;
+        const u4v a = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(kh + (size_t)pos[j] * kHeadDim + 8 * c8));
+        const u4v b = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(vh + (size_t)pos[j] * kHeadDim + 8 * c8));
         kw[j][0] = a[0]; kw[j][1] = a[1]; kw[j][2] = a[2]; kw[j][3] = a[3];
         vw[j][0] = b[0]; vw[j][1] = b[1]; vw[j][2] = b[2]; vw[j][3] = b[3];
+    }
+    if (ntok < TB) {                      // (uniform) the head's last block: rows past the count are zeros
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (!live[j]) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) { kw[j][q] = 0u; vw[j][q] = 0u; }
+            }
     }
 
     // Outlier marking (OUT): om gets a bit per own element whose magnitude is above the threshold --
