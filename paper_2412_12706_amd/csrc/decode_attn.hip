@@ -1275,8 +1275,6 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     l_run = quad_rows_add(l_run);
 #pragma unroll
     for (int c = 0; c < NCG; ++c) oz[c] = quad_rows_add(oz[c]);
-    constexpr int ITEMS = (GQ * kHeadDim + kThreads - 1) / kThreads;   // outputs (head hh, channel d) per merging thread
-    const bool merger = threadIdx.x < kThreads;
     __syncthreads();                     // every wave has left the loop: its LDS is free for the states
     // rows 4kb+i come in (hi, lo) pairs i = (0,1), (2,3) with a common reference: add them here
 #pragma unroll
@@ -1291,86 +1289,50 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
     }
     __syncthreads();
-    // the merge weights exp2(m - M) are shared by all channels of a head: one thread per
-    // (wave, slot, head) derives its weight, then every merging thread reads them back
-    float* sW = sS + nw * 16 * 6;                 // [wave * SLOTS + slot][head] weights, then [head] references
-    if ((int)threadIdx.x < nw * SLOTS * GQ) {
-        const int hh = threadIdx.x % GQ, ws = threadIdx.x / GQ;
+    // One output (head hh, channel d) per thread, every wave of the workgroup taking part: the
+    // common reference over the waves' states and this workgroup's share of the full-precision tail
+    // rows (the first four waves' states in sT), then one pass that weighs and adds them.  All
+    // threads of a head read the same references and sums (LDS broadcasts); nw is a multiple of 4.
+    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
+    for (int item = threadIdx.x; item < GQ * kHeadDim; item += blockDim.x) {
+        const int hh = item / kHeadDim, d = item % kHeadDim;
+        const int cg = d / G;
         float M = kNegBig;
-        for (int u = 0; u < nw * SLOTS; ++u) M = fmaxf(M, sS[((u / SLOTS) * 16 + (u % SLOTS) * 8 + 2 * hh) * 6]);
-        sW[ws * GQ + hh] = exp2f(sS[((ws / SLOTS) * 16 + (ws % SLOTS) * 8 + 2 * hh) * 6] - M);
-        if (ws == 0) sW[nw * SLOTS * GQ + hh] = M;
-    }
-    __syncthreads();
-    float Mi[ITEMS], Ai[ITEMS], Li[ITEMS];
-    if (merger) {
+        for (int w0 = 0; w0 < nw; w0 += kWaves)
 #pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
-            const int hh = item / kHeadDim, d = item % kHeadDim;
-            const int cg = d / G;
-            float acc = 0.f, L = 0.f;
-            for (int w = 0; w < nw; ++w)
+            for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+                for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[((w0 + w) * 16 + sl * 8 + 2 * hh) * 6]);
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sT[(w * GQ + hh) * kPartStride]);
+        float acc = 0.f, L = 0.f;
+        for (int w0 = 0; w0 < nw; w0 += kWaves)
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w)
 #pragma unroll
                 for (int sl = 0; sl < SLOTS; ++sl) {
-                    const float* st = sS + (w * 16 + sl * 8 + 2 * hh) * 6;
-                    const float wgt = sW[(w * SLOTS + sl) * GQ + hh];
-                    float o = sO[(w * 8 + sl * 4 + hh) * kHeadDim + d] * kCodeUnit + st[2 + cg];
-                    if constexpr (OUT) o += s_oc[(w * 8 + sl * 4 + hh) * kHeadDim + d];
+                    const float* st = sS + ((w0 + w) * 16 + sl * 8 + 2 * hh) * 6;
+                    const float wgt = __builtin_amdgcn_exp2f(st[0] - M);
+                    float o = sO[((w0 + w) * 8 + sl * 4 + hh) * kHeadDim + d] * kCodeUnit + st[2 + cg];
+                    if constexpr (OUT) o += s_oc[((w0 + w) * 8 + sl * 4 + hh) * kHeadDim + d];
                     acc = __builtin_fmaf(wgt, o, acc);
                     L = __builtin_fmaf(wgt, st[1], L);
                 }
-            Mi[it] = sW[nw * SLOTS * GQ + hh]; Ai[it] = acc; Li[it] = L;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float* row = sT + (w * GQ + hh) * kPartStride;
+            const float wgt = __builtin_amdgcn_exp2f(row[0] - M);
+            acc = __builtin_fmaf(wgt, row[2 + d], acc);
+            L = __builtin_fmaf(wgt, row[1], L);
+        }
+        if (a.n_splits == 1) {   // the whole head was here: normalise, round once, done
+            a.out[((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc / L));
+        } else {
+            st_dev(dst + hh * kPartStride + 2 + d, acc);
+            if (d == 0) { st_dev(dst + hh * kPartStride, M); st_dev(dst + hh * kPartStride + 1, L); }
         }
     }
-    // this workgroup's share of the full-precision tail rows (first four waves), merged the same way
-    {
-        if (merger) {
-#pragma unroll
-            for (int it = 0; it < ITEMS; ++it) {
-                const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
-                const int hh = item / kHeadDim, d = item % kHeadDim;
-                float M = Mi[it];
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sT[(w * GQ + hh) * kPartStride]);
-                const float keep = exp2f(Mi[it] - M);
-                float acc = Ai[it] * keep, L = Li[it] * keep;
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w) {
-                    const float* row = sT + (w * GQ + hh) * kPartStride;
-                    const float wgt = exp2f(row[0] - M);
-                    acc = __builtin_fmaf(wgt, row[2 + d], acc);
-                    L = __builtin_fmaf(wgt, row[1], L);
-                }
-                Mi[it] = M; Ai[it] = acc; Li[it] = L;
-            }
-        }
-    }
-    if (a.n_splits == 1) {   // the whole head was here: normalise, round once, done
-        if (merger) {
-#pragma unroll
-            for (int it = 0; it < ITEMS; ++it) {
-                const int item = threadIdx.x + it * kThreads;
-                if (item < GQ * kHeadDim) {
-                    const int hh = item / kHeadDim, d = item % kHeadDim;
-                    a.out[((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim + d] = __half_as_ushort(__float2half_rn(Ai[it] / Li[it]));
-                }
-            }
-        }
-        return;
-    }
-    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
-    if (merger) {
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            const int item = threadIdx.x + it * kThreads;
-            if (item < GQ * kHeadDim) {
-                const int hh = item / kHeadDim, d = item % kHeadDim;
-                st_dev(dst + hh * kPartStride + 2 + d, Ai[it]);
-                if (d == 0) { st_dev(dst + hh * kPartStride, Mi[it]); st_dev(dst + hh * kPartStride + 1, Li[it]); }
-            }
-        }
-    }
+    if (a.n_splits == 1) return;
     merge_if_last<GQ>(a, bh);
 }
 
