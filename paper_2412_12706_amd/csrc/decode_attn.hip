@@ -274,60 +274,48 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
         s_last = last;
     }
     __syncthreads();
-    if (!s_last || threadIdx.x >= kThreads) return;   // (workgroups may be larger than the 256 merging threads)
+    if (!s_last) return;
     const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
     const float* base = a.part + (size_t)bh * a.n_partials * GQ * kPartStride;
     const size_t stride = (size_t)GQ * kPartStride;
     // Device-scope loads are slow (they go to the coherence point) and are kept in program order,
-    // so many are put in flight per round trip: kMergeBatch partials of both of a thread's outputs.
+    // so many are put in flight per round trip -- kMergeBatch partials of a thread's output -- and
+    // every wave of the workgroup takes part (one output per thread where the workgroup is large
+    // enough).  (Fetching a partial's reference and sum, which lie side by side, with one 8-byte
+    // load measured slower than two 4-byte ones.)
     constexpr int kMergeBatch = 16;
-    constexpr int ITEMS = (GQ * kHeadDim + kThreads - 1) / kThreads;
-    float M[ITEMS], acc[ITEMS], L[ITEMS];
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) { M[it] = kNegBig; acc[it] = 0.f; L[it] = 0.f; }
-    for (int s0 = 0; s0 < a.n_partials; s0 += kMergeBatch) {
-        float m[ITEMS][kMergeBatch], l[ITEMS][kMergeBatch], o[ITEMS][kMergeBatch];
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            const int item = min((int)threadIdx.x + it * kThreads, GQ * kHeadDim - 1);
-            const int h = item / kHeadDim, d = item % kHeadDim;
+    for (int item = threadIdx.x; item < GQ * kHeadDim; item += blockDim.x) {
+        const int h = item / kHeadDim, d = item % kHeadDim;
+        float M = kNegBig, acc = 0.f, L = 0.f;
+        for (int s0 = 0; s0 < a.n_partials; s0 += kMergeBatch) {
+            float m[kMergeBatch], l[kMergeBatch], o[kMergeBatch];
 #pragma unroll
             for (int u4 = 0; u4 < kMergeBatch; u4 += 4) {
                 if (s0 + u4 < a.n_partials) {          // (uniform: whole groups of four beyond the last partial are not fetched)
 #pragma unroll
                     for (int u = u4; u < u4 + 4; ++u) {
                         const float* q = base + (size_t)h * kPartStride + (size_t)min(s0 + u, a.n_partials - 1) * stride;
-                        m[it][u] = ld_dev(q); l[it][u] = ld_dev(q + 1); o[it][u] = ld_dev(q + 2 + d);
+                        m[u] = ld_dev(q); l[u] = ld_dev(q + 1); o[u] = ld_dev(q + 2 + d);
                     }
                 } else {
 #pragma unroll
-                    for (int u = u4; u < u4 + 4; ++u) { m[it][u] = kNegBig; l[it][u] = 0.f; o[it][u] = 0.f; }
+                    for (int u = u4; u < u4 + 4; ++u) { m[u] = kNegBig; l[u] = 0.f; o[u] = 0.f; }
                 }
             }
-        }
+            float Mn = M;
 #pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            float Mn = M[it];
-#pragma unroll
-            for (int u = 0; u < kMergeBatch; ++u) Mn = fmaxf(Mn, m[it][u]);
-            const float keep = exp2f(M[it] - Mn);
-            acc[it] *= keep; L[it] *= keep;
+            for (int u = 0; u < kMergeBatch; ++u) Mn = fmaxf(Mn, m[u]);
+            const float keep = __builtin_amdgcn_exp2f(M - Mn);
+            acc *= keep; L *= keep;
 #pragma unroll
             for (int u = 0; u < kMergeBatch; ++u) {
-                const float wgt = (s0 + u < a.n_partials) ? exp2f(m[it][u] - Mn) : 0.f;
-                acc[it] = __builtin_fmaf(wgt, o[it][u], acc[it]);
-                L[it] = __builtin_fmaf(wgt, l[it][u], L[it]);
+                const float wgt = (s0 + u < a.n_partials) ? __builtin_amdgcn_exp2f(m[u] - Mn) : 0.f;
+                acc = __builtin_fmaf(wgt, o[u], acc);
+                L = __builtin_fmaf(wgt, l[u], L);
             }
-            M[it] = Mn;
+            M = Mn;
         }
-    }
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const int item = threadIdx.x + it * kThreads;
-        if (item < GQ * kHeadDim) {
-            const int h = item / kHeadDim, d = item % kHeadDim;
-            a.out[((size_t)b * a.n_q_heads + g * GQ + h) * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc[it] / L[it]));
-        }
+        a.out[((size_t)b * a.n_q_heads + g * GQ + h) * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc / L));
     }
 }
 
