@@ -61,15 +61,16 @@ constexpr float kNegBig = -1.0e30f; // finite stand-in for -inf in running maxim
 // Waves per SIMD the pipelined kernel is compiled for: the 2- and 4-bit variants fit 168 registers
 // (three waves) up to four query heads per KV head; wider code words or eight heads need more (two waves).
 constexpr int pipe_waves(int bits, int gq, bool out = false) { return (bits <= 4 && gq <= 4 && !out) ? 3 : 2; }
-constexpr float kLazyLog2 = 2.0f;   // slack of the lazily updated softmax reference
+constexpr float kLazyLog2 = 4.0f;   // slack of the lazily updated softmax reference
 // Probabilities are formed 2^kPBoost times too large (the factor sits in the exponent, at no cost,
 // and a wave hands over its reference lowered by as much, so sums, outputs and merges are all
 // consistent).  The weights p * s of the value product travel as binary16 hi + lo parts, cut off
 // towards zero; a weight below 2^-14 has a subnormal hi part and loses up to 2^-24 of itself, and
 // in a peaked softmax that is most tokens, all losing in the same direction: measured, outputs of
 // quantized caches were off by 1e-4 and more where a 16-bit cache is off by 1e-6.  With the slack
-// above, p stays below 2^(kLazyLog2 + kPBoost) = 2^8, the bound it always had.
-constexpr float kPBoost = 6.0f;
+// above, p stays below 2^(kLazyLog2 + kPBoost) = 2^8, the bound it always had.  (A smaller slack
+// with a larger factor is more exact still, but moves the reference about once per row and wave.)
+constexpr float kPBoost = 4.0f;
 constexpr int kPartStride = kHeadDim + 2;  // floats per (partial, head): m, l, acc[128]
 
 __device__ __forceinline__ float xor16_max(float v) {
