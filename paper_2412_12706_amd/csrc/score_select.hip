@@ -432,15 +432,26 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
 #pragma unroll
     for (int row = 0; row < kRegRows; ++row) pv[row] = -1.0f;
     // A step stages kStageRows * 1024 consecutive votes plus r on either side in LDS (-1, below any
-    // vote, outside the prefix); every thread then takes the maximum over its window per row.
+    // vote, outside the prefix); every thread then takes the maximum over its window per row.  The
+    // votes of the next step are requested before this step's are pooled, so only the first step
+    // waits for memory.
+    float nx[kStageRows + 1];
+    auto fetch = [&](int row0) {
+        const int base = row0 * kSelThreads - r;
+#pragma unroll
+        for (int u = 0; u <= kStageRows; ++u) {
+            const int i = (int)threadIdx.x + u * kSelThreads, j = base + i;
+            nx[u] = (i < kStageRows * kSelThreads + 2 * r && j >= 0 && j < P) ? vote[j] : -1.0f;
+        }
+    };
 #define KVQP_POOL_STEP(ROW0, STORE)                                                                \
     {                                                                                              \
-        const int base = (ROW0) * kSelThreads - r;                                                 \
-        for (int i = threadIdx.x; i < kStageRows * kSelThreads + 2 * r; i += kSelThreads) {        \
-            const int j = base + i;                                                                \
-            stage[i] = (j >= 0 && j < P) ? vote[j] : -1.0f;                                        \
+        _Pragma("unroll") for (int u = 0; u <= kStageRows; ++u) {                                  \
+            const int i = (int)threadIdx.x + u * kSelThreads;                                      \
+            if (i < kStageRows * kSelThreads + 2 * r) stage[i] = nx[u];                            \
         }                                                                                          \
         __syncthreads();                                                                           \
+        if ((ROW0) + kStageRows < n_rows) fetch((ROW0) + kStageRows);                              \
         _Pragma("unroll") for (int q = 0; q < kStageRows; ++q) {                                   \
             const int row = (ROW0) + q;                                                            \
             const int j = row * kSelThreads + (int)threadIdx.x;                                    \
@@ -454,6 +465,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const SelectArgs a) {
         }                                                                                          \
         __syncthreads();                                                                           \
     }
+    fetch(0);
 #pragma unroll
     for (int row0 = 0; row0 < kRegRows; row0 += kStageRows)
         if (row0 < n_rows) KVQP_POOL_STEP(row0, pv[row] = best)
