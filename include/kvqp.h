@@ -306,6 +306,10 @@ int kvqp_quantize_selected_ragged(const kvqp_cfg *cfg, const void *k, const void
  *   out half [batch, Hq, D]   binary32 accumulation, rounded once at the end
  * cfg fields used: batch, heads, head_dim, bits, group_size, key_axis,
  * decode_splits, sm_scale, outlier_threshold, decode_cache_hint.
+ * Numerical range: the weights of the value product travel as binary16 numbers inside
+ * the kernel, so a value group's scale should stay below 256 (a 2-bit group spanning
+ * less than 768, a 4-bit group less than 3840); beyond that a weight can saturate at
+ * the binary16 maximum and the output degrades (it stays finite).
  * n_kept + tail_len must be >= 1.  With head-level
  * counts (cache->head_n_kept non-NULL) head h attends its first
  * head_n_kept[h] tokens; the counts are read on the device, where a count
