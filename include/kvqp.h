@@ -309,7 +309,9 @@ int kvqp_quantize_selected_ragged(const kvqp_cfg *cfg, const void *k, const void
  * Numerical range: the weights of the value product travel as binary16 numbers inside
  * the kernel, so a value group's scale should stay below 256 (a 2-bit group spanning
  * less than 768, a 4-bit group less than 3840); beyond that a weight can saturate at
- * the binary16 maximum and the output degrades (it stays finite).
+ * the binary16 maximum and the output degrades (it stays finite).  Likewise the product
+ * of a query element and its channel's key scale must stay inside the binary16 range
+ * (|q| * scale < 65504: keys spanning tens of thousands at 2 bits would not).
  * n_kept + tail_len must be >= 1.  With head-level
  * counts (cache->head_n_kept non-NULL) head h attends its first
  * head_n_kept[h] tokens; the counts are read on the device, where a count
