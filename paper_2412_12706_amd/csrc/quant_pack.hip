@@ -3,9 +3,12 @@
 // s = (m - z)/(2^B - 1), Q(G) = round((G - z)/s); grouping axes of Section 2 /
 // Section 6.3).  Every survivor row is read once (2 x 256 B, scattered) and
 // k*bpt bytes are written; there is no reuse to exploit.  What bounds it on
-// the MI355X is the vector ALU as much as memory: the 2-bit variant runs with
-// the vector units ~98 % busy (order keys, the quantizer's individually
-// rounded binary32 steps, field packing) at ~5 TB/s of gathers and stores.
+// the MI355X, measured: not the scattered rows (contiguous survivors take the
+// same time) and not the instruction count alone (order keys, the quantizer's
+// individually rounded binary32 steps, field packing: ~18 lane operations per
+// element), but a workgroup's own chain of waits -- two memory round trips,
+// three barriers -- that the six workgroups a CU holds at 78 registers do not
+// fully hide; it moves ~4.7 TB/s of gathers and stores.
 //
 // One workgroup owns TB consecutive kept tokens of one (batch, kv head): whole
 // key groups (G | TB) and whole value superblocks (SB | TB).  Thread
