@@ -306,6 +306,10 @@ int kvqp_quantize_selected_ragged(const kvqp_cfg *cfg, const void *k, const void
  *   out half [batch, Hq, D]   binary32 accumulation, rounded once at the end
  * cfg fields used: batch, heads, head_dim, bits, group_size, key_axis,
  * decode_splits, sm_scale, outlier_threshold, decode_cache_hint.
+ * Reproducibility: the order in which partial sums meet depends on which wave takes
+ * which 64-token chunk, so two runs may differ in the last bits of the binary32
+ * accumulation (and, rarely, in the rounding of an output); kvqp_compress, by contrast,
+ * is bit-for-bit reproducible (indices, codes, scales, zeros, tail).
  * Numerical range: the weights of the value product travel as binary16 numbers inside
  * the kernel, so a value group's scale should stay below 256 (a 2-bit group spanning
  * less than 768, a 4-bit group less than 3840); beyond that a weight can saturate at
