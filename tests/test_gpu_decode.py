@@ -211,3 +211,27 @@ def test_cache_hint_of_the_loads_does_not_change_the_result(orc, bits, Gq, axis,
         err = np.abs(out.cpu().numpy().astype(np.float64) - ref).max()
         print(f"  bits={bits} hint={hint} max-abs error {err:.3e}", flush=True)
         assert err <= TOL
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_large_value_scales(orc, bits):
+    """Values of magnitude several hundred (group scales beyond 256 at 2 bits): the binary16 weights
+    inside the kernel still carry them -- outputs within 1e-3 of the largest output, which at that
+    magnitude is a few binary16 steps -- and values ten times larger again, where a weight can
+    saturate, still give finite outputs.  (The 2e-3 bar is stated for outputs of order one.)"""
+    B, Hq, Hkv, W, n, L = 1, 8, 2, 32, 256, 600
+    idx = np.tile(np.arange(n, dtype=np.int32), (B, Hkv, 1))
+    q = synth.decode_query_host(B, Hq, 128, config=77, step=0)
+    for vmul in (300, 3000):
+        _, k, v = synth.prompt_host(B, Hq, Hkv, L, W, 128, outlier=10.0, config=77)
+        v = (v.view(np.float16).astype(np.float32) * vmul).astype(np.float16).view(np.uint16)
+        oc = orc.quantize_selected(k, v, idx, W=W, bits=bits, G=32, key_axis=0)
+        cfg = kvqp.Cfg(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W, budget=n, bits=bits, group_size=32)
+        out = kvqp.decode_attn(cfg, dev(q), upload_cache(oc))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got))
+        if vmul == 300:
+            ref = orc.decode_attn(q, oc, cfg.sm_scale)
+            assert float(oc.v_scale.view(np.float16).astype(np.float32).max()) > (256 if bits == 2 else 64)
+            assert np.abs(got - ref).max() <= 1e-3 * np.abs(ref).max()
