@@ -346,96 +346,109 @@ __device__ __forceinline__ float row16_add(float v) {
     return v;
 }
 
-// Full-precision tail rows [t0, t1) of one KV head, shared by the four waves of a workgroup.  A wave
-// takes four rows per step: lane = 16 * (row in step) + (8-channel segment).  Each wave leaves its
-// softmax state in LDS, sT[wave][head] = {reference m (log2 domain), sum l, unnormalised o[128]}.
-// Heads go in passes of at most four to bound the registers (rows are re-read from cache).
+// Full-precision tail rows [t0, t1) of one KV head, shared by the four waves of a workgroup, every
+// wave taking part.  The 16 lanes of a DPP row hold one (query head, tail row) pair, 8 channels
+// each: with four or more query heads per KV head the four DPP rows of a wave are four heads side by
+// side and the wave walks its rows one at a time (wave w: rows t0 + w, t0 + w + 4, ...), so nothing
+// is merged across lanes; with two heads (one head) a wave takes two (four) rows per step and the
+// row groups of a head are merged at the end.  Eight heads go in two passes (rows re-read from
+// cache).  Each wave leaves its softmax state in LDS, sT[wave][head] = {reference m (log2 domain),
+// sum l, unnormalised o[128]}.
+// The query rows come from their plain copy in LDS (sq); the lane's first row, tail_first_row(),
+// has been requested by the caller before anything waited on memory and arrives in k_first /
+// v_first: when a head is split over many workgroups that row is all a wave has, and a round trip
+// to memory after the staging barrier would sit on every workgroup's path.
+template <int GQ> struct TailGeom {
+    static constexpr int HB = GQ < 4 ? GQ : 4;   // heads side by side in a wave
+    static constexpr int RP = 4 / HB;            // rows side by side in a wave
+};
 template <int GQ>
-__device__ void tail_rows(const DecodeArgs& a, int bh, int t0, int t1, float* sT) {
-    constexpr int HB = GQ < 4 ? GQ : 4;
-    const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
+__device__ __forceinline__ int tail_first_row(int t0, int t1, int wave, int lane) {
+    const int r = t0 + wave * TailGeom<GQ>::RP + (lane >> 4) / TailGeom<GQ>::HB;
+    return (wave < kWaves && r < t1) ? r : -1;
+}
+template <int GQ>
+__device__ void tail_rows(const DecodeArgs& a, int bh, int t0, int t1, float* sT, const uint16_t* sq, uint4 k_first, uint4 v_first) {
+    constexpr int HB = TailGeom<GQ>::HB, RP = TailGeom<GQ>::RP;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int seg = lane & 15, rg = lane >> 4;
+    const int seg = lane & 15, hb = (lane >> 4) % HB;
     const uint16_t* tk = a.tail_k + (size_t)bh * a.tail_cap * kHeadDim + 8 * seg;
     const uint16_t* tv = a.tail_v + (size_t)bh * a.tail_cap * kHeadDim + 8 * seg;
-    const bool any = t0 + 4 * wave < t1;   // wave-uniform
+    const int r_first = tail_first_row<GQ>(t0, t1, wave, lane);
+    const float c_q = a.sm_scale * kLog2e;
 #pragma unroll 1
     for (int h0 = 0; h0 < GQ; h0 += HB) {
-        float m[HB], l[HB], o[HB][8];
+        float m = kNegBig, l = 0.f, o[8];
 #pragma unroll
-        for (int h = 0; h < HB; ++h) {
-            m[h] = kNegBig; l[h] = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) o[h][j] = 0.f;
-        }
-        if (any) {
-            float qf[HB][8];
-#pragma unroll
-            for (int h = 0; h < HB; ++h) {
-                const uint4 u = *reinterpret_cast<const uint4*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + h0 + h) * kHeadDim + 8 * seg);
+        for (int j = 0; j < 8; ++j) o[j] = 0.f;
+        if (t0 + wave * RP < t1) {   // (wave-uniform: the wave has a row)
+            float qf[8];
+            {
+                const uint4 u = *reinterpret_cast<const uint4*>(sq + (h0 + hb) * kHeadDim + 8 * seg);
                 const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const h2v qq = as_h2(w[j]);
-                    qf[h][2 * j] = (float)qq[0] * (a.sm_scale * kLog2e); qf[h][2 * j + 1] = (float)qq[1] * (a.sm_scale * kLog2e);
+                    qf[2 * j] = (float)qq[0] * c_q; qf[2 * j + 1] = (float)qq[1] * c_q;
                 }
             }
-            for (int r0 = t0 + 4 * wave; r0 < t1; r0 += 4 * kWaves) {
-                const int r = r0 + rg;
-                if (r < t1) {   // whole DPP rows are in or out together
-                    const uint4 ku = *reinterpret_cast<const uint4*>(tk + (size_t)r * kHeadDim);
-                    const uint4 vu = *reinterpret_cast<const uint4*>(tv + (size_t)r * kHeadDim);
-                    const uint32_t kw[4] = {ku.x, ku.y, ku.z, ku.w}, vw[4] = {vu.x, vu.y, vu.z, vu.w};
-                    float kf[8], vf[8];
+            auto row_step = [&](uint4 ku, uint4 vu) {
+                const uint32_t kw[4] = {ku.x, ku.y, ku.z, ku.w}, vw[4] = {vu.x, vu.y, vu.z, vu.w};
+                float sc = 0.f, vf[8];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const h2v kk = as_h2(kw[j]), vv = as_h2(vw[j]);
-                        kf[2 * j] = (float)kk[0]; kf[2 * j + 1] = (float)kk[1];
-                        vf[2 * j] = (float)vv[0]; vf[2 * j + 1] = (float)vv[1];
-                    }
-#pragma unroll
-                    for (int h = 0; h < HB; ++h) {
-                        float sc = 0.f;
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) sc = __builtin_fmaf(qf[h][j], kf[j], sc);
-                        sc = row16_add(sc);
-                        const float mn = fmaxf(m[h], sc);
-                        const float alpha = __builtin_amdgcn_exp2f(m[h] - mn), pr = __builtin_amdgcn_exp2f(sc - mn);
-                        l[h] = __builtin_fmaf(l[h], alpha, pr);
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) o[h][j] = __builtin_fmaf(o[h][j], alpha, pr * vf[j]);
-                        m[h] = mn;
-                    }
+                for (int j = 0; j < 4; ++j) {
+                    const h2v kk = as_h2(kw[j]), vv = as_h2(vw[j]);
+                    sc = __builtin_fmaf(qf[2 * j], (float)kk[0], sc);
+                    sc = __builtin_fmaf(qf[2 * j + 1], (float)kk[1], sc);
+                    vf[2 * j] = (float)vv[0]; vf[2 * j + 1] = (float)vv[1];
                 }
+                sc = row16_add(sc);
+                const float mn = fmaxf(m, sc);
+                const float alpha = __builtin_amdgcn_exp2f(m - mn), pr = __builtin_amdgcn_exp2f(sc - mn);
+                l = __builtin_fmaf(l, alpha, pr);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] = __builtin_fmaf(o[j], alpha, pr * vf[j]);
+                m = mn;
+            };
+            if (r_first >= 0) row_step(k_first, v_first);   // whole DPP rows are in or out together
+            // the lane's further rows, four requested per round trip
+            constexpr int kStep = 4 * RP, kBatch = 4;
+            for (int r = r_first + kStep; r_first >= 0 && r < t1; r += kBatch * kStep) {
+                uint4 ku[kBatch], vu[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const int ru = (r + u * kStep < t1) ? r + u * kStep : r;
+                    ku[u] = *reinterpret_cast<const uint4*>(tk + (size_t)ru * kHeadDim);
+                    vu[u] = *reinterpret_cast<const uint4*>(tv + (size_t)ru * kHeadDim);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u)
+                    if (r + u * kStep < t1) row_step(ku[u], vu[u]);
             }
-            // merge the four row groups (lanes ^ 16, ^ 32)
+            if constexpr (RP > 1) {
+                // merge the row groups of a head: lanes ^ 32 (two heads), then also lanes ^ 16 (one head)
 #pragma unroll
-            for (int h = 0; h < HB; ++h) {
-#pragma unroll
-                for (int step = 0; step < 2; ++step) {
-                    const float mo = step ? xor32_get(m[h]) : xor16_get(m[h]);
-                    const float lo = step ? xor32_get(l[h]) : xor16_get(l[h]);
-                    const float mn = fmaxf(m[h], mo);
-                    const float ws = __builtin_amdgcn_exp2f(m[h] - mn), wo = __builtin_amdgcn_exp2f(mo - mn);
-                    l[h] = l[h] * ws + lo * wo;
+                for (int step = 0; step < (RP == 4 ? 2 : 1); ++step) {
+                    const float mo = step ? xor16_get(m) : xor32_get(m);
+                    const float lo = step ? xor16_get(l) : xor32_get(l);
+                    const float mn = fmaxf(m, mo);
+                    const float ws = __builtin_amdgcn_exp2f(m - mn), wo = __builtin_amdgcn_exp2f(mo - mn);
+                    l = l * ws + lo * wo;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const float oo = step ? xor32_get(o[h][j]) : xor16_get(o[h][j]);
-                        o[h][j] = o[h][j] * ws + oo * wo;
+                        const float oo = step ? xor16_get(o[j]) : xor32_get(o[j]);
+                        o[j] = o[j] * ws + oo * wo;
                     }
-                    m[h] = mn;
+                    m = mn;
                 }
             }
         }
-        if (lane < 16) {
+        if ((lane >> 4) < HB) {
+            float* row = sT + (wave * GQ + h0 + hb) * kPartStride;
+            if (seg == 0) { row[0] = m; row[1] = l; }
 #pragma unroll
-            for (int h = 0; h < HB; ++h) {
-                float* row = sT + (wave * GQ + h0 + h) * kPartStride;
-                if (lane == 0) { row[0] = m[h]; row[1] = l[h]; }
-#pragma unroll
-                for (int j = 0; j < 8; ++j) row[2 + 8 * lane + j] = o[h][j];
-            }
+            for (int j = 0; j < 8; ++j) row[2 + 8 * seg + j] = o[j];
         }
     }
 }
@@ -1131,6 +1144,18 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     constexpr bool kEarlyB = QUANT;
     constexpr bool kJoint = QUANT && !OUT && !(KT && BITS == 2);   // (where it measured faster: see the loop)
     if (chunk < c_end) { load_A(chunk); if (kEarlyB) load_B(chunk, two); }   // issued before anything else waits on memory
+    // ... and with them the wave's first step of this workgroup's share of the full-precision tail rows
+    const int tail_t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
+    const int tail_t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
+    uint4 tail_k0 = make_uint4(0u, 0u, 0u, 0u), tail_v0 = tail_k0;
+    {
+        const int r = tail_first_row<GQ>(tail_t0, tail_t1, wave, lane);
+        if (r >= 0) {
+            const size_t at = ((size_t)bh * a.tail_cap + r) * kHeadDim + 8 * (lane & 15);
+            tail_k0 = *reinterpret_cast<const uint4*>(a.tail_k + at);
+            tail_v0 = *reinterpret_cast<const uint4*>(a.tail_v + at);
+        }
+    }
     // Query rows with each register's field-position factor folded in: MFMA operand layout, lane
     // (head row, channel block kb).  The quantized variants park them in LDS (same for every wave)
     // and re-read them when a key group's scales arrive; that frees 16 registers in the loop.
@@ -1163,7 +1188,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             }
         }
     }
-    if constexpr (QUANT) {
+    {   // plain copy (every variant: the tail rows read it too)
         for (int item = threadIdx.x; item < 8 * kHeadDim / 2; item += blockDim.x) {
             const int hh = item / (kHeadDim / 2), w = item % (kHeadDim / 2);
             const uint32_t v = hh < GQ ? reinterpret_cast<const uint32_t*>(a.q + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[w] : 0u;
@@ -1190,9 +1215,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         for (int ps = 0; ps < KP; ++ps) kt_qs[ps] = quad_rows_add(kt_mine[ps] ? own : 0.f) * (1.0f / kCodeUnit);
     }
     // the tail rows go first, while the first blocks are on their way (their state waits in LDS)
-    const int tail_t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
-    const int tail_t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
-    if (wave < kWaves) tail_rows<GQ>(a, bh, tail_t0, tail_t1, sT);
+    if (wave < kWaves) tail_rows<GQ>(a, bh, tail_t0, tail_t1, sT, sq, tail_k0, tail_v0);
     while (chunk < c_end) {
         if (!kEarlyB) load_B(chunk, two);
         const int next = claim();                            // used half an iteration later
