@@ -71,7 +71,12 @@ constexpr float kLazyLog2 = 4.0f;   // slack of the lazily updated softmax refer
 // above, p stays below 2^(kLazyLog2 + kPBoost) = 2^8, the bound it always had.  (A smaller slack
 // with a larger factor is more exact still, but moves the reference about once per row and wave.)
 constexpr float kPBoost = 4.0f;
-constexpr int kPartStride = kHeadDim + 2;  // floats per (partial, head): m, l, acc[128]
+constexpr int kPartStride = kHeadDim + 2;  // floats per (wave, head) of the tail states in LDS: m, l, acc[128]
+// A split's partial result in the workspace, per query head: 64 x {m, l, o[2j], o[2j+1]} -- the
+// reference and the sum repeated beside every channel pair, so that the workgroup that merges
+// fetches all it needs of one partial with a single 16-byte load per thread.
+constexpr int kPartPairs = kHeadDim / 2;
+constexpr int kPartFloats = 4 * kPartPairs;
 
 __device__ __forceinline__ float xor16_max(float v) {
     auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
@@ -253,8 +258,22 @@ __device__ __forceinline__ int head_chunks_per_split(const DecodeArgs& a, int n_
 // Partials cross workgroups (and XCDs, whose L2 caches are not coherent with each other inside a
 // kernel) without device-wide fences, which would write back / invalidate whole L2s: they are
 // written and read with device-scope accesses that go to the coherence point directly.
-__device__ __forceinline__ void st_dev(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// They move 16 bytes at a time: buffer accesses with the device-scope bit (sc1) of the cache policy
+// -- the instruction form of a relaxed atomic load / store at agent scope, which only comes in 4 and
+// 8 bytes -- through a descriptor over one head's partials (offsets in bytes; accesses outside the
+// descriptor's range read zero / are dropped).  No atomicity across the 16 bytes is needed: a
+// partial is complete and acknowledged before its workgroup bumps the arrival counter.
+constexpr int kAuxDevScope = 16;   // sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t part_rsrc(float* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ void st_dev16(__amdgpu_buffer_rsrc_t r, unsigned off, float x, float y, float z, float w) {
+    u4v v; v[0] = __float_as_uint(x); v[1] = __float_as_uint(y); v[2] = __float_as_uint(z); v[3] = __float_as_uint(w);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, kAuxDevScope);
+}
+__device__ __forceinline__ u4v ld_dev16(__amdgpu_buffer_rsrc_t r, unsigned off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, kAuxDevScope);
+}
 
 // Arrival counters, one per (batch, kv head), at the head of the call's workspace.  Every workgroup
 // of a head bumps its counter after its partial is written; the last one to arrive merges the
@@ -267,12 +286,13 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
     __shared__ int s_last;
     // Ordering of the partials before the counter, without an agent-scope release fence (which
     // writes back the whole L2).  What this relies on, all of it stated for gfx942 / gfx950 in the
-    // AMDGPU memory model: (1) a relaxed atomic store at agent scope is a write-through store: it is
-    // performed at the device's coherence point, not left dirty in the XCD's L2; (2) vmcnt counts
+    // AMDGPU memory model: (1) a store with the device-scope policy bit (what a relaxed atomic store
+    // at agent scope is) is a write-through store: it is performed at the device's coherence point,
+    // not left dirty in the XCD's L2; (2) vmcnt counts
     // stores, and s_waitcnt vmcnt(0) returns only when every earlier store of the wave has been
     // acknowledged from there; (3) the barrier after it orders every wave's wait before thread 0's
     // read-modify-write, which is performed at the same coherence point.  A workgroup that sees the
-    // bumped counter therefore finds the partials with agent-scope loads (which do not hit in its L2).
+    // bumped counter therefore finds the partials with device-scope loads (which do not hit in its L2).
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -285,46 +305,44 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
     __syncthreads();
     if (!s_last) return;
     const int b = bh / a.n_kv_heads, g = bh % a.n_kv_heads;
-    const float* base = a.part + (size_t)bh * a.n_partials * GQ * kPartStride;
-    const size_t stride = (size_t)GQ * kPartStride;
-    // Device-scope loads are slow (they go to the coherence point) and are kept in program order,
-    // so many are put in flight per round trip -- kMergeBatch partials of a thread's output -- and
-    // every wave of the workgroup takes part (one output per thread where the workgroup is large
-    // enough).  (Fetching a partial's reference and sum, which lie side by side, with one 8-byte
-    // load measured slower than two 4-byte ones.)
-    constexpr int kMergeBatch = 16;
-    for (int item = threadIdx.x; item < GQ * kHeadDim; item += blockDim.x) {
-        const int h = item / kHeadDim, d = item % kHeadDim;
-        float M = kNegBig, acc = 0.f, L = 0.f;
+    const unsigned head_bytes = (unsigned)a.n_partials * GQ * kPartFloats * 4u;
+    const __amdgpu_buffer_rsrc_t rs = part_rsrc(a.part + (size_t)bh * a.n_partials * GQ * kPartFloats, head_bytes);
+    // Device-scope loads are slow (they go to the coherence point), so a whole batch of partials is
+    // put in flight per round trip: one 16-byte load per partial and thread, a thread owning one
+    // pair of output channels.
+    constexpr int kMergeBatch = 32;
+    for (int item = threadIdx.x; item < GQ * kPartPairs; item += blockDim.x) {
+        const int h = item / kPartPairs, j = item % kPartPairs;
+        float M = kNegBig, acc0 = 0.f, acc1 = 0.f, L = 0.f;
         for (int s0 = 0; s0 < a.n_partials; s0 += kMergeBatch) {
-            float m[kMergeBatch], l[kMergeBatch], o[kMergeBatch];
+            u4v v[kMergeBatch];
 #pragma unroll
             for (int u4 = 0; u4 < kMergeBatch; u4 += 4) {
                 if (s0 + u4 < a.n_partials) {          // (uniform: whole groups of four beyond the last partial are not fetched)
 #pragma unroll
-                    for (int u = u4; u < u4 + 4; ++u) {
-                        const float* q = base + (size_t)h * kPartStride + (size_t)min(s0 + u, a.n_partials - 1) * stride;
-                        m[u] = ld_dev(q); l[u] = ld_dev(q + 1); o[u] = ld_dev(q + 2 + d);
-                    }
+                    for (int u = u4; u < u4 + 4; ++u)
+                        v[u] = ld_dev16(rs, (unsigned)((min(s0 + u, a.n_partials - 1) * GQ + h) * kPartPairs + j) * 16u);
                 } else {
 #pragma unroll
-                    for (int u = u4; u < u4 + 4; ++u) { m[u] = kNegBig; l[u] = 0.f; o[u] = 0.f; }
+                    for (int u = u4; u < u4 + 4; ++u) { v[u][0] = __float_as_uint(kNegBig); v[u][1] = 0u; v[u][2] = 0u; v[u][3] = 0u; }
                 }
             }
             float Mn = M;
 #pragma unroll
-            for (int u = 0; u < kMergeBatch; ++u) Mn = fmaxf(Mn, m[u]);
+            for (int u = 0; u < kMergeBatch; ++u) Mn = fmaxf(Mn, __uint_as_float(v[u][0]));
             const float keep = __builtin_amdgcn_exp2f(M - Mn);
-            acc *= keep; L *= keep;
+            acc0 *= keep; acc1 *= keep; L *= keep;
 #pragma unroll
             for (int u = 0; u < kMergeBatch; ++u) {
-                const float wgt = (s0 + u < a.n_partials) ? __builtin_amdgcn_exp2f(m[u] - Mn) : 0.f;
-                acc = __builtin_fmaf(wgt, o[u], acc);
-                L = __builtin_fmaf(wgt, l[u], L);
+                const float wgt = (s0 + u < a.n_partials) ? __builtin_amdgcn_exp2f(__uint_as_float(v[u][0]) - Mn) : 0.f;
+                acc0 = __builtin_fmaf(wgt, __uint_as_float(v[u][2]), acc0);
+                acc1 = __builtin_fmaf(wgt, __uint_as_float(v[u][3]), acc1);
+                L = __builtin_fmaf(wgt, __uint_as_float(v[u][1]), L);
             }
             M = Mn;
         }
-        a.out[((size_t)b * a.n_q_heads + g * GQ + h) * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc / L));
+        const uint32_t lo = __half_as_ushort(__float2half_rn(acc0 / L)), hi = __half_as_ushort(__float2half_rn(acc1 / L));
+        reinterpret_cast<uint32_t*>(a.out + ((size_t)b * a.n_q_heads + g * GQ + h) * kHeadDim)[j] = lo | (hi << 16);
     }
 }
 
@@ -1313,7 +1331,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     // common reference over the waves' states and this workgroup's share of the full-precision tail
     // rows (the first four waves' states in sT), then one pass that weighs and adds them.  All
     // threads of a head read the same references and sums (LDS broadcasts); nw is a multiple of 4.
-    float* dst = a.part + ((size_t)bh * a.n_partials + blockIdx.x) * GQ * kPartStride;
+    const __amdgpu_buffer_rsrc_t part_rs = part_rsrc(a.part + (size_t)bh * a.n_partials * GQ * kPartFloats, (unsigned)a.n_partials * GQ * kPartFloats * 4u);
     for (int item = threadIdx.x; item < GQ * kHeadDim; item += blockDim.x) {
         const int hh = item / kHeadDim, d = item % kHeadDim;
         const int cg = d / G;
@@ -1348,8 +1366,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         if (a.n_splits == 1) {   // the whole head was here: normalise, round once, done
             a.out[((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc / L));
         } else {
-            st_dev(dst + hh * kPartStride + 2 + d, acc);
-            if (d == 0) { st_dev(dst + hh * kPartStride, M); st_dev(dst + hh * kPartStride + 1, L); }
+            // the even lane of a channel pair stores both channels (the odd one's through DPP), reference and sum beside them
+            const float other = __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(acc), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+            if ((d & 1) == 0) st_dev16(part_rs, (unsigned)((blockIdx.x * GQ + hh) * kPartPairs + (d >> 1)) * 16u, M, L, acc, other);
         }
     }
     if (a.n_splits == 1) return;
@@ -1437,7 +1456,7 @@ size_t decode_ws_bound(const kvqp_cfg& cfg) {
     int splits = (share + kWaves - 1) / kWaves;
     if (cfg.decode_splits > splits) splits = cfg.decode_splits;
     if (splits < 1) splits = 1;
-    return decode_ws_header_bytes(cfg) + (size_t)heads * splits * gq * kPartStride * sizeof(float);
+    return decode_ws_header_bytes(cfg) + (size_t)heads * splits * gq * kPartFloats * sizeof(float);
 }
 
 DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
@@ -1478,7 +1497,7 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         p.n_splits = p.chunks_per_split ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 1;
         p.n_partials = p.n_splits;
     }
-    p.ws_bytes = decode_ws_header_bytes(cfg) + (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartStride * sizeof(float);
+    p.ws_bytes = decode_ws_header_bytes(cfg) + (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartFloats * sizeof(float);
     return p;
 }
 

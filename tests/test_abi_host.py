@@ -238,7 +238,7 @@ def test_decode_workspace_covers_every_token_count(lib):
     a = kvqp.workspace_bytes(kvqp.Cfg(batch=1, n_q_heads=8, n_kv_heads=2, seq_len=4096, window=32, budget=1024, bits=4))[1]
     b = kvqp.workspace_bytes(kvqp.Cfg(batch=1, n_q_heads=8, n_kv_heads=2, seq_len=4096, window=32, budget=1024, bits=4,
                                       decode_splits=500))[1]
-    assert b >= 2 * 500 * 4 * 130 * 4 and b > a      # the caller's split count is covered
+    assert b >= 2 * 500 * 4 * 256 * 4 and b > a      # the caller's split count is covered
 
 
 def test_binding_raises_with_the_library_message(lib):
@@ -267,7 +267,7 @@ def test_decode_workspace_init_and_static_entry_validate_on_the_host(lib):
     assert lib.kvqp_decode_workspace_init(C.byref(st), None, 1 << 20, None) == -3
     assert lib.kvqp_decode_workspace_init(C.byref(st), fake, 64, None) == -3            # 32 counters need 128 bytes
     assert lib.kvqp_decode_workspace_init(C.byref(st), C.c_void_p(0x1004), 1 << 20, None) == -1
-    assert kvqp.workspace_bytes(cfg)[1] >= 256 + 32 * 4 * 130 * 4                           # counters, then partials
+    assert kvqp.workspace_bytes(cfg)[1] >= 256 + 32 * 4 * 256 * 4                         # counters, then partials
     cs = kvqp.CacheStruct()
     for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v"):
         setattr(cs, name, 0x1000)
