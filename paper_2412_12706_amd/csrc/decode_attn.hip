@@ -1327,13 +1327,13 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
         for (int c = 0; c < NCG; ++c) st[2 + c] = oz[c];
     }
     __syncthreads();
-    // One output (head hh, channel d) per thread, every wave of the workgroup taking part: the
-    // common reference over the waves' states and this workgroup's share of the full-precision tail
-    // rows (the first four waves' states in sT), then one pass that weighs and adds them.  All
-    // threads of a head read the same references and sums (LDS broadcasts); nw is a multiple of 4.
+    // One pair of output channels (head hh, channels d, d + 1) per thread: the common reference over
+    // the waves' states and this workgroup's share of the full-precision tail rows (the first four
+    // waves' states in sT), then one pass that weighs and adds them.  All threads of a head read the
+    // same references and sums (LDS broadcasts); nw is a multiple of 4.
     const __amdgpu_buffer_rsrc_t part_rs = part_rsrc(a.part + (size_t)bh * a.n_partials * GQ * kPartFloats, (unsigned)a.n_partials * GQ * kPartFloats * 4u);
-    for (int item = threadIdx.x; item < GQ * kHeadDim; item += blockDim.x) {
-        const int hh = item / kHeadDim, d = item % kHeadDim;
+    for (int item = threadIdx.x; item < GQ * kPartPairs; item += blockDim.x) {
+        const int hh = item / kPartPairs, d = 2 * (item % kPartPairs);
         const int cg = d / G;
         float M = kNegBig;
         for (int w0 = 0; w0 < nw; w0 += kWaves)
@@ -1343,32 +1343,40 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
                 for (int sl = 0; sl < SLOTS; ++sl) M = fmaxf(M, sS[((w0 + w) * 16 + sl * 8 + 2 * hh) * 6]);
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sT[(w * GQ + hh) * kPartStride]);
-        float acc = 0.f, L = 0.f;
+        float acc0 = 0.f, acc1 = 0.f, L = 0.f;
         for (int w0 = 0; w0 < nw; w0 += kWaves)
 #pragma unroll
             for (int w = 0; w < kWaves; ++w)
 #pragma unroll
                 for (int sl = 0; sl < SLOTS; ++sl) {
                     const float* st = sS + ((w0 + w) * 16 + sl * 8 + 2 * hh) * 6;
-                    const float wgt = __builtin_amdgcn_exp2f(st[0] - M);
-                    float o = sO[((w0 + w) * 8 + sl * 4 + hh) * kHeadDim + d] * kCodeUnit + st[2 + cg];
-                    if constexpr (OUT) o += s_oc[((w0 + w) * 8 + sl * 4 + hh) * kHeadDim + d];
-                    acc = __builtin_fmaf(wgt, o, acc);
-                    L = __builtin_fmaf(wgt, st[1], L);
+                    const float2 ml = *reinterpret_cast<const float2*>(st);
+                    const float wgt = __builtin_amdgcn_exp2f(ml.x - M);
+                    const float2 o2 = *reinterpret_cast<const float2*>(sO + ((w0 + w) * 8 + sl * 4 + hh) * kHeadDim + d);
+                    float o0 = o2.x * kCodeUnit + st[2 + cg], o1 = o2.y * kCodeUnit + st[2 + cg];
+                    if constexpr (OUT) {
+                        const float2 c2 = *reinterpret_cast<const float2*>(s_oc + ((w0 + w) * 8 + sl * 4 + hh) * kHeadDim + d);
+                        o0 += c2.x; o1 += c2.y;
+                    }
+                    acc0 = __builtin_fmaf(wgt, o0, acc0);
+                    acc1 = __builtin_fmaf(wgt, o1, acc1);
+                    L = __builtin_fmaf(wgt, ml.y, L);
                 }
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
             const float* row = sT + (w * GQ + hh) * kPartStride;
-            const float wgt = __builtin_amdgcn_exp2f(row[0] - M);
-            acc = __builtin_fmaf(wgt, row[2 + d], acc);
-            L = __builtin_fmaf(wgt, row[1], L);
+            const float2 ml = *reinterpret_cast<const float2*>(row);
+            const float2 o2 = *reinterpret_cast<const float2*>(row + 2 + d);
+            const float wgt = __builtin_amdgcn_exp2f(ml.x - M);
+            acc0 = __builtin_fmaf(wgt, o2.x, acc0);
+            acc1 = __builtin_fmaf(wgt, o2.y, acc1);
+            L = __builtin_fmaf(wgt, ml.y, L);
         }
         if (a.n_splits == 1) {   // the whole head was here: normalise, round once, done
-            a.out[((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim + d] = __half_as_ushort(__float2half_rn(acc / L));
-        } else {
-            // the even lane of a channel pair stores both channels (the odd one's through DPP), reference and sum beside them
-            const float other = __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(acc), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-            if ((d & 1) == 0) st_dev16(part_rs, (unsigned)((blockIdx.x * GQ + hh) * kPartPairs + (d >> 1)) * 16u, M, L, acc, other);
+            const uint32_t lo = __half_as_ushort(__float2half_rn(acc0 / L)), hi = __half_as_ushort(__float2half_rn(acc1 / L));
+            reinterpret_cast<uint32_t*>(a.out + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[d >> 1] = lo | (hi << 16);
+        } else {                 // this split's record of the pair, reference and sum beside it
+            st_dev16(part_rs, (unsigned)((blockIdx.x * GQ + hh) * kPartPairs + (d >> 1)) * 16u, M, L, acc0, acc1);
         }
     }
     if (a.n_splits == 1) return;
