@@ -87,6 +87,22 @@ def test_split_count_does_not_change_the_result(orc, bits):
         assert np.abs(out.cpu().numpy().astype(np.float64) - ref).max() <= TOL
 
 
+@pytest.mark.parametrize("bits,Gq,n_kept,splits", [(4, 4, 2240, 35), (16, 8, 4096, 64), (2, 2, 2592, 41)])
+def test_more_partials_than_one_merge_round(orc, bits, Gq, n_kept, splits):
+    """The workgroup that merges a head's splits fetches 32 partials per round: heads cut into 35, 41
+    and 64 single-chunk splits take a second round with 3, 9 and 32 partials in it (and a tail row
+    share of zero or one row per split)."""
+    cfg, oc = build_case(orc, bits, 32, 0, Gq, n_kept, 32, 1, 2, cfgid=57)
+    q = synth.decode_query_host(1, cfg.n_q_heads, 128, config=57)
+    ref = orc.decode_attn(q, oc, cfg.sm_scale)
+    cfg.decode_splits = splits
+    out = kvqp.decode_attn(cfg, dev(q), upload_cache(oc))
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref).max()
+    print(f"  bits={bits} Gq={Gq} splits={splits} max-abs error {err:.3e}", flush=True)
+    assert err <= TOL
+
+
 def test_peaked_attention_and_large_logits(orc):
     """One key strongly aligned with the query (softmax mass on one token) and
     x20 outlier channels: the hi/lo operand split has to hold up."""
