@@ -360,7 +360,7 @@ int kvqp_decode_workspace_init(const kvqp_cfg *cfg, void *workspace, size_t work
  *   - The first call on a GPU looks the array's address up and zeroes its
  *     counters with a small kernel on the given stream.
  */
-#define KVQP_STATIC_SCRATCH_BYTES (4u << 20)
+#define KVQP_STATIC_SCRATCH_BYTES (8u << 20)
 int kvqp_decode_attn_static(const kvqp_cfg *cfg, const void *q, const kvqp_cache *cache, void *out,
                             void *hip_stream);
 

@@ -1505,7 +1505,8 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
         p.n_splits = p.chunks_per_split ? (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split : 1;
         p.n_partials = p.n_splits;
     }
-    p.ws_bytes = decode_ws_header_bytes(cfg) + (size_t)heads * (size_t)(p.n_partials > 0 ? p.n_partials : 1) * gq * kPartFloats * sizeof(float);
+    // (a head that stays in one workgroup writes no partial: the counters' bytes are all the launch touches)
+    p.ws_bytes = decode_ws_header_bytes(cfg) + (p.n_splits > 1 ? (size_t)heads * (size_t)p.n_partials * gq * kPartFloats * sizeof(float) : 0);
     return p;
 }
 

@@ -274,6 +274,7 @@ def test_decode_workspace_init_and_static_entry_validate_on_the_host(lib):
     cs.n_kept, cs.tail_len, cs.tail_cap = 1024, 32, 32
     assert lib.kvqp_decode_attn_static(C.byref(st), None, C.byref(cs), fake, None) == -1
     assert lib.kvqp_decode_attn_static(C.byref(st), fake, None, fake, None) == -1
-    big = kvqp.Cfg(batch=8192, n_q_heads=56, n_kv_heads=7, seq_len=4096, window=32, budget=1024, bits=4)
-    assert kvqp.workspace_bytes(big)[1] > (4 << 20)
+    # 128 heads cut into 16 splits by the caller: 16 MB of partials, beyond the library's array
+    big = kvqp.Cfg(batch=16, n_q_heads=64, n_kv_heads=8, seq_len=4096, window=32, budget=1024, bits=4, decode_splits=16)
+    assert kvqp.workspace_bytes(big)[1] > (8 << 20)
     assert lib.kvqp_decode_attn_static(C.byref(big.struct()), fake, C.byref(cs), fake, None) == -3

@@ -44,12 +44,12 @@ def test_static_scratch_entry_matches_the_workspace_entry(orc):
 
 
 def test_static_scratch_entry_rejects_what_does_not_fit():
-    # 65535 heads of eight query heads each: the partials of even one split per head pass the array's size
-    cfg = kvqp.Cfg(batch=8192, n_q_heads=56, n_kv_heads=7, seq_len=128, window=32, budget=64, bits=4, group_size=32)
-    assert kvqp.workspace_bytes(cfg)[1] > (4 << 20)
+    # 128 heads of eight query heads each, cut into 64 splits by the caller: 64 MB of partials (1 KB per split and query head)
+    cfg = kvqp.Cfg(batch=16, n_q_heads=64, n_kv_heads=8, seq_len=4224, window=32, budget=4096, bits=4, group_size=32, decode_splits=64)
+    assert kvqp.workspace_bytes(cfg)[1] > (8 << 20)
     dummy = torch.zeros(64, dtype=torch.uint8, device="cuda")
     cache = kvqp.Cache({n: dummy for n in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "tail_k", "tail_v")},
-                       n_kept=64, tail_len=32, tail_cap=32)
+                       n_kept=4096, tail_len=32, tail_cap=32)
     with pytest.raises(kvqp.KvqpError) as e:
         kvqp.decode_attn_static(cfg, dummy, cache, dummy)        # rejected on the host: nothing is launched
     assert e.value.code == -3
