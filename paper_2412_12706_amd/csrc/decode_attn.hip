@@ -250,9 +250,17 @@ __device__ __forceinline__ int head_tokens(const DecodeArgs& a, int bh) {
     const int n = a.head_n_kept[bh];
     return n < 0 ? 0 : (n > a.n_kept ? a.n_kept : n);
 }
-// 64-token chunks a split workgroup takes: the plan's share, or an even share of the head's own chunks
-__device__ __forceinline__ int head_chunks_per_split(const DecodeArgs& a, int n_chunks) {
-    return a.head_n_kept ? (n_chunks + a.n_splits - 1) / a.n_splits : a.chunks_per_split;
+// Workgroups a head is cut into.  Every workgroup takes the plan's range of 64-token chunks
+// (chunks_per_split); with per-head token counts a head uses only as many of the launch's n_splits
+// ranges as its own chunks fill -- at least one, which also takes the tail rows of a head that has
+// no packed token -- and the workgroups beyond that leave at once.  Heads of different lengths are
+// so cut into pieces of about equal work, and a head that fits one range skips the merge across
+// workgroups altogether.
+__device__ __forceinline__ int head_splits(const DecodeArgs& a, int n_chunks) {
+    if (!a.head_n_kept) return a.n_splits;
+    const int cps = a.chunks_per_split > 0 ? a.chunks_per_split : 1;
+    const int ns = (n_chunks + cps - 1) / cps;
+    return ns < 1 ? 1 : (ns > a.n_splits ? a.n_splits : ns);
 }
 
 // Partials cross workgroups (and XCDs, whose L2 caches are not coherent with each other inside a
@@ -282,7 +290,7 @@ __device__ __forceinline__ u4v ld_dev16(__amdgpu_buffer_rsrc_t r, unsigned off) 
 // with different workspaces share nothing and may overlap in time.
 // Merge the splits of one KV head's query heads and round once to binary16 (last workgroup only).
 template <int GQ>
-__device__ void merge_if_last(const DecodeArgs& a, int bh) {
+__device__ void merge_if_last(const DecodeArgs& a, int bh, int n_parts) {
     __shared__ int s_last;
     // Ordering of the partials before the counter, without an agent-scope release fence (which
     // writes back the whole L2).  What this relies on, all of it stated for gfx942 / gfx950 in the
@@ -298,7 +306,7 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
     __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned prev = __hip_atomic_fetch_add(&a.arrivals[bh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int last = prev == (unsigned)(a.n_partials - 1);
+        const int last = prev == (unsigned)(n_parts - 1);
         if (last) __hip_atomic_store(&a.arrivals[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = last;
     }
@@ -314,14 +322,14 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
     for (int item = threadIdx.x; item < GQ * kPartPairs; item += blockDim.x) {
         const int h = item / kPartPairs, j = item % kPartPairs;
         float M = kNegBig, acc0 = 0.f, acc1 = 0.f, L = 0.f;
-        for (int s0 = 0; s0 < a.n_partials; s0 += kMergeBatch) {
+        for (int s0 = 0; s0 < n_parts; s0 += kMergeBatch) {
             u4v v[kMergeBatch];
 #pragma unroll
             for (int u4 = 0; u4 < kMergeBatch; u4 += 4) {
-                if (s0 + u4 < a.n_partials) {          // (uniform: whole groups of four beyond the last partial are not fetched)
+                if (s0 + u4 < n_parts) {          // (uniform: whole groups of four beyond the last partial are not fetched)
 #pragma unroll
                     for (int u = u4; u < u4 + 4; ++u)
-                        v[u] = ld_dev16(rs, (unsigned)((min(s0 + u, a.n_partials - 1) * GQ + h) * kPartPairs + j) * 16u);
+                        v[u] = ld_dev16(rs, (unsigned)((min(s0 + u, n_parts - 1) * GQ + h) * kPartPairs + j) * 16u);
                 } else {
 #pragma unroll
                     for (int u = u4; u < u4 + 4; ++u) { v[u][0] = __float_as_uint(kNegBig); v[u][1] = 0u; v[u][2] = 0u; v[u][3] = 0u; }
@@ -334,7 +342,7 @@ __device__ void merge_if_last(const DecodeArgs& a, int bh) {
             acc0 *= keep; acc1 *= keep; L *= keep;
 #pragma unroll
             for (int u = 0; u < kMergeBatch; ++u) {
-                const float wgt = (s0 + u < a.n_partials) ? __builtin_amdgcn_exp2f(__uint_as_float(v[u][0]) - Mn) : 0.f;
+                const float wgt = (s0 + u < n_parts) ? __builtin_amdgcn_exp2f(__uint_as_float(v[u][0]) - Mn) : 0.f;
                 acc0 = __builtin_fmaf(wgt, __uint_as_float(v[u][2]), acc0);
                 acc1 = __builtin_fmaf(wgt, __uint_as_float(v[u][3]), acc1);
                 L = __builtin_fmaf(wgt, __uint_as_float(v[u][1]), L);
@@ -601,6 +609,9 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     const uint32_t row_lane = (uint32_t)lane * 4;                                     // dword of a 256-byte scale row
     const uint32_t vrow_lane = (uint32_t)min(lane, VROW / 4 - 1) * 4;                 // dword of a block's value scales
     const int n_kept = head_tokens(a, bh);
+    const int n_chunks = (n_kept + kChunk - 1) / kChunk;
+    const int n_parts = head_splits(a, n_chunks);                     // workgroups of this head (uniform over the workgroup)
+    if ((int)blockIdx.x >= n_parts) return;
     const int n_kgroups = QUANT ? max((n_kept + G - 1) / G, 1) : 0;   // (the last group may hold fewer than G tokens)
     // The loads of the pipeline are unconditional; when a wave has no further chunk they are pointed
     // at one 16-byte spot (lane offsets zeroed) instead of re-reading a whole chunk.
@@ -1139,8 +1150,7 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             O[t8] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[(t8 * 16) / G].v, v_frag<BITS>(vv, vblk, t8).v, O[t8], 0, 0, 0);
     };
 
-    const int n_chunks = (n_kept + kChunk - 1) / kChunk;
-    const int cps = head_chunks_per_split(a, n_chunks);
+    const int cps = a.chunks_per_split;
     const int c_begin = blockIdx.x * cps;
     const int c_end = min(n_chunks, c_begin + cps);
     // Chunks are claimed, not dealt: a wave takes its first chunk by index and every later one from
@@ -1163,8 +1173,8 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
     constexpr bool kJoint = QUANT && !OUT && !(KT && BITS == 2);   // (where it measured faster: see the loop)
     if (chunk < c_end) { load_A(chunk); if (kEarlyB) load_B(chunk, two); }   // issued before anything else waits on memory
     // ... and with them the wave's first step of this workgroup's share of the full-precision tail rows
-    const int tail_t0 = (int)(((long long)a.tail_len * blockIdx.x) / a.n_splits);
-    const int tail_t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / a.n_splits);
+    const int tail_t0 = (int)(((long long)a.tail_len * blockIdx.x) / n_parts);
+    const int tail_t1 = (int)(((long long)a.tail_len * (blockIdx.x + 1)) / n_parts);
     uint4 tail_k0 = make_uint4(0u, 0u, 0u, 0u), tail_v0 = tail_k0;
     {
         const int r = tail_first_row<GQ>(tail_t0, tail_t1, wave, lane);
@@ -1372,15 +1382,15 @@ __global__ __launch_bounds__(64 * pipe_max_waves(BITS, GQ, OUT), 1) void decode_
             acc1 = __builtin_fmaf(wgt, o2.y, acc1);
             L = __builtin_fmaf(wgt, ml.y, L);
         }
-        if (a.n_splits == 1) {   // the whole head was here: normalise, round once, done
+        if (n_parts == 1) {      // the whole head was here: normalise, round once, done
             const uint32_t lo = __half_as_ushort(__float2half_rn(acc0 / L)), hi = __half_as_ushort(__float2half_rn(acc1 / L));
             reinterpret_cast<uint32_t*>(a.out + ((size_t)b * a.n_q_heads + g * GQ + hh) * kHeadDim)[d >> 1] = lo | (hi << 16);
         } else {                 // this split's record of the pair, reference and sum beside it
             st_dev16(part_rs, (unsigned)((blockIdx.x * GQ + hh) * kPartPairs + (d >> 1)) * 16u, M, L, acc0, acc1);
         }
     }
-    if (a.n_splits == 1) return;
-    merge_if_last<GQ>(a, bh);
+    if (n_parts == 1) return;
+    merge_if_last<GQ>(a, bh, n_parts);
 }
 
 // Which chunks of every head a launch reads with the non-temporal hint (streamed round the 256 MB
