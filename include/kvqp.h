@@ -70,7 +70,10 @@ typedef struct kvqp_cfg {
     int32_t bits;         /* B: 2, 4, 8, or 16 (16 = keep half, no scale/zero)           */
     int32_t group_size;   /* G; must divide D                                            */
     int32_t key_axis;     /* KVQP_KEY_PER_CHANNEL or KVQP_KEY_PER_TOKEN                  */
-    int32_t decode_splits;/* token-axis splits of decode attention; 0 = library chooses  */
+    int32_t decode_splits;/* token-axis splits of decode attention; 0 = library chooses.
+                             With per-head token counts the splits are equal token ranges
+                             of the longest possible head, and a head uses as many as its
+                             own tokens fill                                             */
     float sm_scale;       /* logit scale > 0, e.g. 1/sqrt(D) (Eq. (3) omits it)          */
     float outlier_threshold; /* tau; > 0 turns outlier filtering on (below), 0 = off     */
     int32_t decode_cache_hint; /* KVQP_CACHE_*: how kvqp_decode_attn's loads treat the
