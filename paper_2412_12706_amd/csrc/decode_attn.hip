@@ -1500,8 +1500,9 @@ DecodePlan plan_decode(const kvqp_cfg& cfg, int n_kept, int tail_len) {
             nw = waves / kWaves * kWaves;
         } else {                                // several workgroups per head: small ones while CUs are left over
             nw = (int)((long long)waves * heads / n_cu) / kWaves * kWaves;
-            // (the last workgroup of a head fetches sixteen partials per round trip: larger workgroups
-            // rather than more of them while that keeps a head within one round)
+            // (a head is kept within sixteen partials by making the workgroups larger rather than more:
+            // the last workgroup fetches 1 KB per partial and query head through its own CU, and 32
+            // four-wave workgroups per head measured slower than 16 of eight waves)
             const int nw16 = ((waves + 15) / 16 + kWaves - 1) / kWaves * kWaves;
             if (nw < nw16) nw = nw16;
             if (nw > max_nw) nw = max_nw;
