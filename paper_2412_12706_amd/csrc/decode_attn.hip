@@ -273,6 +273,8 @@ __device__ __forceinline__ int head_splits(const DecodeArgs& a, int n_chunks) {
 // partial is complete and acknowledged before its workgroup bumps the arrival counter.
 constexpr int kAuxDevScope = 16;   // sc1
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t part_rsrc(float* base, unsigned bytes) {
+    // stride 0 (raw byte offsets), `bytes` as the range that is checked, and the descriptor's last
+    // word as raw buffers take it on gfx9-family parts: 32-bit data format, no swizzle, no tiling
     return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);
 }
 __device__ __forceinline__ void st_dev16(__amdgpu_buffer_rsrc_t r, unsigned off, float x, float y, float z, float w) {
